@@ -1,0 +1,228 @@
+"""CPU oracle for Tensorized Attention (arXiv 2410.20926).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, float64 definition
+that the GPU library is checked against.  Only the test-suite, the smoke
+check and the benchmark's `cpu_baseline` leg may import it; the product path
+never does.  It shares no code with the HIP path and imports nothing from it.
+
+What it implements, in the paper's own order and notation:
+
+* Eq. 1               -- `attention`: vector-space softmax attention.
+* Eq. 4               -- `axis_attention`: mode-i flattening, batched
+                         softmax(Q_i K_i^T / sqrt(d) o M_i), value update,
+                         mode-i folding.
+* Algorithm 1         -- `tensorized_attention_forward`: O = V, one hop per
+                         tensor axis with the same Q and K, vectorise.
+* chain rule of Alg. 1 -- `tensorized_attention_backward` (the paper only says
+                         that a backward exists, Sec. 3.2; this is the plain
+                         derivative of the forward, hop by hop in reverse).
+
+Readings taken where the paper is silent (all listed in the design notes):
+  - the mask "o M" excludes positions (logit -inf), it does not multiply;
+  - causal means M_i[a, c] = 1 iff c <= a along every axis;
+  - reshape is row-major, first axis slowest (Sec. 4.3: with {32,32,32}, one
+    more step on the first axis adds 1,024 tokens);
+  - hops run in Algorithm 1's order, first axis first, unless told otherwise;
+  - d under the square root is the per-head feature width;
+  - grouped-query heads: query head h uses key/value head h // (H_q / H_kv).
+
+Parity pins (tests/test_oracle_*.py): d=1 against a library attention
+routine, row sums, brute-force N x N Kronecker-form operator built with scalar
+loops, numpy.kron in the separable regime, Q = 0 closed forms, no-leak
+invariant, unit-axis no-ops, finite differences for the backward.
+Nothing in this file is "parity unpinned".
+"""
+from __future__ import annotations
+
+import math
+from typing import Optional, Sequence
+
+import numpy as np
+
+__all__ = [
+    "axis_strides",
+    "attention",
+    "axis_attention",
+    "tensorized_attention_forward",
+    "tensorized_attention_backward",
+]
+
+
+def axis_strides(dims: Sequence[int]) -> list:
+    """Token stride of every tensor axis for the row-major reshape of
+    Sec. 3.1 / App. C.1: token t = sum_i j_i * stride_i, last axis contiguous."""
+    strides = [1] * len(dims)
+    for i in range(len(dims) - 2, -1, -1):
+        strides[i] = strides[i + 1] * int(dims[i + 1])
+    return strides
+
+
+def _softmax_rows(s: np.ndarray, allowed: Optional[np.ndarray]) -> np.ndarray:
+    """Row-wise softmax over the last axis (Eq. 1); positions where `allowed`
+    is False are excluded from the normalisation and get probability 0."""
+    if allowed is not None:
+        s = np.where(allowed, s, -np.inf)
+    s = s - np.max(s, axis=-1, keepdims=True)
+    e = np.exp(s)
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float,
+              causal: bool) -> np.ndarray:
+    """Eq. 1 for one head: A = softmax(q k^T * scale o M), o = A v.
+    q, k: [n, D]; v: [n, Dv]."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    n = q.shape[0]
+    s = (q @ k.T) * scale
+    allowed = np.tril(np.ones((n, n), dtype=bool)) if causal else None
+    return _softmax_rows(s, allowed) @ v
+
+
+def axis_attention(q: np.ndarray, k: np.ndarray, o_prev: np.ndarray,
+                   dims: Sequence[int], axis: int, scale: float, causal: bool,
+                   return_probs: bool = False):
+    """One hop of Eq. 4 for one head.
+
+    q, k: [N, D]; o_prev: [N, Dv]; N = prod(dims).  Mode-`axis` flattening
+    turns each tensor into a batch of N / n_axis fibres of n_axis rows; every
+    fibre gets its own n_axis x n_axis row-softmax attention, applied to the
+    fibre's rows of o_prev; the result is folded back.  Returns o_new [N, Dv]
+    and, on request, A_axis with shape dims[:axis] + dims[axis+1:] + (n, n)
+    (batch axes in tensor order, then query index, then key index)."""
+    dims = [int(n) for n in dims]
+    N = int(np.prod(dims)) if dims else 1
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    o_prev = np.asarray(o_prev, dtype=np.float64)
+    assert q.shape[0] == N and k.shape[0] == N and o_prev.shape[0] == N
+    n = dims[axis]
+    # tensorise (reshape) and mode-i flatten: move axis i next to the features
+    Qi = np.moveaxis(q.reshape(dims + [q.shape[1]]), axis, -2)      # [..., n, D]
+    Ki = np.moveaxis(k.reshape(dims + [k.shape[1]]), axis, -2)
+    Oi = np.moveaxis(o_prev.reshape(dims + [o_prev.shape[1]]), axis, -2)
+    S = np.matmul(Qi, np.swapaxes(Ki, -1, -2)) * scale                # [..., n, n]
+    allowed = np.tril(np.ones((n, n), dtype=bool)) if causal else None
+    A = _softmax_rows(S, allowed)
+    Onew = np.matmul(A, Oi)                                           # [..., n, Dv]
+    # mode-i folding
+    o_new = np.moveaxis(Onew, -2, axis).reshape(N, o_prev.shape[1])
+    if return_probs:
+        return o_new, A
+    return o_new
+
+
+def _hop_order(m: int, hop_order: Optional[Sequence[int]]) -> list:
+    if hop_order is None:
+        return list(range(m))
+    order = [int(a) for a in hop_order]
+    assert sorted(order) == list(range(m)), "hop_order must be a permutation of the axes"
+    return order
+
+
+def tensorized_attention_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
+                                 dims: Sequence[int], causal: bool,
+                                 scale: Optional[float] = None,
+                                 hop_order: Optional[Sequence[int]] = None,
+                                 return_intermediates: bool = False):
+    """Algorithm 1.
+
+    q: [B, N, H_q, D]; k, v: [B, N, H_kv, D] (H_q a multiple of H_kv);
+    N = prod(dims).  Returns o [B, N, H_q, D] in float64.  With
+    `return_intermediates` also returns the list [O_0, O_1, ..., O_m] (O_0 is V
+    expanded to H_q heads, O_j the value tensor after the j-th executed hop)
+    and the list of attention tensors A per executed hop, each of shape
+    [B, H_q] + batch dims + [n, n]."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    B, N, Hq, D = q.shape
+    Hkv = k.shape[2]
+    assert k.shape == (B, N, Hkv, D) and v.shape[:3] == (B, N, Hkv)
+    assert Hq % Hkv == 0
+    dims = [int(n) for n in dims]
+    assert int(np.prod(dims)) == N, "prod(dims) must equal the sequence length"
+    G = Hq // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    order = _hop_order(len(dims), hop_order)
+
+    o = np.empty((B, N, Hq, v.shape[3]), dtype=np.float64)
+    inter = [np.repeat(v, G, axis=2)] + [np.empty_like(o) for _ in order]
+    probs = [None] * len(order)
+    for b in range(B):
+        for h in range(Hq):
+            g = h // G
+            qh, kh = q[b, :, h, :], k[b, :, g, :]
+            oh = v[b, :, g, :]                      # Initialise O = V
+            for pos, axis in enumerate(order):
+                if return_intermediates:
+                    oh, A = axis_attention(qh, kh, oh, dims, axis, scale, causal, True)
+                    if probs[pos] is None:
+                        probs[pos] = np.empty((B, Hq) + A.shape, dtype=np.float64)
+                    probs[pos][b, h] = A
+                    inter[pos + 1][b, :, h, :] = oh
+                else:
+                    oh = axis_attention(qh, kh, oh, dims, axis, scale, causal)
+            o[b, :, h, :] = oh                      # Vectorise
+    if return_intermediates:
+        return o, inter, probs
+    return o
+
+
+def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
+                                  d_o: np.ndarray, dims: Sequence[int],
+                                  causal: bool, scale: Optional[float] = None,
+                                  hop_order: Optional[Sequence[int]] = None):
+    """Gradient of L = sum(O * d_o) through Algorithm 1 w.r.t. q, k, v.
+
+    Hops are undone in reverse.  For one hop on one fibre with rows Qs, Ks,
+    input rows X (= previous O) and upstream gradient G:
+        A      = softmax(Qs Ks^T * scale, mask)
+        dX     = A^T G
+        dA     = G X^T
+        dS     = A o (dA - rowsum(A o dA))
+        dQs   += dS Ks * scale ;  dKs += dS^T Qs * scale
+    The gradient reaching O_0 is dV; dK and dV of a key/value head are the sums
+    over the query heads that share it.  Returns (dq, dk, dv) in float64."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    d_o = np.asarray(d_o, dtype=np.float64)
+    B, N, Hq, D = q.shape
+    Hkv = k.shape[2]
+    G = Hq // Hkv
+    dims = [int(n) for n in dims]
+    if scale is None:
+        scale = 1.0 / math.sqrt(D)
+    order = _hop_order(len(dims), hop_order)
+    _, inter, probs = tensorized_attention_forward(
+        q, k, v, dims, causal, scale, order, return_intermediates=True)
+
+    dq = np.zeros_like(q)
+    dk = np.zeros_like(k)
+    dv = np.zeros_like(v)
+    for b in range(B):
+        for h in range(Hq):
+            g = h // G
+            grad = d_o[b, :, h, :]
+            for pos in range(len(order) - 1, -1, -1):
+                axis = order[pos]
+                A = probs[pos][b, h]                                   # [..., n, n]
+                shape_d = dims + [D]
+                shape_v = dims + [v.shape[3]]
+                Gi = np.moveaxis(grad.reshape(shape_v), axis, -2)
+                Xi = np.moveaxis(inter[pos][b, :, h, :].reshape(shape_v), axis, -2)
+                Qi = np.moveaxis(q[b, :, h, :].reshape(shape_d), axis, -2)
+                Ki = np.moveaxis(k[b, :, g, :].reshape(shape_d), axis, -2)
+                dA = np.matmul(Gi, np.swapaxes(Xi, -1, -2))
+                dX = np.matmul(np.swapaxes(A, -1, -2), Gi)
+                dS = A * (dA - np.sum(A * dA, axis=-1, keepdims=True))
+                dQi = np.matmul(dS, Ki) * scale
+                dKi = np.matmul(np.swapaxes(dS, -1, -2), Qi) * scale
+                dq[b, :, h, :] += np.moveaxis(dQi, -2, axis).reshape(N, D)
+                dk[b, :, g, :] += np.moveaxis(dKi, -2, axis).reshape(N, D)
+                grad = np.moveaxis(dX, -2, axis).reshape(N, v.shape[3])
+            dv[b, :, g, :] += grad
+    return dq, dk, dv

@@ -1,0 +1,301 @@
+"""Pins for the CPU oracle's forward (no GPU): each test checks the oracle
+against something other than itself - a library routine, a brute-force
+construction in scalar loops, numpy.kron, a closed form, an invariant, or a
+number the paper states (tests/golden/paper_facts.json)."""
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import bruteforce as bf
+from oracle import tensattn_oracle as orc
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_facts.json")
+
+
+def rand_qkv(seed, B, N, Hq, Hkv, D):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((B, N, Hq, D)), rng.standard_normal((B, N, Hkv, D)),
+            rng.standard_normal((B, N, Hkv, D)))
+
+
+# --- d = 1: no tensorisation is Eq. 1, checked against a library routine ----------
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_order1_equals_library_attention(causal):
+    B, N, H, D = 2, 37, 3, 16
+    q, k, v = rand_qkv(1, B, N, H, H, D)
+    got = orc.tensorized_attention_forward(q, k, v, [N], causal)
+    tq, tk, tv = (torch.from_numpy(x).permute(0, 2, 1, 3) for x in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=causal)
+    ref = ref.permute(0, 2, 1, 3).numpy()
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_eq1_attention_against_library(causal):
+    rng = np.random.default_rng(2)
+    q, k, v = rng.standard_normal((3, 19, 8))
+    got = orc.attention(q, k, v, 0.3, causal)
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q)[None], torch.from_numpy(k)[None], torch.from_numpy(v)[None],
+        is_causal=causal, scale=0.3)[0].numpy()
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+
+
+def test_default_scale_is_inverse_sqrt_head_dim():
+    q, k, v = rand_qkv(3, 1, 12, 1, 1, 9)
+    a = orc.tensorized_attention_forward(q, k, v, [3, 4], False)
+    b = orc.tensorized_attention_forward(q, k, v, [3, 4], False, scale=1.0 / 3.0)
+    np.testing.assert_array_equal(a, b)
+
+
+# --- row sums -----------------------------------------------------------------------
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_every_attention_row_sums_to_one(causal):
+    q, k, v = rand_qkv(4, 1, 24, 2, 1, 8)
+    _, inter, probs = orc.tensorized_attention_forward(q, k, v, [2, 3, 4], causal,
+                                                       return_intermediates=True)
+    assert len(probs) == 3 and len(inter) == 4
+    for A, n in zip(probs, [2, 3, 4]):
+        assert A.shape[-2:] == (n, n)
+        np.testing.assert_allclose(A.sum(-1), 1.0, rtol=0, atol=1e-12)
+        assert (A >= 0).all()
+        if causal:
+            assert (np.triu(A, 1) == 0).all()
+
+
+# --- brute-force Kronecker-form operator ----------------------------------------------
+
+@pytest.mark.parametrize("dims,causal", [((2, 2, 3), False), ((2, 2, 3), True),
+                                         ((4, 4), False), ((3, 2, 2), True), ((5,), True)])
+def test_brute_force_operator(dims, causal):
+    N, D = int(np.prod(dims)), 6
+    q, k, v = rand_qkv(5, 1, N, 1, 1, D)
+    scale = 1.0 / math.sqrt(D)
+    ql, kl = q[0, :, 0].tolist(), k[0, :, 0].tolist()
+    W1 = np.array(bf.operator_by_products(ql, kl, list(dims), scale, causal))
+    W2 = np.array(bf.operator_by_paths(ql, kl, list(dims), scale, causal))
+    np.testing.assert_allclose(W1, W2, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(W1.sum(1), 1.0, rtol=0, atol=1e-12)       # row-stochastic
+    got = orc.tensorized_attention_forward(q, k, v, dims, causal)[0, :, 0]
+    np.testing.assert_allclose(got, W1 @ v[0, :, 0], rtol=0, atol=1e-12)
+    if causal:
+        # support: source u reaches destination t only if u <= t on every axis
+        for t in range(N):
+            jt = bf.unravel(t, dims)
+            for u in range(N):
+                ku = bf.unravel(u, dims)
+                if any(a > b for a, b in zip(ku, jt)):
+                    assert W1[t, u] == 0.0
+                else:
+                    assert W1[t, u] > 0.0
+
+
+def test_brute_force_operator_config1_shape():
+    """The 256 x 256 operator of the fp32 16x16, D=64 configuration."""
+    dims, D = (16, 16), 64
+    q, k, v = rand_qkv(6, 1, 256, 1, 1, D)
+    ql, kl = q[0, :, 0].tolist(), k[0, :, 0].tolist()
+    W = np.array(bf.operator_by_paths(ql, kl, list(dims), 1.0 / 8.0, False))
+    got = orc.tensorized_attention_forward(q, k, v, dims, False)[0, :, 0]
+    np.testing.assert_allclose(got, W @ v[0, :, 0], rtol=0, atol=1e-12)
+    # and it is not full attention: d=1 on the same inputs differs
+    full = orc.tensorized_attention_forward(q, k, v, (256,), False)[0, :, 0]
+    assert np.abs(full - got).max() > 1e-2
+
+
+def separable_qk(rng, dims, block):
+    """q_t = concat_i a_i[j_i], k_u = concat_i b_i[k_i]: within a mode-i fibre the
+    score is a_i[j_i].b_i[k_i] plus a per-row constant, so A_i is the same for all
+    fibres and the operator is a Kronecker product."""
+    a = [rng.standard_normal((n, block)) for n in dims]
+    b = [rng.standard_normal((n, block)) for n in dims]
+    N = int(np.prod(dims))
+    q = np.zeros((N, block * len(dims)))
+    k = np.zeros_like(q)
+    for t in range(N):
+        j = bf.unravel(t, dims)
+        q[t] = np.concatenate([a[i][j[i]] for i in range(len(dims))])
+        k[t] = np.concatenate([b[i][j[i]] for i in range(len(dims))])
+    return q, k, a, b
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_separable_scores_give_numpy_kron(causal):
+    dims, block = (2, 3, 2), 4
+    rng = np.random.default_rng(7)
+    q, k, a, b = separable_qk(rng, dims, block)
+    N, D = q.shape
+    v = rng.standard_normal((N, 5))
+    scale = 0.37
+    factors = []
+    for i, n in enumerate(dims):
+        factors.append(orc.attention(a[i], b[i], np.eye(n), scale, causal))   # A_i itself
+    W = factors[0]
+    for F in factors[1:]:
+        W = np.kron(W, F)
+    got = orc.tensorized_attention_forward(q[None, :, None], k[None, :, None], v[None, :, None],
+                                           dims, causal, scale=scale)[0, :, 0]
+    np.testing.assert_allclose(got, W @ v, rtol=0, atol=1e-12)
+    # the paper's "irrelevant to the order of updating" holds here
+    for order in [(2, 1, 0), (1, 0, 2)]:
+        alt = orc.tensorized_attention_forward(q[None, :, None], k[None, :, None],
+                                               v[None, :, None], dims, causal, scale=scale,
+                                               hop_order=order)[0, :, 0]
+        np.testing.assert_allclose(alt, got, rtol=0, atol=1e-12)
+
+
+def test_tensor_form_of_operator_is_rank_one_when_separable():
+    """App. C.1: the 12 x 12 operator reshapes to a 4 x 4 x 9 tensor; in the separable
+    regime that tensor is the outer product vec(A_1) x vec(A_2) x vec(A_3)."""
+    fact = json.load(open(GOLDEN))["attention_matrix_tensor_form"]
+    dims = tuple(fact["dims"])
+    rng = np.random.default_rng(8)
+    q, k, a, b = separable_qk(rng, dims, 3)
+    N = q.shape[0]
+    assert N == fact["seq_len"]
+    W = orc.tensorized_attention_forward(q[None, :, None], k[None, :, None],
+                                         np.eye(N)[None, :, None], dims, False, scale=0.5)[0, :, 0]
+    T = W.reshape(dims + dims).transpose(0, 3, 1, 4, 2, 5).reshape([n * n for n in dims])
+    assert list(T.shape) == fact["tensor_shape"]
+    A = [orc.attention(a[i], b[i], np.eye(n), 0.5, False).reshape(-1) for i, n in enumerate(dims)]
+    np.testing.assert_allclose(T, np.einsum("i,j,k->ijk", *A), rtol=0, atol=1e-12)
+
+
+def test_hop_order_matters_in_general_and_default_is_first_axis_first():
+    dims = (3, 4)
+    q, k, v = rand_qkv(9, 1, 12, 1, 1, 5)
+    default = orc.tensorized_attention_forward(q, k, v, dims, False)
+    fwd = orc.tensorized_attention_forward(q, k, v, dims, False, hop_order=(0, 1))
+    rev = orc.tensorized_attention_forward(q, k, v, dims, False, hop_order=(1, 0))
+    np.testing.assert_array_equal(default, fwd)
+    assert np.abs(fwd - rev).max() > 1e-3
+    ql, kl = q[0, :, 0].tolist(), k[0, :, 0].tolist()
+    Wrev = np.array(bf.operator_by_products(ql, kl, list(dims), 1 / math.sqrt(5), False, order=(1, 0)))
+    np.testing.assert_allclose(rev[0, :, 0], Wrev @ v[0, :, 0], rtol=0, atol=1e-12)
+
+
+# --- reshape convention ---------------------------------------------------------------
+
+def test_first_axis_is_slowest_paper_extrapolation_fact():
+    fact = json.load(open(GOLDEN))["extrapolation_first_axis"]
+    dims = fact["dims"]
+    assert orc.axis_strides(dims) == [1024, 32, 1]
+    assert orc.axis_strides(dims)[0] == fact["first_axis_increment_tokens"]
+    assert int(np.prod(dims)) == fact["seq_len"]
+    # behavioural check: a hop on axis 0 of (3, 4) with uniform attention spreads a
+    # one-hot value at token u exactly over tokens u mod 4 + 4 a
+    N, u = 12, 6
+    z = np.zeros((N, 2))
+    v = np.zeros((N, 1)); v[u] = 1.0
+    o0 = orc.axis_attention(z, z, v, (3, 4), 0, 1.0, False)[:, 0]
+    assert set(np.nonzero(o0)[0]) == {2, 6, 10}
+    np.testing.assert_allclose(o0[[2, 6, 10]], 1.0 / 3.0, atol=1e-15)
+    o1 = orc.axis_attention(z, z, v, (3, 4), 1, 1.0, False)[:, 0]
+    assert set(np.nonzero(o1)[0]) == {4, 5, 6, 7}
+
+
+@pytest.mark.parametrize("dims_with,dims_without", [((1, 12), (12,)), ((12, 1), (12,)),
+                                                    ((3, 1, 4), (3, 4)), ((1, 1, 1), None)])
+def test_unit_axes_are_noops(dims_with, dims_without):
+    N = int(np.prod(dims_with))
+    q, k, v = rand_qkv(10, 1, N, 2, 2, 4)
+    got = orc.tensorized_attention_forward(q, k, v, dims_with, True)
+    if dims_without is None:
+        np.testing.assert_allclose(got, v, atol=1e-15)
+    else:
+        np.testing.assert_allclose(got, orc.tensorized_attention_forward(q, k, v, dims_without, True),
+                                   rtol=0, atol=1e-14)
+
+
+# --- closed forms with zero queries -----------------------------------------------------
+
+@pytest.mark.parametrize("dims", [(4, 3, 5), (16, 16), (7,)])
+def test_zero_queries_closed_forms(dims):
+    N = int(np.prod(dims))
+    _, k, v = rand_qkv(11, 1, N, 1, 1, 3)
+    q = np.zeros_like(k)
+    got = orc.tensorized_attention_forward(q, k, v, dims, False)[0, :, 0]
+    np.testing.assert_allclose(got, np.broadcast_to(v[0, :, 0].mean(0), got.shape), atol=1e-13)
+    # causal: mean over {u : u_i <= t_i on every axis} = running mean along every axis
+    got = orc.tensorized_attention_forward(q, k, v, dims, True)[0, :, 0]
+    ref = v[0, :, 0].reshape(tuple(dims) + (3,)).copy()
+    for ax, n in enumerate(dims):
+        ref = np.cumsum(ref, axis=ax)
+        shape = [1] * (len(dims) + 1)
+        shape[ax] = n
+        ref = ref / np.arange(1, n + 1).reshape(shape)
+    np.testing.assert_allclose(got, ref.reshape(N, 3), atol=1e-13)
+
+
+# --- causal reading: nothing flows from later tokens -------------------------------------
+
+def test_causal_has_no_leak_from_later_tokens():
+    dims = (3, 2, 4)
+    N = 24
+    q, k, v = rand_qkv(12, 1, N, 2, 1, 6)
+    base = orc.tensorized_attention_forward(q, k, v, dims, True)
+    rng = np.random.default_rng(13)
+    for t in [0, 5, 11, 17, 22]:
+        q2, k2, v2 = q.copy(), k.copy(), v.copy()
+        q2[:, t + 1:] = rng.standard_normal(q2[:, t + 1:].shape)
+        k2[:, t + 1:] = rng.standard_normal(k2[:, t + 1:].shape)
+        v2[:, t + 1:] = rng.standard_normal(v2[:, t + 1:].shape)
+        pert = orc.tensorized_attention_forward(q2, k2, v2, dims, True)
+        np.testing.assert_array_equal(pert[:, :t + 1], base[:, :t + 1])
+        assert np.abs(pert[:, t + 1:] - base[:, t + 1:]).max() > 1e-3
+    # the non-causal operator does look ahead
+    q2, v2 = q.copy(), v.copy()
+    v2[:, 20:] += 1.0
+    assert np.abs(orc.tensorized_attention_forward(q, k, v2, dims, False)[:, :4]
+                  - orc.tensorized_attention_forward(q, k, v, dims, False)[:, :4]).max() > 1e-3
+
+
+def test_causal_first_token_copies_its_value():
+    q, k, v = rand_qkv(14, 1, 24, 1, 1, 6)
+    o = orc.tensorized_attention_forward(q, k, v, (2, 3, 4), True)
+    np.testing.assert_allclose(o[0, 0], v[0, 0], atol=1e-15)
+
+
+# --- masked logits are excluded, not multiplied by zero ---------------------------------
+
+def test_mask_excludes_rather_than_zeroing_logits():
+    q = np.array([[1.0], [1.0]]); k = np.array([[-5.0], [3.0]]); v = np.array([[1.0], [2.0]])
+    o = orc.attention(q, k, v, 1.0, True)
+    assert o[0, 0] == 1.0                       # row 0 sees only key 0, whatever its logit
+    # a multiplicative 0/1 mask would have given weight e^0 to the hidden key
+    wrong = (math.exp(-5.0) * 1.0 + 1.0 * 2.0) / (math.exp(-5.0) + 1.0)
+    assert abs(o[0, 0] - wrong) > 0.5
+
+
+# --- grouped-query heads -----------------------------------------------------------------
+
+def test_grouped_query_equals_repeated_kv():
+    B, N, Hq, Hkv, D = 2, 12, 4, 2, 5
+    q, k, v = rand_qkv(15, B, N, Hq, Hkv, D)
+    got = orc.tensorized_attention_forward(q, k, v, (3, 4), True)
+    rep = orc.tensorized_attention_forward(q, np.repeat(k, 2, axis=2), np.repeat(v, 2, axis=2),
+                                           (3, 4), True)
+    np.testing.assert_array_equal(got, rep)
+    # head h must use kv head h // 2: heads 0,1 -> 0 ; heads 2,3 -> 1
+    single = orc.tensorized_attention_forward(q[:, :, 2:3], k[:, :, 1:2], v[:, :, 1:2], (3, 4), True)
+    np.testing.assert_array_equal(got[:, :, 2:3], single)
+
+
+# --- complexity model (App. C.2 with the fibre count restored) ------------------------------
+
+def test_flop_count_matches_closed_form():
+    dims, D = (4, 3, 5), 8
+    N = int(np.prod(dims))
+    total = 0
+    for n in dims:
+        fibres = N // n
+        total += fibres * (2 * n * n * D + 2 * n * n * D)
+    assert total == 4 * N * D * sum(dims)
+    fact = json.load(open(GOLDEN))["tensor3_parameter_count"]
+    assert fact["rank"] * sum(n * n for n in fact["dims"]) == fact["parameters"]
