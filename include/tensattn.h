@@ -1,0 +1,175 @@
+/*
+ * tensattn.h - C ABI of the MI355X (gfx950) Tensorized Attention library.
+ *
+ * Tensorized attention (arXiv 2410.20926, Sec. 3.2) views a length-N sequence of
+ * queries, keys and values as an order-m tensor, N = n_1 * ... * n_m, and runs
+ * softmax attention along one tensor axis at a time (Eq. 4), all other axes acting
+ * as batch; Algorithm 1 chains one such hop per axis, starting from O = V and always
+ * using the same Q and K.
+ *
+ * Conventions shared by every call
+ *  - Device buffers are caller-owned DEVICE pointers, 16-byte aligned, holding
+ *    elements of the plan's dtype.  The library never allocates, frees or keeps
+ *    device memory, never synchronises, and only enqueues work on `stream`
+ *    (a hipStream_t passed as void*; NULL = the default stream).  Inputs are never
+ *    written.  Descriptors and plans are HOST memory.
+ *  - Tensor layout: element (b, t, h, x) of a tensor with heads H lives at
+ *    b*stride[0] + t*stride[1] + h*stride[2] + x  (strides in ELEMENTS, feature axis
+ *    contiguous).  All-zero strides mean dense [B, N, H, D].
+ *  - Tensor reshape is row-major: token t = sum_i j_i * stride_i, the first axis is
+ *    the slowest (Sec. 4.3: with {32,32,32} one more step on the first axis is 1,024
+ *    more tokens).  Axes are numbered from 0 here.
+ *  - Grouped-query heads: query head h uses key/value head h / (n_q_heads / n_kv_heads).
+ *  - Every call returns a ta_status_t; nothing aborts, throws or prints.  On error
+ *    nothing has been enqueued.  ta_last_error_detail() gives a thread-local message.
+ *    Kernel faults that happen asynchronously surface at the caller's next
+ *    synchronisation, as with any HIP launch.
+ */
+#ifndef TENSATTN_H
+#define TENSATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TA_MAX_ORDER 8
+
+typedef enum {
+    TA_OK = 0,
+    TA_ERR_NULL = 1,          /* a required pointer is NULL */
+    TA_ERR_INVALID_ARG = 2,   /* bad enum, axis out of range, misaligned pointer ... */
+    TA_ERR_SHAPE = 3,         /* inconsistent sizes (heads not divisible, dims < 1, overflow ...) */
+    TA_ERR_UNSUPPORTED = 4,   /* valid request this build has no kernel for */
+    TA_ERR_ALIAS = 5,         /* an output overlaps an input */
+    TA_ERR_WORKSPACE = 6,     /* workspace too small */
+    TA_ERR_DEVICE = 7         /* HIP reported a launch error */
+} ta_status_t;
+
+typedef enum { TA_F32 = 0, TA_BF16 = 1 } ta_dtype_t;
+
+/* Which tensor a hop reads as its value input (Algorithm 1 initialises O = V, so
+ * the first executed hop reads V, which has n_kv_heads heads and the key/value
+ * layout; every later hop reads a previous O, with n_q_heads heads and O's layout). */
+typedef enum { TA_VIN_KV = 0, TA_VIN_O = 1 } ta_vin_t;
+
+/* Problem descriptor (Algorithm 1's inputs: Q, K, V in R^{n_1 x .. x n_m}, with a
+ * feature axis, and the per-axis mask M_i).  Plain data; copied by ta_plan_create. */
+typedef struct ta_desc_t {
+    int32_t batch;                    /* B >= 1 */
+    int32_t n_q_heads;                /* H_q >= 1 */
+    int32_t n_kv_heads;               /* H_kv >= 1, divides H_q */
+    int32_t head_dim;                 /* D, the d under the square root of Eq. 1 */
+    int32_t order;                    /* m, 1..TA_MAX_ORDER */
+    int32_t dims[TA_MAX_ORDER];       /* n_1..n_m, each >= 1; N = their product */
+    int32_t dtype;                    /* ta_dtype_t of every tensor */
+    int32_t causal;                   /* 0: no mask; 1: M_i[a][c] = (c <= a) on every axis */
+    float   scale;                    /* logit scale; 0 means 1/sqrt(head_dim) (Eq. 1) */
+    int32_t hop_order[TA_MAX_ORDER];  /* permutation of 0..m-1; all -1 = Algorithm 1's order 0,1,..,m-1 */
+    int64_t q_strides[3];             /* (batch, token, head) strides of Q, dQ; all 0 = dense [B,N,H_q,D] */
+    int64_t kv_strides[3];            /* of K, V, dK, dV; all 0 = dense [B,N,H_kv,D] */
+    int64_t o_strides[3];             /* of O, dO and every inter-hop O; all 0 = dense [B,N,H_q,D] */
+} ta_desc_t;
+
+typedef struct ta_plan ta_plan_t;     /* opaque, immutable, host-only, shareable between threads */
+
+/* ---- tensorize / plan (Sec. 3.1 "order-m tensorization ... achieved by reshaping";
+ *      App. C.1).  Host only; touches no device memory. ------------------------------ */
+
+/* Validates `desc`, derives per-axis token strides and fibre counts and picks a kernel
+ * per hop.  Errors: NULL -> TA_ERR_NULL; order, dims, heads, head_dim, strides
+ * inconsistent -> TA_ERR_SHAPE; bad dtype / hop_order -> TA_ERR_INVALID_ARG; a shape no
+ * kernel covers (head_dim not a multiple of 8 or above 256) -> TA_ERR_UNSUPPORTED. */
+ta_status_t ta_plan_create(const ta_desc_t* desc, ta_plan_t** out_plan);
+void        ta_plan_destroy(ta_plan_t* plan);                 /* NULL-safe */
+
+int64_t ta_plan_seq_len(const ta_plan_t* plan);               /* N; -1 on NULL */
+int64_t ta_plan_axis_stride(const ta_plan_t* plan, int axis); /* tokens between neighbours on `axis`; -1 on error */
+int64_t ta_plan_axis_fibres(const ta_plan_t* plan, int axis); /* N / n_axis per (batch, head); -1 on error */
+int     ta_plan_hop_axis(const ta_plan_t* plan, int hop_position); /* axis run at position 0..m-1; -1 on error */
+/* Name of the kernel variant the plan chose for the forward hop on `axis` with value
+ * input `vin` ("mfma_bf16_n32", "generic", ...); NULL on error.  Static storage. */
+const char* ta_plan_hop_kernel(const ta_plan_t* plan, int axis, int vin);
+
+/* Cost model of one hop (App. C.2, Table 5, with the fibre count N/n_i that Eq. 4
+ * implies).  Bytes are ALGORITHMIC HBM bytes: each of Q, K, value-input read once,
+ * O written once, K and V counted once per key/value head:
+ *   B*N*D*elem*(H_q + H_kv + H_vin + H_q),  H_vin = H_kv for TA_VIN_KV else H_q.
+ * Backward (backward != 0): reads Q, K, value-input, dO; writes d(value-input); dQ and
+ * dK written (accumulate = 0) or read and written (accumulate = 1).
+ * FLOPs are the dense executed count 4*B*H_q*N*n_axis*D (forward; 2.5x for backward).
+ * Both return -1.0 on error. */
+double ta_plan_hop_bytes(const ta_plan_t* plan, int axis, int vin, int backward, int accumulate);
+double ta_plan_hop_flops(const ta_plan_t* plan, int axis, int backward);
+
+/* Workspace for ta_multihop_forward, in bytes (0 when m == 1):
+ * save_for_backward == 0: two ping-pong inter-hop O buffers (one when m == 2);
+ * save_for_backward != 0: m-1 retained inter-hop O buffers, O_1..O_{m-1}, in hop order.
+ * Each buffer is a dense or o_strides-shaped O tensor rounded up to 256 bytes. */
+size_t ta_plan_workspace_bytes(const ta_plan_t* plan, int save_for_backward);
+/* Scratch for ta_multihop_backward, in bytes: two ping-pong gradient buffers of O's size. */
+size_t ta_plan_backward_scratch_bytes(const ta_plan_t* plan);
+
+/* ---- per-axis attention, forward (Eq. 4; the loop body of Algorithm 1) --------------
+ * o_out[fibre rows] = softmax(Q_i K_i^T * scale o M_i) * v_in[fibre rows] for every
+ * mode-`axis` fibre of every (batch, head).  q: Q layout; k: key/value layout; v_in:
+ * key/value layout with n_kv_heads (vin = TA_VIN_KV) or O layout with n_q_heads
+ * (TA_VIN_O); o_out: O layout.  o_out must not overlap q, k or v_in (TA_ERR_ALIAS).
+ * Asynchronous on `stream`. */
+ta_status_t ta_axis_attn_forward(const ta_plan_t* plan, int axis,
+                                 const void* q, const void* k, const void* v_in, int vin,
+                                 void* o_out, void* stream);
+
+/* ---- per-axis attention, backward (the paper gives none: Sec. 3.2 only states that a
+ *      backward exists; this is the derivative of the hop above) -----------------------
+ * With A the hop's attention, X = v_in, G = d_o:
+ *   d_v_in = A^T G;  dS = A o (G X^T - rowsum(A o G X^T));
+ *   dq (+)= dS K * scale;  dk (+)= sum over the query heads of the group of dS^T Q * scale.
+ * d_v_in has v_in's layout and head count; for TA_VIN_KV it is summed over the query
+ * heads that share the key/value head.  accumulate = 0 overwrites dq, dk; 1 adds to
+ * them.  dq: Q layout; dk: key/value layout.  Outputs must not overlap inputs or each
+ * other.  Deterministic (no atomics). */
+ta_status_t ta_axis_attn_backward(const ta_plan_t* plan, int axis,
+                                  const void* q, const void* k, const void* v_in, int vin,
+                                  const void* d_o, void* d_v_in, void* dq, void* dk,
+                                  int accumulate, void* stream);
+
+/* ---- full multi-hop forward (Algorithm 1) --------------------------------------------
+ * O_0 = V; one hop per axis in the plan's hop order; o receives the last hop's output.
+ * `workspace` (device, >= ta_plan_workspace_bytes(plan, save_for_backward), 256-byte
+ * aligned; may be NULL when that size is 0) holds the inter-hop O tensors; with
+ * save_for_backward they stay valid for ta_multihop_backward.  TA_ERR_WORKSPACE when
+ * too small. */
+ta_status_t ta_multihop_forward(const ta_plan_t* plan,
+                                const void* q, const void* k, const void* v, void* o,
+                                void* workspace, size_t workspace_bytes,
+                                int save_for_backward, void* stream);
+
+/* ---- full multi-hop backward ----------------------------------------------------------
+ * Gradients of sum(O * d_o) w.r.t. Q, K, V: hops undone in reverse order, dq and dk
+ * accumulated over hops (first processed hop overwrites), dv = gradient reaching O_0.
+ * `workspace` is the one a save_for_backward forward filled for the same q, k, v;
+ * `scratch` (device, >= ta_plan_backward_scratch_bytes, 256-byte aligned) is
+ * overwritten. */
+ta_status_t ta_multihop_backward(const ta_plan_t* plan,
+                                 const void* q, const void* k, const void* v, const void* d_o,
+                                 const void* workspace, size_t workspace_bytes,
+                                 void* dq, void* dk, void* dv,
+                                 void* scratch, size_t scratch_bytes, void* stream);
+
+/* ---- measurement aid: a plain read-and-write copy of `bytes` bytes (multiple of 16)
+ *      from src to dst on `stream`, used to measure the achievable HBM ceiling and to
+ *      calibrate hardware counters against a transfer of known size. ------------------- */
+ta_status_t ta_copy_bytes(const void* src, void* dst, size_t bytes, void* stream);
+
+/* ---- errors and version ------------------------------------------------------------- */
+const char* ta_status_string(ta_status_t status);
+const char* ta_last_error_detail(void);          /* thread-local; "" when none */
+void        ta_version(int* major, int* minor);  /* NULL-safe */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TENSATTN_H */

@@ -1,0 +1,405 @@
+// Host side of the C ABI declared in include/tensattn.h: plan construction and
+// validation, the cost model, argument checks, and the per-hop / multi-hop drivers.
+// All device work happens in the kernel files; this file only enqueues launches.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "ta_internal.h"
+
+struct ta_plan {
+    ta_desc_t desc;              // as given, with defaults resolved
+    int32_t order;
+    int32_t dims[TA_MAX_ORDER];
+    int64_t strides[TA_MAX_ORDER];   // token stride per axis (row-major reshape)
+    int32_t hop_axis[TA_MAX_ORDER];  // axis executed at each hop position
+    int64_t N;
+    int32_t G;
+    int32_t elem;                // bytes per element
+    float scale;
+    int64_t qs[3], kvs[3], os[3];    // resolved element strides (batch, token, head)
+    int64_t o_span;              // elements from the first to one past the last element of an O tensor
+    size_t o_buf_bytes;          // bytes of one inter-hop O buffer, rounded up to 256
+    int kernel_id[TA_MAX_ORDER][2];  // forward kernel per (axis, vin)
+};
+
+namespace {
+
+thread_local char g_detail[256] = "";
+
+ta_status_t fail(ta_status_t st, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+ta_status_t fail(ta_status_t st, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_detail, sizeof(g_detail), fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Byte range [lo, hi) touched by a strided [B, N, H, D] tensor.
+struct Range { uintptr_t lo, hi; };
+Range span_of(const void* p, const int64_t s[3], int64_t B, int64_t N, int64_t H, int64_t D, int elem) {
+    const int64_t last = (B - 1) * s[0] + (N - 1) * s[1] + (H - 1) * s[2] + D;
+    const uintptr_t lo = reinterpret_cast<uintptr_t>(p);
+    return {lo, lo + (uintptr_t)last * (uintptr_t)elem};
+}
+inline bool overlaps(Range a, Range b) { return a.lo < b.hi && b.lo < a.hi; }
+
+bool strides_ok(const int64_t s[3], int64_t B, int64_t N, int64_t H, int64_t D) {
+    // every stride positive, a multiple of 8 elements (16-byte rows), rows disjoint:
+    // sort the three (stride, extent) pairs and require stride_k >= extent_{k-1} * stride_{k-1}.
+    int64_t st[3] = {s[0], s[1], s[2]};
+    int64_t ex[3] = {B, N, H};
+    for (int i = 0; i < 3; ++i)
+        if (st[i] <= 0 || (st[i] % 8) != 0) return false;
+    for (int i = 0; i < 3; ++i)
+        for (int j = i + 1; j < 3; ++j)
+            if (st[j] < st[i]) { int64_t t = st[i]; st[i] = st[j]; st[j] = t; t = ex[i]; ex[i] = ex[j]; ex[j] = t; }
+    int64_t need = D;
+    for (int i = 0; i < 3; ++i) {
+        if (ex[i] > 1 && st[i] < need) return false;
+        need = st[i] * ex[i];
+    }
+    return true;
+}
+
+void resolve_strides(const int64_t in[3], int64_t out[3], int64_t N, int64_t H, int64_t D) {
+    if (in[0] == 0 && in[1] == 0 && in[2] == 0) {
+        out[2] = D; out[1] = H * D; out[0] = N * H * D;
+    } else {
+        out[0] = in[0]; out[1] = in[1]; out[2] = in[2];
+    }
+}
+
+ta::Tensor make_tensor(const void* p, const int64_t s[3]) {
+    return ta::Tensor{const_cast<void*>(p), s[0], s[1], s[2]};
+}
+
+ta::HopParams hop_params(const ta_plan* pl, int axis, const void* q, const void* k, const void* vin,
+                         int vin_kind, void* o) {
+    ta::HopParams hp;
+    hp.q = make_tensor(q, pl->qs);
+    hp.k = make_tensor(k, pl->kvs);
+    hp.vin = make_tensor(vin, vin_kind == TA_VIN_KV ? pl->kvs : pl->os);
+    hp.o = make_tensor(o, pl->os);
+    hp.B = pl->desc.batch; hp.Hq = pl->desc.n_q_heads; hp.Hkv = pl->desc.n_kv_heads; hp.G = pl->G;
+    hp.D = pl->desc.head_dim;
+    hp.n = pl->dims[axis];
+    hp.vin_heads = vin_kind == TA_VIN_KV ? pl->desc.n_kv_heads : pl->desc.n_q_heads;
+    hp.causal = pl->desc.causal;
+    hp.stride = pl->strides[axis];
+    hp.fibres = pl->N / pl->dims[axis];
+    hp.scale = pl->scale;
+    return hp;
+}
+
+ta_status_t check_axis_vin(const ta_plan* pl, int axis, int vin) {
+    if (!pl) return fail(TA_ERR_NULL, "plan is NULL");
+    if (axis < 0 || axis >= pl->order) return fail(TA_ERR_INVALID_ARG, "axis %d out of range [0, %d)", axis, pl->order);
+    if (vin != TA_VIN_KV && vin != TA_VIN_O) return fail(TA_ERR_INVALID_ARG, "vin must be TA_VIN_KV or TA_VIN_O");
+    return TA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ta_status_string(ta_status_t st) {
+    switch (st) {
+        case TA_OK: return "TA_OK";
+        case TA_ERR_NULL: return "TA_ERR_NULL";
+        case TA_ERR_INVALID_ARG: return "TA_ERR_INVALID_ARG";
+        case TA_ERR_SHAPE: return "TA_ERR_SHAPE";
+        case TA_ERR_UNSUPPORTED: return "TA_ERR_UNSUPPORTED";
+        case TA_ERR_ALIAS: return "TA_ERR_ALIAS";
+        case TA_ERR_WORKSPACE: return "TA_ERR_WORKSPACE";
+        case TA_ERR_DEVICE: return "TA_ERR_DEVICE";
+    }
+    return "TA_ERR_?";
+}
+
+const char* ta_last_error_detail(void) { return g_detail; }
+
+void ta_version(int* major, int* minor) {
+    if (major) *major = 0;
+    if (minor) *minor = 1;
+}
+
+ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
+    g_detail[0] = 0;
+    if (!d || !out) return fail(TA_ERR_NULL, "desc or out_plan is NULL");
+    *out = nullptr;
+    if (d->order < 1 || d->order > TA_MAX_ORDER) return fail(TA_ERR_SHAPE, "order %d not in 1..%d", d->order, TA_MAX_ORDER);
+    if (d->batch < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->head_dim < 1)
+        return fail(TA_ERR_SHAPE, "batch, head counts and head_dim must be >= 1");
+    if (d->n_q_heads % d->n_kv_heads != 0)
+        return fail(TA_ERR_SHAPE, "n_q_heads %d is not a multiple of n_kv_heads %d", d->n_q_heads, d->n_kv_heads);
+    if (d->dtype != TA_F32 && d->dtype != TA_BF16) return fail(TA_ERR_INVALID_ARG, "unknown dtype %d", d->dtype);
+    if (d->causal != 0 && d->causal != 1) return fail(TA_ERR_INVALID_ARG, "causal must be 0 or 1");
+    if (!(d->scale >= 0.f) || isinf(d->scale)) return fail(TA_ERR_INVALID_ARG, "scale must be finite and >= 0");
+    int64_t N = 1;
+    for (int i = 0; i < d->order; ++i) {
+        if (d->dims[i] < 1) return fail(TA_ERR_SHAPE, "dims[%d] = %d < 1", i, d->dims[i]);
+        if (N > (int64_t)1 << 40) return fail(TA_ERR_SHAPE, "sequence length overflows");
+        N *= d->dims[i];
+    }
+    if (N > (int64_t)1 << 40) return fail(TA_ERR_SHAPE, "sequence length overflows");
+    if (d->head_dim % 8 != 0 || d->head_dim > 256)
+        return fail(TA_ERR_UNSUPPORTED, "head_dim %d: need a multiple of 8, at most 256", d->head_dim);
+
+    ta_plan* pl = new (std::nothrow) ta_plan;
+    if (!pl) return fail(TA_ERR_INVALID_ARG, "out of host memory");
+    memset(pl, 0, sizeof(*pl));
+    pl->desc = *d;
+    pl->order = d->order;
+    pl->N = N;
+    pl->G = d->n_q_heads / d->n_kv_heads;
+    pl->elem = d->dtype == TA_F32 ? 4 : 2;
+    pl->scale = d->scale > 0.f ? d->scale : (float)(1.0 / sqrt((double)d->head_dim));
+    for (int i = 0; i < d->order; ++i) pl->dims[i] = d->dims[i];
+    pl->strides[d->order - 1] = 1;
+    for (int i = d->order - 2; i >= 0; --i) pl->strides[i] = pl->strides[i + 1] * pl->dims[i + 1];
+
+    // hop order: all -1 = Algorithm 1's order, else a permutation of the axes
+    bool all_default = true;
+    for (int i = 0; i < d->order; ++i) all_default = all_default && d->hop_order[i] == -1;
+    if (all_default) {
+        for (int i = 0; i < d->order; ++i) pl->hop_axis[i] = i;
+    } else {
+        bool seen[TA_MAX_ORDER] = {false};
+        for (int i = 0; i < d->order; ++i) {
+            const int a = d->hop_order[i];
+            if (a < 0 || a >= d->order || seen[a]) {
+                delete pl;
+                return fail(TA_ERR_INVALID_ARG, "hop_order is not a permutation of 0..%d", d->order - 1);
+            }
+            seen[a] = true;
+            pl->hop_axis[i] = a;
+        }
+    }
+
+    const int64_t D = d->head_dim;
+    resolve_strides(d->q_strides, pl->qs, N, d->n_q_heads, D);
+    resolve_strides(d->kv_strides, pl->kvs, N, d->n_kv_heads, D);
+    resolve_strides(d->o_strides, pl->os, N, d->n_q_heads, D);
+    if (!strides_ok(pl->qs, d->batch, N, d->n_q_heads, D) || !strides_ok(pl->kvs, d->batch, N, d->n_kv_heads, D) ||
+        !strides_ok(pl->os, d->batch, N, d->n_q_heads, D)) {
+        delete pl;
+        return fail(TA_ERR_SHAPE, "strides must be positive multiples of 8 elements describing non-overlapping rows");
+    }
+    pl->o_span = (d->batch - 1) * pl->os[0] + (N - 1) * pl->os[1] + (d->n_q_heads - 1) * pl->os[2] + D;
+    pl->o_buf_bytes = (((size_t)pl->o_span * pl->elem) + 255) & ~(size_t)255;
+
+    for (int i = 0; i < d->order; ++i)
+        for (int vin = 0; vin < 2; ++vin) {
+            int kid = ta::K_GENERIC;
+            ta::mfma_forward_supports(pl->dims[i], d->head_dim, d->dtype, &kid);
+            pl->kernel_id[i][vin] = kid;
+        }
+    *out = pl;
+    return TA_OK;
+}
+
+void ta_plan_destroy(ta_plan_t* pl) { delete pl; }
+
+int64_t ta_plan_seq_len(const ta_plan_t* pl) { return pl ? pl->N : -1; }
+int64_t ta_plan_axis_stride(const ta_plan_t* pl, int axis) {
+    return (pl && axis >= 0 && axis < pl->order) ? pl->strides[axis] : -1;
+}
+int64_t ta_plan_axis_fibres(const ta_plan_t* pl, int axis) {
+    return (pl && axis >= 0 && axis < pl->order) ? pl->N / pl->dims[axis] : -1;
+}
+int ta_plan_hop_axis(const ta_plan_t* pl, int pos) {
+    return (pl && pos >= 0 && pos < pl->order) ? pl->hop_axis[pos] : -1;
+}
+const char* ta_plan_hop_kernel(const ta_plan_t* pl, int axis, int vin) {
+    if (!pl || axis < 0 || axis >= pl->order || (vin != 0 && vin != 1)) return nullptr;
+    switch (pl->kernel_id[axis][vin]) {
+        case ta::K_GENERIC: return "generic";
+        case ta::K_MFMA_BF16_N16: return "mfma_bf16_n16";
+        case ta::K_MFMA_BF16_N32: return "mfma_bf16_n32";
+        case ta::K_MFMA_BF16_N64: return "mfma_bf16_n64";
+    }
+    return nullptr;
+}
+
+double ta_plan_hop_bytes(const ta_plan_t* pl, int axis, int vin, int backward, int accumulate) {
+    if (!pl || axis < 0 || axis >= pl->order || (vin != 0 && vin != 1)) return -1.0;
+    const double per_head = (double)pl->desc.batch * (double)pl->N * pl->desc.head_dim * pl->elem;
+    const double Hq = pl->desc.n_q_heads, Hkv = pl->desc.n_kv_heads;
+    const double Hvin = vin == TA_VIN_KV ? Hkv : Hq;
+    if (!backward) return per_head * (Hq + Hkv + Hvin + Hq);
+    // reads Q, K, value input, dO; writes d(value input), dQ, dK; accumulate re-reads dQ, dK
+    double heads = Hq + Hkv + Hvin + Hq + Hvin + Hq + Hkv;
+    if (accumulate) heads += Hq + Hkv;
+    return per_head * heads;
+}
+
+double ta_plan_hop_flops(const ta_plan_t* pl, int axis, int backward) {
+    if (!pl || axis < 0 || axis >= pl->order) return -1.0;
+    const double fwd = 4.0 * pl->desc.batch * pl->desc.n_q_heads * (double)pl->N * pl->dims[axis] * pl->desc.head_dim;
+    return backward ? 2.5 * fwd : fwd;
+}
+
+size_t ta_plan_workspace_bytes(const ta_plan_t* pl, int save_for_backward) {
+    if (!pl || pl->order <= 1) return 0;
+    const int nbuf = save_for_backward ? pl->order - 1 : (pl->order == 2 ? 1 : 2);
+    return (size_t)nbuf * pl->o_buf_bytes;
+}
+
+size_t ta_plan_backward_scratch_bytes(const ta_plan_t* pl) {
+    if (!pl) return 0;
+    return 2 * pl->o_buf_bytes;
+}
+
+ta_status_t ta_axis_attn_forward(const ta_plan_t* pl, int axis, const void* q, const void* k, const void* v_in,
+                                 int vin, void* o_out, void* stream) {
+    g_detail[0] = 0;
+    ta_status_t st = check_axis_vin(pl, axis, vin);
+    if (st != TA_OK) return st;
+    if (!q || !k || !v_in || !o_out) return fail(TA_ERR_NULL, "q, k, v_in or o_out is NULL");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v_in) || !aligned16(o_out))
+        return fail(TA_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
+    const ta_desc_t& d = pl->desc;
+    const Range ro = span_of(o_out, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
+    const Range rq = span_of(q, pl->qs, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
+    const Range rk = span_of(k, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem);
+    const Range rv = vin == TA_VIN_KV ? span_of(v_in, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem)
+                                      : span_of(v_in, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
+    if (overlaps(ro, rq) || overlaps(ro, rk) || overlaps(ro, rv))
+        return fail(TA_ERR_ALIAS, "o_out overlaps an input");
+
+    const ta::HopParams hp = hop_params(pl, axis, q, k, v_in, vin, o_out);
+    const int kid = pl->kernel_id[axis][vin];
+    hipError_t e = kid == ta::K_GENERIC ? ta::launch_generic_forward(hp, d.dtype, (hipStream_t)stream)
+                                        : ta::launch_mfma_forward(hp, kid, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(TA_ERR_DEVICE, "forward launch failed: %s", hipGetErrorString(e));
+    return TA_OK;
+}
+
+ta_status_t ta_axis_attn_backward(const ta_plan_t* pl, int axis, const void* q, const void* k, const void* v_in,
+                                  int vin, const void* d_o, void* d_v_in, void* dq, void* dk, int accumulate,
+                                  void* stream) {
+    g_detail[0] = 0;
+    ta_status_t st = check_axis_vin(pl, axis, vin);
+    if (st != TA_OK) return st;
+    if (!q || !k || !v_in || !d_o || !d_v_in || !dq || !dk) return fail(TA_ERR_NULL, "a tensor pointer is NULL");
+    if (accumulate != 0 && accumulate != 1) return fail(TA_ERR_INVALID_ARG, "accumulate must be 0 or 1");
+    const void* ptrs[7] = {q, k, v_in, d_o, d_v_in, dq, dk};
+    for (const void* p : ptrs)
+        if (!aligned16(p)) return fail(TA_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
+    const ta_desc_t& d = pl->desc;
+    const int64_t* vs = vin == TA_VIN_KV ? pl->kvs : pl->os;
+    const int vh = vin == TA_VIN_KV ? d.n_kv_heads : d.n_q_heads;
+    const Range in[4] = {span_of(q, pl->qs, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem),
+                         span_of(k, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem),
+                         span_of(v_in, vs, d.batch, pl->N, vh, d.head_dim, pl->elem),
+                         span_of(d_o, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem)};
+    const Range outr[3] = {span_of(d_v_in, vs, d.batch, pl->N, vh, d.head_dim, pl->elem),
+                           span_of(dq, pl->qs, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem),
+                           span_of(dk, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem)};
+    for (int i = 0; i < 3; ++i) {
+        for (int j = 0; j < 4; ++j)
+            if (overlaps(outr[i], in[j])) return fail(TA_ERR_ALIAS, "a gradient output overlaps an input");
+        for (int j = i + 1; j < 3; ++j)
+            if (overlaps(outr[i], outr[j])) return fail(TA_ERR_ALIAS, "gradient outputs overlap each other");
+    }
+    if (!ta::generic_backward_supports(pl->dims[axis], pl->G, d.head_dim))
+        return fail(TA_ERR_UNSUPPORTED, "backward: axis length %d with %d heads per group exceeds the kernel's limit",
+                    pl->dims[axis], pl->G);
+
+    ta::BwdParams bp;
+    bp.hop = hop_params(pl, axis, q, k, v_in, vin, nullptr);
+    bp.d_o = make_tensor(d_o, pl->os);
+    bp.d_vin = make_tensor(d_v_in, vs);
+    bp.dq = make_tensor(dq, pl->qs);
+    bp.dk = make_tensor(dk, pl->kvs);
+    bp.accumulate = accumulate;
+    hipError_t e = ta::launch_generic_backward(bp, d.dtype, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(TA_ERR_DEVICE, "backward launch failed: %s", hipGetErrorString(e));
+    return TA_OK;
+}
+
+ta_status_t ta_multihop_forward(const ta_plan_t* pl, const void* q, const void* k, const void* v, void* o,
+                                void* workspace, size_t workspace_bytes, int save_for_backward, void* stream) {
+    g_detail[0] = 0;
+    if (!pl) return fail(TA_ERR_NULL, "plan is NULL");
+    if (!q || !k || !v || !o) return fail(TA_ERR_NULL, "q, k, v or o is NULL");
+    const size_t need = ta_plan_workspace_bytes(pl, save_for_backward);
+    if (need > 0) {
+        if (!workspace) return fail(TA_ERR_NULL, "workspace is NULL but %zu bytes are needed", need);
+        if (workspace_bytes < need) return fail(TA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+        if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return fail(TA_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+        const ta_desc_t& d = pl->desc;
+        const Range rw = {reinterpret_cast<uintptr_t>(workspace), reinterpret_cast<uintptr_t>(workspace) + need};
+        if (overlaps(rw, span_of(q, pl->qs, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem)) ||
+            overlaps(rw, span_of(k, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem)) ||
+            overlaps(rw, span_of(v, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem)) ||
+            overlaps(rw, span_of(o, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem)))
+            return fail(TA_ERR_ALIAS, "workspace overlaps a tensor");
+    }
+    const int m = pl->order;
+    char* ws = static_cast<char*>(workspace);
+    const void* cur = v;
+    int cur_kind = TA_VIN_KV;
+    for (int pos = 0; pos < m; ++pos) {
+        void* dst;
+        if (pos == m - 1) dst = o;
+        else if (save_for_backward) dst = ws + (size_t)pos * pl->o_buf_bytes;
+        else dst = ws + (size_t)(pos & 1) * pl->o_buf_bytes;
+        ta_status_t st = ta_axis_attn_forward(pl, pl->hop_axis[pos], q, k, cur, cur_kind, dst, stream);
+        if (st != TA_OK) return st;
+        cur = dst;
+        cur_kind = TA_VIN_O;
+    }
+    return TA_OK;
+}
+
+ta_status_t ta_multihop_backward(const ta_plan_t* pl, const void* q, const void* k, const void* v, const void* d_o,
+                                 const void* workspace, size_t workspace_bytes, void* dq, void* dk, void* dv,
+                                 void* scratch, size_t scratch_bytes, void* stream) {
+    g_detail[0] = 0;
+    if (!pl) return fail(TA_ERR_NULL, "plan is NULL");
+    if (!q || !k || !v || !d_o || !dq || !dk || !dv) return fail(TA_ERR_NULL, "a tensor pointer is NULL");
+    const int m = pl->order;
+    const size_t need_ws = ta_plan_workspace_bytes(pl, 1);
+    if (need_ws > 0) {
+        if (!workspace) return fail(TA_ERR_NULL, "workspace is NULL");
+        if (workspace_bytes < need_ws) return fail(TA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need_ws);
+    }
+    if (m > 1) {
+        const size_t need_sc = ta_plan_backward_scratch_bytes(pl);
+        if (!scratch) return fail(TA_ERR_NULL, "scratch is NULL");
+        if (scratch_bytes < need_sc) return fail(TA_ERR_WORKSPACE, "scratch has %zu bytes, %zu needed", scratch_bytes, need_sc);
+        if ((reinterpret_cast<uintptr_t>(scratch) & 255u) != 0) return fail(TA_ERR_INVALID_ARG, "scratch must be 256-byte aligned");
+    }
+    const char* ws = static_cast<const char*>(workspace);
+    char* sc = static_cast<char*>(scratch);
+    const void* grad = d_o;
+    for (int pos = m - 1; pos >= 0; --pos) {
+        const void* x = pos == 0 ? v : ws + (size_t)(pos - 1) * pl->o_buf_bytes;
+        const int kind = pos == 0 ? TA_VIN_KV : TA_VIN_O;
+        void* gprev = pos == 0 ? dv : sc + (size_t)(pos & 1) * pl->o_buf_bytes;
+        ta_status_t st = ta_axis_attn_backward(pl, pl->hop_axis[pos], q, k, x, kind, grad, gprev, dq, dk,
+                                               pos == m - 1 ? 0 : 1, stream);
+        if (st != TA_OK) return st;
+        grad = gprev;
+    }
+    return TA_OK;
+}
+
+ta_status_t ta_copy_bytes(const void* src, void* dst, size_t bytes, void* stream) {
+    g_detail[0] = 0;
+    if (!src || !dst) return fail(TA_ERR_NULL, "src or dst is NULL");
+    if (bytes % 16 != 0 || !aligned16(src) || !aligned16(dst)) return fail(TA_ERR_INVALID_ARG, "copy needs 16-byte alignment and size");
+    hipError_t e = ta::launch_copy(src, dst, bytes, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(TA_ERR_DEVICE, "copy launch failed: %s", hipGetErrorString(e));
+    return TA_OK;
+}
+
+}  // extern "C"

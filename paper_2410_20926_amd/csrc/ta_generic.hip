@@ -1,0 +1,433 @@
+// Generic per-axis attention kernels (forward and backward) for gfx950.
+//
+// These cover every shape the library accepts - any axis length, head width up to 256,
+// fp32 or bf16 storage - with fp32 arithmetic on the vector ALUs and a streaming
+// (online) softmax over key tiles.  They are the fp32 path and the fallback for shapes
+// the MFMA kernels do not take; they are written for clarity, not speed.
+//
+// One hop follows Eq. 4 of arXiv 2410.20926: for every mode-i fibre (n rows, row pitch
+// `stride` tokens) A = softmax(Q_i K_i^T * scale, mask), O_i = A * Vin_i.
+#include "ta_internal.h"
+
+namespace ta {
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;
+constexpr int kQB = 16;            // query rows per forward block (4 per wave)
+
+__device__ inline float to_f32(float x) { return x; }
+__device__ inline float to_f32(uint16_t x) { return __uint_as_float(((uint32_t)x) << 16); }
+
+__device__ inline void from_f32(float* dst, float x) { *dst = x; }
+__device__ inline void from_f32(uint16_t* dst, float x) {
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) {            // NaN stays NaN
+        *dst = (uint16_t)((u >> 16) | 0x40u);
+        return;
+    }
+    u += 0x7fffu + ((u >> 16) & 1u);                  // round to nearest, ties to even
+    *dst = (uint16_t)(u >> 16);
+}
+
+__device__ inline float wave_max(float x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x = fmaxf(x, __shfl_xor(x, o));
+    return x;
+}
+__device__ inline float wave_sum(float x) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o);
+    return x;
+}
+
+template <typename T>
+__device__ inline const T* row_ptr(const Tensor& t, int64_t b, int64_t tok, int64_t h) {
+    return reinterpret_cast<const T*>(t.p) + b * t.sb + tok * t.st + h * t.sh;
+}
+template <typename T>
+__device__ inline T* row_ptr_w(const Tensor& t, int64_t b, int64_t tok, int64_t h) {
+    return reinterpret_cast<T*>(t.p) + b * t.sb + tok * t.st + h * t.sh;
+}
+
+// Copy `rows` rows of D elements (row r at token tok0 + (r0 + r) * stride) into an LDS
+// tile of pitch `pitch` floats; rows at or past n are zero-filled.
+template <typename T>
+__device__ inline void load_tile(float* tile, int pitch, int rows, int r0, const Tensor& t,
+                                 int64_t b, int64_t tok0, int64_t stride, int64_t h, int n, int D) {
+    for (int idx = threadIdx.x; idx < rows * D; idx += kThreads) {
+        const int r = idx / D, d = idx - r * D;
+        const int a = r0 + r;
+        float x = 0.f;
+        if (a < n) x = to_f32(row_ptr<T>(t, b, tok0 + (int64_t)a * stride, h)[d]);
+        tile[r * pitch + d] = x;
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Forward.  Block = (batch, query head, fibre, block of 16 query rows); wave w owns rows
+// 4w..4w+3 of the block.  Keys are streamed in tiles of TK rows through LDS; lane
+// (c, half) forms half of the dot product q_a . k_c, a lane owns output columns
+// lane, lane+64, ...
+template <typename T>
+__global__ __launch_bounds__(kThreads) void generic_forward_kernel(HopParams p, int TK, int qblocks) {
+    extern __shared__ float smem[];
+    const int D = p.D, n = p.n;
+    float* Qs = smem;                       // [kQB][D]
+    float* Ks = Qs + kQB * D;               // [TK][D+1]
+    float* Vs = Ks + TK * (D + 1);          // [TK][D]
+
+    int64_t bid = blockIdx.x;
+    const int qb = (int)(bid % qblocks); bid /= qblocks;
+    const int64_t f = bid % p.fibres; bid /= p.fibres;
+    const int h = (int)(bid % p.Hq);
+    const int b = (int)(bid / p.Hq);
+    const int g = h / p.G;
+    const int hv = (p.vin_heads == p.Hq) ? h : g;
+    const int64_t tok0 = fibre_base_token(f, p.stride, n);
+
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int c_l = lane & 31, hh = lane >> 5;
+    const int ncol = (D + 63) / 64;
+    const int dh = D / 2;
+
+    load_tile<T>(Qs, D, kQB, qb * kQB, p.q, b, tok0, p.stride, h, n, D);
+
+    float m[4], l[4], acc[4][4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        m[r] = -INFINITY; l[r] = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[r][j] = 0.f;
+    }
+    const int a_last = min(n - 1, qb * kQB + kQB - 1);
+    const int kend = p.causal ? a_last + 1 : n;         // keys past the block's last row are masked
+    for (int k0 = 0; k0 < kend; k0 += TK) {
+        __syncthreads();
+        load_tile<T>(Ks, D + 1, TK, k0, p.k, b, tok0, p.stride, g, n, D);
+        load_tile<T>(Vs, D, TK, k0, p.vin, b, tok0, p.stride, hv, n, D);
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int a = qb * kQB + w * 4 + r;
+            if (a >= n) continue;
+            const float* qrow = Qs + (w * 4 + r) * D;
+            const float* krow = Ks + c_l * (D + 1);
+            float part = 0.f;
+            if (c_l < TK)
+                for (int d = hh * dh; d < (hh + 1) * dh; ++d) part += qrow[d] * krow[d];
+            float s = part + __shfl_xor(part, 32);
+            const int c = k0 + c_l;
+            const bool valid = (c_l < TK) && (c < n) && (!p.causal || c <= a);
+            s = valid ? s * p.scale : -INFINITY;
+            const float tmax = wave_max(s);
+            if (tmax == -INFINITY) continue;            // nothing visible in this tile
+            const float mn = fmaxf(m[r], tmax);
+            const float pr = valid ? expf(s - mn) : 0.f;
+            const float corr = expf(m[r] - mn);
+            l[r] = l[r] * corr + wave_sum(hh == 0 ? pr : 0.f);
+            m[r] = mn;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[r][j] *= corr;
+            for (int cc = 0; cc < TK; ++cc) {
+                const float pc = __shfl(pr, cc);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int col = lane + 64 * j;
+                    if (j < ncol && col < D) acc[r][j] += pc * Vs[cc * D + col];
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int a = qb * kQB + w * 4 + r;
+        if (a >= n) continue;
+        T* orow = row_ptr_w<T>(p.o, b, tok0 + (int64_t)a * p.stride, h);
+        const float inv = 1.f / l[r];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int col = lane + 64 * j;
+            if (j < ncol && col < D) from_f32(orow + col, acc[r][j] * inv);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// Backward.  Block = (batch, key/value head, fibre); it walks the G query heads of the
+// group so that dK (and dV when the value input is V) are summed inside the block,
+// without atomics.
+//   Phase A (per head, one query row per wave at a time): recompute the row's softmax
+//   statistics and output (as the forward does), delta_a = dO_a . O_a, then
+//   dS = A o (dA - delta) and dQ_a = dS K * scale.
+//   Phase B (one key per wave at a time): dK_c = sum_h sum_a dS[a,c] q_a * scale and
+//   d(value input)_c = sum_a A[a,c] dO_a, using the statistics of phase A.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void generic_backward_kernel(BwdParams bp, int TK) {
+    extern __shared__ float smem[];
+    const HopParams& p = bp.hop;
+    const int D = p.D, n = p.n, G = p.G;
+    const int pitch = D + 1;
+    float* st_m = smem;                     // [G][n] row max
+    float* st_l = st_m + G * n;             // [G][n] row sum
+    float* st_d = st_l + G * n;             // [G][n] delta
+    float* tA = st_d + G * n;               // [TK][D+1]
+    float* tB = tA + TK * pitch;            // [TK][D+1]
+    float* rowbuf = tB + TK * pitch;        // [kWaves][2][D]
+
+    int64_t bid = blockIdx.x;
+    const int64_t f = bid % p.fibres; bid /= p.fibres;
+    const int g = (int)(bid % p.Hkv);
+    const int b = (int)(bid / p.Hkv);
+    const int64_t tok0 = fibre_base_token(f, p.stride, n);
+    const bool vin_is_o = (p.vin_heads == p.Hq);
+
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int c_l = lane & 31, hh = lane >> 5;
+    const int dh = D / 2;
+    float* r0 = rowbuf + (w * 2 + 0) * D;
+    float* r1 = rowbuf + (w * 2 + 1) * D;
+
+    // ---------------- phase A ----------------
+    for (int hl = 0; hl < G; ++hl) {
+        const int h = g * G + hl;
+        const int hv = vin_is_o ? h : g;
+        for (int rb = 0; rb * kWaves < n; ++rb) {
+            const int a = rb * kWaves + w;
+            const bool active = a < n;
+            __syncthreads();
+            if (active) {
+                const T* qrow = row_ptr<T>(p.q, b, tok0 + (int64_t)a * p.stride, h);
+                const T* grow = row_ptr<T>(bp.d_o, b, tok0 + (int64_t)a * p.stride, h);
+                for (int d = lane; d < D; d += 64) { r0[d] = to_f32(qrow[d]); r1[d] = to_f32(grow[d]); }
+            }
+            float m = -INFINITY, l = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
+            const int kend = p.causal ? min(n, rb * kWaves + kWaves) : n;
+            // pass 1: statistics and the row of O
+            for (int k0 = 0; k0 < kend; k0 += TK) {
+                __syncthreads();
+                load_tile<T>(tA, pitch, TK, k0, p.k, b, tok0, p.stride, g, n, D);
+                load_tile<T>(tB, pitch, TK, k0, p.vin, b, tok0, p.stride, hv, n, D);
+                __syncthreads();
+                if (!active) continue;
+                float part = 0.f;
+                if (c_l < TK)
+                    for (int d = hh * dh; d < (hh + 1) * dh; ++d) part += r0[d] * tA[c_l * pitch + d];
+                float s = part + __shfl_xor(part, 32);
+                const int c = k0 + c_l;
+                const bool valid = (c_l < TK) && (c < n) && (!p.causal || c <= a);
+                s = valid ? s * p.scale : -INFINITY;
+                const float tmax = wave_max(s);
+                if (tmax == -INFINITY) continue;
+                const float mn = fmaxf(m, tmax);
+                const float pr = valid ? expf(s - mn) : 0.f;
+                const float corr = expf(m - mn);
+                l = l * corr + wave_sum(hh == 0 ? pr : 0.f);
+                m = mn;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[j] *= corr;
+                for (int cc = 0; cc < TK; ++cc) {
+                    const float pc = __shfl(pr, cc);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int col = lane + 64 * j;
+                        if (col < D) acc[j] += pc * tB[cc * pitch + col];
+                    }
+                }
+            }
+            float delta = 0.f;
+            if (active) {
+                float part = 0.f;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int col = lane + 64 * j;
+                    if (col < D) part += r1[col] * (acc[j] / l);
+                }
+                delta = wave_sum(part);
+                if (lane == 0) { st_m[hl * n + a] = m; st_l[hl * n + a] = l; st_d[hl * n + a] = delta; }
+            }
+            // pass 2: dS and dQ_a
+            float dqa[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int k0 = 0; k0 < kend; k0 += TK) {
+                __syncthreads();
+                load_tile<T>(tA, pitch, TK, k0, p.k, b, tok0, p.stride, g, n, D);
+                load_tile<T>(tB, pitch, TK, k0, p.vin, b, tok0, p.stride, hv, n, D);
+                __syncthreads();
+                if (!active) continue;
+                float ps = 0.f, pa = 0.f;
+                if (c_l < TK)
+                    for (int d = hh * dh; d < (hh + 1) * dh; ++d) {
+                        ps += r0[d] * tA[c_l * pitch + d];
+                        pa += r1[d] * tB[c_l * pitch + d];
+                    }
+                const float s = (ps + __shfl_xor(ps, 32)) * p.scale;
+                const float dA = pa + __shfl_xor(pa, 32);
+                const int c = k0 + c_l;
+                const bool valid = (c_l < TK) && (c < n) && (!p.causal || c <= a);
+                const float pr = valid ? expf(s - m) / l : 0.f;
+                const float dS = pr * (dA - delta);
+                for (int cc = 0; cc < TK; ++cc) {
+                    const float x = __shfl(dS, cc);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int col = lane + 64 * j;
+                        if (col < D) dqa[j] += x * tA[cc * pitch + col];
+                    }
+                }
+            }
+            if (active) {
+                T* dqrow = row_ptr_w<T>(bp.dq, b, tok0 + (int64_t)a * p.stride, h);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int col = lane + 64 * j;
+                    if (col < D) {
+                        float x = dqa[j] * p.scale;
+                        if (bp.accumulate) x += to_f32(dqrow[col]);
+                        from_f32(dqrow + col, x);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---------------- phase B ----------------
+    for (int kb = 0; kb * kWaves < n; ++kb) {
+        const int c = kb * kWaves + w;
+        const bool active = c < n;
+        float accK[4] = {0.f, 0.f, 0.f, 0.f}, accX[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int hl = 0; hl < G; ++hl) {
+            const int h = g * G + hl;
+            const int hv = vin_is_o ? h : g;
+            __syncthreads();
+            if (active) {
+                const T* krow = row_ptr<T>(p.k, b, tok0 + (int64_t)c * p.stride, g);
+                const T* xrow = row_ptr<T>(p.vin, b, tok0 + (int64_t)c * p.stride, hv);
+                for (int d = lane; d < D; d += 64) { r0[d] = to_f32(krow[d]); r1[d] = to_f32(xrow[d]); }
+            }
+            if (vin_is_o) { accX[0] = accX[1] = accX[2] = accX[3] = 0.f; }
+            const int qstart = p.causal ? (kb * kWaves / TK) * TK : 0;   // rows before the block's first key see none of its keys
+            for (int q0 = qstart; q0 < n; q0 += TK) {
+                __syncthreads();
+                load_tile<T>(tA, pitch, TK, q0, p.q, b, tok0, p.stride, h, n, D);
+                load_tile<T>(tB, pitch, TK, q0, bp.d_o, b, tok0, p.stride, h, n, D);
+                __syncthreads();
+                if (!active) continue;
+                float ps = 0.f, pa = 0.f;
+                if (c_l < TK)
+                    for (int d = hh * dh; d < (hh + 1) * dh; ++d) {
+                        ps += tA[c_l * pitch + d] * r0[d];
+                        pa += tB[c_l * pitch + d] * r1[d];
+                    }
+                const float s = (ps + __shfl_xor(ps, 32)) * p.scale;
+                const float dA = pa + __shfl_xor(pa, 32);
+                const int a = q0 + c_l;
+                const bool valid = (c_l < TK) && (a < n) && (!p.causal || c <= a);
+                float pr = 0.f, dS = 0.f;
+                if (valid) {
+                    pr = expf(s - st_m[hl * n + a]) / st_l[hl * n + a];
+                    dS = pr * (dA - st_d[hl * n + a]);
+                }
+                for (int aa = 0; aa < TK; ++aa) {
+                    const float xs = __shfl(dS, aa);
+                    const float xp = __shfl(pr, aa);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int col = lane + 64 * j;
+                        if (col < D) {
+                            accK[j] += xs * tA[aa * pitch + col];
+                            accX[j] += xp * tB[aa * pitch + col];
+                        }
+                    }
+                }
+            }
+            if (active && vin_is_o) {
+                T* dx = row_ptr_w<T>(bp.d_vin, b, tok0 + (int64_t)c * p.stride, h);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int col = lane + 64 * j;
+                    if (col < D) from_f32(dx + col, accX[j]);
+                }
+            }
+        }
+        if (active) {
+            T* dkrow = row_ptr_w<T>(bp.dk, b, tok0 + (int64_t)c * p.stride, g);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int col = lane + 64 * j;
+                if (col < D) {
+                    float x = accK[j] * p.scale;
+                    if (bp.accumulate) x += to_f32(dkrow[col]);
+                    from_f32(dkrow + col, x);
+                }
+            }
+            if (!vin_is_o) {
+                T* dx = row_ptr_w<T>(bp.d_vin, b, tok0 + (int64_t)c * p.stride, g);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int col = lane + 64 * j;
+                    if (col < D) from_f32(dx + col, accX[j]);
+                }
+            }
+        }
+    }
+}
+
+inline int tile_rows(int D) { return D <= 128 ? 32 : 16; }
+
+}  // namespace
+
+hipError_t launch_generic_forward(const HopParams& p, int dtype, hipStream_t s) {
+    const int TK = tile_rows(p.D);
+    const int qblocks = (p.n + kQB - 1) / kQB;
+    const int64_t blocks = (int64_t)p.B * p.Hq * p.fibres * qblocks;
+    const size_t smem = sizeof(float) * ((size_t)kQB * p.D + (size_t)TK * (p.D + 1) + (size_t)TK * p.D);
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (dtype == TA_F32)
+        hipLaunchKernelGGL(generic_forward_kernel<float>, dim3((unsigned)blocks), dim3(kThreads), smem, s, p, TK, qblocks);
+    else
+        hipLaunchKernelGGL(generic_forward_kernel<uint16_t>, dim3((unsigned)blocks), dim3(kThreads), smem, s, p, TK, qblocks);
+    return hipGetLastError();
+}
+
+static size_t backward_smem(int32_t n, int32_t G, int32_t D) {
+    const int TK = tile_rows(D);
+    return sizeof(float) * ((size_t)3 * G * n + (size_t)2 * TK * (D + 1) + (size_t)kWaves * 2 * D);
+}
+
+bool generic_backward_supports(int32_t n, int32_t G, int32_t D) {
+    return backward_smem(n, G, D) <= 64 * 1024;
+}
+
+hipError_t launch_generic_backward(const BwdParams& bp, int dtype, hipStream_t s) {
+    const HopParams& p = bp.hop;
+    const int TK = tile_rows(p.D);
+    const int64_t blocks = (int64_t)p.B * p.Hkv * p.fibres;
+    const size_t smem = backward_smem(p.n, p.G, p.D);
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (dtype == TA_F32)
+        hipLaunchKernelGGL(generic_backward_kernel<float>, dim3((unsigned)blocks), dim3(kThreads), smem, s, bp, TK);
+    else
+        hipLaunchKernelGGL(generic_backward_kernel<uint16_t>, dim3((unsigned)blocks), dim3(kThreads), smem, s, bp, TK);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
+// Plain copy: 16 bytes per lane, grid-stride, used to measure the HBM ceiling.
+namespace {
+__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += step) dst[i] = src[i];
+}
+}  // namespace
+
+hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
+                       reinterpret_cast<const uint4*>(src), reinterpret_cast<uint4*>(dst), n16);
+    return hipGetLastError();
+}
+
+}  // namespace ta

@@ -1,0 +1,64 @@
+// Internal declarations shared by the host API and the HIP kernel files.
+// Nothing here is part of the C ABI (see include/tensattn.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tensattn.h"
+
+namespace ta {
+
+// A strided [B, N, H, D] tensor: element (b, t, h, x) at p + b*sb + t*st + h*sh + x (elements).
+struct Tensor {
+    void* p;
+    int64_t sb, st, sh;
+};
+
+// One hop of Eq. 4: attention along one tensor axis, every other axis batched.
+struct HopParams {
+    Tensor q, k, vin, o;     // forward: o is written.  backward: see BwdParams
+    int32_t B, Hq, Hkv, G;   // G = Hq / Hkv
+    int32_t D;               // head width
+    int32_t n;               // axis length n_i
+    int32_t vin_heads;       // Hkv (value input is V) or Hq (value input is a previous O)
+    int32_t causal;
+    int64_t stride;          // tokens between neighbours along the axis
+    int64_t fibres;          // N / n_i
+    float scale;
+};
+
+struct BwdParams {
+    HopParams hop;           // hop.o is unused
+    Tensor d_o;              // upstream gradient, O layout, Hq heads
+    Tensor d_vin;            // gradient of the value input, vin layout/heads
+    Tensor dq;               // Q layout
+    Tensor dk;               // key/value layout
+    int32_t accumulate;      // 0: overwrite dq, dk; 1: add
+};
+
+// First token of fibre f: fibres enumerate (outer, inner) with inner fastest, so that
+// consecutive fibres are neighbouring tokens.
+__host__ __device__ inline int64_t fibre_base_token(int64_t f, int64_t stride, int32_t n) {
+    const int64_t outer = f / stride;
+    const int64_t inner = f - outer * stride;
+    return outer * stride * n + inner;
+}
+
+enum KernelId : int {
+    K_GENERIC = 0,
+    K_MFMA_BF16_N16 = 1,
+    K_MFMA_BF16_N32 = 2,
+    K_MFMA_BF16_N64 = 3,
+};
+
+// Launchers.  Each checks nothing: the API layer has validated shapes against what
+// the kernel assumes.  Each returns the hipError_t of the launch.
+hipError_t launch_generic_forward(const HopParams& p, int dtype, hipStream_t s);
+hipError_t launch_generic_backward(const BwdParams& p, int dtype, hipStream_t s);
+bool       generic_backward_supports(int32_t n, int32_t G, int32_t D);
+hipError_t launch_mfma_forward(const HopParams& p, int kernel_id, hipStream_t s);
+bool       mfma_forward_supports(int32_t n, int32_t D, int dtype, int* kernel_id);
+hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+
+}  // namespace ta
