@@ -34,6 +34,8 @@ def parse_args():
     ap.add_argument("--rotate", type=int, default=3, help="independent buffer sets cycled through, so that the "
                     "256 MB Infinity Cache cannot serve one step's re-reads from the previous step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true", help="also launch the plain copy kernel on 1 GiB a few "
+                    "times, so that a hardware-counter run of this command has a transfer of known size to scale by")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -174,6 +176,14 @@ def main():
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                 "avg_launch_us": round(avg_dur * 1e6, 2), "algorithmic_bytes_per_launch": avg_bytes,
                 "launches_timed": launches, "per_hop": hops}
+
+    if args.copy_calibration:
+        nbytes = 1 << 30
+        src = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+        dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            ta.ta_copy_bytes(src, dst, nbytes)
+        torch.cuda.synchronize()
 
     out = {
         "metric": "tensorized-attn tokens/s + per-hop HBM GB/s (% peak) at N=32k, 128k",

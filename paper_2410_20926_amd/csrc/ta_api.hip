@@ -199,6 +199,8 @@ ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
         for (int vin = 0; vin < 2; ++vin) {
             int kid = ta::K_GENERIC;
             ta::mfma_forward_supports(pl->dims[i], d->head_dim, d->dtype, &kid);
+            if (kid != ta::K_GENERIC && !ta::mfma_forward_layout_ok(hop_params(pl, i, nullptr, nullptr, nullptr, vin, nullptr)))
+                kid = ta::K_GENERIC;
             pl->kernel_id[i][vin] = kid;
         }
     *out = pl;

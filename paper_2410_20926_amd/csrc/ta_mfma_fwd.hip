@@ -1,23 +1,25 @@
 // bf16 MFMA per-axis attention forward for gfx950 (CDNA4), one hop of Eq. 4 of
 // arXiv 2410.20926.
 //
-// Work unit: one 32-row "tile" of one query head: floor(32 / n) mode-i fibres packed one
-// after the other (rows past the last fibre are padding), handled by ONE wavefront with
-// no workgroup barrier.  Fibres in a tile never see each other: the mask is block
-// diagonal (and lower triangular inside a block for the causal variant).
+// Work unit: 32 query rows of one query head, handled by ONE wavefront with no workgroup
+// barrier.  For an axis of length n <= 32 the 32 rows are floor(32 / n) mode-i fibres
+// packed one after the other (rows past the last fibre are padding) and the mask is block
+// diagonal (lower triangular inside a block for the causal variant).  For 32 < n <= 64 a
+// fibre has two query tiles (two units) and each unit walks up to two 32-key tiles.
 //
 // Per wave:
 //   1. gather: rows of Q, K and the value input come from HBM with 16-byte loads, 16
-//      lanes per 256-byte row, i.e. fully coalesced whatever the axis stride is;
+//      lanes per 256-byte row (D = 128), i.e. fully coalesced whatever the axis stride is;
+//      every load of the unit is issued before the first use;
 //   2. Q and K pass through an LDS transit buffer (padded rows) and come back in MFMA
 //      operand layout;
 //   3. S^T = K Q^T with v_mfma_f32_32x32x16_bf16: the accumulator then holds, per lane,
 //      16 of the 32 keys of ONE query row (the other 16 are in lane^32), so the row
 //      softmax needs in-lane reductions and a single cross-lane exchange;
 //   4. the un-normalised probabilities, rounded to bf16, are already in B-operand
-//      layout for O^T = V^T P^T; V goes through LDS with pairs of rows interleaved so
-//      that a 32-bit LDS read yields two consecutive keys of one feature column, which
-//      is the A-operand layout of V^T;
+//      layout for O^T = V^T P^T (keys c and c + 8 share a 32-bit word); V goes through
+//      LDS with rows c and c + 8 interleaved the same way, so that a 32-bit LDS read
+//      yields the two keys of one feature column, which is the A-operand layout of V^T;
 //   5. O^T is scaled by 1/rowsum in fp32, rounded to bf16, transposed through LDS and
 //      stored with 16-byte coalesced stores (fold).
 #include "ta_internal.h"
@@ -26,17 +28,20 @@ namespace ta {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 constexpr int kWavesPerBlock = 4;
 constexpr int kTile = 32;
 constexpr float kLog2e = 1.4426950408889634f;
 
-__device__ inline uint32_t bf16_rne(float x) {           // finite inputs only
-    uint32_t u = __float_as_uint(x);
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {      // v_cvt_pk_bf16_f32, round to nearest even
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
-__device__ inline uint32_t pack_bf16x2(float lo, float hi) { return bf16_rne(lo) | (bf16_rne(hi) << 16); }
 
 __device__ inline void lds_wave_sync() {
     // LDS operations of one wave complete in issue order; this only stops the compiler
@@ -51,226 +56,326 @@ struct Geo {
     static constexpr int kRowsPerPass = 64 / kChunks;     // rows one wave-wide load covers
     static constexpr int kPasses = kTile / kRowsPerPass;  // loads per lane per 32-row tile
     static constexpr int kPitch = D * 2 + 16;             // bytes, Q/K/O transit rows
-    static constexpr int kVPitch = D * 4 + 64;            // bytes, one interleaved row pair of V
-    static constexpr int kVPasses = (kTile / 2) / kRowsPerPass;
+    static constexpr int kVPitch = D * 4 + 32;            // bytes, one interleaved row pair of V (4 pitches = 32 banks mod 64)
     static constexpr int kKSteps = D / 16;                // MFMA steps over the feature axis
     static constexpr int kDTiles = D / 32;                // 32-column tiles of the output
     static constexpr int kBufBytes = (kTile * kPitch > (kTile / 2) * kVPitch) ? kTile * kPitch : (kTile / 2) * kVPitch;
-    static constexpr int kWaveBytes = kBufBytes + kTile * 8;   // + row -> element-offset table
 };
 
-// One tile per wave.  `fpt` = fibres per tile, `tiles` = tiles per (batch, head).
-template <int D>
-__global__ __launch_bounds__(kWavesPerBlock * 64) void mfma_fwd_tile32(HopParams p, int fpt, int64_t tiles, int64_t units) {
+// Launch geometry computed on the host.
+struct TileParams {
+    int32_t fpt;          // fibres per 32-row tile (n <= 32), else 1
+    int32_t qtiles;       // query tiles per fibre: 1 (n <= 32) or 2
+    uint32_t tiles;       // units per (batch, head)
+    uint32_t tiles_lo;    // gridDim.y; gridDim.z = B * ceil(tiles / tiles_lo)
+    uint32_t tiles_hi;
+    uint32_t q_row, k_row, v_row, o_row;   // token pitch of each tensor in BYTES
+    float inv_n;          // 1 / n
+};
+
+// KT = number of 32-key tiles a unit may walk (1: n <= 32, 2: n <= 64).
+template <int D, int KT>
+__global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopParams p, TileParams tp) {
     using G = Geo<D>;
+    constexpr int kRows = kTile * KT;                     // rows of the unit's fibre set that have a table entry
+    constexpr int kWaveBytes = G::kBufBytes + kRows * 16;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int lane = threadIdx.x & 63;
-    const int w = threadIdx.x >> 6;
-    const int64_t unit = (int64_t)blockIdx.x * kWavesPerBlock + w;
-    if (unit >= units) return;                            // no workgroup barrier below
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
-    char* buf = smem + w * G::kWaveBytes;
-    int64_t* rowtok = reinterpret_cast<int64_t*>(buf + G::kBufBytes);
-
-    // unit -> (batch, tile, head): heads fastest, so the waves of a block share K
-    const int h = (int)(unit % p.Hq);
-    const int64_t rest = unit / p.Hq;
-    const int64_t tt = rest % tiles;
-    const int b = (int)(rest / tiles);
+    // block -> (head block, tile, batch); heads fastest so that co-resident waves read
+    // the same tokens (whole DRAM rows) and the four waves of a block share K
+    const int h = blockIdx.x * kWavesPerBlock + w;
+    const uint32_t zb = blockIdx.z / tp.tiles_hi;
+    const uint32_t tt = (blockIdx.z - zb * tp.tiles_hi) * tp.tiles_lo + blockIdx.y;
+    if (h >= p.Hq || tt >= tp.tiles) return;              // no workgroup barrier below
+    const int b = (int)zb;
     const int g = h / p.G;
     const int hv = (p.vin_heads == p.Hq) ? h : g;
     const int n = p.n;
-    const int64_t f0 = tt * fpt;
-    const int nf = (int)min((int64_t)fpt, p.fibres - f0);
-    const int rows_valid = nf * n;
 
-    // token of every tile row (lanes 0..31), shared through LDS
-    if (lane < kTile) {
-        const int fi = lane / n;
-        const int a = lane - fi * n;
-        int64_t tok = 0;
-        if (lane < rows_valid) tok = fibre_base_token(f0 + fi, p.stride, n) + (int64_t)a * p.stride;
-        rowtok[lane] = tok;
+    char* buf = smem + w * kWaveBytes;
+    u32x4* rowoff = reinterpret_cast<u32x4*>(buf + G::kBufBytes);   // per row: byte offsets in (q, k, v_in, o)
+
+    // fibre(s) and query tile of this unit
+    uint32_t f0;
+    int qt, rows_valid;                                   // rows_valid: rows of the table that exist
+    if (KT == 1) {
+        f0 = tt * tp.fpt;
+        qt = 0;
+        rows_valid = (int)min((uint32_t)tp.fpt, (uint32_t)p.fibres - f0) * n;
+    } else {
+        f0 = tt / tp.qtiles;
+        qt = (int)(tt - f0 * tp.qtiles);
+        rows_valid = n;
+    }
+    // byte offset of every row of the fibre set, clamped to the last valid row, so that
+    // loads need no predicate (padding rows are masked in the softmax and never stored)
+    {
+        const uint32_t stride = (uint32_t)p.stride;
+        for (int r = lane; r < kRows; r += 64) {
+            const int rc = min(r, rows_valid - 1);
+            const uint32_t fi = (KT == 1) ? (uint32_t)((rc + 0.5f) * tp.inv_n) : 0u;
+            const uint32_t a = rc - fi * n;
+            const uint32_t f = f0 + fi;
+            const uint32_t outer = f / stride;
+            const uint32_t tok = outer * stride * n + (f - outer * stride) + a * stride;
+            rowoff[r] = u32x4{tok * tp.q_row, tok * tp.k_row, tok * tp.v_row, tok * tp.o_row};
+        }
     }
     lds_wave_sync();
 
-    const uint16_t* qb = reinterpret_cast<const uint16_t*>(p.q.p) + (int64_t)b * p.q.sb + (int64_t)h * p.q.sh;
-    const uint16_t* kb = reinterpret_cast<const uint16_t*>(p.k.p) + (int64_t)b * p.k.sb + (int64_t)g * p.k.sh;
-    const uint16_t* vb = reinterpret_cast<const uint16_t*>(p.vin.p) + (int64_t)b * p.vin.sb + (int64_t)hv * p.vin.sh;
-    uint16_t* ob = reinterpret_cast<uint16_t*>(p.o.p) + (int64_t)b * p.o.sb + (int64_t)h * p.o.sh;
+    const char* qb = reinterpret_cast<const char*>(p.q.p) + ((int64_t)b * p.q.sb + (int64_t)h * p.q.sh) * 2;
+    const char* kb = reinterpret_cast<const char*>(p.k.p) + ((int64_t)b * p.k.sb + (int64_t)g * p.k.sh) * 2;
+    const char* vb = reinterpret_cast<const char*>(p.vin.p) + ((int64_t)b * p.vin.sb + (int64_t)hv * p.vin.sh) * 2;
+    char* ob = reinterpret_cast<char*>(p.o.p) + ((int64_t)b * p.o.sb + (int64_t)h * p.o.sh) * 2;
 
     const int lrow = lane / G::kChunks;                   // row within a pass
     const int lcol = lane % G::kChunks;                   // 16-byte chunk within the row
+    const uint32_t lbyte = lcol * 16;
+    const int kt_end = (KT == 1) ? 1 : (p.causal ? qt + 1 : (n > kTile ? 2 : 1));   // key tiles this unit walks
 
-    // ---- 1. gather Q, K, V rows (all loads issued before any use) ------------------
-    uint4 qreg[G::kPasses], kreg[G::kPasses], vreg[2 * G::kVPasses];
+    // ---- 1. gather ---------------------------------------------------------------------
+    // Lane (lrow, lcol) loads chunk lcol of rows i * kRowsPerPass + lrow of every tile.
+    // Q, every K tile and the first V tile are requested here, before the first wait; a
+    // second V tile is requested as soon as the first K tile has left its registers.
+    u32x4 qreg[G::kPasses], kreg[KT][G::kPasses], vreg[KT][G::kPasses];
+    uint32_t ooff[G::kPasses], voff[KT][G::kPasses];
 #pragma unroll
-    for (int i = 0; i < G::kPasses; ++i) {
-        const int row = i * G::kRowsPerPass + lrow;
-        const int64_t tok = rowtok[row];
-        qreg[i] = make_uint4(0, 0, 0, 0);
-        kreg[i] = make_uint4(0, 0, 0, 0);
-        if (row < rows_valid) {
-            qreg[i] = *reinterpret_cast<const uint4*>(qb + tok * p.q.st + lcol * 8);
-            kreg[i] = *reinterpret_cast<const uint4*>(kb + tok * p.k.st + lcol * 8);
+    for (int j = 0; j < KT; ++j) {
+        if (j < kt_end) {
+#pragma unroll
+            for (int i = 0; i < G::kPasses; ++i) {
+                const u32x4 off = rowoff[j * kTile + i * G::kRowsPerPass + lrow];
+                kreg[j][i] = *reinterpret_cast<const u32x4*>(kb + (off.y + lbyte));
+                voff[j][i] = off.z + lbyte;
+                if (j == 0) vreg[j][i] = *reinterpret_cast<const u32x4*>(vb + voff[j][i]);
+                if (KT == 1) {
+                    qreg[i] = *reinterpret_cast<const u32x4*>(qb + (off.x + lbyte));
+                    ooff[i] = off.w + lbyte;
+                }
+            }
         }
     }
+    if (KT > 1) {
 #pragma unroll
-    for (int i = 0; i < G::kVPasses; ++i) {
-        const int pr = i * G::kRowsPerPass + lrow;        // row pair
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const int row = 2 * pr + e;
-            vreg[2 * i + e] = make_uint4(0, 0, 0, 0);
-            if (row < rows_valid)
-                vreg[2 * i + e] = *reinterpret_cast<const uint4*>(vb + rowtok[row] * p.vin.st + lcol * 8);
+        for (int i = 0; i < G::kPasses; ++i) {
+            const u32x4 off = rowoff[qt * kTile + i * G::kRowsPerPass + lrow];
+            qreg[i] = *reinterpret_cast<const u32x4*>(qb + (off.x + lbyte));
+            ooff[i] = off.w + lbyte;
         }
     }
+    __builtin_amdgcn_sched_barrier(0);                    // keep these loads ahead of the first wait
 
     const int r32 = lane & 31;                            // tile row this lane owns in operands
     const int hf = lane >> 5;                             // which 8-wide half of a 16-wide MFMA step
+    const char* oprd = buf + r32 * G::kPitch + hf * 16;   // operand read base
+    char* stg = buf + lrow * G::kPitch + lbyte;           // row-major staging base
 
     // ---- 2. Q through LDS into B-operand layout -------------------------------------
-    uint4 qop[G::kKSteps], kop[G::kKSteps];
+    u32x4 qop[G::kKSteps];
 #pragma unroll
     for (int i = 0; i < G::kPasses; ++i)
-        *reinterpret_cast<uint4*>(buf + (i * G::kRowsPerPass + lrow) * G::kPitch + lcol * 16) = qreg[i];
+        *reinterpret_cast<u32x4*>(stg + i * G::kRowsPerPass * G::kPitch) = qreg[i];
     lds_wave_sync();
 #pragma unroll
-    for (int s = 0; s < G::kKSteps; ++s)
-        qop[s] = *reinterpret_cast<const uint4*>(buf + r32 * G::kPitch + (2 * s + hf) * 16);
-    lds_wave_sync();
-    // ---- K through LDS into A-operand layout ----------------------------------------
-#pragma unroll
-    for (int i = 0; i < G::kPasses; ++i)
-        *reinterpret_cast<uint4*>(buf + (i * G::kRowsPerPass + lrow) * G::kPitch + lcol * 16) = kreg[i];
-    lds_wave_sync();
-#pragma unroll
-    for (int s = 0; s < G::kKSteps; ++s)
-        kop[s] = *reinterpret_cast<const uint4*>(buf + r32 * G::kPitch + (2 * s + hf) * 16);
+    for (int s = 0; s < G::kKSteps; ++s) qop[s] = *reinterpret_cast<const u32x4*>(oprd + s * 32);
     lds_wave_sync();
 
-    // ---- 3. S^T = K Q^T : acc[r] = S[a = r32][c = 8*(r/4) + 4*hf + r%4] ---------------
-    f32x16 st = {};
+    // ---- 3. per key tile: K through LDS, S^T = K Q^T ----------------------------------
+    // st[j][r] = S[a = r32][c = 32 j + 8*(r/4) + 4*hf + r%4]
+    f32x16 st[KT];
 #pragma unroll
-    for (int s = 0; s < G::kKSteps; ++s)
-        st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kop[s]), __builtin_bit_cast(bf16x8, qop[s]), st, 0, 0, 0);
-
-    // ---- V through LDS, row pairs interleaved (overlaps the MFMAs above) --------------
+    for (int j = 0; j < KT; ++j) {
+        st[j] = f32x16{};
+        if (j < kt_end) {
+            u32x4 kop[G::kKSteps];
 #pragma unroll
-    for (int i = 0; i < G::kVPasses; ++i) {
-        const uint4 x = vreg[2 * i], y = vreg[2 * i + 1];
-        const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
-        uint32_t o[8];
+            for (int i = 0; i < G::kPasses; ++i)
+                *reinterpret_cast<u32x4*>(stg + i * G::kRowsPerPass * G::kPitch) = kreg[j][i];
+            lds_wave_sync();
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            o[2 * j] = (xs[j] & 0xffffu) | (ys[j] << 16);
-            o[2 * j + 1] = (xs[j] >> 16) | (ys[j] & 0xffff0000u);
+            for (int s = 0; s < G::kKSteps; ++s) kop[s] = *reinterpret_cast<const u32x4*>(oprd + s * 32);
+            lds_wave_sync();
+            if (KT > 1 && j == 0 && kt_end > 1) {         // K tile 0 is out of its registers: request V tile 1
+#pragma unroll
+                for (int i = 0; i < G::kPasses; ++i) vreg[1][i] = *reinterpret_cast<const u32x4*>(vb + voff[1][i]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int s = 0; s < G::kKSteps; ++s)
+                st[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kop[s]),
+                                                                __builtin_bit_cast(bf16x8, qop[s]), st[j], 0, 0, 0);
         }
-        char* dst = buf + (i * G::kRowsPerPass + lrow) * G::kVPitch + lcol * 32;
-        *reinterpret_cast<uint4*>(dst) = make_uint4(o[0], o[1], o[2], o[3]);
-        *reinterpret_cast<uint4*>(dst + 16) = make_uint4(o[4], o[5], o[6], o[7]);
     }
-    lds_wave_sync();
 
-    // ---- 4. masked row softmax --------------------------------------------------------
-    // keys visible to query row r32: its own fibre's rows, up to itself when causal
-    uint32_t vis = 0;
-    if (r32 < rows_valid) {
-        const int fi = r32 / n;
-        const int lo = fi * n;
-        const int hi = p.causal ? r32 + 1 : lo + n;
-        vis = (hi >= 32 ? 0xffffffffu : ((1u << hi) - 1u)) & ~((1u << lo) - 1u);
+    // ---- 4. masked row softmax over all key tiles ---------------------------------------
+    // keys visible to this lane's query row: its own fibre's rows, up to itself when causal
+    const int qrow = qt * kTile + r32;                    // row index in the fibre set
+    uint32_t vis[KT];
+    {
+        int lo = 0, hi = 0;                               // visible keys = [lo, hi)
+        if (qrow < rows_valid) {
+            if (KT == 1) {
+                const int fi = (int)((qrow + 0.5f) * tp.inv_n);
+                lo = fi * n;
+                hi = p.causal ? qrow + 1 : lo + n;
+            } else {
+                hi = p.causal ? qrow + 1 : n;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < KT; ++j) {
+            const int l = min(max(lo - 32 * j, 0), 32), hh = min(max(hi - 32 * j, 0), 32);
+            const uint32_t mh = hh >= 32 ? 0xffffffffu : ((1u << hh) - 1u);
+            const uint32_t ml = l >= 32 ? 0xffffffffu : ((1u << l) - 1u);
+            vis[j] = (mh & ~ml) >> (4 * hf);
+        }
     }
-    const uint32_t vish = vis >> (4 * hf);
     const float sl2 = p.scale * kLog2e;
     float mx = -INFINITY;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const bool ok = (vish >> (8 * (r / 4) + (r % 4))) & 1u;
-        st[r] = ok ? st[r] * sl2 : -INFINITY;
-        mx = fmaxf(mx, st[r]);
-    }
+    for (int j = 0; j < KT; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const bool ok = (vis[j] >> (8 * (r / 4) + (r % 4))) & 1u;
+            st[j][r] = ok ? st[j][r] * sl2 : -INFINITY;
+            mx = fmaxf(mx, st[j][r]);
+        }
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     if (mx == -INFINITY) mx = 0.f;                        // padding rows: everything masked
-    uint32_t pop[2][4];                                   // P^T as two B operands (16 keys each)
+    uint32_t pop[KT][2][4];                               // P^T as B operands, 16 keys each
     float sum = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; r += 2) {
-        const float e0 = __builtin_amdgcn_exp2f(st[r] - mx);
-        const float e1 = __builtin_amdgcn_exp2f(st[r + 1] - mx);
-        const uint32_t pk = pack_bf16x2(e0, e1);
-        sum += __uint_as_float(pk << 16) + __uint_as_float(pk & 0xffff0000u);
-        pop[r / 8][(r % 8) / 2] = pk;
-    }
+    for (int j = 0; j < KT; ++j)
+#pragma unroll
+        for (int ri = 0; ri < 8; ++ri) {
+            const int r = (ri / 4) * 8 + ri % 4;          // r pairs with r + 4: keys c and c + 8
+            const float e0 = __builtin_amdgcn_exp2f(st[j][r] - mx);
+            const float e1 = __builtin_amdgcn_exp2f(st[j][r + 4] - mx);
+            const uint32_t pk = pack_bf16x2(e0, e1);
+            sum += __uint_as_float(pk << 16) + __uint_as_float(pk & 0xffff0000u);   // sum of the ROUNDED weights
+            pop[j][r / 8][r % 4] = pk;
+        }
     sum += __shfl_xor(sum, 32);
     const float inv = sum > 0.f ? 1.f / sum : 0.f;
 
-    // ---- O^T = V^T P^T ------------------------------------------------------------------
+    // ---- per key tile: V through LDS (row pairs interleaved), O^T += V^T P^T -------------
     f32x16 ot[G::kDTiles];
 #pragma unroll
-    for (int t = 0; t < G::kDTiles; ++t) {
-        ot[t] = f32x16{};
+    for (int t = 0; t < G::kDTiles; ++t) ot[t] = f32x16{};
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-            uint32_t a[4];
+    for (int j = 0; j < KT; ++j) {
+        if (j < kt_end) {
+            // rows rho and rho + 8 (rho mod 16 < 8) share a 32-bit word per column: slot
+            // (rho / 16) * 8 + rho % 16 of the buffer
 #pragma unroll
-            for (int jp = 0; jp < 4; ++jp) {
-                const int cp = 8 * s2 + 4 * (jp / 2) + 2 * hf + (jp % 2);      // row pair holding keys c, c+1
-                a[jp] = *reinterpret_cast<const uint32_t*>(buf + cp * G::kVPitch + (32 * t + r32) * 4);
+            for (int pi = 0; pi < G::kPasses / 2; ++pi) {
+                constexpr int kStep = 8 / G::kRowsPerPass;                  // passes between rho and rho + 8
+                const int i = (pi / kStep) * 2 * kStep + pi % kStep;        // passes whose rows have rho mod 16 < 8
+                const int rho = i * G::kRowsPerPass;                        // + lrow
+                const int slot = (rho / 16) * 8 + rho % 16;                 // + lrow
+                const u32x4 x = vreg[j][i], y = vreg[j][i + kStep];
+                const uint32_t xs[4] = {x.x, x.y, x.z, x.w}, ys[4] = {y.x, y.y, y.z, y.w};
+                uint32_t o[8];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    o[2 * e] = __builtin_amdgcn_perm(ys[e], xs[e], 0x05040100u);      // (x.lo, y.lo)
+                    o[2 * e + 1] = __builtin_amdgcn_perm(ys[e], xs[e], 0x07060302u);  // (x.hi, y.hi)
+                }
+                char* dst = buf + (slot + lrow) * G::kVPitch + lcol * 32;
+                *reinterpret_cast<u32x4*>(dst) = u32x4{o[0], o[1], o[2], o[3]};
+                *reinterpret_cast<u32x4*>(dst + 16) = u32x4{o[4], o[5], o[6], o[7]};
             }
-            const uint4 av = make_uint4(a[0], a[1], a[2], a[3]);
-            const uint4 bv = make_uint4(pop[s2][0], pop[s2][1], pop[s2][2], pop[s2][3]);
-            ot[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), __builtin_bit_cast(bf16x8, bv), ot[t], 0, 0, 0);
+            lds_wave_sync();
+#pragma unroll
+            for (int t = 0; t < G::kDTiles; ++t) {
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    uint32_t a[4];
+#pragma unroll
+                    for (int jp = 0; jp < 4; ++jp)              // keys c = 16 s2 + 4 hf + jp and c + 8
+                        a[jp] = *reinterpret_cast<const uint32_t*>(buf + (8 * s2 + 4 * hf + jp) * G::kVPitch + (32 * t + r32) * 4);
+                    const u32x4 av = u32x4{a[0], a[1], a[2], a[3]};
+                    const u32x4 bv = u32x4{pop[j][s2][0], pop[j][s2][1], pop[j][s2][2], pop[j][s2][3]};
+                    ot[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av),
+                                                                    __builtin_bit_cast(bf16x8, bv), ot[t], 0, 0, 0);
+                }
+            }
+            lds_wave_sync();
         }
     }
-    lds_wave_sync();
 
     // ---- 5. normalise, round, transpose through LDS, store -------------------------------
 #pragma unroll
     for (int t = 0; t < G::kDTiles; ++t)
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
-            uint2 v;
+            u32x2 v;
             v.x = pack_bf16x2(ot[t][4 * q4] * inv, ot[t][4 * q4 + 1] * inv);
             v.y = pack_bf16x2(ot[t][4 * q4 + 2] * inv, ot[t][4 * q4 + 3] * inv);
-            *reinterpret_cast<uint2*>(buf + r32 * G::kPitch + (32 * t + 8 * q4 + 4 * hf) * 2) = v;
+            *reinterpret_cast<u32x2*>(buf + r32 * G::kPitch + (32 * t + 8 * q4 + 4 * hf) * 2) = v;
         }
     lds_wave_sync();
 #pragma unroll
     for (int i = 0; i < G::kPasses; ++i) {
-        const int row = i * G::kRowsPerPass + lrow;
+        const int row = qt * kTile + i * G::kRowsPerPass + lrow;
         if (row < rows_valid) {
-            const uint4 v = *reinterpret_cast<const uint4*>(buf + row * G::kPitch + lcol * 16);
-            *reinterpret_cast<uint4*>(ob + rowtok[row] * p.o.st + lcol * 8) = v;
+            const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
+            *reinterpret_cast<u32x4*>(ob + ooff[i]) = v;
         }
     }
 }
 
+template <int D, int KT>
+hipError_t launch(const HopParams& p, const TileParams& tp, hipStream_t s) {
+    const size_t smem = (size_t)kWavesPerBlock * (Geo<D>::kBufBytes + kTile * KT * 16);
+    const dim3 grid((unsigned)((p.Hq + kWavesPerBlock - 1) / kWavesPerBlock), tp.tiles_lo, (unsigned)p.B * tp.tiles_hi);
+    hipLaunchKernelGGL((mfma_fwd_kernel<D, KT>), grid, dim3(kWavesPerBlock * 64), smem, s, p, tp);
+    return hipGetLastError();
+}
+
+// Largest byte offset inside one (batch, head) slice must fit 32 bits.
+bool fits_u32(const Tensor& t, int64_t N) { return (N - 1) * t.st * 2 + 512 < (int64_t)0xffffffffLL; }
+
 }  // namespace
+
+bool mfma_forward_layout_ok(const HopParams& p) {
+    const int64_t N = p.fibres * p.n;
+    return N < ((int64_t)1 << 31) && p.B <= 65535 && fits_u32(p.q, N) && fits_u32(p.k, N) && fits_u32(p.vin, N) &&
+           fits_u32(p.o, N);
+}
 
 bool mfma_forward_supports(int32_t n, int32_t D, int dtype, int* kernel_id) {
     int kid = K_GENERIC;
-    if (dtype == TA_BF16 && (D == 64 || D == 128) && n >= 1 && n <= 32) kid = K_MFMA_BF16_N32;
+    if (dtype == TA_BF16 && (D == 64 || D == 128) && n >= 1) {
+        if (n <= 32) kid = K_MFMA_BF16_N32;
+        else if (n <= 64) kid = K_MFMA_BF16_N64;
+    }
     if (kernel_id) *kernel_id = kid;
     return kid != K_GENERIC;
 }
 
 hipError_t launch_mfma_forward(const HopParams& p, int kernel_id, hipStream_t s) {
-    if (kernel_id != K_MFMA_BF16_N32 || p.n < 1 || p.n > kTile || (p.D != 64 && p.D != 128)) return hipErrorInvalidValue;
-    const int fpt = kTile / p.n;
-    const int64_t tiles = (p.fibres + fpt - 1) / fpt;
-    const int64_t units = (int64_t)p.B * p.Hq * tiles;
-    const int64_t blocks = (units + kWavesPerBlock - 1) / kWavesPerBlock;
-    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    if (p.D == 128) {
-        const size_t smem = (size_t)kWavesPerBlock * Geo<128>::kWaveBytes;
-        hipLaunchKernelGGL(mfma_fwd_tile32<128>, dim3((unsigned)blocks), dim3(kWavesPerBlock * 64), smem, s, p, fpt, tiles, units);
-    } else {
-        const size_t smem = (size_t)kWavesPerBlock * Geo<64>::kWaveBytes;
-        hipLaunchKernelGGL(mfma_fwd_tile32<64>, dim3((unsigned)blocks), dim3(kWavesPerBlock * 64), smem, s, p, fpt, tiles, units);
-    }
-    return hipGetLastError();
+    const int KT = kernel_id == K_MFMA_BF16_N32 ? 1 : (kernel_id == K_MFMA_BF16_N64 ? 2 : 0);
+    if (KT == 0 || p.n < 1 || p.n > kTile * KT || (p.D != 64 && p.D != 128) || !mfma_forward_layout_ok(p))
+        return hipErrorInvalidValue;
+    TileParams tp;
+    tp.fpt = KT == 1 ? kTile / p.n : 1;
+    tp.qtiles = KT == 1 ? 1 : (p.n + kTile - 1) / kTile;
+    const int64_t tiles = KT == 1 ? (p.fibres + tp.fpt - 1) / tp.fpt : p.fibres * tp.qtiles;
+    if (tiles <= 0 || tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    tp.tiles = (uint32_t)tiles;
+    tp.tiles_lo = (uint32_t)(tiles < 32768 ? tiles : 32768);
+    tp.tiles_hi = (uint32_t)((tiles + tp.tiles_lo - 1) / tp.tiles_lo);
+    if ((int64_t)p.B * tp.tiles_hi > 65535) return hipErrorInvalidValue;
+    tp.q_row = (uint32_t)(p.q.st * 2);
+    tp.k_row = (uint32_t)(p.k.st * 2);
+    tp.v_row = (uint32_t)(p.vin.st * 2);
+    tp.o_row = (uint32_t)(p.o.st * 2);
+    tp.inv_n = 1.0f / (float)p.n;
+    if (p.D == 128) return KT == 1 ? launch<128, 1>(p, tp, s) : launch<128, 2>(p, tp, s);
+    return KT == 1 ? launch<64, 1>(p, tp, s) : launch<64, 2>(p, tp, s);
 }
 
 }  // namespace ta
