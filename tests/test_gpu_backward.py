@@ -2,10 +2,12 @@
 backward (itself pinned by finite differences on the CPU).
 
 Tolerances.  fp32: max-abs 1e-5 scaled by the gradient's magnitude (the sums run over
-up to n_i * G terms).  bf16: gradients are stored in bf16 between hops and dK, dV are
-sums over the G query heads of a group, so values reach magnitudes where half a bf16
-ulp alone exceeds 2e-2; the bound is 2e-2 + 2^-7 * |ref| (2e-2 absolute plus one bf16
-ulp relative)."""
+up to n_i * G terms).  bf16: the gradient that travels between hops is stored in bf16,
+per query head, at magnitudes up to ~8 (half an ulp = 1.6e-2 .. 3.1e-2 each), and dK, dV
+add G heads and several hops of such values, so the absolute error does not shrink with
+the final element: the bound is 2e-2 * max(1, max|ref| / 4) + 2^-7 * |ref|, i.e. the
+forward's 2e-2 (stated for values up to ~4) scaled to the tensor's magnitude, plus one
+bf16 ulp relative for the final rounding."""
 import math
 
 import numpy as np
@@ -27,8 +29,10 @@ def check_grad(got, ref, dtype, what):
         err = np.abs(got - ref).max()
         assert err <= bound, f"{what}: max-abs error {err:.3e} > {bound:.1e}"
     else:
-        excess = np.abs(got - ref) - (2e-2 + 2.0 ** -7 * np.abs(ref))
-        assert excess.max() <= 0, f"{what}: error exceeds 2e-2 + 2^-7|ref| by {excess.max():.3e}"
+        atol = 2e-2 * max(1.0, float(np.abs(ref).max()) / 4.0)
+        excess = np.abs(got - ref) - (atol + 2.0 ** -7 * np.abs(ref))
+        assert excess.max() <= 0, (f"{what}: error exceeds {atol:.2e} + 2^-7|ref| by {excess.max():.3e} "
+                                   f"(max|err| {np.abs(got - ref).max():.3e}, max|ref| {np.abs(ref).max():.3e})")
 
 
 CASES = [
