@@ -92,6 +92,9 @@ int     ta_plan_hop_axis(const ta_plan_t* plan, int hop_position); /* axis run a
 /* Name of the kernel variant the plan chose for the forward hop on `axis` with value
  * input `vin` ("mfma_bf16_n32", "generic", ...); NULL on error.  Static storage. */
 const char* ta_plan_hop_kernel(const ta_plan_t* plan, int axis, int vin);
+/* Same for the backward of that hop ("mfma_bf16_bwd_n32", "generic", or "unsupported" when
+ * ta_axis_attn_backward would return TA_ERR_UNSUPPORTED); NULL on error. */
+const char* ta_plan_hop_backward_kernel(const ta_plan_t* plan, int axis, int vin);
 
 /* Cost model of one hop (App. C.2, Table 5, with the fibre count N/n_i that Eq. 4
  * implies).  Bytes are ALGORITHMIC HBM bytes: each of Q, K, value-input read once,

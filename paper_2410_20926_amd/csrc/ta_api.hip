@@ -230,6 +230,19 @@ const char* ta_plan_hop_kernel(const ta_plan_t* pl, int axis, int vin) {
     return nullptr;
 }
 
+const char* ta_plan_hop_backward_kernel(const ta_plan_t* pl, int axis, int vin) {
+    if (!pl || axis < 0 || axis >= pl->order || (vin != 0 && vin != 1)) return nullptr;
+    ta::BwdParams bp;
+    bp.hop = hop_params(pl, axis, nullptr, nullptr, nullptr, vin, nullptr);
+    bp.d_o = make_tensor(nullptr, pl->os);
+    bp.d_vin = make_tensor(nullptr, vin == TA_VIN_KV ? pl->kvs : pl->os);
+    bp.dq = make_tensor(nullptr, pl->qs);
+    bp.dk = make_tensor(nullptr, pl->kvs);
+    bp.accumulate = 0;
+    if (ta::mfma_backward_supports(bp, pl->desc.dtype)) return "mfma_bf16_bwd_n32";
+    return ta::generic_backward_supports(pl->dims[axis], pl->G, pl->desc.head_dim) ? "generic" : "unsupported";
+}
+
 double ta_plan_hop_bytes(const ta_plan_t* pl, int axis, int vin, int backward, int accumulate) {
     if (!pl || axis < 0 || axis >= pl->order || (vin != 0 && vin != 1)) return -1.0;
     const double per_head = (double)pl->desc.batch * (double)pl->N * pl->desc.head_dim * pl->elem;
@@ -311,10 +324,6 @@ ta_status_t ta_axis_attn_backward(const ta_plan_t* pl, int axis, const void* q, 
         for (int j = i + 1; j < 3; ++j)
             if (overlaps(outr[i], outr[j])) return fail(TA_ERR_ALIAS, "gradient outputs overlap each other");
     }
-    if (!ta::generic_backward_supports(pl->dims[axis], pl->G, d.head_dim))
-        return fail(TA_ERR_UNSUPPORTED, "backward: axis length %d with %d heads per group exceeds the kernel's limit",
-                    pl->dims[axis], pl->G);
-
     ta::BwdParams bp;
     bp.hop = hop_params(pl, axis, q, k, v_in, vin, nullptr);
     bp.d_o = make_tensor(d_o, pl->os);
@@ -322,7 +331,15 @@ ta_status_t ta_axis_attn_backward(const ta_plan_t* pl, int axis, const void* q, 
     bp.dq = make_tensor(dq, pl->qs);
     bp.dk = make_tensor(dk, pl->kvs);
     bp.accumulate = accumulate;
-    hipError_t e = ta::launch_generic_backward(bp, d.dtype, (hipStream_t)stream);
+    hipError_t e;
+    if (ta::mfma_backward_supports(bp, d.dtype)) {
+        e = ta::launch_mfma_backward(bp, (hipStream_t)stream);
+    } else {
+        if (!ta::generic_backward_supports(pl->dims[axis], pl->G, d.head_dim))
+            return fail(TA_ERR_UNSUPPORTED, "backward: axis length %d with %d heads per group exceeds the kernel's limit",
+                        pl->dims[axis], pl->G);
+        e = ta::launch_generic_backward(bp, d.dtype, (hipStream_t)stream);
+    }
     if (e != hipSuccess) return fail(TA_ERR_DEVICE, "backward launch failed: %s", hipGetErrorString(e));
     return TA_OK;
 }

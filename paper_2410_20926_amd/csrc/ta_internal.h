@@ -60,6 +60,8 @@ bool       generic_backward_supports(int32_t n, int32_t G, int32_t D);
 hipError_t launch_mfma_forward(const HopParams& p, int kernel_id, hipStream_t s);
 bool       mfma_forward_supports(int32_t n, int32_t D, int dtype, int* kernel_id);
 bool       mfma_forward_layout_ok(const HopParams& p);   // strides and sizes fit the kernel's 32-bit row offsets
+bool       mfma_backward_supports(const BwdParams& bp, int dtype);
+hipError_t launch_mfma_backward(const BwdParams& bp, hipStream_t s);
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 
 }  // namespace ta

@@ -22,56 +22,14 @@
 //      yields the two keys of one feature column, which is the A-operand layout of V^T;
 //   5. O^T is scaled by 1/rowsum in fp32, rounded to bf16, transposed through LDS and
 //      stored with 16-byte coalesced stores (fold).
-#include "ta_internal.h"
+#include "ta_mfma_common.h"
 
 namespace ta {
 namespace {
 
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
-typedef __attribute__((ext_vector_type(2))) float f32x2;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+using namespace mfma;
 
 constexpr int kWavesPerBlock = 4;
-constexpr int kTile = 32;
-constexpr float kLog2e = 1.4426950408889634f;
-
-__device__ inline uint32_t pack_bf16x2(float lo, float hi) {      // v_cvt_pk_bf16_f32, round to nearest even
-    const f32x2 v = {lo, hi};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
-
-__device__ inline void lds_wave_sync() {
-    // LDS operations of one wave complete in issue order; this only stops the compiler
-    // from moving shared-memory accesses across the point where lanes exchange data.
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
-
-template <int D>
-struct Geo {
-    static constexpr int kChunks = D / 8;                 // 16-byte chunks per row
-    static constexpr int kRowsPerPass = 64 / kChunks;     // rows one wave-wide load covers
-    static constexpr int kPasses = kTile / kRowsPerPass;  // loads per lane per 32-row tile
-    static constexpr int kPitch = D * 2 + 16;             // bytes, Q/K/O transit rows
-    static constexpr int kVPitch = D * 4 + 32;            // bytes, one interleaved row pair of V (4 pitches = 32 banks mod 64)
-    static constexpr int kKSteps = D / 16;                // MFMA steps over the feature axis
-    static constexpr int kDTiles = D / 32;                // 32-column tiles of the output
-    static constexpr int kBufBytes = (kTile * kPitch > (kTile / 2) * kVPitch) ? kTile * kPitch : (kTile / 2) * kVPitch;
-};
-
-// Launch geometry computed on the host.
-struct TileParams {
-    int32_t fpt;          // fibres per 32-row tile (n <= 32), else 1
-    int32_t qtiles;       // query tiles per fibre: 1 (n <= 32) or 2
-    uint32_t tiles;       // units per (batch, head)
-    uint32_t tiles_lo;    // gridDim.y; gridDim.z = B * ceil(tiles / tiles_lo)
-    uint32_t tiles_hi;
-    uint32_t q_row, k_row, v_row, o_row;   // token pitch of each tensor in BYTES
-    float inv_n;          // 1 / n
-};
 
 // KT = number of 32-key tiles a unit may walk (1: n <= 32, 2: n <= 64).
 template <int D, int KT>
@@ -335,9 +293,6 @@ hipError_t launch(const HopParams& p, const TileParams& tp, hipStream_t s) {
     return hipGetLastError();
 }
 
-// Largest byte offset inside one (batch, head) slice must fit 32 bits.
-bool fits_u32(const Tensor& t, int64_t N) { return (N - 1) * t.st * 2 + 512 < (int64_t)0xffffffffLL; }
-
 }  // namespace
 
 bool mfma_forward_layout_ok(const HopParams& p) {
@@ -361,19 +316,7 @@ hipError_t launch_mfma_forward(const HopParams& p, int kernel_id, hipStream_t s)
     if (KT == 0 || p.n < 1 || p.n > kTile * KT || (p.D != 64 && p.D != 128) || !mfma_forward_layout_ok(p))
         return hipErrorInvalidValue;
     TileParams tp;
-    tp.fpt = KT == 1 ? kTile / p.n : 1;
-    tp.qtiles = KT == 1 ? 1 : (p.n + kTile - 1) / kTile;
-    const int64_t tiles = KT == 1 ? (p.fibres + tp.fpt - 1) / tp.fpt : p.fibres * tp.qtiles;
-    if (tiles <= 0 || tiles > 0x7fffffffLL) return hipErrorInvalidValue;
-    tp.tiles = (uint32_t)tiles;
-    tp.tiles_lo = (uint32_t)(tiles < 32768 ? tiles : 32768);
-    tp.tiles_hi = (uint32_t)((tiles + tp.tiles_lo - 1) / tp.tiles_lo);
-    if ((int64_t)p.B * tp.tiles_hi > 65535) return hipErrorInvalidValue;
-    tp.q_row = (uint32_t)(p.q.st * 2);
-    tp.k_row = (uint32_t)(p.k.st * 2);
-    tp.v_row = (uint32_t)(p.vin.st * 2);
-    tp.o_row = (uint32_t)(p.o.st * 2);
-    tp.inv_n = 1.0f / (float)p.n;
+    if (!make_tile_params(p, KT, &tp)) return hipErrorInvalidValue;
     if (p.D == 128) return KT == 1 ? launch<128, 1>(p, tp, s) : launch<128, 2>(p, tp, s);
     return KT == 1 ? launch<64, 1>(p, tp, s) : launch<64, 2>(p, tp, s);
 }

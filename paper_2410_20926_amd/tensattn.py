@@ -17,7 +17,7 @@ _lib = None
 
 EXPORTS = [
     "ta_plan_create", "ta_plan_destroy", "ta_plan_seq_len", "ta_plan_axis_stride", "ta_plan_axis_fibres",
-    "ta_plan_hop_axis", "ta_plan_hop_kernel", "ta_plan_hop_bytes", "ta_plan_hop_flops",
+    "ta_plan_hop_axis", "ta_plan_hop_kernel", "ta_plan_hop_backward_kernel", "ta_plan_hop_bytes", "ta_plan_hop_flops",
     "ta_plan_workspace_bytes", "ta_plan_backward_scratch_bytes", "ta_axis_attn_forward",
     "ta_axis_attn_backward", "ta_multihop_forward", "ta_multihop_backward", "ta_copy_bytes",
     "ta_status_string", "ta_last_error_detail", "ta_version",
@@ -68,6 +68,8 @@ def load_library():
     lib.ta_plan_hop_axis.restype = i
     lib.ta_plan_hop_kernel.argtypes = [vp, i, i]
     lib.ta_plan_hop_kernel.restype = C.c_char_p
+    lib.ta_plan_hop_backward_kernel.argtypes = [vp, i, i]
+    lib.ta_plan_hop_backward_kernel.restype = C.c_char_p
     lib.ta_plan_hop_bytes.argtypes = [vp, i, i, i, i]
     lib.ta_plan_hop_bytes.restype = dbl
     lib.ta_plan_hop_flops.argtypes = [vp, i, i]
@@ -175,6 +177,10 @@ class Plan:
 
     def hop_kernel(self, axis: int, vin: int) -> Optional[str]:
         s = load_library().ta_plan_hop_kernel(self._h, axis, vin)
+        return s.decode() if s is not None else None
+
+    def hop_backward_kernel(self, axis: int, vin: int) -> Optional[str]:
+        s = load_library().ta_plan_hop_backward_kernel(self._h, axis, vin)
         return s.decode() if s is not None else None
 
     def hop_bytes(self, axis: int, vin: int, backward: bool = False, accumulate: bool = False) -> float:

@@ -25,7 +25,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = ta.load_library()
     names = declared_symbols()
-    assert len(names) >= 19
+    assert len(names) >= 20
     for name in names:
         assert hasattr(lib, name), f"{name} declared in tensattn.h but not exported"
     assert sorted(binding.EXPORTS) == names

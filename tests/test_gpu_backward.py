@@ -45,7 +45,11 @@ CASES = [
     ((3, 20), 1, 2, 1, 256, True, "f32"),
     ((32, 16), 1, 4, 1, 128, True, "bf16"),
     ((16, 32, 4), 2, 4, 2, 128, True, "bf16"),
-    ((64, 8), 1, 2, 2, 64, False, "bf16"),
+    ((64, 8), 1, 2, 2, 64, False, "bf16"),           # n = 64 falls back to the generic kernel
+    ((3, 16, 8), 1, 2, 1, 128, True, "bf16"),        # packed fibres (2 and 4 per tile), 2 heads per group
+    ((5, 7, 3), 2, 4, 4, 64, True, "bf16"),          # odd lengths: ragged tiles with padding rows
+    ((32, 3), 1, 8, 2, 128, False, "bf16"),
+    ((6, 32), 1, 8, 1, 64, True, "bf16"),            # 8 heads per group: generic fallback
 ]
 
 
@@ -105,6 +109,8 @@ def test_config5_shape_sampled_groups():
     w = WORKLOADS["c5"]
     q, k, v, d_o = make_workload_inputs(w)
     _, plan, dev = multihop_forward(q, k, v, w.dims, w.dtype, w.causal, save=True)
+    assert plan.hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_n32"
+    assert plan.hop_backward_kernel(2, ta.TA_VIN_O) == "mfma_bf16_bwd_n32"
     dq, dk, dv = multihop_backward(plan, dev, d_o, w.dtype)
     G = w.n_q_heads // w.n_kv_heads
     for g in (0, 5):
