@@ -1,8 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the tensorized-attention hot path on one MI355X.
 
-One "step" = one pass of Algorithm 1 (all hops of ta_multihop_forward) over one batch
-of synthetic Q, K, V that already live in HBM.  Prints ONE JSON line:
+One "step" = one pass of Algorithm 1 (all hops of ta_multihop_forward; for the training
+workload c5 also ta_multihop_backward) over one batch of synthetic Q, K, V (and dO) that
+already live in HBM.  Prints ONE JSON line:
   metric/value/unit : tokens/s of the whole multi-hop forward (B*N / step time)
   roofline          : the per-axis attention kernel against the 8 TB/s HBM peak, from
                       HIP-event timings of every hop launch (algorithmic bytes / time)
@@ -47,7 +48,8 @@ def make_sets(torch, w, rotate):
     plan = ta.ta_plan_create(B, Hq, Hkv, D, w.dims, ta.TA_BF16, w.causal)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(w.seed)
-    wsb = plan.workspace_bytes(False)
+    wsb = plan.workspace_bytes(w.backward)
+    scb = plan.backward_scratch_bytes() if w.backward else 0
     sets = []
     for _ in range(rotate):
         q = (torch.randn(B, N, Hq, D, device="cuda", generator=gen) * w.qk_prescale).to(torch.bfloat16)
@@ -55,49 +57,79 @@ def make_sets(torch, w, rotate):
         v = torch.randn(B, N, Hkv, D, device="cuda", generator=gen).to(torch.bfloat16)
         o = torch.empty(B, N, Hq, D, device="cuda", dtype=torch.bfloat16)
         ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
-        sets.append((q, k, v, o, ws))
-    return plan, sets, wsb
+        st = {"q": q, "k": k, "v": v, "o": o, "ws": ws}
+        if w.backward:
+            st["d_o"] = torch.randn(B, N, Hq, D, device="cuda", generator=gen).to(torch.bfloat16)
+            st["dq"], st["dk"], st["dv"] = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+            st["sc"] = torch.empty(max(scb, 256), dtype=torch.uint8, device="cuda")
+        sets.append(st)
+    return plan, sets, wsb, scb
 
 
-def time_steps(torch, ta, plan, sets, wsb, steps, warmup):
-    """Wall time of exactly `steps` multi-hop forwards, synchronised on both sides."""
+def one_step(ta, plan, st, wsb, scb, backward):
+    """One pass of the whole hot path: Algorithm 1 forward, plus the backward for a training workload."""
+    ta.ta_multihop_forward(plan, st["q"], st["k"], st["v"], st["o"], st["ws"], wsb, backward)
+    if backward:
+        ta.ta_multihop_backward(plan, st["q"], st["k"], st["v"], st["d_o"], st["ws"], wsb,
+                                st["dq"], st["dk"], st["dv"], st["sc"], scb)
+
+
+def time_steps(torch, ta, plan, sets, wsb, scb, backward, steps, warmup):
+    """Wall time of exactly `steps` steps, synchronised on both sides."""
     for i in range(warmup):
-        q, k, v, o, ws = sets[i % len(sets)]
-        ta.ta_multihop_forward(plan, q, k, v, o, ws, wsb, False)
+        one_step(ta, plan, sets[i % len(sets)], wsb, scb, backward)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
-        q, k, v, o, ws = sets[i % len(sets)]
-        ta.ta_multihop_forward(plan, q, k, v, o, ws, wsb, False)
+        one_step(ta, plan, sets[i % len(sets)], wsb, scb, backward)
     torch.cuda.synchronize()
     return time.perf_counter() - t0
 
 
 def time_hops(torch, ta, plan, sets, w, steps):
     """HIP-event duration of every per-axis launch, on the stream the kernels run on
-    (torch's current stream, which the binding hands to the library).  Returns per hop
-    position the list of durations in seconds."""
+    (torch's current stream, which the binding hands to the library).  Returns a list of
+    records (direction, hop position, axis, value-input kind, seconds)."""
     B, N, Hq, D = w.batch, w.seq_len, w.n_q_heads, w.head_dim
     m = len(w.dims)
     o_elems = B * N * Hq * D
-    per_hop = [[] for _ in range(m)]
+    ob = plan_o_bytes(plan, w)
     events = []
+
+    def timed(tag, fn):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        fn()
+        e1.record()
+        events.append(tag + (e0, e1))
+
+    def view(buf, j):
+        return buf[j * ob:][:o_elems * 2].view(torch.bfloat16).view(B, N, Hq, D)
+
     for i in range(steps):
-        q, k, v, o, ws = sets[i % len(sets)]
-        bufs = [ws[j * plan_o_bytes(plan, w):][:o_elems * 2].view(torch.bfloat16).view(B, N, Hq, D) for j in range(2)]
+        st = sets[i % len(sets)]
+        q, k, v, o, ws = st["q"], st["k"], st["v"], st["o"], st["ws"]
+        inter = [view(ws, j) for j in range(m - 1)] if w.backward else [view(ws, j) for j in range(min(2, m - 1))]
+        srcs = []
         cur, kind = v, ta.TA_VIN_KV
         for pos in range(m):
-            dst = o if pos == m - 1 else bufs[pos & 1]
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            ta.ta_axis_attn_forward(plan, plan.hop_axis(pos), q, k, cur, kind, dst)
-            e1.record()
-            events.append((pos, e0, e1))
+            dst = o if pos == m - 1 else (inter[pos] if w.backward else inter[pos & 1])
+            axis = plan.hop_axis(pos)
+            timed(("fwd", pos, axis, kind), lambda: ta.ta_axis_attn_forward(plan, axis, q, k, cur, kind, dst))
+            srcs.append((cur, kind))
             cur, kind = dst, ta.TA_VIN_O
+        if w.backward:
+            grad = st["d_o"]
+            for pos in range(m - 1, -1, -1):
+                x, kind = srcs[pos]
+                gprev = st["dv"] if pos == 0 else view(st["sc"], pos & 1)
+                axis = plan.hop_axis(pos)
+                acc = pos != m - 1
+                timed(("bwd", pos, axis, kind), lambda: ta.ta_axis_attn_backward(
+                    plan, axis, q, k, x, kind, grad, gprev, st["dq"], st["dk"], acc))
+                grad = gprev
     torch.cuda.synchronize()
-    for pos, e0, e1 in events:
-        per_hop[pos].append(e0.elapsed_time(e1) * 1e-3)
-    return per_hop
+    return [(d, pos, axis, kind, e0.elapsed_time(e1) * 1e-3) for d, pos, axis, kind, e0, e1 in events]
 
 
 def plan_o_bytes(plan, w):
@@ -111,12 +143,15 @@ def cpu_baseline(w, target_seconds):
     import numpy as np
     from oracle import tensattn_oracle as orc
     from paper_2410_20926_amd.workloads import make_inputs
-    q, k, v = make_inputs(1, w.seq_len, 1, 1, w.head_dim, w.seed, "bf16", w.qk_prescale)
+    q, k, v, d_o = make_inputs(1, w.seq_len, 1, 1, w.head_dim, w.seed, "bf16", w.qk_prescale, with_grad=True)
     heads = 0
     c0 = time.process_time()
     t0 = time.perf_counter()
     while True:
-        orc.tensorized_attention_forward(q, k, v, w.dims, w.causal)
+        if w.backward:                                  # the oracle's backward runs its own forward first
+            orc.tensorized_attention_backward(q, k, v, d_o, w.dims, w.causal)
+        else:
+            orc.tensorized_attention_forward(q, k, v, w.dims, w.causal)
         heads += 1
         el = time.perf_counter() - t0
         if el + el / heads > target_seconds:
@@ -128,7 +163,8 @@ def cpu_baseline(w, target_seconds):
     return {
         "value": tokens_per_s, "unit": "tokens/s", "cores": max(1, int(round(cpu / wall))),
         "host_cores": len(os.sched_getaffinity(0)), "kind": "oracle",
-        "sample": f"{heads} single-head passes of {w.name} (all {w.seq_len} tokens, all hops; the job has "
+        "sample": f"{heads} single-head passes of {w.name} (all {w.seq_len} tokens, all hops"
+                  f"{', forward + backward' if w.backward else ''}; the job has "
                   f"{w.batch * w.n_q_heads} such heads), {wall:.1f} s wall; scaled by heads",
     }
 
@@ -147,34 +183,48 @@ def main():
         sys.exit(1)
     ta.load_library()                                   # fails loudly when the HIP library is missing
     w = WORKLOADS[args.workload]
-    plan, sets, wsb = make_sets(torch, w, args.rotate)
+    plan, sets, wsb, scb = make_sets(torch, w, args.rotate)
     m = len(w.dims)
 
-    wall = time_steps(torch, ta, plan, sets, wsb, args.steps, args.warmup)
+    wall = time_steps(torch, ta, plan, sets, wsb, scb, w.backward, args.steps, args.warmup)
     ms_per_step = wall / args.steps * 1e3
     tokens_per_s = w.batch * w.seq_len / (wall / args.steps)
 
-    per_hop = time_hops(torch, ta, plan, sets, w, args.steps)
-    hop_bytes = [plan.hop_bytes(plan.hop_axis(pos), ta.TA_VIN_KV if pos == 0 else ta.TA_VIN_O) for pos in range(m)]
-    hop_flops = [plan.hop_flops(plan.hop_axis(pos)) for pos in range(m)]
-    hop_avg = [sum(ts) / len(ts) for ts in per_hop]
+    records = time_hops(torch, ta, plan, sets, w, args.steps)
     hops = []
-    for pos in range(m):
-        axis = plan.hop_axis(pos)
-        gbs = hop_bytes[pos] / hop_avg[pos] / 1e9
-        hops.append({"hop": pos, "axis": axis, "n": w.dims[axis],
-                     "kernel": plan.hop_kernel(axis, ta.TA_VIN_KV if pos == 0 else ta.TA_VIN_O),
-                     "us": round(hop_avg[pos] * 1e6, 2), "algorithmic_bytes": hop_bytes[pos],
-                     "GBps": round(gbs, 1), "frac_of_8TBps": round(gbs / HBM_PEAK_GBS, 4),
-                     "TFLOPs_executed": round(hop_flops[pos] / hop_avg[pos] / 1e12, 1)})
-    # the per-axis attention kernel is the only kernel on the path: all launches, averaged
-    launches = sum(len(ts) for ts in per_hop)
-    avg_bytes = sum(hop_bytes[pos] * len(per_hop[pos]) for pos in range(m)) / launches
-    avg_dur = sum(sum(ts) for ts in per_hop) / launches
-    achieved = avg_bytes / avg_dur / 1e9
-    roofline = {"bound": "hbm", "kernel": hops[-1]["kernel"], "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                "avg_launch_us": round(avg_dur * 1e6, 2), "algorithmic_bytes_per_launch": avg_bytes,
+    groups = {}
+    for d, pos, axis, kind, sec in records:
+        groups.setdefault((d, pos, axis, kind), []).append(sec)
+    kernel_totals = {}                                   # kernel name -> [bytes, seconds, launches]
+    for (d, pos, axis, kind), ts in groups.items():
+        bwd = d == "bwd"
+        nbytes = plan.hop_bytes(axis, kind, bwd, bwd and pos != m - 1)
+        flops = plan.hop_flops(axis, bwd)
+        avg = sum(ts) / len(ts)
+        name = plan.hop_backward_kernel(axis, kind) if bwd else plan.hop_kernel(axis, kind)
+        gbs = nbytes / avg / 1e9
+        hops.append({"pass": d, "hop": pos, "axis": axis, "n": w.dims[axis], "kernel": name, "us": round(avg * 1e6, 2),
+                     "algorithmic_bytes": nbytes, "GBps": round(gbs, 1), "frac_of_8TBps": round(gbs / HBM_PEAK_GBS, 4),
+                     "TFLOPs_executed": round(flops / avg / 1e12, 1)})
+        tot = kernel_totals.setdefault(name, [0.0, 0.0, 0])
+        tot[0] += nbytes * len(ts)
+        tot[1] += sum(ts)
+        tot[2] += len(ts)
+    # roofline of the dominant kernel (most time in the timed region), all its launches averaged
+    dom = max(kernel_totals, key=lambda k_: kernel_totals[k_][1])
+    nb, sec, launches = kernel_totals[dom]
+    achieved = nb / sec / 1e9
+    # HBM bytes per launch from the hardware counters of an earlier rocprofv3 --pmc run of this
+    # command (FETCH_SIZE and WRITE_SIZE, scaled by the copy kernel; see profiles/), when one is stored
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
+    if os.path.exists(tpath):
+        rec = json.load(open(tpath)).get(dom)
+        if rec:
+            traffic = rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"]
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "avg_launch_us": round(sec / launches * 1e6, 2), "algorithmic_bytes_per_launch": nb / launches,
                 "launches_timed": launches, "per_hop": hops}
 
     if args.copy_calibration:
@@ -190,8 +240,9 @@ def main():
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{w.name}: bf16 forward, B={w.batch}, {w.n_q_heads} query / {w.n_kv_heads} kv heads, "
+        "config": {"workload": f"{w.name}: bf16, B={w.batch}, {w.n_q_heads} query / {w.n_kv_heads} kv heads, "
                                f"D={w.head_dim}, N={w.seq_len} as {'x'.join(map(str, w.dims))}, "
+                               f"{'forward + backward, ' if w.backward else ''}"
                                f"{'causal' if w.causal else 'non-causal'}",
                    "rotating_buffer_sets": args.rotate},
         "roofline": roofline,
