@@ -226,6 +226,7 @@ const char* ta_plan_hop_kernel(const ta_plan_t* pl, int axis, int vin) {
         case ta::K_MFMA_BF16_N16: return "mfma_bf16_n16";
         case ta::K_MFMA_BF16_N32: return "mfma_bf16_n32";
         case ta::K_MFMA_BF16_N64: return "mfma_bf16_n64";
+        case ta::K_MFMA_BF16_STREAM: return "mfma_bf16_stream";
     }
     return nullptr;
 }

@@ -50,6 +50,7 @@ enum KernelId : int {
     K_MFMA_BF16_N16 = 1,
     K_MFMA_BF16_N32 = 2,
     K_MFMA_BF16_N64 = 3,
+    K_MFMA_BF16_STREAM = 4,
 };
 
 // Launchers.  Each checks nothing: the API layer has validated shapes against what
@@ -58,6 +59,7 @@ hipError_t launch_generic_forward(const HopParams& p, int dtype, hipStream_t s);
 hipError_t launch_generic_backward(const BwdParams& p, int dtype, hipStream_t s);
 bool       generic_backward_supports(int32_t n, int32_t G, int32_t D);
 hipError_t launch_mfma_forward(const HopParams& p, int kernel_id, hipStream_t s);
+hipError_t launch_mfma_forward_stream(const HopParams& p, hipStream_t s);
 bool       mfma_forward_supports(int32_t n, int32_t D, int dtype, int* kernel_id);
 bool       mfma_forward_layout_ok(const HopParams& p);   // strides and sizes fit the kernel's 32-bit row offsets
 bool       mfma_backward_supports(const BwdParams& bp, int dtype);

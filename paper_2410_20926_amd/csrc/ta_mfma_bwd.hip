@@ -34,55 +34,6 @@ struct BGeo : Geo<D> {
     static constexpr int kRedBytes = Geo<D>::kDTiles * 16 * 64 * 4;   // one fp32 accumulator set, lane-major
 };
 
-// rows of the tile this lane gets from a transposed read: see read_transposed()
-template <int D>
-__device__ inline void stage_rows(char* stg, const u32x4 (&raw)[Geo<D>::kPasses]) {
-#pragma unroll
-    for (int i = 0; i < Geo<D>::kPasses; ++i)
-        *reinterpret_cast<u32x4*>(stg + i * Geo<D>::kRowsPerPass * Geo<D>::kPitch) = raw[i];
-}
-
-// Operand whose contraction index is the feature: lane (row r32, half hf) reads 8 features
-// per 16-wide MFMA step.  Serves as A (rows = tile rows) or B (columns = tile rows).
-template <int D>
-__device__ inline void read_natural(const char* oprd, u32x4 (&op)[Geo<D>::kKSteps]) {
-#pragma unroll
-    for (int s = 0; s < Geo<D>::kKSteps; ++s) op[s] = *reinterpret_cast<const u32x4*>(oprd + s * 32);
-}
-
-// Operand whose contraction index is the tile row: for feature tile t and 16-row step s2,
-// lane (feature 32 t + lane % 32, half hf) gets rows 16 s2 + 8 u + 4 hf + (0..3), u = 0, 1.
-// ds_read_b64_tr_b16 works on groups of 16 lanes: lane L of a group supplies the address
-// of 4 consecutive features of row (L / 4), at feature offset 4 (L % 4); lane L receives
-// feature L of the group's 16, from the 4 rows.
-template <int D>
-__device__ inline void read_transposed(const char* trbase, u32x4 (&op)[Geo<D>::kDTiles][2]) {
-#pragma unroll
-    for (int t = 0; t < Geo<D>::kDTiles; ++t)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-            const char* a0 = trbase + (16 * s2) * Geo<D>::kPitch + 64 * t;
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a0));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a0 + 8 * Geo<D>::kPitch));
-            const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-            op[t][s2] = u32x4{l2.x, l2.y, h2.x, h2.y};
-        }
-}
-
-// 16 accumulator values of one lane (rows 8 (r/4) + 4 hf + r % 4) -> two B operands.
-__device__ inline void pack_rows(const float (&x)[16], u32x4 (&op)[2]) {
-#pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2)
-        op[s2] = u32x4{pack_bf16x2(x[8 * s2 + 0], x[8 * s2 + 1]), pack_bf16x2(x[8 * s2 + 2], x[8 * s2 + 3]),
-                       pack_bf16x2(x[8 * s2 + 4], x[8 * s2 + 5]), pack_bf16x2(x[8 * s2 + 6], x[8 * s2 + 7])};
-}
-
-__device__ inline uint32_t range_mask(int lo, int hi) {   // bits [lo, hi), 0 <= lo, hi <= 32
-    const uint32_t mh = hi >= 32 ? 0xffffffffu : ((1u << hi) - 1u);
-    const uint32_t ml = lo >= 32 ? 0xffffffffu : ((1u << lo) - 1u);
-    return mh & ~ml;
-}
-
 // acc[t][r] holds (row = lane % 32, feature 32 t + 8 (r/4) + 4 hf + r % 4).  Multiplies by
 // `mult`, optionally adds the tensor's current contents, rounds to bf16 and stores the
 // rows with 16-byte stores; the transposition goes through LDS in fp32, 64 features at a time.

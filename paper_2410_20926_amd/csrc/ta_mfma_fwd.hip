@@ -306,12 +306,14 @@ bool mfma_forward_supports(int32_t n, int32_t D, int dtype, int* kernel_id) {
     if (dtype == TA_BF16 && (D == 64 || D == 128) && n >= 1) {
         if (n <= 32) kid = K_MFMA_BF16_N32;
         else if (n <= 64) kid = K_MFMA_BF16_N64;
+        else kid = K_MFMA_BF16_STREAM;
     }
     if (kernel_id) *kernel_id = kid;
     return kid != K_GENERIC;
 }
 
 hipError_t launch_mfma_forward(const HopParams& p, int kernel_id, hipStream_t s) {
+    if (kernel_id == K_MFMA_BF16_STREAM) return launch_mfma_forward_stream(p, s);
     const int KT = kernel_id == K_MFMA_BF16_N32 ? 1 : (kernel_id == K_MFMA_BF16_N64 ? 2 : 0);
     if (KT == 0 || p.n < 1 || p.n > kTile * KT || (p.D != 64 && p.D != 128) || !mfma_forward_layout_ok(p))
         return hipErrorInvalidValue;

@@ -1,0 +1,220 @@
+// bf16 MFMA per-axis attention forward for LONG axes (any axis length; used above 64) on
+// gfx950: one hop of Eq. 4 of arXiv 2410.20926 with the keys of a fibre streamed in tiles
+// of 32 and an online (running max / running sum) softmax, so that registers and LDS do not
+// grow with the axis length.  The paper's own extrapolation recipe (Sec. 4.3) lengthens
+// the first axis of a {32,32,32} model to reach 128k tokens; this kernel covers those axes.
+//
+// Work unit: 32 query rows of one fibre of one query head, one wavefront, no workgroup
+// barrier.  Per 32-key tile: K tile -> LDS -> A operand, S^T = K Q^T, mask, running
+// max/sum update, probabilities rounded to bf16 as the B operand, V tile -> LDS ->
+// transposed read (ds_read_b64_tr_b16) as the A operand, O^T = corr * O^T + V^T P^T.
+// The loads of tile j + 1 are issued as soon as tile j has left its registers.
+#include "ta_mfma_common.h"
+
+namespace ta {
+namespace {
+
+using namespace mfma;
+
+constexpr int kWavesPerBlock = 4;
+
+struct StreamParams {
+    uint32_t qtiles;          // 32-row query tiles per fibre = ceil(n / 32)
+    uint32_t tiles;           // fibres * qtiles
+    uint32_t tiles_lo, tiles_hi;
+    uint32_t q_row, k_row, v_row, o_row;       // token pitch in bytes
+    uint32_t q_step, k_step, v_step, o_step;   // bytes between neighbouring rows of a fibre (stride * token pitch)
+};
+
+template <int D>
+__global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel(HopParams p, StreamParams sp) {
+    using G = Geo<D>;
+    constexpr int kBuf = kTile * G::kPitch;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = blockIdx.x * kWavesPerBlock + w;
+    const uint32_t zb = blockIdx.z / sp.tiles_hi;
+    const uint32_t tt = (blockIdx.z - zb * sp.tiles_hi) * sp.tiles_lo + blockIdx.y;
+    if (h >= p.Hq || tt >= sp.tiles) return;              // no workgroup barrier below
+    const int b = (int)zb;
+    const int g = h / p.G;
+    const int hv = (p.vin_heads == p.Hq) ? h : g;
+    const int n = p.n;
+    char* buf = smem + w * kBuf;
+
+    // heavier (later) query tiles of a fibre first: under the causal mask tile qt walks qt + 1 key tiles
+    const uint32_t f = tt / sp.qtiles;
+    const int qt = (int)(sp.qtiles - 1 - (tt - f * sp.qtiles));
+    const uint32_t stride = (uint32_t)p.stride;
+    const uint32_t outer = f / stride;
+    const uint32_t tok0 = outer * stride * n + (f - outer * stride);       // first token of the fibre
+
+    const char* qb = reinterpret_cast<const char*>(p.q.p) + ((int64_t)b * p.q.sb + (int64_t)h * p.q.sh) * 2 + tok0 * sp.q_row;
+    const char* kb = reinterpret_cast<const char*>(p.k.p) + ((int64_t)b * p.k.sb + (int64_t)g * p.k.sh) * 2 + tok0 * sp.k_row;
+    const char* vb = reinterpret_cast<const char*>(p.vin.p) + ((int64_t)b * p.vin.sb + (int64_t)hv * p.vin.sh) * 2 + tok0 * sp.v_row;
+    char* ob = reinterpret_cast<char*>(p.o.p) + ((int64_t)b * p.o.sb + (int64_t)h * p.o.sh) * 2 + tok0 * sp.o_row;
+
+    const int lrow = lane / G::kChunks, lcol = lane % G::kChunks;
+    const uint32_t lbyte = lcol * 16;
+    const int r32 = lane & 31, hf = lane >> 5;
+    const int ktiles = (n + kTile - 1) / kTile;
+    const int jend = p.causal ? qt + 1 : ktiles;
+
+    // rows past the end of the fibre alias its last row: loads need no predicate
+    u32x4 qreg[G::kPasses], kreg[G::kPasses], vreg[G::kPasses];
+    uint32_t ooff[G::kPasses];
+#pragma unroll
+    for (int i = 0; i < G::kPasses; ++i) {
+        const uint32_t rq = (uint32_t)min(qt * kTile + i * G::kRowsPerPass + lrow, n - 1);
+        const uint32_t rk = (uint32_t)min(i * G::kRowsPerPass + lrow, n - 1);
+        qreg[i] = *reinterpret_cast<const u32x4*>(qb + (rq * sp.q_step + lbyte));
+        kreg[i] = *reinterpret_cast<const u32x4*>(kb + (rk * sp.k_step + lbyte));
+        vreg[i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
+        ooff[i] = rq * sp.o_step + lbyte;
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    char* stg = buf + lrow * G::kPitch + lbyte;
+    const char* oprd = buf + r32 * G::kPitch + hf * 16;
+    const char* trbase = buf + (4 * hf + ((lane & 15) >> 2)) * G::kPitch + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+
+    u32x4 qop[G::kKSteps];
+    stage_rows<D>(stg, qreg);
+    lds_wave_sync();
+    read_natural<D>(oprd, qop);
+    lds_wave_sync();
+
+    const int qrow = qt * kTile + r32;                    // this lane's query row in the fibre
+    const int khi = qrow < n ? (p.causal ? qrow + 1 : n) : 0;              // it sees keys [0, khi)
+    const float sl2 = p.scale * kLog2e;
+    float m = -INFINITY, l = 0.f;
+    f32x16 ot[G::kDTiles];
+#pragma unroll
+    for (int t = 0; t < G::kDTiles; ++t) ot[t] = f32x16{};
+
+    for (int j = 0; j < jend; ++j) {
+        // ---- K tile j: LDS transit, then request tile j + 1 into the same registers ------
+        u32x4 kop[G::kKSteps];
+        stage_rows<D>(stg, kreg);
+        lds_wave_sync();
+        read_natural<D>(oprd, kop);
+        lds_wave_sync();
+        if (j + 1 < jend) {
+#pragma unroll
+            for (int i = 0; i < G::kPasses; ++i) {
+                const uint32_t rk = (uint32_t)min((j + 1) * kTile + i * G::kRowsPerPass + lrow, n - 1);
+                kreg[i] = *reinterpret_cast<const u32x4*>(kb + (rk * sp.k_step + lbyte));
+            }
+        }
+        f32x16 st = {};
+#pragma unroll
+        for (int s = 0; s < G::kKSteps; ++s) st = mma(kop[s], qop[s], st);
+
+        // ---- mask, running max and sum ------------------------------------------------------
+        const uint32_t vis = range_mask(0, min(max(khi - kTile * j, 0), kTile)) >> (4 * hf);
+        float e[16], tmax = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const bool ok = (vis >> (8 * (r / 4) + (r % 4))) & 1u;
+            e[r] = ok ? st[r] * sl2 : -INFINITY;
+            tmax = fmaxf(tmax, e[r]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float mnew = fmaxf(m, tmax);
+        const float msafe = mnew == -INFINITY ? 0.f : mnew;
+        const float corr = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - msafe);
+        m = mnew;
+        u32x4 pop[2];
+        float psum = 0.f;
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            uint32_t wds[4];
+#pragma unroll
+            for (int jp = 0; jp < 4; ++jp) {
+                const int r = 8 * s2 + 2 * jp;
+                const uint32_t pk = pack_bf16x2(__builtin_amdgcn_exp2f(e[r] - msafe), __builtin_amdgcn_exp2f(e[r + 1] - msafe));
+                psum += bf16_lo(pk) + bf16_hi(pk);        // sum of the ROUNDED weights
+                wds[jp] = pk;
+            }
+            pop[s2] = u32x4{wds[0], wds[1], wds[2], wds[3]};
+        }
+        psum += __shfl_xor(psum, 32);
+        l = l * corr + psum;
+
+        // ---- V tile j: LDS transit, transposed operands, then request tile j + 1 ------------
+        u32x4 vT[G::kDTiles][2];
+        stage_rows<D>(stg, vreg);
+        lds_wave_sync();
+        read_transposed<D>(trbase, vT);
+        lds_wave_sync();
+        if (j + 1 < jend) {
+#pragma unroll
+            for (int i = 0; i < G::kPasses; ++i) {
+                const uint32_t rk = (uint32_t)min((j + 1) * kTile + i * G::kRowsPerPass + lrow, n - 1);
+                vreg[i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < G::kDTiles; ++t) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) ot[t][r] *= corr;
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) ot[t] = mma(vT[t][s2], pop[s2], ot[t]);
+        }
+    }
+
+    // ---- normalise, round, transpose through LDS, store -------------------------------------
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+#pragma unroll
+    for (int t = 0; t < G::kDTiles; ++t)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            u32x2 v;
+            v.x = pack_bf16x2(ot[t][4 * q4] * inv, ot[t][4 * q4 + 1] * inv);
+            v.y = pack_bf16x2(ot[t][4 * q4 + 2] * inv, ot[t][4 * q4 + 3] * inv);
+            *reinterpret_cast<u32x2*>(buf + r32 * G::kPitch + (32 * t + 8 * q4 + 4 * hf) * 2) = v;
+        }
+    lds_wave_sync();
+#pragma unroll
+    for (int i = 0; i < G::kPasses; ++i) {
+        const int row = qt * kTile + i * G::kRowsPerPass + lrow;
+        if (row < n) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
+            *reinterpret_cast<u32x4*>(ob + ooff[i]) = v;
+        }
+    }
+}
+
+template <int D>
+hipError_t launch(const HopParams& p, const StreamParams& sp, hipStream_t s) {
+    const size_t smem = (size_t)kWavesPerBlock * kTile * Geo<D>::kPitch;
+    const dim3 grid((unsigned)((p.Hq + kWavesPerBlock - 1) / kWavesPerBlock), sp.tiles_lo, (unsigned)p.B * sp.tiles_hi);
+    hipLaunchKernelGGL((mfma_fwd_stream_kernel<D>), grid, dim3(kWavesPerBlock * 64), smem, s, p, sp);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_mfma_forward_stream(const HopParams& p, hipStream_t s) {
+    if (p.n < 1 || (p.D != 64 && p.D != 128) || !mfma_forward_layout_ok(p)) return hipErrorInvalidValue;
+    StreamParams sp;
+    sp.qtiles = (uint32_t)((p.n + kTile - 1) / kTile);
+    const int64_t tiles = p.fibres * sp.qtiles;
+    if (tiles <= 0 || tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    sp.tiles = (uint32_t)tiles;
+    sp.tiles_lo = (uint32_t)(tiles < 32768 ? tiles : 32768);
+    sp.tiles_hi = (uint32_t)((tiles + sp.tiles_lo - 1) / sp.tiles_lo);
+    if ((int64_t)p.B * sp.tiles_hi > 65535) return hipErrorInvalidValue;
+    sp.q_row = (uint32_t)(p.q.st * 2);
+    sp.k_row = (uint32_t)(p.k.st * 2);
+    sp.v_row = (uint32_t)(p.vin.st * 2);
+    sp.o_row = (uint32_t)(p.o.st * 2);
+    sp.q_step = (uint32_t)(p.stride * p.q.st * 2);
+    sp.k_step = (uint32_t)(p.stride * p.k.st * 2);
+    sp.v_step = (uint32_t)(p.stride * p.vin.st * 2);
+    sp.o_step = (uint32_t)(p.stride * p.o.st * 2);
+    return p.D == 128 ? launch<128>(p, sp, s) : launch<64>(p, sp, s);
+}
+
+}  // namespace ta

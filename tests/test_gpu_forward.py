@@ -50,8 +50,12 @@ CASES = [
     ((32, 32), 2, 8, 2, 128, False, "bf16", 1.0),
     ((64, 32), 1, 4, 1, 128, True, "bf16", 1.0),
     ((16, 64), 1, 2, 2, 64, True, "bf16", 1.0),
-    ((7, 48, 5), 1, 2, 1, 64, True, "bf16", 1.0),      # shapes no MFMA kernel takes
-    ((130,), 1, 2, 2, 128, False, "bf16", 1.0),
+    ((7, 48, 5), 1, 2, 1, 64, True, "bf16", 1.0),      # ragged tiles: 4 fibres of 7, one padded 48-row fibre, 6 fibres of 5
+    ((130,), 1, 2, 2, 128, False, "bf16", 1.0),        # streaming kernel, ragged last key tile
+    ((130,), 1, 2, 1, 128, True, "bf16", 1.0),
+    ((128, 4, 2), 1, 4, 1, 128, True, "bf16", 1.0),    # extrapolated first axis (Sec. 4.3), strided
+    ((3, 97), 2, 2, 2, 64, True, "bf16", 1.0),
+    ((257,), 1, 1, 1, 64, False, "bf16", 1.0),
 ]
 
 
