@@ -34,12 +34,32 @@ struct BGeo : Geo<D> {
     static constexpr int kRedBytes = Geo<D>::kDTiles * 16 * 64 * 4;   // one fp32 accumulator set, lane-major
 };
 
+// The epilogue's lane -> (row, 16-byte chunk) mapping: pass i of feature half `half` covers
+// row 8 i + lane / 8, chunk lane % 8 of the half (8 lanes x 16 B = 128 contiguous bytes).
+template <int D>
+__device__ inline uint32_t tile_out_offset(const u32x4* rowoff, int which, int half, int i, int lane) {
+    const u32x4 off4 = rowoff[8 * i + (lane >> 3)];
+    return (which == 0 ? off4.x : which == 1 ? off4.y : off4.z) + (half * 64 + (lane & 7) * 8) * 2;
+}
+
+// Requests the current contents of an output tile (for accumulate = 1) long before the
+// epilogue needs them, in the epilogue's mapping.
+template <int D>
+__device__ inline void prefetch_tile(u32x4 (&old)[Geo<D>::kDTiles * 2], const u32x4* rowoff, int which, const char* gbase, int lane) {
+#pragma unroll
+    for (int half = 0; half < Geo<D>::kDTiles / 2; ++half)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            old[half * 4 + i] = *reinterpret_cast<const u32x4*>(gbase + tile_out_offset<D>(rowoff, which, half, i, lane));
+}
+
 // acc[t][r] holds (row = lane % 32, feature 32 t + 8 (r/4) + 4 hf + r % 4).  Multiplies by
-// `mult`, optionally adds the tensor's current contents, rounds to bf16 and stores the
-// rows with 16-byte stores; the transposition goes through LDS in fp32, 64 features at a time.
+// `mult`, optionally adds the tensor's previous contents (`old`, from prefetch_tile), rounds
+// to bf16 and stores the rows with 16-byte stores; the transposition goes through LDS in
+// fp32, 64 features at a time.
 template <int D>
 __device__ inline void store_tile(const f32x16 (&acc)[Geo<D>::kDTiles], float mult, char* buf, const u32x4* rowoff,
-                                  int which, char* gbase, bool accumulate, int rows_valid, int lane) {
+                                  int which, char* gbase, const u32x4 (&old)[Geo<D>::kDTiles * 2], bool add_old, int rows_valid, int lane) {
     using G = BGeo<D>;
     const int r32 = lane & 31, hf = lane >> 5;
 #pragma unroll
@@ -55,20 +75,18 @@ __device__ inline void store_tile(const f32x16 (&acc)[Geo<D>::kDTiles], float mu
         lds_wave_sync();
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int row = 8 * i + (lane >> 3), cc = lane & 7;        // 8 lanes x 16 B = 128 B of one row
+            const int row = 8 * i + (lane >> 3), cc = lane & 7;
             const f32x4 x0 = *reinterpret_cast<const f32x4*>(buf + row * G::kFPitch + cc * 32);
             const f32x4 x1 = *reinterpret_cast<const f32x4*>(buf + row * G::kFPitch + cc * 32 + 16);
-            const u32x4 off4 = rowoff[row];
-            const uint32_t off = (which == 0 ? off4.x : which == 1 ? off4.y : off4.z) + (half * 64 + cc * 8) * 2;
             if (row < rows_valid) {
                 float y[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
-                u32x4* dst = reinterpret_cast<u32x4*>(gbase + off);
-                if (accumulate) {
-                    const u32x4 old = *dst;
+                if (add_old) {
+                    const u32x4 o = old[half * 4 + i];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { y[2 * e] += bf16_lo(old[e]); y[2 * e + 1] += bf16_hi(old[e]); }
+                    for (int e = 0; e < 4; ++e) { y[2 * e] += bf16_lo(o[e]); y[2 * e + 1] += bf16_hi(o[e]); }
                 }
-                *dst = u32x4{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])};
+                *reinterpret_cast<u32x4*>(gbase + tile_out_offset<D>(rowoff, which, half, i, lane)) =
+                    u32x4{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])};
             }
         }
         lds_wave_sync();
@@ -214,6 +232,10 @@ __global__ __launch_bounds__(256, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
         dpN = mma(gop[s], xop[s], dpN);
     }
 
+    // previous dQ (accumulate): requested now, consumed after the dQ products
+    u32x4 oldq[G::kDTiles * 2] = {};
+    if (bp.accumulate) prefetch_tile<D>(oldq, rowoff, 0, dqb, lane);
+
     // ---- softmax and dS, one query row per lane -------------------------------------------
     const float sl2 = p.scale * kLog2e;
     int flo = 0, fhi = 0;                                 // this lane's row's fibre occupies tile rows [flo, fhi)
@@ -281,7 +303,7 @@ __global__ __launch_bounds__(256, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) acc[t] = mma(kT[t][s2], dsTop[s2], acc[t]);
     }
-    store_tile<D>(acc, p.scale, buf, rowoff, 0, dqb, bp.accumulate != 0, rows_valid, lane);
+    store_tile<D>(acc, p.scale, buf, rowoff, 0, dqb, oldq, bp.accumulate != 0, rows_valid, lane);
 
     // ---- dX^T = G^T P : per head, or summed over the group when the value input is V ------
 #pragma unroll
@@ -291,11 +313,14 @@ __global__ __launch_bounds__(256, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
         for (int s2 = 0; s2 < 2; ++s2) acc[t] = mma(gT[t][s2], pNop[s2], acc[t]);
     }
     if (vin_is_o) {
-        store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, false, rows_valid, lane);
+        store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, oldq, false, rows_valid, lane);
     } else {
         chain_sum<D>(acc, red, w, nw, lane);
-        if (w == nw - 1) store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, false, rows_valid, lane);
+        if (w == nw - 1) store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, oldq, false, rows_valid, lane);
     }
+    // previous dK (accumulate): only the wave that ends up with the group's sum needs it
+    u32x4 oldk[G::kDTiles * 2] = {};
+    if (bp.accumulate && w == nw - 1) prefetch_tile<D>(oldk, rowoff, 1, dkb, lane);
 
     // ---- dK^T = Q^T dS : summed over the group ----------------------------------------------
 #pragma unroll
@@ -305,7 +330,7 @@ __global__ __launch_bounds__(256, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
         for (int s2 = 0; s2 < 2; ++s2) acc[t] = mma(qT[t][s2], dsNop[s2], acc[t]);
     }
     chain_sum<D>(acc, red, w, nw, lane);
-    if (w == nw - 1) store_tile<D>(acc, p.scale, buf, rowoff, 1, dkb, bp.accumulate != 0, rows_valid, lane);
+    if (w == nw - 1) store_tile<D>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.accumulate != 0, rows_valid, lane);
 }
 
 template <int D>
