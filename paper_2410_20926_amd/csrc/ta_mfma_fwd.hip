@@ -285,6 +285,238 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Group-shared variant, for grouped-query heads with 4 (or a multiple of 4) query heads per
+// key/value head: the 4 waves of a workgroup are 4 query heads of ONE group working on the
+// same rows, so the K tile (and the V tile, when the value input is V) is fetched ONCE per
+// workgroup - each wave loads a quarter of its rows - into a shared row-major LDS tile, and
+// every wave reads its MFMA operands from there (K: row reads; V: ds_read_b64_tr_b16).
+// This quarters the K/V traffic between L2 and the compute unit; a per-head value input
+// (a previous O) still goes through the wave's private transit tile.
+template <int D, int KT>
+__global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel(HopParams p, TileParams tp) {
+    using G = Geo<D>;
+    constexpr int kRows = kTile * KT;
+    constexpr int kTileBytes = kTile * G::kPitch;                           // one row-major 32-row tile
+    constexpr int kWaveBytes = kTileBytes + kRows * 16;                     // private transit tile + row table
+    constexpr int kShare = G::kPasses / kWavesPerBlock;                     // load passes per wave per shared tile
+    static_assert(G::kPasses % kWavesPerBlock == 0, "a shared tile must split evenly over the waves");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+
+    const int h = blockIdx.x * kWavesPerBlock + w;                          // host guarantees Hq % 4 == 0 and G % 4 == 0
+    const uint32_t zb = blockIdx.z / tp.tiles_hi;
+    const uint32_t tt = (blockIdx.z - zb * tp.tiles_hi) * tp.tiles_lo + blockIdx.y;
+    if (tt >= tp.tiles) return;                                             // the whole workgroup leaves together
+    const int b = (int)zb;
+    const int g = h / p.G;
+    const bool v_shared = (p.vin_heads != p.Hq);
+    const int hv = v_shared ? g : h;
+    const int n = p.n;
+
+    char* sK = smem;                                                        // [KT] shared K tiles
+    char* sV = smem + KT * kTileBytes;                                      // [KT] shared V tiles (only when v_shared)
+    char* buf = smem + 2 * KT * kTileBytes + w * kWaveBytes;
+    u32x4* rowoff = reinterpret_cast<u32x4*>(buf + kTileBytes);
+
+    uint32_t f0;
+    int qt, rows_valid;
+    if (KT == 1) {
+        f0 = tt * tp.fpt;
+        qt = 0;
+        rows_valid = (int)min((uint32_t)tp.fpt, (uint32_t)p.fibres - f0) * n;
+    } else {
+        f0 = tt / tp.qtiles;
+        qt = (int)(tt - f0 * tp.qtiles);
+        rows_valid = n;
+    }
+    {
+        const uint32_t stride = (uint32_t)p.stride;
+        for (int r = lane; r < kRows; r += 64) {
+            const int rc = min(r, rows_valid - 1);
+            const uint32_t fi = (KT == 1) ? (uint32_t)((rc + 0.5f) * tp.inv_n) : 0u;
+            const uint32_t a = rc - fi * n;
+            const uint32_t f = f0 + fi;
+            const uint32_t outer = f / stride;
+            const uint32_t tok = outer * stride * n + (f - outer * stride) + a * stride;
+            rowoff[r] = u32x4{tok * tp.q_row, tok * tp.k_row, tok * tp.v_row, tok * tp.o_row};
+        }
+    }
+    lds_wave_sync();
+
+    const char* qb = reinterpret_cast<const char*>(p.q.p) + ((int64_t)b * p.q.sb + (int64_t)h * p.q.sh) * 2;
+    const char* kb = reinterpret_cast<const char*>(p.k.p) + ((int64_t)b * p.k.sb + (int64_t)g * p.k.sh) * 2;
+    const char* vb = reinterpret_cast<const char*>(p.vin.p) + ((int64_t)b * p.vin.sb + (int64_t)hv * p.vin.sh) * 2;
+    char* ob = reinterpret_cast<char*>(p.o.p) + ((int64_t)b * p.o.sb + (int64_t)h * p.o.sh) * 2;
+
+    const int lrow = lane / G::kChunks, lcol = lane % G::kChunks;
+    const uint32_t lbyte = lcol * 16;
+    const int kt_end = (KT == 1) ? 1 : (p.causal ? qt + 1 : (n > kTile ? 2 : 1));
+
+    // ---- gather: Q (private), this wave's quarter of every K tile, and V: its quarter of
+    //      every shared tile, or its own tiles when the value input is per head -------------
+    u32x4 qreg[G::kPasses], ksh[KT][kShare], vsh[KT][kShare], vreg[KT][G::kPasses];
+    uint32_t ooff[G::kPasses];
+#pragma unroll
+    for (int i = 0; i < G::kPasses; ++i) {
+        const u32x4 off = rowoff[qt * kTile + i * G::kRowsPerPass + lrow];
+        qreg[i] = *reinterpret_cast<const u32x4*>(qb + (off.x + lbyte));
+        ooff[i] = off.w + lbyte;
+    }
+#pragma unroll
+    for (int j = 0; j < KT; ++j) {
+        if (j < kt_end) {
+#pragma unroll
+            for (int i = 0; i < kShare; ++i) {
+                const u32x4 off = rowoff[j * kTile + (w * kShare + i) * G::kRowsPerPass + lrow];
+                ksh[j][i] = *reinterpret_cast<const u32x4*>(kb + (off.y + lbyte));
+                if (v_shared) vsh[j][i] = *reinterpret_cast<const u32x4*>(vb + (off.z + lbyte));
+            }
+            if (!v_shared) {
+#pragma unroll
+                for (int i = 0; i < G::kPasses; ++i) {
+                    const u32x4 off = rowoff[j * kTile + i * G::kRowsPerPass + lrow];
+                    vreg[j][i] = *reinterpret_cast<const u32x4*>(vb + (off.z + lbyte));
+                }
+            }
+        }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    const int r32 = lane & 31, hf = lane >> 5;
+    char* stg = buf + lrow * G::kPitch + lbyte;
+    const int opoff = r32 * G::kPitch + hf * 16;                            // natural operand read offset in a tile
+    const int troff = (4 * hf + ((lane & 15) >> 2)) * G::kPitch + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+
+    // ---- this wave's quarter of the shared tiles -> LDS; Q through the private tile -------
+#pragma unroll
+    for (int j = 0; j < KT; ++j) {
+        if (j < kt_end) {
+#pragma unroll
+            for (int i = 0; i < kShare; ++i) {
+                const int rowb = ((w * kShare + i) * G::kRowsPerPass + lrow) * G::kPitch + lbyte;
+                *reinterpret_cast<u32x4*>(sK + j * kTileBytes + rowb) = ksh[j][i];
+                if (v_shared) *reinterpret_cast<u32x4*>(sV + j * kTileBytes + rowb) = vsh[j][i];
+            }
+        }
+    }
+    u32x4 qop[G::kKSteps];
+    stage_rows<D>(stg, qreg);
+    lds_wave_sync();
+    read_natural<D>(buf + opoff, qop);
+    __syncthreads();                                                        // shared tiles complete
+
+    // ---- S^T = K Q^T per key tile -----------------------------------------------------------
+    f32x16 st[KT];
+#pragma unroll
+    for (int j = 0; j < KT; ++j) {
+        st[j] = f32x16{};
+        if (j < kt_end) {
+            u32x4 kop[G::kKSteps];
+            read_natural<D>(sK + j * kTileBytes + opoff, kop);
+#pragma unroll
+            for (int s = 0; s < G::kKSteps; ++s) st[j] = mma(kop[s], qop[s], st[j]);
+        }
+    }
+
+    // ---- masked row softmax over all key tiles -------------------------------------------------
+    const int qrow = qt * kTile + r32;
+    int lo = 0, hi = 0;                                                     // visible keys = [lo, hi)
+    if (qrow < rows_valid) {
+        if (KT == 1) {
+            lo = (int)((qrow + 0.5f) * tp.inv_n) * n;
+            hi = p.causal ? qrow + 1 : lo + n;
+        } else {
+            hi = p.causal ? qrow + 1 : n;
+        }
+    }
+    const float sl2 = p.scale * kLog2e;
+    float mx = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < KT; ++j) {
+        const uint32_t vis = range_mask(min(max(lo - 32 * j, 0), 32), min(max(hi - 32 * j, 0), 32)) >> (4 * hf);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const bool ok = (vis >> (8 * (r / 4) + (r % 4))) & 1u;
+            st[j][r] = ok ? st[j][r] * sl2 : -INFINITY;
+            mx = fmaxf(mx, st[j][r]);
+        }
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    if (mx == -INFINITY) mx = 0.f;
+    u32x4 pop[KT][2];
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < KT; ++j)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            uint32_t wds[4];
+#pragma unroll
+            for (int jp = 0; jp < 4; ++jp) {
+                const int r = 8 * s2 + 2 * jp;
+                const uint32_t pk = pack_bf16x2(__builtin_amdgcn_exp2f(st[j][r] - mx), __builtin_amdgcn_exp2f(st[j][r + 1] - mx));
+                sum += bf16_lo(pk) + bf16_hi(pk);                           // sum of the ROUNDED weights
+                wds[jp] = pk;
+            }
+            pop[j][s2] = u32x4{wds[0], wds[1], wds[2], wds[3]};
+        }
+    sum += __shfl_xor(sum, 32);
+    const float inv = sum > 0.f ? 1.f / sum : 0.f;
+
+    // ---- O^T = V^T P^T per key tile ---------------------------------------------------------------
+    f32x16 ot[G::kDTiles];
+#pragma unroll
+    for (int t = 0; t < G::kDTiles; ++t) ot[t] = f32x16{};
+#pragma unroll
+    for (int j = 0; j < KT; ++j) {
+        if (j < kt_end) {
+            u32x4 vT[G::kDTiles][2];
+            if (v_shared) {
+                read_transposed<D>(sV + j * kTileBytes + troff, vT);
+            } else {
+                lds_wave_sync();
+                stage_rows<D>(stg, vreg[j]);
+                lds_wave_sync();
+                read_transposed<D>(buf + troff, vT);
+            }
+#pragma unroll
+            for (int t = 0; t < G::kDTiles; ++t)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) ot[t] = mma(vT[t][s2], pop[j][s2], ot[t]);
+        }
+    }
+    lds_wave_sync();
+
+    // ---- normalise, round, transpose through the private tile, store ---------------------------------
+#pragma unroll
+    for (int t = 0; t < G::kDTiles; ++t)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            u32x2 v;
+            v.x = pack_bf16x2(ot[t][4 * q4] * inv, ot[t][4 * q4 + 1] * inv);
+            v.y = pack_bf16x2(ot[t][4 * q4 + 2] * inv, ot[t][4 * q4 + 3] * inv);
+            *reinterpret_cast<u32x2*>(buf + r32 * G::kPitch + (32 * t + 8 * q4 + 4 * hf) * 2) = v;
+        }
+    lds_wave_sync();
+#pragma unroll
+    for (int i = 0; i < G::kPasses; ++i) {
+        const int row = qt * kTile + i * G::kRowsPerPass + lrow;
+        if (row < rows_valid) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
+            *reinterpret_cast<u32x4*>(ob + ooff[i]) = v;
+        }
+    }
+}
+
+template <int D, int KT>
+hipError_t launch_shared(const HopParams& p, const TileParams& tp, hipStream_t s) {
+    const size_t smem = (size_t)2 * KT * kTile * Geo<D>::kPitch + (size_t)kWavesPerBlock * (kTile * Geo<D>::kPitch + kTile * KT * 16);
+    const dim3 grid((unsigned)(p.Hq / kWavesPerBlock), tp.tiles_lo, (unsigned)p.B * tp.tiles_hi);
+    hipLaunchKernelGGL((mfma_fwd_shared_kernel<D, KT>), grid, dim3(kWavesPerBlock * 64), smem, s, p, tp);
+    return hipGetLastError();
+}
+
 template <int D, int KT>
 hipError_t launch(const HopParams& p, const TileParams& tp, hipStream_t s) {
     const size_t smem = (size_t)kWavesPerBlock * (Geo<D>::kBufBytes + kTile * KT * 16);
@@ -319,6 +551,10 @@ hipError_t launch_mfma_forward(const HopParams& p, int kernel_id, hipStream_t s)
         return hipErrorInvalidValue;
     TileParams tp;
     if (!make_tile_params(p, KT, &tp)) return hipErrorInvalidValue;
+    if (p.G % kWavesPerBlock == 0) {                   // 4 query heads of a workgroup share their key/value head
+        if (p.D == 128) return KT == 1 ? launch_shared<128, 1>(p, tp, s) : launch_shared<128, 2>(p, tp, s);
+        return KT == 1 ? launch_shared<64, 1>(p, tp, s) : launch_shared<64, 2>(p, tp, s);
+    }
     if (p.D == 128) return KT == 1 ? launch<128, 1>(p, tp, s) : launch<128, 2>(p, tp, s);
     return KT == 1 ? launch<64, 1>(p, tp, s) : launch<64, 2>(p, tp, s);
 }
