@@ -34,11 +34,16 @@ def parse_args():
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
     ap.add_argument("--rotate", type=int, default=3, help="independent buffer sets cycled through, so that the "
                     "256 MB Infinity Cache cannot serve one step's re-reads from the previous step")
+    ap.add_argument("--also", default=None, help="comma-separated further workloads measured in the same run and "
+                    "reported under other_workloads (default: c4,c5 next to c3, none otherwise)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true", help="also launch the plain copy kernel on 1 GiB a few "
                     "times, so that a hardware-counter run of this command has a transfer of known size to scale by")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
-    return ap.parse_args()
+    args = ap.parse_args()
+    if args.also is None:
+        args.also = "c4,c5" if args.workload == "c3" else ""
+    return args
 
 
 def make_sets(torch, w, rotate):
@@ -169,28 +174,17 @@ def cpu_baseline(w, target_seconds):
     }
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build measures one GPU only (every box here has one); run with --gpus 1",
-              file=sys.stderr)
-        sys.exit(2)
-    import torch
-    import paper_2410_20926_amd as ta
-    from paper_2410_20926_amd.workloads import WORKLOADS
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(1)
-    ta.load_library()                                   # fails loudly when the HIP library is missing
-    w = WORKLOADS[args.workload]
+def measure(torch, ta, w, args, steps, warmup):
+    """Times `steps` whole steps and every hop launch of workload `w`; returns
+    (tokens/s, ms per step, roofline record of the dominant kernel)."""
     plan, sets, wsb, scb = make_sets(torch, w, args.rotate)
     m = len(w.dims)
 
-    wall = time_steps(torch, ta, plan, sets, wsb, scb, w.backward, args.steps, args.warmup)
-    ms_per_step = wall / args.steps * 1e3
-    tokens_per_s = w.batch * w.seq_len / (wall / args.steps)
+    wall = time_steps(torch, ta, plan, sets, wsb, scb, w.backward, steps, warmup)
+    ms_per_step = wall / steps * 1e3
+    tokens_per_s = w.batch * w.seq_len / (wall / steps)
 
-    records = time_hops(torch, ta, plan, sets, w, args.steps)
+    records = time_hops(torch, ta, plan, sets, w, steps)
     hops = []
     groups = {}
     for d, pos, axis, kind, sec in records:
@@ -227,6 +221,41 @@ def main():
                 "avg_launch_us": round(sec / launches * 1e6, 2), "algorithmic_bytes_per_launch": nb / launches,
                 "launches_timed": launches, "per_hop": hops}
 
+    del sets
+    torch.cuda.empty_cache()
+    return tokens_per_s, ms_per_step, roofline
+
+
+def describe(w):
+    return (f"{w.name}: bf16, B={w.batch}, {w.n_q_heads} query / {w.n_kv_heads} kv heads, D={w.head_dim}, "
+            f"N={w.seq_len} as {'x'.join(map(str, w.dims))}, {'forward + backward, ' if w.backward else ''}"
+            f"{'causal' if w.causal else 'non-causal'}")
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one GPU only (every box here has one); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2410_20926_amd as ta
+    from paper_2410_20926_amd.workloads import WORKLOADS
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    ta.load_library()                                   # fails loudly when the HIP library is missing
+    w = WORKLOADS[args.workload]
+    tokens_per_s, ms_per_step, roofline = measure(torch, ta, w, args, args.steps, args.warmup)
+    others = {}
+    for name in [x for x in args.also.split(",") if x and x != args.workload]:
+        ow = WORKLOADS[name]
+        tps, ms, rf = measure(torch, ta, ow, args, max(5, args.steps // 2), max(2, args.warmup // 2))
+        others[name] = {"tokens_per_s": tps, "ms_per_step": ms, "workload": describe(ow),
+                        "roofline_kernel": rf["kernel"], "roofline_GBps": rf["achieved"], "roofline_frac": rf["frac"],
+                        "per_hop": [{k_: h_[k_] for k_ in ("pass", "hop", "n", "kernel", "us", "GBps", "frac_of_8TBps")}
+                                    for h_ in rf["per_hop"]]}
+
     if args.copy_calibration:
         nbytes = 1 << 30
         src = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
@@ -240,13 +269,11 @@ def main():
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{w.name}: bf16, B={w.batch}, {w.n_q_heads} query / {w.n_kv_heads} kv heads, "
-                               f"D={w.head_dim}, N={w.seq_len} as {'x'.join(map(str, w.dims))}, "
-                               f"{'forward + backward, ' if w.backward else ''}"
-                               f"{'causal' if w.causal else 'non-causal'}",
-                   "rotating_buffer_sets": args.rotate},
+        "config": {"workload": describe(w), "rotating_buffer_sets": args.rotate},
         "roofline": roofline,
     }
+    if others:
+        out["other_workloads"] = others
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds)
     print(json.dumps(out), flush=True)
