@@ -121,3 +121,54 @@ def test_config5_shape_sampled_groups():
         check_grad(dk[:, :, g:g + 1], rk, w.dtype, f"dk group {g}")
         check_grad(dv[:, :, g:g + 1], rv, w.dtype, f"dv group {g}")
     assert np.isfinite(dq).all() and np.isfinite(dk).all() and np.isfinite(dv).all()
+
+
+def test_backward_is_deterministic_and_leaves_inputs_alone():
+    """No atomics anywhere: two runs give bit-identical gradients; q, k, v, dO are untouched."""
+    dims, B, Hq, Hkv, D = (8, 32, 16), 1, 8, 2, 128
+    N = int(np.prod(dims))
+    q, k, v, d_o = make_inputs(B, N, Hq, Hkv, D, seed=41, dtype="bf16", with_grad=True)
+    _, plan, dev = multihop_forward(q, k, v, dims, "bf16", True, save=True)
+    a = multihop_backward(plan, dev, d_o, "bf16")
+    b = multihop_backward(plan, dev, d_o, "bf16")
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    assert np.array_equal(to_host(dev["q"]), q) and np.array_equal(to_host(dev["k"]), k)
+    assert np.array_equal(to_host(dev["v"]), v)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_backward_strided_head_major_layout(dtype):
+    """Every tensor stored [B, H, N, D]; gradients must match the oracle as in the dense case."""
+    B, Hq, Hkv, D, dims = 2, 4, 2, 64, (6, 32)
+    N = 192
+    q, k, v, d_o = make_inputs(B, N, Hq, Hkv, D, seed=43, dtype=dtype, with_grad=True)
+    rq, rk, rv = orc.tensorized_attention_backward(q, k, v, d_o, dims, True)
+    sq = (Hq * N * D, D, N * D)
+    skv = (Hkv * N * D, D, N * D)
+    plan = ta.ta_plan_create(B, Hq, Hkv, D, dims, ta_dtype(dtype), True, q_strides=sq, kv_strides=skv, o_strides=sq)
+    hm = lambda a: to_dev(np.ascontiguousarray(a.transpose(0, 2, 1, 3)), dtype)
+    tq, tk, tv, tg = hm(q), hm(k), hm(v), hm(d_o)
+    o = torch.empty_like(tq)
+    wsb = plan.workspace_bytes(True)
+    ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda")
+    ta.ta_multihop_forward(plan, tq, tk, tv, o, ws, wsb, True)
+    dq, dk, dv = torch.full_like(tq, float("nan")), torch.full_like(tk, float("nan")), torch.full_like(tv, float("nan"))
+    scb = plan.backward_scratch_bytes()
+    sc = torch.empty(max(scb, 256), dtype=torch.uint8, device="cuda")
+    ta.ta_multihop_backward(plan, tq, tk, tv, tg, ws, wsb, dq, dk, dv, sc, scb)
+    torch.cuda.synchronize()
+    for got, ref, name in ((dq, rq, "dq"), (dk, rk, "dk"), (dv, rv, "dv")):
+        check_grad(to_host(got).transpose(0, 2, 1, 3), ref, dtype, name)
+
+
+def test_backward_reports_unsupported_shapes():
+    """An axis whose row statistics do not fit the generic kernel's LDS budget is refused, not mis-computed."""
+    plan = ta.ta_plan_create(1, 8, 1, 64, (4096, 2), ta.TA_F32, True)
+    assert plan.hop_backward_kernel(0, ta.TA_VIN_KV) == "unsupported"
+    assert plan.hop_backward_kernel(1, ta.TA_VIN_O) == "generic"
+    t = torch.zeros(1, 8192, 8, 64, device="cuda")
+    tk = torch.zeros(1, 8192, 1, 64, device="cuda")
+    with pytest.raises(ta.TaError) as ei:
+        ta.ta_axis_attn_backward(plan, 0, t, tk, tk, ta.TA_VIN_KV, t.clone(), tk.clone(), t.clone(), tk.clone(), False)
+    assert ei.value.name == "TA_ERR_UNSUPPORTED"
