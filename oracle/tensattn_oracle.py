@@ -24,7 +24,11 @@ Readings taken where the paper is silent (all listed in the design notes):
     more step on the first axis adds 1,024 tokens);
   - hops run in Algorithm 1's order, first axis first, unless told otherwise;
   - d under the square root is the per-head feature width;
-  - grouped-query heads: query head h uses key/value head h // (H_q / H_kv).
+  - grouped-query heads: query head h uses key/value head h // (H_q / H_kv);
+  - further per-axis masks M_i (Eq. 3 allows any; Sec. 2.1 mentions sparsity masks): a
+    band of width w_i along axis i (key c visible from row a iff |a - c| < w_i, and
+    c <= a when causal) and padding (tokens at or past `valid_len` are never attended
+    to; their own rows see nothing and come out as zero).
 
 Parity pins (tests/test_oracle_*.py): d=1 against a library attention
 routine, row sums, brute-force N x N Kronecker-form operator built with scalar
@@ -41,6 +45,7 @@ import numpy as np
 
 __all__ = [
     "axis_strides",
+    "band_mask",
     "attention",
     "axis_attention",
     "tensorized_attention_forward",
@@ -59,30 +64,46 @@ def axis_strides(dims: Sequence[int]) -> list:
 
 def _softmax_rows(s: np.ndarray, allowed: Optional[np.ndarray]) -> np.ndarray:
     """Row-wise softmax over the last axis (Eq. 1); positions where `allowed`
-    is False are excluded from the normalisation and get probability 0."""
+    is False are excluded from the normalisation and get probability 0.  A row
+    with no allowed position gets all-zero probabilities."""
     if allowed is not None:
         s = np.where(allowed, s, -np.inf)
-    s = s - np.max(s, axis=-1, keepdims=True)
-    e = np.exp(s)
-    return e / np.sum(e, axis=-1, keepdims=True)
+    mx = np.max(s, axis=-1, keepdims=True)
+    mx = np.where(np.isfinite(mx), mx, 0.0)
+    e = np.exp(s - mx)
+    z = np.sum(e, axis=-1, keepdims=True)
+    return e / np.where(z > 0, z, 1.0)
+
+
+def band_mask(n: int, causal: bool, window: int = 0) -> Optional[np.ndarray]:
+    """M_i for one axis: [a, c] True iff key c is visible from row a: c <= a when
+    causal, and |a - c| < window when window > 0.  None when nothing is masked."""
+    if not causal and window <= 0:
+        return None
+    a = np.arange(n)[:, None]
+    c = np.arange(n)[None, :]
+    m = np.ones((n, n), dtype=bool)
+    if causal:
+        m &= c <= a
+    if window > 0:
+        m &= np.abs(a - c) < window
+    return m
 
 
 def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float,
-              causal: bool) -> np.ndarray:
+              causal: bool, window: int = 0) -> np.ndarray:
     """Eq. 1 for one head: A = softmax(q k^T * scale o M), o = A v.
     q, k: [n, D]; v: [n, Dv]."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
-    n = q.shape[0]
     s = (q @ k.T) * scale
-    allowed = np.tril(np.ones((n, n), dtype=bool)) if causal else None
-    return _softmax_rows(s, allowed) @ v
+    return _softmax_rows(s, band_mask(q.shape[0], causal, window)) @ v
 
 
 def axis_attention(q: np.ndarray, k: np.ndarray, o_prev: np.ndarray,
                    dims: Sequence[int], axis: int, scale: float, causal: bool,
-                   return_probs: bool = False):
+                   return_probs: bool = False, window: int = 0, valid_len: Optional[int] = None):
     """One hop of Eq. 4 for one head.
 
     q, k: [N, D]; o_prev: [N, Dv]; N = prod(dims).  Mode-`axis` flattening
@@ -90,7 +111,8 @@ def axis_attention(q: np.ndarray, k: np.ndarray, o_prev: np.ndarray,
     fibre gets its own n_axis x n_axis row-softmax attention, applied to the
     fibre's rows of o_prev; the result is folded back.  Returns o_new [N, Dv]
     and, on request, A_axis with shape dims[:axis] + dims[axis+1:] + (n, n)
-    (batch axes in tensor order, then query index, then key index)."""
+    (batch axes in tensor order, then query index, then key index).
+    `window` and `valid_len` add the band and padding masks described above."""
     dims = [int(n) for n in dims]
     N = int(np.prod(dims)) if dims else 1
     q = np.asarray(q, dtype=np.float64)
@@ -103,7 +125,12 @@ def axis_attention(q: np.ndarray, k: np.ndarray, o_prev: np.ndarray,
     Ki = np.moveaxis(k.reshape(dims + [k.shape[1]]), axis, -2)
     Oi = np.moveaxis(o_prev.reshape(dims + [o_prev.shape[1]]), axis, -2)
     S = np.matmul(Qi, np.swapaxes(Ki, -1, -2)) * scale                # [..., n, n]
-    allowed = np.tril(np.ones((n, n), dtype=bool)) if causal else None
+    allowed = band_mask(n, causal, window)
+    if valid_len is not None and valid_len < N:
+        # a token is real iff its index is below valid_len; a padded token is no key and its own row sees nothing
+        real = np.moveaxis((np.arange(N) < valid_len).reshape(dims + [1]), axis, -2)[..., 0]   # [..., n]
+        pad = real[..., :, None] & real[..., None, :]
+        allowed = pad if allowed is None else (allowed & pad)
     A = _softmax_rows(S, allowed)
     Onew = np.matmul(A, Oi)                                           # [..., n, Dv]
     # mode-i folding
@@ -125,7 +152,9 @@ def tensorized_attention_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
                                  dims: Sequence[int], causal: bool,
                                  scale: Optional[float] = None,
                                  hop_order: Optional[Sequence[int]] = None,
-                                 return_intermediates: bool = False):
+                                 return_intermediates: bool = False,
+                                 window: Optional[Sequence[int]] = None,
+                                 valid_len: Optional[int] = None):
     """Algorithm 1.
 
     q: [B, N, H_q, D]; k, v: [B, N, H_kv, D] (H_q a multiple of H_kv);
@@ -147,6 +176,7 @@ def tensorized_attention_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
     if scale is None:
         scale = 1.0 / math.sqrt(D)
     order = _hop_order(len(dims), hop_order)
+    window = [0] * len(dims) if window is None else [int(x) for x in window]
 
     o = np.empty((B, N, Hq, v.shape[3]), dtype=np.float64)
     inter = [np.repeat(v, G, axis=2)] + [np.empty_like(o) for _ in order]
@@ -158,13 +188,13 @@ def tensorized_attention_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
             oh = v[b, :, g, :]                      # Initialise O = V
             for pos, axis in enumerate(order):
                 if return_intermediates:
-                    oh, A = axis_attention(qh, kh, oh, dims, axis, scale, causal, True)
+                    oh, A = axis_attention(qh, kh, oh, dims, axis, scale, causal, True, window[axis], valid_len)
                     if probs[pos] is None:
                         probs[pos] = np.empty((B, Hq) + A.shape, dtype=np.float64)
                     probs[pos][b, h] = A
                     inter[pos + 1][b, :, h, :] = oh
                 else:
-                    oh = axis_attention(qh, kh, oh, dims, axis, scale, causal)
+                    oh = axis_attention(qh, kh, oh, dims, axis, scale, causal, False, window[axis], valid_len)
             o[b, :, h, :] = oh                      # Vectorise
     if return_intermediates:
         return o, inter, probs
@@ -174,7 +204,9 @@ def tensorized_attention_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
 def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
                                   d_o: np.ndarray, dims: Sequence[int],
                                   causal: bool, scale: Optional[float] = None,
-                                  hop_order: Optional[Sequence[int]] = None):
+                                  hop_order: Optional[Sequence[int]] = None,
+                                  window: Optional[Sequence[int]] = None,
+                                  valid_len: Optional[int] = None):
     """Gradient of L = sum(O * d_o) through Algorithm 1 w.r.t. q, k, v.
 
     Hops are undone in reverse.  For one hop on one fibre with rows Qs, Ks,
@@ -198,7 +230,7 @@ def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
         scale = 1.0 / math.sqrt(D)
     order = _hop_order(len(dims), hop_order)
     _, inter, probs = tensorized_attention_forward(
-        q, k, v, dims, causal, scale, order, return_intermediates=True)
+        q, k, v, dims, causal, scale, order, return_intermediates=True, window=window, valid_len=valid_len)
 
     dq = np.zeros_like(q)
     dk = np.zeros_like(k)

@@ -25,10 +25,12 @@ def ravel(coords, dims):
     return t
 
 
-def fibre_probs(q, k, dims, axis, fixed, scale, causal):
+def fibre_probs(q, k, dims, axis, fixed, scale, causal, window=0, valid_len=None):
     """The n x n row-softmax attention of one mode-`axis` fibre (Eq. 4).
     `fixed` gives the coordinates on every axis; its entry at `axis` is ignored.
-    q, k: nested lists [N][D]."""
+    q, k: nested lists [N][D].  window > 0: key c is hidden from row a unless
+    |a - c| < window; valid_len: tokens at or past it are padding (never a key; their
+    own rows see nothing and get all-zero probabilities)."""
     n = dims[axis]
     tok = []
     for a in range(n):
@@ -39,13 +41,18 @@ def fibre_probs(q, k, dims, axis, fixed, scale, causal):
     for a in range(n):
         logits = []
         for c in range(n):
-            if causal and c > a:
+            hidden = (causal and c > a) or (window > 0 and abs(a - c) >= window)
+            if valid_len is not None and (tok[a] >= valid_len or tok[c] >= valid_len):
+                hidden = True
+            if hidden:
                 logits.append(None)
                 continue
             s = 0.0
             for x, y in zip(q[tok[a]], k[tok[c]]):
                 s += x * y
             logits.append(s * scale)
+        if all(l is None for l in logits):
+            continue                                  # a padded row: all zeros
         mx = max(l for l in logits if l is not None)
         ex = [0.0 if l is None else math.exp(l - mx) for l in logits]
         z = sum(ex)
@@ -54,7 +61,7 @@ def fibre_probs(q, k, dims, axis, fixed, scale, causal):
     return A
 
 
-def hop_matrix(q, k, dims, axis, scale, causal):
+def hop_matrix(q, k, dims, axis, scale, causal, window=0, valid_len=None):
     """P_axis [N][N]: P[t][u] = A^{(fibre)}[j_axis][k_axis] when tokens t = (j)
     and u = (k) agree on every other axis, else 0."""
     N = 1
@@ -63,7 +70,7 @@ def hop_matrix(q, k, dims, axis, scale, causal):
     P = [[0.0] * N for _ in range(N)]
     other = [range(n) if i != axis else range(1) for i, n in enumerate(dims)]
     for fixed in itertools.product(*other):
-        A = fibre_probs(q, k, dims, axis, fixed, scale, causal)
+        A = fibre_probs(q, k, dims, axis, fixed, scale, causal, window, valid_len)
         for a in range(dims[axis]):
             ca = list(fixed)
             ca[axis] = a
@@ -91,12 +98,13 @@ def matmul(X, Y):
     return out
 
 
-def operator_by_products(q, k, dims, scale, causal, order=None):
+def operator_by_products(q, k, dims, scale, causal, order=None, window=None, valid_len=None):
     """W = P_{last hop} ... P_{first hop}: the first executed hop is rightmost."""
     order = list(range(len(dims))) if order is None else list(order)
+    window = [0] * len(dims) if window is None else list(window)
     W = None
     for axis in order:
-        P = hop_matrix(q, k, dims, axis, scale, causal)
+        P = hop_matrix(q, k, dims, axis, scale, causal, window[axis], valid_len)
         W = P if W is None else matmul(P, W)
     return W
 
