@@ -95,6 +95,8 @@ ta::HopParams hop_params(const ta_plan* pl, int axis, const void* q, const void*
     hp.stride = pl->strides[axis];
     hp.fibres = pl->N / pl->dims[axis];
     hp.scale = pl->scale;
+    hp.window = pl->desc.window[axis];
+    hp.valid_len = pl->desc.valid_len > 0 ? pl->desc.valid_len : pl->N;
     return hp;
 }
 
@@ -127,7 +129,7 @@ const char* ta_last_error_detail(void) { return g_detail; }
 
 void ta_version(int* major, int* minor) {
     if (major) *major = 0;
-    if (minor) *minor = 1;
+    if (minor) *minor = 2;
 }
 
 ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
@@ -149,6 +151,10 @@ ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
         N *= d->dims[i];
     }
     if (N > (int64_t)1 << 40) return fail(TA_ERR_SHAPE, "sequence length overflows");
+    for (int i = 0; i < d->order; ++i)
+        if (d->window[i] < 0) return fail(TA_ERR_INVALID_ARG, "window[%d] = %d is negative", i, d->window[i]);
+    if (d->valid_len < 0) return fail(TA_ERR_INVALID_ARG, "valid_len is negative");
+    if (d->valid_len > N) return fail(TA_ERR_SHAPE, "valid_len %lld exceeds the sequence length %lld", (long long)d->valid_len, (long long)N);
     if (d->head_dim % 8 != 0 || d->head_dim > 256)
         return fail(TA_ERR_UNSUPPORTED, "head_dim %d: need a multiple of 8, at most 256", d->head_dim);
 

@@ -64,6 +64,14 @@ __device__ inline void load_tile(float* tile, int pitch, int rows, int r0, const
     }
 }
 
+// M_i[a][c] of this hop: causal triangle, band of width `window`, and padding (rows whose
+// token is at or past valid_len neither see nor are seen).
+__device__ inline bool visible(const HopParams& p, int64_t tok0, int a, int c) {
+    if (p.causal && c > a) return false;
+    if (p.window > 0 && (a - c >= p.window || c - a >= p.window)) return false;
+    return tok0 + (int64_t)(a > c ? a : c) * p.stride < p.valid_len;
+}
+
 // ------------------------------------------------------------------------------------
 // Forward.  Block = (batch, query head, fibre, block of 16 query rows); wave w owns rows
 // 4w..4w+3 of the block.  Keys are streamed in tiles of TK rows through LDS; lane
@@ -118,7 +126,7 @@ __global__ __launch_bounds__(kThreads) void generic_forward_kernel(HopParams p, 
                 for (int d = hh * dh; d < (hh + 1) * dh; ++d) part += qrow[d] * krow[d];
             float s = part + __shfl_xor(part, 32);
             const int c = k0 + c_l;
-            const bool valid = (c_l < TK) && (c < n) && (!p.causal || c <= a);
+            const bool valid = (c_l < TK) && (c < n) && visible(p, tok0, a, c);
             s = valid ? s * p.scale : -INFINITY;
             const float tmax = wave_max(s);
             if (tmax == -INFINITY) continue;            // nothing visible in this tile
@@ -144,7 +152,7 @@ __global__ __launch_bounds__(kThreads) void generic_forward_kernel(HopParams p, 
         const int a = qb * kQB + w * 4 + r;
         if (a >= n) continue;
         T* orow = row_ptr_w<T>(p.o, b, tok0 + (int64_t)a * p.stride, h);
-        const float inv = 1.f / l[r];
+        const float inv = l[r] > 0.f ? 1.f / l[r] : 0.f;   // a padded row sees nothing: zero output
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int col = lane + 64 * j;
@@ -215,7 +223,7 @@ __global__ __launch_bounds__(kThreads) void generic_backward_kernel(BwdParams bp
                     for (int d = hh * dh; d < (hh + 1) * dh; ++d) part += r0[d] * tA[c_l * pitch + d];
                 float s = part + __shfl_xor(part, 32);
                 const int c = k0 + c_l;
-                const bool valid = (c_l < TK) && (c < n) && (!p.causal || c <= a);
+                const bool valid = (c_l < TK) && (c < n) && visible(p, tok0, a, c);
                 s = valid ? s * p.scale : -INFINITY;
                 const float tmax = wave_max(s);
                 if (tmax == -INFINITY) continue;
@@ -236,12 +244,13 @@ __global__ __launch_bounds__(kThreads) void generic_backward_kernel(BwdParams bp
                 }
             }
             float delta = 0.f;
+            const float invl = l > 0.f ? 1.f / l : 0.f;  // l == 0: a padded row
             if (active) {
                 float part = 0.f;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int col = lane + 64 * j;
-                    if (col < D) part += r1[col] * (acc[j] / l);
+                    if (col < D) part += r1[col] * (acc[j] * invl);
                 }
                 delta = wave_sum(part);
                 if (lane == 0) { st_m[hl * n + a] = m; st_l[hl * n + a] = l; st_d[hl * n + a] = delta; }
@@ -263,9 +272,9 @@ __global__ __launch_bounds__(kThreads) void generic_backward_kernel(BwdParams bp
                 const float s = (ps + __shfl_xor(ps, 32)) * p.scale;
                 const float dA = pa + __shfl_xor(pa, 32);
                 const int c = k0 + c_l;
-                const bool valid = (c_l < TK) && (c < n) && (!p.causal || c <= a);
-                const float pr = valid ? expf(s - m) / l : 0.f;
-                const float dS = pr * (dA - delta);
+                const bool valid = (c_l < TK) && (c < n) && visible(p, tok0, a, c);
+                const float pr = valid ? expf(s - m) * invl : 0.f;
+                const float dS = valid ? pr * (dA - delta) : 0.f;
                 for (int cc = 0; cc < TK; ++cc) {
                     const float x = __shfl(dS, cc);
 #pragma unroll
@@ -321,7 +330,7 @@ __global__ __launch_bounds__(kThreads) void generic_backward_kernel(BwdParams bp
                 const float s = (ps + __shfl_xor(ps, 32)) * p.scale;
                 const float dA = pa + __shfl_xor(pa, 32);
                 const int a = q0 + c_l;
-                const bool valid = (c_l < TK) && (a < n) && (!p.causal || c <= a);
+                const bool valid = (c_l < TK) && (a < n) && visible(p, tok0, a, c);
                 float pr = 0.f, dS = 0.f;
                 if (valid) {
                     pr = expf(s - st_m[hl * n + a]) / st_l[hl * n + a];

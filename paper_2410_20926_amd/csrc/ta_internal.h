@@ -26,6 +26,8 @@ struct HopParams {
     int64_t stride;          // tokens between neighbours along the axis
     int64_t fibres;          // N / n_i
     float scale;
+    int32_t window;          // band width on this axis, 0 = none
+    int64_t valid_len;       // tokens at or past it are padding; equals N when there is none
 };
 
 struct BwdParams {

@@ -152,15 +152,21 @@ __global__ __launch_bounds__(256, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
 
     const uint32_t f0 = tt * tp.fpt;
     const int rows_valid = (int)min((uint32_t)tp.fpt, (uint32_t)p.fibres - f0) * n;
-    if (lane < kTile) {
-        const uint32_t stride = (uint32_t)p.stride;
-        const int rc = min(lane, rows_valid - 1);         // padding rows alias the last valid row: loads need no predicate
-        const uint32_t fi = (uint32_t)((rc + 0.5f) * tp.inv_n);
-        const uint32_t a = rc - fi * n;
-        const uint32_t f = f0 + fi;
-        const uint32_t outer = f / stride;
-        const uint32_t tok = outer * stride * n + (f - outer * stride) + a * stride;
-        rowoff[lane] = u32x4{tok * tp.q_row, tok * tp.k_row, tok * tp.v_row, tok * tp.o_row};
+    uint32_t real_rows;                                   // bit r: tile row r exists and its token is not padding
+    {
+        bool real = false;
+        if (lane < kTile) {
+            const uint32_t stride = (uint32_t)p.stride;
+            const int rc = min(lane, rows_valid - 1);     // rows past the last fibre alias the last valid row: loads need no predicate
+            const uint32_t fi = (uint32_t)((rc + 0.5f) * tp.inv_n);
+            const uint32_t a = rc - fi * n;
+            const uint32_t f = f0 + fi;
+            const uint32_t outer = f / stride;
+            const uint32_t tok = outer * stride * n + (f - outer * stride) + a * stride;
+            rowoff[lane] = u32x4{tok * tp.q_row, tok * tp.k_row, tok * tp.v_row, tok * tp.o_row};
+            real = lane < rows_valid && tok < (uint32_t)p.valid_len;
+        }
+        real_rows = (uint32_t)__ballot(real);
     }
     lds_wave_sync();
 
@@ -238,14 +244,14 @@ __global__ __launch_bounds__(256, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
 
     // ---- softmax and dS, one query row per lane -------------------------------------------
     const float sl2 = p.scale * kLog2e;
-    int flo = 0, fhi = 0;                                 // this lane's row's fibre occupies tile rows [flo, fhi)
-    if (r32 < rows_valid) {
-        flo = (int)((r32 + 0.5f) * tp.inv_n) * n;
-        fhi = flo + n;
-    }
+    const bool row_real = (real_rows >> r32) & 1u;        // this lane's tile row exists and is not padding
+    const int flo = (int)((min(r32, rows_valid - 1) + 0.5f) * tp.inv_n) * n;   // its fibre occupies tile rows [flo, fhi)
+    const int fhi = flo + n;
     u32x4 dsTop[2];                                       // dS^T as B operands (contraction over keys)
     {
-        const uint32_t vis = range_mask(flo, r32 < rows_valid ? (p.causal ? r32 + 1 : fhi) : 0) >> (4 * hf);
+        int lo = 0, hi = 0;
+        if (row_real) visible_range(r32, flo, fhi, p.causal, p.window, lo, hi);
+        const uint32_t vis = (range_mask(lo, hi) & real_rows) >> (4 * hf);
         float e[16], mx = -INFINITY;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -275,7 +281,9 @@ __global__ __launch_bounds__(256, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
     u32x4 pNop[2], dsNop[2];
     {
         // query rows that see this lane's key: its own fibre's rows, from itself on when causal
-        const uint32_t vis = range_mask(p.causal ? r32 : flo, r32 < rows_valid ? min(fhi, rows_valid) : 0) >> (4 * hf);
+        int lo = 0, hi = 0;
+        if (row_real) seen_range(r32, flo, fhi, p.causal, p.window, lo, hi);
+        const uint32_t vis = (range_mask(lo, hi) & real_rows) >> (4 * hf);
         float pr[16], ds[16];
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {

@@ -99,6 +99,20 @@ __device__ inline uint32_t range_mask(int lo, int hi) {   // bits [lo, hi), 0 <=
     return mh & ~ml;
 }
 
+// Tile rows [lo, hi) visible from query row `row` of a fibre occupying tile rows [flo, fhi):
+// the causal triangle and a band of width `window` (0 = none).  The same range, read the
+// other way round (rows that see key `row`), is seen_range().
+__device__ inline void visible_range(int row, int flo, int fhi, int causal, int window, int& lo, int& hi) {
+    lo = flo;
+    hi = causal ? row + 1 : fhi;
+    if (window > 0) { lo = max(lo, row - window + 1); hi = min(hi, row + window); }
+}
+__device__ inline void seen_range(int row, int flo, int fhi, int causal, int window, int& lo, int& hi) {
+    lo = causal ? row : flo;
+    hi = fhi;
+    if (window > 0) { lo = max(lo, row - window + 1); hi = min(hi, row + window); }
+}
+
 // Launch geometry computed on the host.
 struct TileParams {
     int32_t fpt;          // fibres per 32-row tile (n <= 32), else 1

@@ -69,17 +69,21 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
     }
     // byte offset of every row of the fibre set, clamped to the last valid row, so that
     // loads need no predicate (padding rows are masked in the softmax and never stored)
+    uint64_t real_rows;                                   // bit r: table row r exists and its token is not padding
     {
         const uint32_t stride = (uint32_t)p.stride;
-        for (int r = lane; r < kRows; r += 64) {
-            const int rc = min(r, rows_valid - 1);
+        bool real = false;
+        if (lane < kRows) {
+            const int rc = min(lane, rows_valid - 1);
             const uint32_t fi = (KT == 1) ? (uint32_t)((rc + 0.5f) * tp.inv_n) : 0u;
             const uint32_t a = rc - fi * n;
             const uint32_t f = f0 + fi;
             const uint32_t outer = f / stride;
             const uint32_t tok = outer * stride * n + (f - outer * stride) + a * stride;
-            rowoff[r] = u32x4{tok * tp.q_row, tok * tp.k_row, tok * tp.v_row, tok * tp.o_row};
+            rowoff[lane] = u32x4{tok * tp.q_row, tok * tp.k_row, tok * tp.v_row, tok * tp.o_row};
+            real = lane < rows_valid && tok < (uint32_t)p.valid_len;
         }
+        real_rows = __ballot(real);
     }
     lds_wave_sync();
 
@@ -173,22 +177,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
     uint32_t vis[KT];
     {
         int lo = 0, hi = 0;                               // visible keys = [lo, hi)
-        if (qrow < rows_valid) {
-            if (KT == 1) {
-                const int fi = (int)((qrow + 0.5f) * tp.inv_n);
-                lo = fi * n;
-                hi = p.causal ? qrow + 1 : lo + n;
-            } else {
-                hi = p.causal ? qrow + 1 : n;
-            }
+        if ((real_rows >> qrow) & 1) {
+            const int flo = (KT == 1) ? (int)((qrow + 0.5f) * tp.inv_n) * n : 0;
+            visible_range(qrow, flo, flo + n, p.causal, p.window, lo, hi);
         }
 #pragma unroll
-        for (int j = 0; j < KT; ++j) {
-            const int l = min(max(lo - 32 * j, 0), 32), hh = min(max(hi - 32 * j, 0), 32);
-            const uint32_t mh = hh >= 32 ? 0xffffffffu : ((1u << hh) - 1u);
-            const uint32_t ml = l >= 32 ? 0xffffffffu : ((1u << l) - 1u);
-            vis[j] = (mh & ~ml) >> (4 * hf);
-        }
+        for (int j = 0; j < KT; ++j)
+            vis[j] = (range_mask(min(max(lo - 32 * j, 0), 32), min(max(hi - 32 * j, 0), 32)) & (uint32_t)(real_rows >> (32 * j))) >> (4 * hf);
     }
     const float sl2 = p.scale * kLog2e;
     float mx = -INFINITY;
@@ -331,17 +326,21 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
         qt = (int)(tt - f0 * tp.qtiles);
         rows_valid = n;
     }
+    uint64_t real_rows;                                   // bit r: table row r exists and its token is not padding
     {
         const uint32_t stride = (uint32_t)p.stride;
-        for (int r = lane; r < kRows; r += 64) {
-            const int rc = min(r, rows_valid - 1);
+        bool real = false;
+        if (lane < kRows) {
+            const int rc = min(lane, rows_valid - 1);
             const uint32_t fi = (KT == 1) ? (uint32_t)((rc + 0.5f) * tp.inv_n) : 0u;
             const uint32_t a = rc - fi * n;
             const uint32_t f = f0 + fi;
             const uint32_t outer = f / stride;
             const uint32_t tok = outer * stride * n + (f - outer * stride) + a * stride;
-            rowoff[r] = u32x4{tok * tp.q_row, tok * tp.k_row, tok * tp.v_row, tok * tp.o_row};
+            rowoff[lane] = u32x4{tok * tp.q_row, tok * tp.k_row, tok * tp.v_row, tok * tp.o_row};
+            real = lane < rows_valid && tok < (uint32_t)p.valid_len;
         }
+        real_rows = __ballot(real);
     }
     lds_wave_sync();
 
@@ -423,19 +422,15 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
     // ---- masked row softmax over all key tiles -------------------------------------------------
     const int qrow = qt * kTile + r32;
     int lo = 0, hi = 0;                                                     // visible keys = [lo, hi)
-    if (qrow < rows_valid) {
-        if (KT == 1) {
-            lo = (int)((qrow + 0.5f) * tp.inv_n) * n;
-            hi = p.causal ? qrow + 1 : lo + n;
-        } else {
-            hi = p.causal ? qrow + 1 : n;
-        }
+    if ((real_rows >> qrow) & 1) {
+        const int flo = (KT == 1) ? (int)((qrow + 0.5f) * tp.inv_n) * n : 0;
+        visible_range(qrow, flo, flo + n, p.causal, p.window, lo, hi);
     }
     const float sl2 = p.scale * kLog2e;
     float mx = -INFINITY;
 #pragma unroll
     for (int j = 0; j < KT; ++j) {
-        const uint32_t vis = range_mask(min(max(lo - 32 * j, 0), 32), min(max(hi - 32 * j, 0), 32)) >> (4 * hf);
+        const uint32_t vis = (range_mask(min(max(lo - 32 * j, 0), 32), min(max(hi - 32 * j, 0), 32)) & (uint32_t)(real_rows >> (32 * j))) >> (4 * hf);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const bool ok = (vis >> (8 * (r / 4) + (r % 4))) & 1u;

@@ -59,7 +59,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
     const uint32_t lbyte = lcol * 16;
     const int r32 = lane & 31, hf = lane >> 5;
     const int ktiles = (n + kTile - 1) / kTile;
-    const int jend = p.causal ? qt + 1 : ktiles;
+    // key tiles that any row of this query tile can see (causal triangle, band)
+    int jbeg = 0, jend = p.causal ? qt + 1 : ktiles;
+    if (p.window > 0) {
+        jbeg = max(0, qt * kTile - p.window + 1) / kTile;
+        jend = min(jend, (qt * kTile + kTile - 1 + p.window - 1) / kTile + 1);
+    }
 
     // rows past the end of the fibre alias its last row: loads need no predicate
     u32x4 qreg[G::kPasses], kreg[G::kPasses], vreg[G::kPasses];
@@ -67,7 +72,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
 #pragma unroll
     for (int i = 0; i < G::kPasses; ++i) {
         const uint32_t rq = (uint32_t)min(qt * kTile + i * G::kRowsPerPass + lrow, n - 1);
-        const uint32_t rk = (uint32_t)min(i * G::kRowsPerPass + lrow, n - 1);
+        const uint32_t rk = (uint32_t)min(jbeg * kTile + i * G::kRowsPerPass + lrow, n - 1);
         qreg[i] = *reinterpret_cast<const u32x4*>(qb + (rq * sp.q_step + lbyte));
         kreg[i] = *reinterpret_cast<const u32x4*>(kb + (rk * sp.k_step + lbyte));
         vreg[i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
@@ -85,15 +90,22 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
     read_natural<D>(oprd, qop);
     lds_wave_sync();
 
+    // rows of the fibre whose token is not padding form a prefix [0, nreal)
+    const uint32_t vl = (uint32_t)p.valid_len;
+    const int nreal = tok0 >= vl ? 0 : (int)min((uint32_t)n, (vl - tok0 + stride - 1) / stride);
     const int qrow = qt * kTile + r32;                    // this lane's query row in the fibre
-    const int khi = qrow < n ? (p.causal ? qrow + 1 : n) : 0;              // it sees keys [0, khi)
+    int klo = 0, khi = 0;                                 // it sees keys [klo, khi)
+    if (qrow < nreal) {
+        visible_range(qrow, 0, n, p.causal, p.window, klo, khi);
+        khi = min(khi, nreal);
+    }
     const float sl2 = p.scale * kLog2e;
     float m = -INFINITY, l = 0.f;
     f32x16 ot[G::kDTiles];
 #pragma unroll
     for (int t = 0; t < G::kDTiles; ++t) ot[t] = f32x16{};
 
-    for (int j = 0; j < jend; ++j) {
+    for (int j = jbeg; j < jend; ++j) {
         // ---- K tile j: LDS transit, then request tile j + 1 into the same registers ------
         u32x4 kop[G::kKSteps];
         stage_rows<D>(stg, kreg);
@@ -112,7 +124,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
         for (int s = 0; s < G::kKSteps; ++s) st = mma(kop[s], qop[s], st);
 
         // ---- mask, running max and sum ------------------------------------------------------
-        const uint32_t vis = range_mask(0, min(max(khi - kTile * j, 0), kTile)) >> (4 * hf);
+        const uint32_t vis = range_mask(min(max(klo - kTile * j, 0), kTile), min(max(khi - kTile * j, 0), kTile)) >> (4 * hf);
         float e[16], tmax = -INFINITY;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {

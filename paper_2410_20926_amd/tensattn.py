@@ -30,6 +30,7 @@ class TaDesc(C.Structure):
         ("order", C.c_int32), ("dims", C.c_int32 * TA_MAX_ORDER), ("dtype", C.c_int32), ("causal", C.c_int32),
         ("scale", C.c_float), ("hop_order", C.c_int32 * TA_MAX_ORDER),
         ("q_strides", C.c_int64 * 3), ("kv_strides", C.c_int64 * 3), ("o_strides", C.c_int64 * 3),
+        ("window", C.c_int32 * TA_MAX_ORDER), ("valid_len", C.c_int64),
     ]
 
 
@@ -124,7 +125,8 @@ def _stream(stream) -> Optional[int]:
 
 def make_desc(batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dims: Sequence[int], dtype: int,
               causal: bool, scale: float = 0.0, hop_order: Optional[Sequence[int]] = None,
-              q_strides=None, kv_strides=None, o_strides=None) -> TaDesc:
+              q_strides=None, kv_strides=None, o_strides=None, window: Optional[Sequence[int]] = None,
+              valid_len: int = 0) -> TaDesc:
     d = TaDesc()
     d.batch, d.n_q_heads, d.n_kv_heads, d.head_dim = batch, n_q_heads, n_kv_heads, head_dim
     d.order = len(dims)
@@ -135,6 +137,9 @@ def make_desc(batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dims: 
         for j, a in enumerate(hop_order[:TA_MAX_ORDER]):
             d.hop_order[j] = int(a)
     d.dtype, d.causal, d.scale = dtype, int(bool(causal)), float(scale)
+    for j in range(TA_MAX_ORDER):
+        d.window[j] = int(window[j]) if window is not None and j < len(window) else 0
+    d.valid_len = int(valid_len)
     for name, s in (("q_strides", q_strides), ("kv_strides", kv_strides), ("o_strides", o_strides)):
         arr = getattr(d, name)
         for j in range(3):

@@ -32,7 +32,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_status_strings():
-    assert ta.ta_version() == (0, 1)
+    assert ta.ta_version() == (0, 2)
     lib = ta.load_library()
     assert lib.ta_status_string(0) == b"TA_OK"
     assert lib.ta_status_string(5) == b"TA_ERR_ALIAS"
@@ -94,6 +94,9 @@ def test_cost_model_closed_forms():
     (dict(q_strides=(64, 64, 64)), "TA_ERR_SHAPE"),             # overlapping rows
     (dict(o_strides=(4 * 3 * 2 * 64, 2 * 64, 60)), "TA_ERR_SHAPE"),   # not a multiple of 8
     (dict(dims=(1 << 20, 1 << 20, 1 << 20)), "TA_ERR_SHAPE"),   # overflow
+    (dict(window=(0, -2)), "TA_ERR_INVALID_ARG"),
+    (dict(valid_len=-1), "TA_ERR_INVALID_ARG"),
+    (dict(valid_len=13), "TA_ERR_SHAPE"),
 ])
 def test_plan_rejects_bad_descriptors(kw, status):
     args = dict(batch=1, n_q_heads=2, n_kv_heads=2, head_dim=64, dims=(4, 3), dtype=ta.TA_F32, causal=False)
