@@ -192,3 +192,68 @@ def test_zero_queries_closed_form_at_full_size(name, causal):
     got, _, _ = multihop_forward(q, k, v, w.dims, "bf16", causal)
     ref = zero_query_reference(v, w.dims, w.n_q_heads // w.n_kv_heads, causal)
     check(got, ref, TOL["bf16"], f"{name} Q=0 causal={causal}")
+
+
+def test_offsets_near_the_32_bit_limit():
+    """524,288 tokens of 32 heads x 128 bf16 features: the last row of Q starts 4,294,959,104
+    bytes into the batch element, just inside the MFMA kernels' 32-bit row offsets.  Checked
+    with the Q = 0 closed form (a running mean along every axis), which touches every fibre."""
+    dims, Hq, Hkv, D = (128, 64, 64), 32, 8, 128
+    N = int(np.prod(dims))
+    rng = np.random.default_rng(99)
+    from paper_2410_20926_amd.workloads import draw
+    v = draw((1, N, Hkv, D), rng, 1.0, "bf16")
+    plan = ta.ta_plan_create(1, Hq, Hkv, D, dims, ta.TA_BF16, True)
+    assert [plan.hop_kernel(a, 1) for a in range(3)] == ["mfma_bf16_stream", "mfma_bf16_n64_shared", "mfma_bf16_n64_shared"]
+    tq = torch.zeros(1, N, Hq, D, dtype=torch.bfloat16, device="cuda")
+    tk = torch.zeros(1, N, Hkv, D, dtype=torch.bfloat16, device="cuda")
+    tv = to_dev(v, "bf16")
+    o = torch.empty_like(tq)
+    wsb = plan.workspace_bytes(False)
+    ws = alloc_bytes(wsb)
+    ta.ta_multihop_forward(plan, tq, tk, tv, o, ws, wsb, False)
+    torch.cuda.synchronize()
+    del ws, tq, tk
+    ref = zero_query_reference(v, dims, 1, True)                     # per key/value head
+    for g in (0, 7):                                                  # first and last group: lowest and highest addresses
+        for h in (4 * g, 4 * g + 3):
+            got = to_host(o[:, :, h])
+            check(got, ref[:, :, g], TOL["bf16"], f"head {h}")
+    # one token past this size the offsets no longer fit and the plan falls back
+    big = ta.ta_plan_create(1, Hq, Hkv, D, (128, 64, 65), ta.TA_BF16, True)
+    assert big.hop_kernel(2, 1) == "generic"
+
+
+def test_multihop_forward_under_graph_capture():
+    """The library only enqueues kernels on the given stream (no allocation, no memset, no
+    synchronisation), so a multi-hop forward can be captured into a HIP graph; every replay,
+    with eager work and synchronisations in between, must reproduce the eager result."""
+    dims, B, Hq, Hkv, D = (16, 32, 8), 1, 8, 2, 128
+    N = int(np.prod(dims))
+    plan = ta.ta_plan_create(B, Hq, Hkv, D, dims, ta.TA_BF16, True)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(5)
+    q = torch.randn(B, N, Hq, D, device="cuda", generator=gen).bfloat16()
+    k = torch.randn(B, N, Hkv, D, device="cuda", generator=gen).bfloat16()
+    v = torch.randn(B, N, Hkv, D, device="cuda", generator=gen).bfloat16()
+    o = torch.zeros(B, N, Hq, D, device="cuda", dtype=torch.bfloat16)
+    wsb = plan.workspace_bytes(False)
+    ws = alloc_bytes(wsb)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ta.ta_multihop_forward(plan, q, k, v, o, ws, wsb, False)     # warm-up on the capture stream
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        ta.ta_multihop_forward(plan, q, k, v, o, ws, wsb, False)
+    for it in range(3):
+        q.copy_(torch.randn(B, N, Hq, D, device="cuda", generator=gen).bfloat16())
+        v.copy_(torch.randn(B, N, Hkv, D, device="cuda", generator=gen).bfloat16())
+        eager = torch.empty_like(o)
+        ws2 = alloc_bytes(wsb)
+        ta.ta_multihop_forward(plan, q, k, v, eager, ws2, wsb, False)
+        torch.cuda.synchronize()
+        o.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o, eager), f"replay {it} differs from the eager result"
