@@ -17,7 +17,7 @@ What it implements, in the paper's own order and notation:
                          that a backward exists, Sec. 3.2; this is the plain
                          derivative of the forward, hop by hop in reverse).
 
-Readings taken where the paper is silent (all listed in the design notes):
+Readings taken where the paper is silent:
   - the mask "o M" excludes positions (logit -inf), it does not multiply;
   - causal means M_i[a, c] = 1 iff c <= a along every axis;
   - reshape is row-major, first axis slowest (Sec. 4.3: with {32,32,32}, one
