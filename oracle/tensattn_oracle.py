@@ -34,7 +34,10 @@ Parity pins (tests/test_oracle_*.py): d=1 against a library attention
 routine, row sums, brute-force N x N Kronecker-form operator built with scalar
 loops, numpy.kron in the separable regime, Q = 0 closed forms, no-leak
 invariant, unit-axis no-ops, finite differences for the backward.
-Nothing in this file is "parity unpinned".
+Nothing in the attention functions is "parity unpinned".  `tensorized_rope` is pinned
+for its rotary mechanics (a library routine at m = 1, relative-position property, norm and
+inverse) but the paper does not say which features get which axis position: that
+assignment is a reading, so its parity is "parity unpinned" to that extent.
 """
 from __future__ import annotations
 
@@ -50,6 +53,7 @@ __all__ = [
     "axis_attention",
     "tensorized_attention_forward",
     "tensorized_attention_backward",
+    "tensorized_rope",
 ]
 
 
@@ -258,3 +262,46 @@ def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
                 grad = np.moveaxis(dX, -2, axis).reshape(N, v.shape[3])
             dv[b, :, g, :] += grad
     return dq, dk, dv
+
+
+def tensorized_rope(x: np.ndarray, dims: Sequence[int], axis: int = -1, base: float = 10000.0,
+                    inverse: bool = False) -> np.ndarray:
+    """Tensorized positional encoding (Sec. 3.2): the position of token t is the vector of
+    its tensor coordinates (j_1..j_m), and rotary embedding is applied with per-axis positions.
+
+    The paper gives no formula (its appendix on it is absent), so the mechanics are the
+    rotary embedding's own definition - feature pair (2p, 2p+1) of a block of width W is
+    rotated by the angle pos * base^(-2p/W) - and the assignment of positions to features is
+    this reading:
+      axis >= 0 : the whole feature vector (W = D) is rotated with pos = j_axis, the encoding
+                  a hop along that axis uses (scores then depend on j_axis - k_axis only);
+      axis = -1 : the features are split into m consecutive blocks of W = 2*floor(D/(2m)),
+                  block i rotated with pos = j_i; left-over features stay as they are.
+    `inverse` rotates by the negative angle (the transpose: what the backward applies).
+    x: [B, N, H, D] -> same shape, float64."""
+    x = np.asarray(x, dtype=np.float64)
+    B, N, H, D = x.shape
+    dims = [int(n) for n in dims]
+    m = len(dims)
+    assert int(np.prod(dims)) == N
+    coords = np.stack(np.unravel_index(np.arange(N), dims), axis=1)          # [N, m], row-major reshape
+    out = x.copy()
+
+    def rotate(lo, width, pos):
+        p = np.arange(width // 2)
+        ang = pos[:, None] * base ** (-2.0 * p / width)[None, :]             # [N, width/2]
+        if inverse:
+            ang = -ang
+        c, s = np.cos(ang)[None, :, None, :], np.sin(ang)[None, :, None, :]
+        even = x[..., lo:lo + width:2]
+        odd = x[..., lo + 1:lo + width:2]
+        out[..., lo:lo + width:2] = even * c - odd * s
+        out[..., lo + 1:lo + width:2] = even * s + odd * c
+
+    if axis >= 0:
+        rotate(0, D - D % 2, coords[:, axis].astype(np.float64))
+    else:
+        width = 2 * (D // (2 * m))
+        for i in range(m):
+            rotate(i * width, width, coords[:, i].astype(np.float64))
+    return out
