@@ -169,6 +169,21 @@ ta_status_t ta_multihop_backward(const ta_plan_t* plan,
                                  void* dq, void* dk, void* dv,
                                  void* scratch, size_t scratch_bytes, void* stream);
 
+/* ---- tensorized positional encoding (Sec. 3.2: a token's position is the vector of its tensor
+ *      coordinates, and rotary embedding is applied with per-axis positions) -----------------
+ * y = R x for a tensor in the Q layout with n_q_heads (which = 0) or in the key/value layout
+ * with n_kv_heads (which = 1).  The paper gives no formula; this library rotates feature pair
+ * (2p, 2p+1) of a block of width W by pos * base^(-2p/W), with
+ *   axis in 0..m-1 : one block, W = head_dim, pos = the token's coordinate on that axis (the
+ *                    encoding a hop along that axis would use);
+ *   axis = -1      : m consecutive blocks of W = 2*floor(head_dim/(2m)), block i with pos = the
+ *                    coordinate on axis i; left-over features are copied.
+ * base = 0 means 10000.  inverse != 0 rotates by the negative angle (what a backward pass
+ * applies to the gradient).  y may be x itself (in place); any other overlap is TA_ERR_ALIAS.
+ * Needs N < 2^31. */
+ta_status_t ta_rope_apply(const ta_plan_t* plan, int which, int axis, float base, int inverse,
+                          const void* x, void* y, void* stream);
+
 /* ---- measurement aid: a plain read-and-write copy of `bytes` bytes (multiple of 16)
  *      from src to dst on `stream`, used to measure the achievable HBM ceiling and to
  *      calibrate hardware counters against a transfer of known size. ------------------- */

@@ -420,6 +420,37 @@ ta_status_t ta_multihop_backward(const ta_plan_t* pl, const void* q, const void*
     return TA_OK;
 }
 
+ta_status_t ta_rope_apply(const ta_plan_t* pl, int which, int axis, float base, int inverse, const void* x, void* y,
+                          void* stream) {
+    g_detail[0] = 0;
+    if (!pl) return fail(TA_ERR_NULL, "plan is NULL");
+    if (!x || !y) return fail(TA_ERR_NULL, "x or y is NULL");
+    if (which != 0 && which != 1) return fail(TA_ERR_INVALID_ARG, "which must be 0 (Q layout) or 1 (key/value layout)");
+    if (axis < -1 || axis >= pl->order) return fail(TA_ERR_INVALID_ARG, "axis %d out of range [-1, %d)", axis, pl->order);
+    if (!(base >= 0.f) || isinf(base)) return fail(TA_ERR_INVALID_ARG, "base must be finite and >= 0");
+    if (!aligned16(x) || !aligned16(y)) return fail(TA_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
+    if (pl->N >= ((int64_t)1 << 31)) return fail(TA_ERR_UNSUPPORTED, "sequence length %lld is too long for the encoding kernel", (long long)pl->N);
+    const ta_desc_t& d = pl->desc;
+    const int64_t* st = which == 0 ? pl->qs : pl->kvs;
+    const int H = which == 0 ? d.n_q_heads : d.n_kv_heads;
+    if (x != y && overlaps(span_of(x, st, d.batch, pl->N, H, d.head_dim, pl->elem), span_of(y, st, d.batch, pl->N, H, d.head_dim, pl->elem)))
+        return fail(TA_ERR_ALIAS, "y overlaps x without being x");
+    ta::RopeParams rp;
+    rp.x = make_tensor(x, st);
+    rp.y = make_tensor(y, st);
+    rp.B = d.batch; rp.H = H; rp.D = d.head_dim; rp.order = pl->order; rp.N = (uint32_t)pl->N;
+    for (int i = 0; i < TA_MAX_ORDER; ++i) {
+        rp.dims[i] = i < pl->order ? (uint32_t)pl->dims[i] : 1u;
+        rp.strides[i] = i < pl->order ? (uint32_t)pl->strides[i] : 1u;
+    }
+    rp.axis = axis;
+    rp.inverse = inverse != 0;
+    rp.log2_base = (float)log2(base > 0.f ? (double)base : 10000.0);
+    hipError_t e = ta::launch_rope(rp, d.dtype, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(TA_ERR_DEVICE, "encoding launch failed: %s", hipGetErrorString(e));
+    return TA_OK;
+}
+
 ta_status_t ta_copy_bytes(const void* src, void* dst, size_t bytes, void* stream) {
     g_detail[0] = 0;
     if (!src || !dst) return fail(TA_ERR_NULL, "src or dst is NULL");

@@ -39,6 +39,17 @@ struct BwdParams {
     int32_t accumulate;      // 0: overwrite dq, dk; 1: add
 };
 
+// Tensorized rotary position encoding of one [B, N, H, D] tensor (x -> y, same layout).
+struct RopeParams {
+    Tensor x, y;
+    int32_t B, H, D, order;
+    uint32_t N;
+    uint32_t dims[TA_MAX_ORDER], strides[TA_MAX_ORDER];   // axis lengths and token strides
+    int32_t axis;            // 0..order-1: every feature uses that coordinate; -1: one feature block per axis
+    int32_t inverse;         // rotate by the negative angle
+    float log2_base;
+};
+
 // First token of fibre f: fibres enumerate (outer, inner) with inner fastest, so that
 // consecutive fibres are neighbouring tokens.
 __host__ __device__ inline int64_t fibre_base_token(int64_t f, int64_t stride, int32_t n) {
@@ -66,6 +77,7 @@ bool       mfma_forward_supports(int32_t n, int32_t D, int dtype, int* kernel_id
 bool       mfma_forward_layout_ok(const HopParams& p);   // strides and sizes fit the kernel's 32-bit row offsets
 bool       mfma_backward_supports(const BwdParams& bp, int dtype);
 hipError_t launch_mfma_backward(const BwdParams& bp, hipStream_t s);
+hipError_t launch_rope(const RopeParams& rp, int dtype, hipStream_t s);
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 
 }  // namespace ta

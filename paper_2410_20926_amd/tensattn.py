@@ -19,7 +19,7 @@ EXPORTS = [
     "ta_plan_create", "ta_plan_destroy", "ta_plan_seq_len", "ta_plan_axis_stride", "ta_plan_axis_fibres",
     "ta_plan_hop_axis", "ta_plan_hop_kernel", "ta_plan_hop_backward_kernel", "ta_plan_hop_bytes", "ta_plan_hop_flops",
     "ta_plan_workspace_bytes", "ta_plan_backward_scratch_bytes", "ta_axis_attn_forward",
-    "ta_axis_attn_backward", "ta_multihop_forward", "ta_multihop_backward", "ta_copy_bytes",
+    "ta_axis_attn_backward", "ta_multihop_forward", "ta_multihop_backward", "ta_rope_apply", "ta_copy_bytes",
     "ta_status_string", "ta_last_error_detail", "ta_version",
 ]
 
@@ -87,6 +87,8 @@ def load_library():
     lib.ta_multihop_forward.restype = i
     lib.ta_multihop_backward.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, sz, vp]
     lib.ta_multihop_backward.restype = i
+    lib.ta_rope_apply.argtypes = [vp, i, i, C.c_float, i, vp, vp, vp]
+    lib.ta_rope_apply.restype = i
     lib.ta_copy_bytes.argtypes = [vp, vp, sz, vp]
     lib.ta_copy_bytes.restype = i
     lib.ta_status_string.argtypes = [i]
@@ -228,6 +230,11 @@ def ta_multihop_backward(plan: Plan, q, k, v, d_o, workspace, workspace_bytes: i
     _check(load_library().ta_multihop_backward(plan.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(d_o), _ptr(workspace),
                                                workspace_bytes, _ptr(dq), _ptr(dk), _ptr(dv), _ptr(scratch),
                                                scratch_bytes, _stream(stream)))
+
+
+def ta_rope_apply(plan: Plan, which: int, axis: int, x, y, base: float = 0.0, inverse: bool = False, stream=None) -> None:
+    _check(load_library().ta_rope_apply(plan.handle, which, axis, float(base), int(inverse), _ptr(x), _ptr(y),
+                                        _stream(stream)))
 
 
 def ta_copy_bytes(src, dst, nbytes: int, stream=None) -> None:

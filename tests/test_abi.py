@@ -25,7 +25,7 @@ def declared_symbols():
 def test_library_exports_every_declared_symbol():
     lib = ta.load_library()
     names = declared_symbols()
-    assert len(names) >= 20
+    assert len(names) >= 21
     for name in names:
         assert hasattr(lib, name), f"{name} declared in tensattn.h but not exported"
     assert sorted(binding.EXPORTS) == names
@@ -157,6 +157,11 @@ def test_entry_points_reject_bad_arguments_without_launching():
     assert status(ta.ta_axis_attn_backward, p, 0, Q, K, V, 0, O, W, W, W + (1 << 20), False, S) == "TA_ERR_ALIAS"
     assert status(ta.ta_axis_attn_backward, p, 0, Q, K, V, 0, None, W, W, W, False, S) == "TA_ERR_NULL"
     assert status(ta.ta_multihop_backward, p, Q, K, V, O, W, 16, W, W, W, W, 0, S) == "TA_ERR_WORKSPACE"
+    assert status(ta.ta_rope_apply, p, 2, 0, Q, O, 0.0, False, S) == "TA_ERR_INVALID_ARG"
+    assert status(ta.ta_rope_apply, p, 0, 2, Q, O, 0.0, False, S) == "TA_ERR_INVALID_ARG"
+    assert status(ta.ta_rope_apply, p, 0, -1, Q, Q + 32, 0.0, False, S) == "TA_ERR_ALIAS"
+    assert status(ta.ta_rope_apply, p, 0, -1, None, O, 0.0, False, S) == "TA_ERR_NULL"
+    assert status(ta.ta_rope_apply, p, 1, 0, Q, O, -3.0, False, S) == "TA_ERR_INVALID_ARG"
     assert status(ta.ta_copy_bytes, Q, K, 24, S) == "TA_ERR_INVALID_ARG"
     assert status(ta.ta_copy_bytes, None, K, 32, S) == "TA_ERR_NULL"
 
