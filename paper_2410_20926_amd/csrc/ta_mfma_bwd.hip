@@ -6,7 +6,7 @@
 //     P  = softmax(Q K^T * scale, mask)          dP = G X^T
 //     dS = P o (dP - rowsum(P o dP))
 //     dX = P^T G      dQ = dS K * scale      dK = dS^T Q * scale
-// One wavefront handles one (tile, query head); a workgroup is the G <= 4 query heads that
+// One wavefront handles one (tile, query head); a workgroup is the G <= 8 query heads that
 // share a key/value head, so dK (and dX when the value input is V) are summed across the
 // workgroup's waves in a fixed order through LDS: deterministic, no atomics.
 //
@@ -125,9 +125,9 @@ __device__ inline void chain_sum(f32x16 (&acc)[Geo<D>::kDTiles], float* red, int
     __syncthreads();                                      // red may be reused
 }
 
-// blockDim.x = 64 * G (G = query heads per key/value head, 1, 2 or 4); grid = (Hkv, tiles_lo, B * tiles_hi).
+// blockDim.x = 64 * G (G = query heads per key/value head: 1, 2, 4 or 8); grid = (Hkv, tiles_lo, B * tiles_hi).
 template <int D>
-__global__ __launch_bounds__(256, 2) void mfma_bwd_kernel(BwdParams bp, TileParams tp) {
+__global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TileParams tp) {
     using G = BGeo<D>;
     const HopParams& p = bp.hop;
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -355,7 +355,7 @@ hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
 bool mfma_backward_supports(const BwdParams& bp, int dtype) {
     const HopParams& p = bp.hop;
     if (dtype != TA_BF16 || (p.D != 64 && p.D != 128) || p.n < 1 || p.n > kTile) return false;
-    if (p.G != 1 && p.G != 2 && p.G != 4) return false;
+    if (p.G != 1 && p.G != 2 && p.G != 4 && p.G != 8) return false;
     const int64_t N = p.fibres * p.n;
     return N < ((int64_t)1 << 31) && p.B <= 65535 && fits_u32(p.q, N) && fits_u32(p.k, N) && fits_u32(p.vin, N) &&
            fits_u32(bp.d_o, N) && fits_u32(bp.d_vin, N) && fits_u32(bp.dq, N) && fits_u32(bp.dk, N);

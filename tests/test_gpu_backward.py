@@ -49,7 +49,9 @@ CASES = [
     ((3, 16, 8), 1, 2, 1, 128, True, "bf16"),        # packed fibres (2 and 4 per tile), 2 heads per group
     ((5, 7, 3), 2, 4, 4, 64, True, "bf16"),          # odd lengths: ragged tiles with padding rows
     ((32, 3), 1, 8, 2, 128, False, "bf16"),
-    ((6, 32), 1, 8, 1, 64, True, "bf16"),            # 8 heads per group: generic fallback
+    ((6, 32), 1, 8, 1, 64, True, "bf16"),            # 8 heads per group: workgroups of 8 waves
+    ((4, 16), 1, 16, 1, 128, True, "bf16"),          # 16 heads per group: generic fallback
+    ((32, 8), 2, 16, 2, 128, False, "bf16"),         # 8 heads per group, full-width heads
 ]
 
 
