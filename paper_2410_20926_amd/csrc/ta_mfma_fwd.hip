@@ -293,7 +293,6 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
     using G = Geo<D>;
     constexpr int kRows = kTile * KT;
     constexpr int kTileBytes = kTile * G::kPitch;                           // one row-major 32-row tile
-    constexpr int kWaveBytes = kTileBytes + kRows * 16;                     // private transit tile + row table
     constexpr int kShare = G::kPasses / kWavesPerBlock;                     // load passes per wave per shared tile
     static_assert(G::kPasses % kWavesPerBlock == 0, "a shared tile must split evenly over the waves");
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -310,10 +309,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
     const int hv = v_shared ? g : h;
     const int n = p.n;
 
-    char* sK = smem;                                                        // [KT] shared K tiles
-    char* sV = smem + KT * kTileBytes;                                      // [KT] shared V tiles (only when v_shared)
-    char* buf = smem + 2 * KT * kTileBytes + w * kWaveBytes;
-    u32x4* rowoff = reinterpret_cast<u32x4*>(buf + kTileBytes);
+    // LDS: [KT] shared K tiles | [KT] shared V tiles (only when v_shared) | row table | 4 private tiles.
+    // The row table is the same for the 4 waves (same rows): each wave writes it, with identical values.
+    char* sK = smem;
+    char* sV = smem + KT * kTileBytes;
+    u32x4* rowoff = reinterpret_cast<u32x4*>(smem + (v_shared ? 2 : 1) * KT * kTileBytes);
+    char* buf = reinterpret_cast<char*>(rowoff + kRows) + w * kTileBytes;
 
     uint32_t f0;
     int qt, rows_valid;
@@ -506,7 +507,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
 
 template <int D, int KT>
 hipError_t launch_shared(const HopParams& p, const TileParams& tp, hipStream_t s) {
-    const size_t smem = (size_t)2 * KT * kTile * Geo<D>::kPitch + (size_t)kWavesPerBlock * (kTile * Geo<D>::kPitch + kTile * KT * 16);
+    const size_t tile = (size_t)kTile * Geo<D>::kPitch;
+    const size_t smem = (p.vin_heads != p.Hq ? 2 : 1) * KT * tile + (size_t)kTile * KT * 16 + kWavesPerBlock * tile;
     const dim3 grid((unsigned)(p.Hq / kWavesPerBlock), tp.tiles_lo, (unsigned)p.B * tp.tiles_hi);
     hipLaunchKernelGGL((mfma_fwd_shared_kernel<D, KT>), grid, dim3(kWavesPerBlock * 64), smem, s, p, tp);
     return hipGetLastError();
