@@ -288,7 +288,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
 // every wave reads its MFMA operands from there (K: row reads; V: ds_read_b64_tr_b16).
 // This quarters the K/V traffic between L2 and the compute unit; a per-head value input
 // (a previous O) still goes through the wave's private transit tile.
-template <int D, int KT>
+// VS: the value input is shared too (first hop).  Then the private tile only carries Q in and O
+// out, one lane per row, and is used in two halves of 16 rows to halve its LDS footprint.
+template <int D, int KT, bool VS>
 __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel(HopParams p, TileParams tp) {
     using G = Geo<D>;
     constexpr int kRows = kTile * KT;
@@ -305,7 +307,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
     if (tt >= tp.tiles) return;                                             // the whole workgroup leaves together
     const int b = (int)zb;
     const int g = h / p.G;
-    const bool v_shared = (p.vin_heads != p.Hq);
+    constexpr bool v_shared = VS;
+    constexpr int kHalves = VS ? 2 : 1;                                     // passes through the private tile per 32 rows
+    constexpr int kHalfRows = kTile / kHalves;
+    constexpr int kHalfPasses = G::kPasses / kHalves;
     const int hv = v_shared ? g : h;
     const int n = p.n;
 
@@ -314,7 +319,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
     char* sK = smem;
     char* sV = smem + KT * kTileBytes;
     u32x4* rowoff = reinterpret_cast<u32x4*>(smem + (v_shared ? 2 : 1) * KT * kTileBytes);
-    char* buf = reinterpret_cast<char*>(rowoff + kRows) + w * kTileBytes;
+    char* buf = reinterpret_cast<char*>(rowoff + kRows) + w * (kTileBytes / kHalves);
 
     uint32_t f0;
     int qt, rows_valid;
@@ -402,9 +407,15 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
         }
     }
     u32x4 qop[G::kKSteps];
-    stage_rows<D>(stg, qreg);
-    lds_wave_sync();
-    read_natural<D>(buf + opoff, qop);
+#pragma unroll
+    for (int hs = 0; hs < kHalves; ++hs) {
+        if (hs) lds_wave_sync();
+#pragma unroll
+        for (int i = 0; i < kHalfPasses; ++i)
+            *reinterpret_cast<u32x4*>(stg + i * G::kRowsPerPass * G::kPitch) = qreg[hs * kHalfPasses + i];
+        lds_wave_sync();
+        if (r32 / kHalfRows == hs) read_natural<D>(buf + (r32 % kHalfRows) * G::kPitch + hf * 16, qop);
+    }
     __syncthreads();                                                        // shared tiles complete
 
     // ---- S^T = K Q^T per key tile -----------------------------------------------------------
@@ -486,31 +497,39 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
 
     // ---- normalise, round, transpose through the private tile, store ---------------------------------
 #pragma unroll
-    for (int t = 0; t < G::kDTiles; ++t)
+    for (int hs = 0; hs < kHalves; ++hs) {
+        if (r32 / kHalfRows == hs) {
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            u32x2 v;
-            v.x = pack_bf16x2(ot[t][4 * q4] * inv, ot[t][4 * q4 + 1] * inv);
-            v.y = pack_bf16x2(ot[t][4 * q4 + 2] * inv, ot[t][4 * q4 + 3] * inv);
-            *reinterpret_cast<u32x2*>(buf + r32 * G::kPitch + (32 * t + 8 * q4 + 4 * hf) * 2) = v;
-        }
-    lds_wave_sync();
+            for (int t = 0; t < G::kDTiles; ++t)
 #pragma unroll
-    for (int i = 0; i < G::kPasses; ++i) {
-        const int row = qt * kTile + i * G::kRowsPerPass + lrow;
-        if (row < rows_valid) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
-            *reinterpret_cast<u32x4*>(ob + ooff[i]) = v;
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    u32x2 v;
+                    v.x = pack_bf16x2(ot[t][4 * q4] * inv, ot[t][4 * q4 + 1] * inv);
+                    v.y = pack_bf16x2(ot[t][4 * q4 + 2] * inv, ot[t][4 * q4 + 3] * inv);
+                    *reinterpret_cast<u32x2*>(buf + (r32 % kHalfRows) * G::kPitch + (32 * t + 8 * q4 + 4 * hf) * 2) = v;
+                }
         }
+        lds_wave_sync();
+#pragma unroll
+        for (int i = 0; i < kHalfPasses; ++i) {
+            const int row = qt * kTile + (hs * kHalfPasses + i) * G::kRowsPerPass + lrow;
+            if (row < rows_valid) {
+                const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
+                *reinterpret_cast<u32x4*>(ob + ooff[hs * kHalfPasses + i]) = v;
+            }
+        }
+        lds_wave_sync();
     }
 }
 
 template <int D, int KT>
 hipError_t launch_shared(const HopParams& p, const TileParams& tp, hipStream_t s) {
     const size_t tile = (size_t)kTile * Geo<D>::kPitch;
-    const size_t smem = (p.vin_heads != p.Hq ? 2 : 1) * KT * tile + (size_t)kTile * KT * 16 + kWavesPerBlock * tile;
+    const bool vs = p.vin_heads != p.Hq;
+    const size_t smem = (vs ? 2 : 1) * KT * tile + (size_t)kTile * KT * 16 + kWavesPerBlock * (vs ? tile / 2 : tile);
     const dim3 grid((unsigned)(p.Hq / kWavesPerBlock), tp.tiles_lo, (unsigned)p.B * tp.tiles_hi);
-    hipLaunchKernelGGL((mfma_fwd_shared_kernel<D, KT>), grid, dim3(kWavesPerBlock * 64), smem, s, p, tp);
+    if (vs) hipLaunchKernelGGL((mfma_fwd_shared_kernel<D, KT, true>), grid, dim3(kWavesPerBlock * 64), smem, s, p, tp);
+    else hipLaunchKernelGGL((mfma_fwd_shared_kernel<D, KT, false>), grid, dim3(kWavesPerBlock * 64), smem, s, p, tp);
     return hipGetLastError();
 }
 
