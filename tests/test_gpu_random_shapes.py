@@ -1,0 +1,62 @@
+"""GPU parity on seeded random configurations: tensor order, axis lengths (crossing the 32- and
+64-row kernel boundaries), head counts, head width, masks and dtype are all drawn at random, so
+that every kernel variant and their dispatch rules are exercised in combinations nobody
+hand-picked.  Forward always; backward when the shape has a backward kernel."""
+import numpy as np
+import pytest
+
+import paper_2410_20926_amd as ta
+from gpu_util import TOL, multihop_backward, multihop_forward, ta_dtype
+from oracle import tensattn_oracle as orc
+from paper_2410_20926_amd.workloads import make_inputs
+from test_gpu_backward import check_grad
+
+pytestmark = pytest.mark.gpu
+
+
+def draw_case(seed):
+    rng = np.random.default_rng(seed)
+    order = int(rng.integers(1, 5))
+    pools = [[1, 2, 3, 5, 8, 16, 17, 31, 32], [33, 40, 48, 64], [65, 96, 130]]
+    dims = []
+    for _ in range(order):
+        pool = pools[int(rng.choice(3, p=[0.7, 0.2, 0.1]))]
+        dims.append(int(rng.choice(pool)))
+    while int(np.prod(dims)) > 20000:                     # keep the oracle quick
+        dims[int(np.argmax(dims))] = max(1, max(dims) // 2)
+    Hkv = int(rng.choice([1, 2, 3]))
+    G = int(rng.choice([1, 2, 4, 8]))
+    dtype = "bf16" if rng.random() < 0.75 else "f32"
+    D = int(rng.choice([64, 128])) if dtype == "bf16" and rng.random() < 0.85 else int(rng.choice([8, 40, 64, 256]))
+    causal = bool(rng.integers(0, 2))
+    window = [int(rng.integers(1, n + 2)) if rng.random() < 0.3 else 0 for n in dims]
+    N = int(np.prod(dims))
+    valid_len = int(rng.integers(1, N + 1)) if rng.random() < 0.3 else None
+    B = int(rng.choice([1, 2]))
+    return dict(dims=tuple(dims), B=B, Hq=Hkv * G, Hkv=Hkv, D=D, dtype=dtype, causal=causal,
+                window=tuple(window), valid_len=valid_len)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_configuration(seed):
+    c = draw_case(9000 + seed)
+    N = int(np.prod(c["dims"]))
+    q, k, v, d_o = make_inputs(c["B"], N, c["Hq"], c["Hkv"], c["D"], seed=seed, dtype=c["dtype"], with_grad=True)
+    kw = dict(window=c["window"])
+    if c["valid_len"] is not None:
+        kw["valid_len"] = c["valid_len"]
+    got, plan, dev = multihop_forward(q, k, v, c["dims"], c["dtype"], c["causal"], save=True, **kw)
+    ref = orc.tensorized_attention_forward(q, k, v, c["dims"], c["causal"], window=c["window"], valid_len=c["valid_len"])
+    assert np.isfinite(got).all(), c
+    err = np.abs(got - ref).max()
+    assert err <= TOL[c["dtype"]], f"{c}: forward max-abs error {err:.3e}"
+    m = len(c["dims"])
+    kernels = [plan.hop_backward_kernel(plan.hop_axis(p), 0 if p == 0 else 1) for p in range(m)]
+    if "unsupported" in kernels:
+        return
+    dq, dk, dv = multihop_backward(plan, dev, d_o, c["dtype"])
+    rq, rk, rv = orc.tensorized_attention_backward(q, k, v, d_o, c["dims"], c["causal"], window=c["window"],
+                                                   valid_len=c["valid_len"])
+    check_grad(dq, rq, c["dtype"], f"{c} dq")
+    check_grad(dk, rk, c["dtype"], f"{c} dk")
+    check_grad(dv, rv, c["dtype"], f"{c} dv")
