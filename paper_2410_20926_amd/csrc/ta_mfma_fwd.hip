@@ -366,7 +366,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
 #pragma unroll
     for (int i = 0; i < G::kPasses; ++i) {
         const u32x4 off = rowoff[qt * kTile + i * G::kRowsPerPass + lrow];
-        qreg[i] = *reinterpret_cast<const u32x4*>(qb + (off.x + lbyte));
+        qreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (off.x + lbyte)));
         ooff[i] = off.w + lbyte;
     }
 #pragma unroll
@@ -382,7 +382,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
 #pragma unroll
                 for (int i = 0; i < G::kPasses; ++i) {
                     const u32x4 off = rowoff[j * kTile + i * G::kRowsPerPass + lrow];
-                    vreg[j][i] = *reinterpret_cast<const u32x4*>(vb + (off.z + lbyte));
+                    vreg[j][i] = (KT == 1) ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + (off.z + lbyte)))
+                                           : *reinterpret_cast<const u32x4*>(vb + (off.z + lbyte));   // with two query tiles a value tile is read twice: keep it cached
                 }
             }
         }
@@ -515,7 +516,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
             const int row = qt * kTile + (hs * kHalfPasses + i) * G::kRowsPerPass + lrow;
             if (row < rows_valid) {
                 const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
-                *reinterpret_cast<u32x4*>(ob + ooff[hs * kHalfPasses + i]) = v;
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(ob + ooff[hs * kHalfPasses + i]));
             }
         }
         lds_wave_sync();
