@@ -50,7 +50,7 @@ __device__ inline void prefetch_tile(u32x4 (&old)[Geo<D>::kDTiles * 2], const u3
     for (int half = 0; half < Geo<D>::kDTiles / 2; ++half)
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            old[half * 4 + i] = *reinterpret_cast<const u32x4*>(gbase + tile_out_offset<D>(rowoff, which, half, i, lane));
+            old[half * 4 + i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gbase + tile_out_offset<D>(rowoff, which, half, i, lane)));
 }
 
 // acc[t][r] holds (row = lane % 32, feature 32 t + 8 (r/4) + 4 hf + r % 4).  Multiplies by
@@ -85,8 +85,9 @@ __device__ inline void store_tile(const f32x16 (&acc)[Geo<D>::kDTiles], float mu
 #pragma unroll
                     for (int e = 0; e < 4; ++e) { y[2 * e] += bf16_lo(o[e]); y[2 * e + 1] += bf16_hi(o[e]); }
                 }
-                *reinterpret_cast<u32x4*>(gbase + tile_out_offset<D>(rowoff, which, half, i, lane)) =
-                    u32x4{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])};
+                __builtin_nontemporal_store(
+                    u32x4{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])},
+                    reinterpret_cast<u32x4*>(gbase + tile_out_offset<D>(rowoff, which, half, i, lane)));
             }
         }
         lds_wave_sync();
@@ -187,10 +188,12 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
 #pragma unroll
     for (int i = 0; i < G::kPasses; ++i) {
         const u32x4 off = rowoff[i * G::kRowsPerPass + lrow];
-        qraw[i] = *reinterpret_cast<const u32x4*>(qb + (off.x + lbyte));
+        // Rows read by this wave alone are streamed; rows every wave of the group reads stay cached.
+        qraw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (off.x + lbyte)));
         kraw[i] = *reinterpret_cast<const u32x4*>(kb + (off.y + lbyte));
-        xraw[i] = *reinterpret_cast<const u32x4*>(xb + (off.z + lbyte));
-        graw[i] = *reinterpret_cast<const u32x4*>(gb + (off.w + lbyte));
+        xraw[i] = vin_is_o ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xb + (off.z + lbyte)))
+                           : *reinterpret_cast<const u32x4*>(xb + (off.z + lbyte));
+        graw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gb + (off.w + lbyte)));
     }
     __builtin_amdgcn_sched_barrier(0);
 
