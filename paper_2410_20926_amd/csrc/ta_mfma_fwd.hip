@@ -101,6 +101,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
     // Lane (lrow, lcol) loads chunk lcol of rows i * kRowsPerPass + lrow of every tile.
     // Q, every K tile and the first V tile are requested here, before the first wait; a
     // second V tile is requested as soon as the first K tile has left its registers.
+    // Rows that no other wave reads (Q always; K and V rows of a one-tile fibre whose head
+    // is not shared by a group) are streamed past the caches, and so is O.
+    const bool k_once = (KT == 1) && p.G == 1;
+    const bool v_once = (KT == 1) && (p.G == 1 || p.vin_heads == p.Hq);
     u32x4 qreg[G::kPasses], kreg[KT][G::kPasses], vreg[KT][G::kPasses];
     uint32_t ooff[G::kPasses], voff[KT][G::kPasses];
 #pragma unroll
@@ -109,11 +113,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
 #pragma unroll
             for (int i = 0; i < G::kPasses; ++i) {
                 const u32x4 off = rowoff[j * kTile + i * G::kRowsPerPass + lrow];
-                kreg[j][i] = *reinterpret_cast<const u32x4*>(kb + (off.y + lbyte));
+                kreg[j][i] = k_once ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + (off.y + lbyte)))
+                                    : *reinterpret_cast<const u32x4*>(kb + (off.y + lbyte));
                 voff[j][i] = off.z + lbyte;
-                if (j == 0) vreg[j][i] = *reinterpret_cast<const u32x4*>(vb + voff[j][i]);
+                if (j == 0) vreg[j][i] = v_once ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + voff[j][i]))
+                                                : *reinterpret_cast<const u32x4*>(vb + voff[j][i]);
                 if (KT == 1) {
-                    qreg[i] = *reinterpret_cast<const u32x4*>(qb + (off.x + lbyte));
+                    qreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (off.x + lbyte)));
                     ooff[i] = off.w + lbyte;
                 }
             }
@@ -123,7 +129,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
 #pragma unroll
         for (int i = 0; i < G::kPasses; ++i) {
             const u32x4 off = rowoff[qt * kTile + i * G::kRowsPerPass + lrow];
-            qreg[i] = *reinterpret_cast<const u32x4*>(qb + (off.x + lbyte));
+            qreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (off.x + lbyte)));
             ooff[i] = off.w + lbyte;
         }
     }
@@ -275,7 +281,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
         const int row = qt * kTile + i * G::kRowsPerPass + lrow;
         if (row < rows_valid) {
             const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
-            *reinterpret_cast<u32x4*>(ob + ooff[i]) = v;
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(ob + ooff[i]));
         }
     }
 }

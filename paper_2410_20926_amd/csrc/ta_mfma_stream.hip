@@ -73,7 +73,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
     for (int i = 0; i < G::kPasses; ++i) {
         const uint32_t rq = (uint32_t)min(qt * kTile + i * G::kRowsPerPass + lrow, n - 1);
         const uint32_t rk = (uint32_t)min(jbeg * kTile + i * G::kRowsPerPass + lrow, n - 1);
-        qreg[i] = *reinterpret_cast<const u32x4*>(qb + (rq * sp.q_step + lbyte));
+        qreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (rq * sp.q_step + lbyte)));   // read by this wave alone
         kreg[i] = *reinterpret_cast<const u32x4*>(kb + (rk * sp.k_step + lbyte));
         vreg[i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
         ooff[i] = rq * sp.o_step + lbyte;
@@ -193,7 +193,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
         const int row = qt * kTile + i * G::kRowsPerPass + lrow;
         if (row < n) {
             const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
-            *reinterpret_cast<u32x4*>(ob + ooff[i]) = v;
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(ob + ooff[i]));
         }
     }
 }
