@@ -230,9 +230,10 @@ const char* ta_plan_hop_kernel(const ta_plan_t* pl, int axis, int vin) {
     switch (pl->kernel_id[axis][vin]) {
         case ta::K_GENERIC: return "generic";
         case ta::K_MFMA_BF16_N16: return "mfma_bf16_n16";
-        // with 4 (or a multiple of 4) query heads per key/value head the group-shared variant runs
-        case ta::K_MFMA_BF16_N32: return pl->G % 4 == 0 ? "mfma_bf16_n32_shared" : "mfma_bf16_n32";
-        case ta::K_MFMA_BF16_N64: return pl->G % 4 == 0 ? "mfma_bf16_n64_shared" : "mfma_bf16_n64";
+        // with 4 (or a multiple of 4) query heads per key/value head the group-shared variant runs;
+        // its instantiation that also shares the value tile (value input per key/value head) is "_kv"
+        case ta::K_MFMA_BF16_N32: return pl->G % 4 != 0 ? "mfma_bf16_n32" : vin == TA_VIN_KV ? "mfma_bf16_n32_shared_kv" : "mfma_bf16_n32_shared";
+        case ta::K_MFMA_BF16_N64: return pl->G % 4 != 0 ? "mfma_bf16_n64" : vin == TA_VIN_KV ? "mfma_bf16_n64_shared_kv" : "mfma_bf16_n64_shared";
         case ta::K_MFMA_BF16_STREAM: return "mfma_bf16_stream";
     }
     return nullptr;
