@@ -28,7 +28,9 @@ Readings taken where the paper is silent:
   - further per-axis masks M_i (Eq. 3 allows any; Sec. 2.1 mentions sparsity masks): a
     band of width w_i along axis i (key c visible from row a iff |a - c| < w_i, and
     c <= a when causal) and padding (tokens at or past `valid_len` are never attended
-    to; their own rows see nothing and come out as zero).
+    to; their own rows see nothing and come out as zero), and an explicit n_i x n_i
+    boolean table per axis (`axis_masks`), all of them intersected; a row left with no
+    visible key comes out as zero.
 
 Parity pins (tests/test_oracle_*.py): d=1 against a library attention
 routine, row sums, brute-force N x N Kronecker-form operator built with scalar
@@ -107,7 +109,8 @@ def attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float,
 
 def axis_attention(q: np.ndarray, k: np.ndarray, o_prev: np.ndarray,
                    dims: Sequence[int], axis: int, scale: float, causal: bool,
-                   return_probs: bool = False, window: int = 0, valid_len: Optional[int] = None):
+                   return_probs: bool = False, window: int = 0, valid_len: Optional[int] = None,
+                   mask: Optional[np.ndarray] = None):
     """One hop of Eq. 4 for one head.
 
     q, k: [N, D]; o_prev: [N, Dv]; N = prod(dims).  Mode-`axis` flattening
@@ -116,7 +119,8 @@ def axis_attention(q: np.ndarray, k: np.ndarray, o_prev: np.ndarray,
     fibre's rows of o_prev; the result is folded back.  Returns o_new [N, Dv]
     and, on request, A_axis with shape dims[:axis] + dims[axis+1:] + (n, n)
     (batch axes in tensor order, then query index, then key index).
-    `window` and `valid_len` add the band and padding masks described above."""
+    `window` and `valid_len` add the band and padding masks described above; `mask`
+    is an explicit M_i, boolean [n, n], True where query row a may attend key c."""
     dims = [int(n) for n in dims]
     N = int(np.prod(dims)) if dims else 1
     q = np.asarray(q, dtype=np.float64)
@@ -135,6 +139,10 @@ def axis_attention(q: np.ndarray, k: np.ndarray, o_prev: np.ndarray,
         real = np.moveaxis((np.arange(N) < valid_len).reshape(dims + [1]), axis, -2)[..., 0]   # [..., n]
         pad = real[..., :, None] & real[..., None, :]
         allowed = pad if allowed is None else (allowed & pad)
+    if mask is not None:
+        mask = np.asarray(mask, dtype=bool)
+        assert mask.shape == (n, n)
+        allowed = mask if allowed is None else (allowed & mask)
     A = _softmax_rows(S, allowed)
     Onew = np.matmul(A, Oi)                                           # [..., n, Dv]
     # mode-i folding
@@ -158,7 +166,8 @@ def tensorized_attention_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
                                  hop_order: Optional[Sequence[int]] = None,
                                  return_intermediates: bool = False,
                                  window: Optional[Sequence[int]] = None,
-                                 valid_len: Optional[int] = None):
+                                 valid_len: Optional[int] = None,
+                                 axis_masks: Optional[Sequence[Optional[np.ndarray]]] = None):
     """Algorithm 1.
 
     q: [B, N, H_q, D]; k, v: [B, N, H_kv, D] (H_q a multiple of H_kv);
@@ -181,6 +190,7 @@ def tensorized_attention_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
         scale = 1.0 / math.sqrt(D)
     order = _hop_order(len(dims), hop_order)
     window = [0] * len(dims) if window is None else [int(x) for x in window]
+    axis_masks = [None] * len(dims) if axis_masks is None else list(axis_masks)
 
     o = np.empty((B, N, Hq, v.shape[3]), dtype=np.float64)
     inter = [np.repeat(v, G, axis=2)] + [np.empty_like(o) for _ in order]
@@ -192,13 +202,13 @@ def tensorized_attention_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
             oh = v[b, :, g, :]                      # Initialise O = V
             for pos, axis in enumerate(order):
                 if return_intermediates:
-                    oh, A = axis_attention(qh, kh, oh, dims, axis, scale, causal, True, window[axis], valid_len)
+                    oh, A = axis_attention(qh, kh, oh, dims, axis, scale, causal, True, window[axis], valid_len, axis_masks[axis])
                     if probs[pos] is None:
                         probs[pos] = np.empty((B, Hq) + A.shape, dtype=np.float64)
                     probs[pos][b, h] = A
                     inter[pos + 1][b, :, h, :] = oh
                 else:
-                    oh = axis_attention(qh, kh, oh, dims, axis, scale, causal, False, window[axis], valid_len)
+                    oh = axis_attention(qh, kh, oh, dims, axis, scale, causal, False, window[axis], valid_len, axis_masks[axis])
             o[b, :, h, :] = oh                      # Vectorise
     if return_intermediates:
         return o, inter, probs
@@ -210,7 +220,8 @@ def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
                                   causal: bool, scale: Optional[float] = None,
                                   hop_order: Optional[Sequence[int]] = None,
                                   window: Optional[Sequence[int]] = None,
-                                  valid_len: Optional[int] = None):
+                                  valid_len: Optional[int] = None,
+                                  axis_masks: Optional[Sequence[Optional[np.ndarray]]] = None):
     """Gradient of L = sum(O * d_o) through Algorithm 1 w.r.t. q, k, v.
 
     Hops are undone in reverse.  For one hop on one fibre with rows Qs, Ks,
@@ -234,7 +245,7 @@ def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
         scale = 1.0 / math.sqrt(D)
     order = _hop_order(len(dims), hop_order)
     _, inter, probs = tensorized_attention_forward(
-        q, k, v, dims, causal, scale, order, return_intermediates=True, window=window, valid_len=valid_len)
+        q, k, v, dims, causal, scale, order, return_intermediates=True, window=window, valid_len=valid_len, axis_masks=axis_masks)
 
     dq = np.zeros_like(q)
     dk = np.zeros_like(k)

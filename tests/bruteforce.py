@@ -25,12 +25,13 @@ def ravel(coords, dims):
     return t
 
 
-def fibre_probs(q, k, dims, axis, fixed, scale, causal, window=0, valid_len=None):
+def fibre_probs(q, k, dims, axis, fixed, scale, causal, window=0, valid_len=None, mask=None):
     """The n x n row-softmax attention of one mode-`axis` fibre (Eq. 4).
     `fixed` gives the coordinates on every axis; its entry at `axis` is ignored.
     q, k: nested lists [N][D].  window > 0: key c is hidden from row a unless
     |a - c| < window; valid_len: tokens at or past it are padding (never a key; their
-    own rows see nothing and get all-zero probabilities)."""
+    own rows see nothing and get all-zero probabilities); mask: nested list [n][n] of
+    truth values, key c hidden from row a where mask[a][c] is false."""
     n = dims[axis]
     tok = []
     for a in range(n):
@@ -43,6 +44,8 @@ def fibre_probs(q, k, dims, axis, fixed, scale, causal, window=0, valid_len=None
         for c in range(n):
             hidden = (causal and c > a) or (window > 0 and abs(a - c) >= window)
             if valid_len is not None and (tok[a] >= valid_len or tok[c] >= valid_len):
+                hidden = True
+            if mask is not None and not mask[a][c]:
                 hidden = True
             if hidden:
                 logits.append(None)
@@ -61,7 +64,7 @@ def fibre_probs(q, k, dims, axis, fixed, scale, causal, window=0, valid_len=None
     return A
 
 
-def hop_matrix(q, k, dims, axis, scale, causal, window=0, valid_len=None):
+def hop_matrix(q, k, dims, axis, scale, causal, window=0, valid_len=None, mask=None):
     """P_axis [N][N]: P[t][u] = A^{(fibre)}[j_axis][k_axis] when tokens t = (j)
     and u = (k) agree on every other axis, else 0."""
     N = 1
@@ -70,7 +73,7 @@ def hop_matrix(q, k, dims, axis, scale, causal, window=0, valid_len=None):
     P = [[0.0] * N for _ in range(N)]
     other = [range(n) if i != axis else range(1) for i, n in enumerate(dims)]
     for fixed in itertools.product(*other):
-        A = fibre_probs(q, k, dims, axis, fixed, scale, causal, window, valid_len)
+        A = fibre_probs(q, k, dims, axis, fixed, scale, causal, window, valid_len, mask)
         for a in range(dims[axis]):
             ca = list(fixed)
             ca[axis] = a
@@ -98,13 +101,14 @@ def matmul(X, Y):
     return out
 
 
-def operator_by_products(q, k, dims, scale, causal, order=None, window=None, valid_len=None):
+def operator_by_products(q, k, dims, scale, causal, order=None, window=None, valid_len=None, axis_masks=None):
     """W = P_{last hop} ... P_{first hop}: the first executed hop is rightmost."""
     order = list(range(len(dims))) if order is None else list(order)
     window = [0] * len(dims) if window is None else list(window)
+    axis_masks = [None] * len(dims) if axis_masks is None else list(axis_masks)
     W = None
     for axis in order:
-        P = hop_matrix(q, k, dims, axis, scale, causal, window[axis], valid_len)
+        P = hop_matrix(q, k, dims, axis, scale, causal, window[axis], valid_len, axis_masks[axis])
         W = P if W is None else matmul(P, W)
     return W
 

@@ -1,5 +1,5 @@
 """Pins for the oracle's additional per-axis masks (band of width w_i, padding past
-valid_len): a library attention routine with an explicit mask at d = 1, the scalar-loop
+valid_len, explicit boolean tables M_i): a library attention routine with an explicit mask at d = 1, the scalar-loop
 brute-force operator, closed forms and invariants (no GPU)."""
 import math
 
@@ -110,3 +110,104 @@ def test_masked_backward_matches_finite_differences(causal, window, valid_len):
             assert abs(fd - g.reshape(-1)[i]) <= 1e-6 * max(1e-3, abs(fd)) + 1e-9
     if valid_len is not None:
         assert (dq[:, valid_len:] == 0).all() and (dk[:, valid_len:] == 0).all() and (dv[:, valid_len:] == 0).all()
+
+
+# ---- explicit per-axis tables M_i -----------------------------------------------------------
+
+def random_mask(rng, n, density=0.6, keep_diagonal=True):
+    m = rng.random((n, n)) < density
+    if keep_diagonal:
+        m |= np.eye(n, dtype=bool)
+    return m
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_order1_explicit_mask_against_library(causal):
+    N, H, D = 23, 2, 8
+    rng = np.random.default_rng(58)
+    q, k, v = rand_qkv(59, 1, N, H, H, D)
+    m = random_mask(rng, N)
+    got = orc.tensorized_attention_forward(q, k, v, [N], causal, axis_masks=[m])
+    full = torch.from_numpy(m & (np.tril(np.ones((N, N), dtype=bool)) if causal else True))
+    tq, tk, tv = (torch.from_numpy(x).permute(0, 2, 1, 3) for x in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=full).permute(0, 2, 1, 3).numpy()
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-12)
+
+
+@pytest.mark.parametrize("dims,causal,masked_axes,valid_len", [
+    ((2, 3, 4), False, (1, 2), None),
+    ((2, 3, 4), True, (0, 2), None),
+    ((3, 4), False, (0, 1), 10),
+])
+def test_explicit_mask_brute_force_operator(dims, causal, masked_axes, valid_len):
+    N, D = int(np.prod(dims)), 5
+    rng = np.random.default_rng(60)
+    q, k, v = rand_qkv(61, 1, N, 1, 1, D)
+    masks = [random_mask(rng, n) if i in masked_axes else None for i, n in enumerate(dims)]
+    scale = 1 / math.sqrt(D)
+    W = np.array(bf.operator_by_products(q[0, :, 0].tolist(), k[0, :, 0].tolist(), list(dims), scale, causal,
+                                         valid_len=valid_len,
+                                         axis_masks=[None if m is None else m.tolist() for m in masks]))
+    got = orc.tensorized_attention_forward(q, k, v, dims, causal, valid_len=valid_len, axis_masks=masks)[0, :, 0]
+    np.testing.assert_allclose(got, W @ v[0, :, 0], rtol=0, atol=1e-12)
+
+
+def test_explicit_masks_that_spell_causal_and_band_give_the_built_in_results():
+    dims = (3, 5, 4)
+    q, k, v = rand_qkv(62, 1, 60, 2, 1, 6)
+    tril = [np.tril(np.ones((n, n), dtype=bool)) for n in dims]
+    np.testing.assert_array_equal(orc.tensorized_attention_forward(q, k, v, dims, False, axis_masks=tril),
+                                  orc.tensorized_attention_forward(q, k, v, dims, True))
+    window = (2, 0, 3)
+    band = [None if w == 0 else np.abs(np.subtract.outer(np.arange(n), np.arange(n))) < w for n, w in zip(dims, window)]
+    np.testing.assert_array_equal(orc.tensorized_attention_forward(q, k, v, dims, True, axis_masks=band),
+                                  orc.tensorized_attention_forward(q, k, v, dims, True, window=window))
+
+
+def test_block_diagonal_mask_on_one_axis_is_the_hop_over_the_last_of_two_axes():
+    """Attention over a single axis of length n1*n2 with the block-diagonal table
+    (blocks of n2) is, by Eq. 4, the hop along the last axis of the (n1, n2) tensor."""
+    n1, n2, D = 4, 5, 6
+    q, k, v = rand_qkv(63, 1, n1 * n2, 1, 1, D)
+    block = np.kron(np.eye(n1, dtype=bool), np.ones((n2, n2), dtype=bool))
+    scale = 1 / math.sqrt(D)
+    for causal in (False, True):
+        one_axis = orc.tensorized_attention_forward(q, k, v, [n1 * n2], causal, axis_masks=[block])
+        hop = orc.axis_attention(q[0, :, 0], k[0, :, 0], v[0, :, 0], [n1, n2], 1, scale, causal)
+        np.testing.assert_allclose(one_axis[0, :, 0], hop, rtol=0, atol=1e-13)
+
+
+def test_fully_hidden_row_is_zero_and_gets_no_gradient():
+    dims, D = (3, 4), 5
+    rng = np.random.default_rng(64)
+    q, k, v = rand_qkv(65, 1, 12, 1, 1, D)
+    m = np.ones((4, 4), dtype=bool); m[2, :] = False                 # row 2 of the last axis sees nothing
+    o = orc.tensorized_attention_forward(q, k, v, dims, False, hop_order=(0, 1), axis_masks=[None, m])
+    assert (o[0, 2::4] == 0).all() and (o[0, 0::4] != 0).any()
+    d_o = rng.standard_normal(q.shape)
+    # with a single axis the hidden row's query takes part in nothing, so its gradient is zero
+    dq, dk, dv = orc.tensorized_attention_backward(q[:, :4], k[:, :4], v[:, :4], d_o[:, :4], (4,), False, axis_masks=[m])
+    assert (dq[0, 2] == 0).all() and (dq[0, 1] != 0).any()
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_explicit_mask_backward_matches_finite_differences(causal):
+    dims, D = (3, 4), 5
+    rng = np.random.default_rng(66)
+    q, k, v = rand_qkv(67, 1, 12, 2, 1, D)
+    masks = [random_mask(rng, 3), random_mask(rng, 4, 0.5)]
+    d_o = rng.standard_normal(q.shape)
+    dq, dk, dv = orc.tensorized_attention_backward(q, k, v, d_o, dims, causal, axis_masks=masks)
+
+    def loss():
+        return float(np.sum(orc.tensorized_attention_forward(q, k, v, dims, causal, axis_masks=masks) * d_o))
+
+    for x, g in ((q, dq), (k, dk), (v, dv)):
+        flat = x.reshape(-1)
+        for i in rng.choice(x.size, size=10, replace=False):
+            old = flat[i]
+            flat[i] = old + 1e-5; fp = loss()
+            flat[i] = old - 1e-5; fm = loss()
+            flat[i] = old
+            fd = (fp - fm) / 2e-5
+            assert abs(fd - g.reshape(-1)[i]) <= 1e-6 * max(1e-3, abs(fd)) + 1e-9
