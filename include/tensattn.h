@@ -71,11 +71,20 @@ typedef struct ta_desc_t {
     int64_t q_strides[3];             /* (batch, token, head) strides of Q, dQ; all 0 = dense [B,N,H_q,D] */
     int64_t kv_strides[3];            /* of K, V, dK, dV; all 0 = dense [B,N,H_kv,D] */
     int64_t o_strides[3];             /* of O, dO and every inter-hop O; all 0 = dense [B,N,H_q,D] */
-    /* Further per-axis masks M_i (Eq. 3 admits any; these two are what this library offers): */
+    /* Further per-axis masks M_i (Eq. 3 admits any; Sec. 2.1 mentions sparsity masks).  All of
+     * them, and `causal`, are intersected; a row left with no visible key gives a zero output
+     * row and takes no gradient. */
     int32_t window[TA_MAX_ORDER];     /* w_i > 0: on axis i key c is visible from row a only if |a - c| < w_i
                                          (together with c <= a when causal); 0 = no band on that axis */
     int64_t valid_len;                /* L in 1..N: tokens t >= L of every batch element are padding - never
                                          attended to, and their own outputs and gradients are zero; 0 = none */
+    const void* axis_mask[TA_MAX_ORDER]; /* DEVICE pointers, or NULL for no table on that axis.  Table of axis i:
+                                         n_i rows of ceil(n_i / 32) uint32 words, row-major; bit (c % 32) of
+                                         word c / 32 of row a is 1 iff query position a may attend key
+                                         position c on that axis (the same table for every fibre, head and
+                                         batch element).  4-byte aligned, caller-owned, read-only, and must
+                                         stay valid and unchanged while the plan is in use; entries at or
+                                         beyond `order` are ignored. */
 } ta_desc_t;
 
 typedef struct ta_plan ta_plan_t;     /* opaque, immutable, host-only, shareable between threads */
@@ -86,7 +95,7 @@ typedef struct ta_plan ta_plan_t;     /* opaque, immutable, host-only, shareable
 /* Validates `desc`, derives per-axis token strides and fibre counts and picks a kernel
  * per hop.  Errors: NULL -> TA_ERR_NULL; order, dims, heads, head_dim, strides
  * inconsistent, valid_len > N -> TA_ERR_SHAPE; bad dtype / hop_order / negative window or
- * valid_len -> TA_ERR_INVALID_ARG; a shape no
+ * valid_len, misaligned axis_mask -> TA_ERR_INVALID_ARG; a shape no
  * kernel covers (head_dim not a multiple of 8 or above 256) -> TA_ERR_UNSUPPORTED. */
 ta_status_t ta_plan_create(const ta_desc_t* desc, ta_plan_t** out_plan);
 void        ta_plan_destroy(ta_plan_t* plan);                 /* NULL-safe */

@@ -97,6 +97,8 @@ ta::HopParams hop_params(const ta_plan* pl, int axis, const void* q, const void*
     hp.scale = pl->scale;
     hp.window = pl->desc.window[axis];
     hp.valid_len = pl->desc.valid_len > 0 ? pl->desc.valid_len : pl->N;
+    hp.mask = static_cast<const uint32_t*>(pl->desc.axis_mask[axis]);
+    hp.mask_words = (pl->dims[axis] + 31) / 32;
     return hp;
 }
 
@@ -129,7 +131,7 @@ const char* ta_last_error_detail(void) { return g_detail; }
 
 void ta_version(int* major, int* minor) {
     if (major) *major = 0;
-    if (minor) *minor = 2;
+    if (minor) *minor = 3;
 }
 
 ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
@@ -153,6 +155,8 @@ ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
     if (N > (int64_t)1 << 40) return fail(TA_ERR_SHAPE, "sequence length overflows");
     for (int i = 0; i < d->order; ++i)
         if (d->window[i] < 0) return fail(TA_ERR_INVALID_ARG, "window[%d] = %d is negative", i, d->window[i]);
+    for (int i = 0; i < d->order; ++i)
+        if (reinterpret_cast<uintptr_t>(d->axis_mask[i]) % 4 != 0) return fail(TA_ERR_INVALID_ARG, "axis_mask[%d] is not 4-byte aligned", i);
     if (d->valid_len < 0) return fail(TA_ERR_INVALID_ARG, "valid_len is negative");
     if (d->valid_len > N) return fail(TA_ERR_SHAPE, "valid_len %lld exceeds the sequence length %lld", (long long)d->valid_len, (long long)N);
     if (d->head_dim % 8 != 0 || d->head_dim > 256)

@@ -64,11 +64,12 @@ __device__ inline void load_tile(float* tile, int pitch, int rows, int r0, const
     }
 }
 
-// M_i[a][c] of this hop: causal triangle, band of width `window`, and padding (rows whose
-// token is at or past valid_len neither see nor are seen).
+// M_i[a][c] of this hop: causal triangle, band of width `window`, the caller's bit table, and
+// padding (rows whose token is at or past valid_len neither see nor are seen).
 __device__ inline bool visible(const HopParams& p, int64_t tok0, int a, int c) {
     if (p.causal && c > a) return false;
     if (p.window > 0 && (a - c >= p.window || c - a >= p.window)) return false;
+    if (p.mask && a < p.n && c < p.n && !((p.mask[(int64_t)a * p.mask_words + (c >> 5)] >> (c & 31)) & 1u)) return false;
     return tok0 + (int64_t)(a > c ? a : c) * p.stride < p.valid_len;
 }
 

@@ -28,6 +28,8 @@ struct HopParams {
     float scale;
     int32_t window;          // band width on this axis, 0 = none
     int64_t valid_len;       // tokens at or past it are padding; equals N when there is none
+    const uint32_t* mask;    // device table of this axis (n rows of mask_words words, bit c of row a = visible) or nullptr
+    int32_t mask_words;      // ceil(n / 32)
 };
 
 struct BwdParams {

@@ -127,7 +127,8 @@ __device__ inline void chain_sum(f32x16 (&acc)[Geo<D>::kDTiles], float* red, int
 }
 
 // blockDim.x = 64 * G (G = query heads per key/value head: 1, 2, 4 or 8); grid = (Hkv, tiles_lo, B * tiles_hi).
-template <int D>
+// TABLE: the axis has a caller's bit table (a separate instantiation keeps the common case free of it).
+template <int D, bool TABLE>
 __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TileParams tp) {
     using G = BGeo<D>;
     const HopParams& p = bp.hop;
@@ -253,8 +254,9 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
     u32x4 dsTop[2];                                       // dS^T as B operands (contraction over keys)
     {
         int lo = 0, hi = 0;
-        if (row_real) visible_range(r32, flo, fhi, p.causal, p.window, lo, hi);
-        const uint32_t vis = (range_mask(lo, hi) & real_rows) >> (4 * hf);
+        uint32_t tw = 0xffffffffu;
+        if (row_real) { visible_range(r32, flo, fhi, p.causal, p.window, lo, hi); if (TABLE) tw = table_word(p, r32 - flo, 0) << flo; }
+        const uint32_t vis = (range_mask(lo, hi) & tw & real_rows) >> (4 * hf);
         float e[16], mx = -INFINITY;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -285,8 +287,9 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
     {
         // query rows that see this lane's key: its own fibre's rows, from itself on when causal
         int lo = 0, hi = 0;
-        if (row_real) seen_range(r32, flo, fhi, p.causal, p.window, lo, hi);
-        const uint32_t vis = (range_mask(lo, hi) & real_rows) >> (4 * hf);
+        uint32_t tw = 0xffffffffu;
+        if (row_real) { seen_range(r32, flo, fhi, p.causal, p.window, lo, hi); if (TABLE) tw = table_column(p, r32 - flo) << flo; }
+        const uint32_t vis = (range_mask(lo, hi) & tw & real_rows) >> (4 * hf);
         float pr[16], ds[16];
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
@@ -349,7 +352,8 @@ hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
     const HopParams& p = bp.hop;
     const size_t smem = (size_t)(p.G > 1 ? BGeo<D>::kRedBytes : 0) + (size_t)p.G * BGeo<D>::kWaveBytes;
     const dim3 grid((unsigned)p.Hkv, tp.tiles_lo, (unsigned)p.B * tp.tiles_hi);
-    hipLaunchKernelGGL((mfma_bwd_kernel<D>), grid, dim3(64 * p.G), smem, s, bp, tp);
+    if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true>), grid, dim3(64 * p.G), smem, s, bp, tp);
+    else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false>), grid, dim3(64 * p.G), smem, s, bp, tp);
     return hipGetLastError();
 }
 

@@ -113,6 +113,20 @@ __device__ inline void seen_range(int row, int flo, int fhi, int causal, int win
     if (window > 0) { lo = max(lo, row - window + 1); hi = min(hi, row + window); }
 }
 
+// The caller's bit table of the axis (row a, word j: keys 32 j .. 32 j + 31 visible from query
+// position a), all ones when there is none.
+__device__ inline uint32_t table_word(const HopParams& p, int a, int j) {
+    return p.mask ? p.mask[a * p.mask_words + j] : 0xffffffffu;
+}
+// Its transpose for key position c of an axis of at most 32 positions: bit a = query
+// position a sees key c.
+__device__ inline uint32_t table_column(const HopParams& p, int c) {
+    if (!p.mask) return 0xffffffffu;
+    uint32_t col = 0;
+    for (int a = 0; a < p.n; ++a) col |= ((p.mask[a] >> c) & 1u) << a;
+    return col;
+}
+
 // Launch geometry computed on the host.
 struct TileParams {
     int32_t fpt;          // fibres per 32-row tile (n <= 32), else 1

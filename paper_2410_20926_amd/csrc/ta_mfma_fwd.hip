@@ -183,13 +183,18 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
     uint32_t vis[KT];
     {
         int lo = 0, hi = 0;                               // visible keys = [lo, hi)
+        uint32_t tw[KT];                                  // the axis table's words for this row, in tile-row coordinates
+#pragma unroll
+        for (int j = 0; j < KT; ++j) tw[j] = 0xffffffffu;
         if ((real_rows >> qrow) & 1) {
             const int flo = (KT == 1) ? (int)((qrow + 0.5f) * tp.inv_n) * n : 0;
             visible_range(qrow, flo, flo + n, p.causal, p.window, lo, hi);
+#pragma unroll
+            for (int j = 0; j < KT; ++j) tw[j] = (KT == 1) ? table_word(p, qrow - flo, 0) << flo : table_word(p, qrow, j);
         }
 #pragma unroll
         for (int j = 0; j < KT; ++j)
-            vis[j] = (range_mask(min(max(lo - 32 * j, 0), 32), min(max(hi - 32 * j, 0), 32)) & (uint32_t)(real_rows >> (32 * j))) >> (4 * hf);
+            vis[j] = (range_mask(min(max(lo - 32 * j, 0), 32), min(max(hi - 32 * j, 0), 32)) & tw[j] & (uint32_t)(real_rows >> (32 * j))) >> (4 * hf);
     }
     const float sl2 = p.scale * kLog2e;
     float mx = -INFINITY;
@@ -441,15 +446,20 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
     // ---- masked row softmax over all key tiles -------------------------------------------------
     const int qrow = qt * kTile + r32;
     int lo = 0, hi = 0;                                                     // visible keys = [lo, hi)
+    uint32_t tw[KT];                                                        // the axis table's words for this row, in tile-row coordinates
+#pragma unroll
+    for (int j = 0; j < KT; ++j) tw[j] = 0xffffffffu;
     if ((real_rows >> qrow) & 1) {
         const int flo = (KT == 1) ? (int)((qrow + 0.5f) * tp.inv_n) * n : 0;
         visible_range(qrow, flo, flo + n, p.causal, p.window, lo, hi);
+#pragma unroll
+        for (int j = 0; j < KT; ++j) tw[j] = (KT == 1) ? table_word(p, qrow - flo, 0) << flo : table_word(p, qrow, j);
     }
     const float sl2 = p.scale * kLog2e;
     float mx = -INFINITY;
 #pragma unroll
     for (int j = 0; j < KT; ++j) {
-        const uint32_t vis = (range_mask(min(max(lo - 32 * j, 0), 32), min(max(hi - 32 * j, 0), 32)) & (uint32_t)(real_rows >> (32 * j))) >> (4 * hf);
+        const uint32_t vis = (range_mask(min(max(lo - 32 * j, 0), 32), min(max(hi - 32 * j, 0), 32)) & tw[j] & (uint32_t)(real_rows >> (32 * j))) >> (4 * hf);
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             const bool ok = (vis >> (8 * (r / 4) + (r % 4))) & 1u;

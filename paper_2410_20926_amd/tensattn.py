@@ -31,6 +31,7 @@ class TaDesc(C.Structure):
         ("scale", C.c_float), ("hop_order", C.c_int32 * TA_MAX_ORDER),
         ("q_strides", C.c_int64 * 3), ("kv_strides", C.c_int64 * 3), ("o_strides", C.c_int64 * 3),
         ("window", C.c_int32 * TA_MAX_ORDER), ("valid_len", C.c_int64),
+        ("axis_mask", C.c_void_p * TA_MAX_ORDER),
     ]
 
 
@@ -128,7 +129,9 @@ def _stream(stream) -> Optional[int]:
 def make_desc(batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dims: Sequence[int], dtype: int,
               causal: bool, scale: float = 0.0, hop_order: Optional[Sequence[int]] = None,
               q_strides=None, kv_strides=None, o_strides=None, window: Optional[Sequence[int]] = None,
-              valid_len: int = 0) -> TaDesc:
+              valid_len: int = 0, axis_masks: Optional[Sequence] = None) -> TaDesc:
+    """`axis_masks`: per axis None or a device tensor of packed bit rows (see pack_axis_mask);
+    the descriptor keeps a reference to each so the memory outlives the plan."""
     d = TaDesc()
     d.batch, d.n_q_heads, d.n_kv_heads, d.head_dim = batch, n_q_heads, n_kv_heads, head_dim
     d.order = len(dims)
@@ -142,11 +145,31 @@ def make_desc(batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dims: 
     for j in range(TA_MAX_ORDER):
         d.window[j] = int(window[j]) if window is not None and j < len(window) else 0
     d.valid_len = int(valid_len)
+    d._mask_refs = []
+    for j in range(TA_MAX_ORDER):
+        t = axis_masks[j] if axis_masks is not None and j < len(axis_masks) else None
+        d.axis_mask[j] = _ptr(t) if t is not None else None
+        d._mask_refs.append(t)
     for name, s in (("q_strides", q_strides), ("kv_strides", kv_strides), ("o_strides", o_strides)):
         arr = getattr(d, name)
         for j in range(3):
             arr[j] = int(s[j]) if s is not None else 0
     return d
+
+
+def pack_axis_mask(mask):
+    """Packs a boolean [n, n] table (row a, column c true = query position a may attend key
+    position c) into the library's layout: uint32 [n, ceil(n / 32)], bit c % 32 of word c / 32.
+    Returns a host array (viewed as int32, which torch can hold); move it to the device and
+    pass it in `axis_masks`."""
+    import numpy as np
+    m = np.asarray(mask, dtype=bool)
+    n = m.shape[0]
+    assert m.shape == (n, n)
+    words = (n + 31) // 32
+    padded = np.zeros((n, words * 32), dtype=bool)
+    padded[:, :n] = m
+    return np.packbits(padded.reshape(n, words, 32), axis=-1, bitorder="little").view(np.uint32).reshape(n, words).view(np.int32)
 
 
 class Plan:

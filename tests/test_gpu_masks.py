@@ -1,8 +1,11 @@
-"""GPU parity for the per-axis band mask (window) and the padding mask (valid_len),
-forward and backward, across every kernel variant, against the masked oracle."""
+"""GPU parity for the per-axis band mask (window), the padding mask (valid_len) and explicit
+per-axis bit tables, forward and backward, across every kernel variant, against the masked
+oracle."""
 import numpy as np
 import pytest
+import torch
 
+import paper_2410_20926_amd as ta
 from gpu_util import TOL, multihop_backward, multihop_forward
 from oracle import tensattn_oracle as orc
 from paper_2410_20926_amd.workloads import make_inputs
@@ -60,3 +63,86 @@ def test_masked_backward_matches_oracle(dims, B, Hq, Hkv, D, causal, dtype, wind
     check_grad(dv, rv, dtype, "dv")
     if valid_len is not None:
         assert (dq[:, valid_len:] == 0).all() and (dk[:, valid_len:] == 0).all() and (dv[:, valid_len:] == 0).all()
+
+
+# ---- explicit per-axis tables ----------------------------------------------------------------
+
+TABLE_CASES = [
+    # dims, B, Hq, Hkv, D, causal, dtype, axes with a table, window, valid_len
+    ((5, 3, 7), 2, 4, 2, 40, True, "f32", (0, 2), None, None),            # generic kernels
+    ((6, 40), 1, 2, 1, 64, False, "f32", (1,), (0, 30), 230),             # two-word rows
+    ((32, 16), 1, 2, 2, 128, True, "bf16", (0, 1), None, None),           # MFMA, plain variant, packed fibres on axis 1
+    ((16, 32), 2, 3, 3, 128, False, "bf16", (1,), (0, 20), 300),
+    ((8, 32, 4), 1, 4, 1, 128, True, "bf16", (0, 1, 2), None, 801),       # group-shared variant
+    ((32, 32), 1, 8, 2, 64, False, "bf16", (0,), None, None),
+    ((64, 8), 1, 4, 1, 128, True, "bf16", (0, 1), None, 411),             # two key tiles, two-word rows
+    ((48, 6), 1, 2, 2, 128, False, "bf16", (0,), (40, 0), None),
+    ((200, 3), 1, 4, 1, 128, True, "bf16", (0,), None, 500),              # streaming kernel, 7-word rows
+    ((3, 130), 1, 2, 2, 64, False, "bf16", (1,), (0, 90), None),
+]
+
+
+def make_tables(dims, axes, seed):
+    """Random tables at 60 % density with the diagonal kept, plus one fully hidden row on the
+    first masked axis (its outputs must be zero after that hop)."""
+    rng = np.random.default_rng(seed)
+    host, dev = [], []
+    for i, n in enumerate(dims):
+        if i not in axes:
+            host.append(None); dev.append(None)
+            continue
+        m = (rng.random((n, n)) < 0.6) | np.eye(n, dtype=bool)
+        if i == axes[0] and n > 2:
+            m[n // 2, :] = False
+        host.append(m)
+        dev.append(torch.from_numpy(ta.pack_axis_mask(m)).cuda())
+    return host, dev
+
+
+@pytest.mark.parametrize("dims,B,Hq,Hkv,D,causal,dtype,axes,window,valid_len", TABLE_CASES)
+def test_table_forward_matches_oracle(dims, B, Hq, Hkv, D, causal, dtype, axes, window, valid_len):
+    N = int(np.prod(dims))
+    q, k, v = make_inputs(B, N, Hq, Hkv, D, seed=5000 + N + D, dtype=dtype)
+    host, dev = make_tables(dims, axes, 5100 + N)
+    kw = dict(axis_masks=dev)
+    if window is not None:
+        kw["window"] = window
+    if valid_len is not None:
+        kw["valid_len"] = valid_len
+    got, plan, _ = multihop_forward(q, k, v, dims, dtype, causal, **kw)
+    ref = orc.tensorized_attention_forward(q, k, v, dims, causal, window=window, valid_len=valid_len, axis_masks=host)
+    assert np.isfinite(got).all()
+    err = np.abs(got - ref).max()
+    assert err <= TOL[dtype], f"max-abs error {err:.3e}"
+
+
+TABLE_BWD_CASES = [c for c in TABLE_CASES if max(c[0]) <= 70]
+
+
+@pytest.mark.parametrize("dims,B,Hq,Hkv,D,causal,dtype,axes,window,valid_len", TABLE_BWD_CASES)
+def test_table_backward_matches_oracle(dims, B, Hq, Hkv, D, causal, dtype, axes, window, valid_len):
+    N = int(np.prod(dims))
+    q, k, v, d_o = make_inputs(B, N, Hq, Hkv, D, seed=6000 + N + D, dtype=dtype, with_grad=True)
+    host, dev = make_tables(dims, axes, 6100 + N)
+    kw = dict(axis_masks=dev)
+    if window is not None:
+        kw["window"] = window
+    if valid_len is not None:
+        kw["valid_len"] = valid_len
+    _, plan, devt = multihop_forward(q, k, v, dims, dtype, causal, save=True, **kw)
+    dq, dk, dv = multihop_backward(plan, devt, d_o, dtype)
+    rq, rk, rv = orc.tensorized_attention_backward(q, k, v, d_o, dims, causal, window=window, valid_len=valid_len,
+                                                   axis_masks=host)
+    check_grad(dq, rq, dtype, "dq")
+    check_grad(dk, rk, dtype, "dk")
+    check_grad(dv, rv, dtype, "dv")
+
+
+def test_table_spelling_causal_is_bit_identical_to_the_causal_flag():
+    dims, B, Hq, Hkv, D = (32, 32, 32), 1, 8, 2, 128
+    N = int(np.prod(dims))
+    q, k, v = make_inputs(B, N, Hq, Hkv, D, seed=7000, dtype="bf16")
+    tril = [torch.from_numpy(ta.pack_axis_mask(np.tril(np.ones((n, n), dtype=bool)))).cuda() for n in dims]
+    a, _, _ = multihop_forward(q, k, v, dims, "bf16", True)
+    b, _, _ = multihop_forward(q, k, v, dims, "bf16", False, axis_masks=tril)
+    assert np.array_equal(a, b)
