@@ -94,7 +94,9 @@ def time_steps(torch, ta, plan, sets, wsb, scb, backward, steps, warmup):
 def time_hops(torch, ta, plan, sets, w, steps):
     """HIP-event duration of every per-axis launch, on the stream the kernels run on
     (torch's current stream, which the binding hands to the library).  Returns a list of
-    records (direction, hop position, axis, value-input kind, seconds)."""
+    records (direction, hop position, axis, value-input kind, seconds); direction "fwd2" is the
+    fused launch of two hops (the one at `axis` and the next), which the inference forward uses
+    for its last two hops when the plan offers it."""
     B, N, Hq, D = w.batch, w.seq_len, w.n_q_heads, w.head_dim
     m = len(w.dims)
     o_elems = B * N * Hq * D
@@ -114,12 +116,16 @@ def time_hops(torch, ta, plan, sets, w, steps):
     for i in range(steps):
         st = sets[i % len(sets)]
         q, k, v, o, ws = st["q"], st["k"], st["v"], st["o"], st["ws"]
-        inter = [view(ws, j) for j in range(m - 1)] if w.backward else [view(ws, j) for j in range(min(2, m - 1))]
+        inter = [view(ws, j) for j in range(ws.numel() // ob)]    # as many inter-hop buffers as the plan asked for
         srcs = []
         cur, kind = v, ta.TA_VIN_KV
+        fused = -1 if w.backward else plan.fused_position()
         for pos in range(m):
-            dst = o if pos == m - 1 else (inter[pos] if w.backward else inter[pos & 1])
             axis = plan.hop_axis(pos)
+            if pos == fused:
+                timed(("fwd2", pos, axis, kind), lambda: ta.ta_axis_pair_attn_forward(plan, axis, q, k, cur, kind, o))
+                break
+            dst = o if pos == m - 1 else (inter[pos] if w.backward else inter[pos % len(inter)])
             timed(("fwd", pos, axis, kind), lambda: ta.ta_axis_attn_forward(plan, axis, q, k, cur, kind, dst))
             srcs.append((cur, kind))
             cur, kind = dst, ta.TA_VIN_O
@@ -192,10 +198,15 @@ def measure(torch, ta, w, args, steps, warmup):
     kernel_totals = {}                                   # kernel name -> [bytes, seconds, launches]
     for (d, pos, axis, kind), ts in groups.items():
         bwd = d == "bwd"
-        nbytes = plan.hop_bytes(axis, kind, bwd, bwd and pos != m - 1)
-        flops = plan.hop_flops(axis, bwd)
+        if d == "fwd2":
+            nbytes = plan.pair_bytes(axis, kind)
+            flops = plan.hop_flops(axis, False) + plan.hop_flops(axis + 1, False)
+            name = plan.pair_kernel(axis, kind)
+        else:
+            nbytes = plan.hop_bytes(axis, kind, bwd, bwd and pos != m - 1)
+            flops = plan.hop_flops(axis, bwd)
+            name = plan.hop_backward_kernel(axis, kind) if bwd else plan.hop_kernel(axis, kind)
         avg = sum(ts) / len(ts)
-        name = plan.hop_backward_kernel(axis, kind) if bwd else plan.hop_kernel(axis, kind)
         gbs = nbytes / avg / 1e9
         hops.append({"pass": d, "hop": pos, "axis": axis, "n": w.dims[axis], "kernel": name, "us": round(avg * 1e6, 2),
                      "algorithmic_bytes": nbytes, "GBps": round(gbs, 1), "frac_of_8TBps": round(gbs / HBM_PEAK_GBS, 4),

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtensattn.so")
-SOURCES = ["ta_api.hip", "ta_generic.hip", "ta_mfma_fwd.hip", "ta_mfma_bwd.hip", "ta_mfma_stream.hip", "ta_rope.hip"]
+SOURCES = ["ta_api.hip", "ta_generic.hip", "ta_mfma_fwd.hip", "ta_mfma_bwd.hip", "ta_mfma_stream.hip", "ta_mfma_pair.hip", "ta_rope.hip"]
 
 
 def hipcc() -> str:

@@ -256,6 +256,30 @@ const char* ta_plan_hop_backward_kernel(const ta_plan_t* pl, int axis, int vin) 
     return ta::generic_backward_supports(pl->dims[axis], pl->G, pl->desc.head_dim) ? "generic" : "unsupported";
 }
 
+static bool pair_ok(const ta_plan* pl, int axis, int vin) {
+    if (axis < 0 || axis + 1 >= pl->order) return false;
+    const ta::HopParams h1 = hop_params(pl, axis, nullptr, nullptr, nullptr, vin, nullptr);
+    const ta::HopParams h2 = hop_params(pl, axis + 1, nullptr, nullptr, nullptr, vin, nullptr);
+    return ta::mfma_pair_supports(h1, h2, pl->desc.dtype);
+}
+
+const char* ta_plan_pair_kernel(const ta_plan_t* pl, int axis, int vin) {
+    if (!pl || axis < 0 || axis >= pl->order || (vin != 0 && vin != 1)) return nullptr;
+    return pair_ok(pl, axis, vin) ? "mfma_bf16_pair_n32" : "unsupported";
+}
+
+double ta_plan_pair_bytes(const ta_plan_t* pl, int axis, int vin) {
+    // one pass: Q, K and the value input read once, O written once
+    return ta_plan_hop_bytes(pl, axis, vin, 0, 0);
+}
+
+int ta_plan_fused_position(const ta_plan_t* pl) {
+    if (!pl || pl->order < 2) return -1;
+    const int m = pl->order;
+    if (pl->hop_axis[m - 2] != m - 2 || pl->hop_axis[m - 1] != m - 1) return -1;
+    return pair_ok(pl, m - 2, m == 2 ? TA_VIN_KV : TA_VIN_O) ? m - 2 : -1;
+}
+
 double ta_plan_hop_bytes(const ta_plan_t* pl, int axis, int vin, int backward, int accumulate) {
     if (!pl || axis < 0 || axis >= pl->order || (vin != 0 && vin != 1)) return -1.0;
     const double per_head = (double)pl->desc.batch * (double)pl->N * pl->desc.head_dim * pl->elem;
@@ -276,7 +300,9 @@ double ta_plan_hop_flops(const ta_plan_t* pl, int axis, int backward) {
 
 size_t ta_plan_workspace_bytes(const ta_plan_t* pl, int save_for_backward) {
     if (!pl || pl->order <= 1) return 0;
-    const int nbuf = save_for_backward ? pl->order - 1 : (pl->order == 2 ? 1 : 2);
+    // hops that write an intermediate O: all but the last, and one fewer when the last two run fused
+    const int writers = pl->order - 1 - (!save_for_backward && ta_plan_fused_position(pl) >= 0 ? 1 : 0);
+    const int nbuf = save_for_backward ? writers : (writers < 2 ? writers : 2);
     return (size_t)nbuf * pl->o_buf_bytes;
 }
 
@@ -307,6 +333,32 @@ ta_status_t ta_axis_attn_forward(const ta_plan_t* pl, int axis, const void* q, c
     hipError_t e = kid == ta::K_GENERIC ? ta::launch_generic_forward(hp, d.dtype, (hipStream_t)stream)
                                         : ta::launch_mfma_forward(hp, kid, (hipStream_t)stream);
     if (e != hipSuccess) return fail(TA_ERR_DEVICE, "forward launch failed: %s", hipGetErrorString(e));
+    return TA_OK;
+}
+
+ta_status_t ta_axis_pair_attn_forward(const ta_plan_t* pl, int axis, const void* q, const void* k, const void* v_in,
+                                      int vin, void* o_out, void* stream) {
+    g_detail[0] = 0;
+    ta_status_t st = check_axis_vin(pl, axis, vin);
+    if (st != TA_OK) return st;
+    if (axis + 1 >= pl->order) return fail(TA_ERR_INVALID_ARG, "axis %d has no inner neighbour", axis);
+    if (!q || !k || !v_in || !o_out) return fail(TA_ERR_NULL, "q, k, v_in or o_out is NULL");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v_in) || !aligned16(o_out))
+        return fail(TA_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
+    const ta_desc_t& d = pl->desc;
+    const Range ro = span_of(o_out, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
+    const Range rq = span_of(q, pl->qs, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
+    const Range rk = span_of(k, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem);
+    const Range rv = vin == TA_VIN_KV ? span_of(v_in, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem)
+                                      : span_of(v_in, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
+    if (overlaps(ro, rq) || overlaps(ro, rk) || overlaps(ro, rv))
+        return fail(TA_ERR_ALIAS, "o_out overlaps an input");
+    const ta::HopParams h1 = hop_params(pl, axis, q, k, v_in, vin, o_out);
+    const ta::HopParams h2 = hop_params(pl, axis + 1, q, k, v_in, vin, o_out);
+    if (!ta::mfma_pair_supports(h1, h2, d.dtype))
+        return fail(TA_ERR_UNSUPPORTED, "no fused kernel for axes %d and %d of this plan (needs bf16, head_dim 128, the two innermost axes both of length 32, no padding)", axis, axis + 1);
+    hipError_t e = ta::launch_mfma_forward_pair(h1, h2, (hipStream_t)stream);
+    if (e != hipSuccess) return fail(TA_ERR_DEVICE, "fused forward launch failed: %s", hipGetErrorString(e));
     return TA_OK;
 }
 
@@ -379,7 +431,10 @@ ta_status_t ta_multihop_forward(const ta_plan_t* pl, const void* q, const void* 
     char* ws = static_cast<char*>(workspace);
     const void* cur = v;
     int cur_kind = TA_VIN_KV;
+    const int fused = save_for_backward ? -1 : ta_plan_fused_position(pl);
     for (int pos = 0; pos < m; ++pos) {
+        if (pos == fused)                                  // the last two hops in one launch, no intermediate O
+            return ta_axis_pair_attn_forward(pl, pl->hop_axis[pos], q, k, cur, cur_kind, o, stream);
         void* dst;
         if (pos == m - 1) dst = o;
         else if (save_for_backward) dst = ws + (size_t)pos * pl->o_buf_bytes;

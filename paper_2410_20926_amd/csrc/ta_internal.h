@@ -79,6 +79,9 @@ bool       mfma_forward_supports(int32_t n, int32_t D, int dtype, int* kernel_id
 bool       mfma_forward_layout_ok(const HopParams& p);   // strides and sizes fit the kernel's 32-bit row offsets
 bool       mfma_backward_supports(const BwdParams& bp, int dtype);
 hipError_t launch_mfma_backward(const BwdParams& bp, hipStream_t s);
+// Fused pair of hops (axes h1 then h2 = the two innermost axes) in one kernel.
+bool       mfma_pair_supports(const HopParams& h1, const HopParams& h2, int dtype);
+hipError_t launch_mfma_forward_pair(const HopParams& h1, const HopParams& h2, hipStream_t s);
 hipError_t launch_rope(const RopeParams& rp, int dtype, hipStream_t s);
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 

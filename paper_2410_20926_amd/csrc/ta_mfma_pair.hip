@@ -1,0 +1,352 @@
+// Two consecutive hops of Algorithm 1 in one kernel: the hop along the second-innermost
+// tensor axis followed by the hop along the innermost one (Eq. 4 twice, with the same Q and
+// K), for 32 x 32 slabs, bf16, head width 128.  The intermediate value tensor of the pair
+// never leaves the chip, and Q, K, the value input and the output each cross HBM once.
+//
+// A slab is the 1,024 consecutive tokens (i, j), i on the outer of the two axes, j on the
+// inner one, of one (batch, head).  One workgroup of 8 waves owns one slab:
+//
+//   phase A  scores of both hops.  The slab's Q and K rows enter LDS 32 features at a time
+//            (each row is read from HBM once, by the wave that owns its i); a wave
+//            accumulates S^T = K Q^T for its 4 "column" fibres (j fixed, the first hop) and
+//            its 4 "row" fibres (i fixed, the second hop) over the 4 feature chunks, then
+//            does the masked row softmax of each in registers and keeps the rounded
+//            probabilities as MFMA B operands.
+//   phase B  values, 64 features at a time: the value input's rows enter LDS, every column
+//            fibre replaces its rows by P1 X in place, then every row fibre computes P2 (P1 X)
+//            from them and stores its output rows.
+//
+// Workgroups are numbered so that the query heads of one key/value head run on the same
+// XCD at the same time and share its K rows through that XCD's L2.
+#include "ta_mfma_common.h"
+
+namespace ta {
+
+using namespace mfma;
+
+namespace {
+
+constexpr int kN = 32;                       // both axis lengths
+constexpr int kSlab = kN * kN;               // tokens per slab
+constexpr int kWaves = 8;                    // waves per workgroup; wave w owns i (and j) in [4 w, 4 w + 4)
+constexpr int kOwn = kN / kWaves;            // fibres of each kind per wave
+constexpr int kD = 128;
+constexpr int kCA = 32;                      // features per phase-A chunk (64 bytes of a row)
+constexpr int kCB = 64;                      // features per phase-B chunk (128 bytes of a row)
+constexpr int kARow = kCA * 2;               // bytes of one token's phase-A chunk row (half a 128-byte line)
+constexpr int kAK = kN * kARow;              // within an i-block: the 32 Q rows, then the 32 K rows
+constexpr int kABlock = 2 * kAK + 16;        // i-block pitch; the odd number of 16-byte units spreads a column fibre over the banks
+constexpr int kABytes = kN * kABlock;
+constexpr int kBPitch = kCB * 2 + 16;        // phase-B row pitch
+constexpr int kBRowsPerI = kN + 1;           // one spare row slot per i keeps column fibres off a single bank group
+constexpr int kBBytes = kN * kBRowsPerI * kBPitch;
+constexpr int kLdsBytes = (kABytes > kBBytes) ? kABytes : kBBytes;
+
+struct PairParams {
+    Tensor q, k, vin, o;
+    int32_t B, Hq, Hkv, G, vin_heads, causal;
+    float scale;
+    int32_t window1, window2;                // band widths on the outer / inner axis, 0 = none
+    const uint32_t* mask1;                   // bit tables of the outer / inner axis (32 words) or nullptr
+    const uint32_t* mask2;
+    uint32_t slabs;                          // slabs per batch element
+    uint32_t groups;                         // B * slabs * Hkv
+    uint32_t q_row, k_row, v_row, o_row;     // token pitch of each tensor in bytes
+};
+
+// Phase-A LDS layout.  Token (i, j)'s 64-byte chunk row of Q sits at i * kABlock + j * 64, that
+// of K kAK bytes further; inside a row the four 16-byte units are rotated by j / 2, so that
+// unit u is at position (u + j / 2) mod 4.  Consecutive j (a row fibre) then alternate between
+// the halves of a 128-byte line and walk through the units; consecutive i (a column fibre) are
+// an odd number of units apart: both access patterns cover all banks.
+
+// Masked row softmax of one 32 x 32 score tile held as S^T (lane = query row, 16 keys per
+// lane, the other 16 in lane ^ 32).  Returns the rounded, un-normalised probabilities as
+// two B operands and 1 / (their row sum).
+__device__ inline void softmax_tile(const f32x16& st, int r32, int hf, int causal, int window, const uint32_t* table,
+                                    float sl2, u32x4 (&pop)[2], float& inv) {
+    int lo, hi;
+    visible_range(r32, 0, kN, causal, window, lo, hi);
+    uint32_t vis = range_mask(lo, hi);
+    if (table) vis &= table[r32];
+    vis >>= 4 * hf;
+    float e[16], mx = -INFINITY;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const bool ok = (vis >> (8 * (r / 4) + (r % 4))) & 1u;
+        e[r] = ok ? st[r] * sl2 : -INFINITY;
+        mx = fmaxf(mx, e[r]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    if (mx == -INFINITY) mx = 0.f;
+    float sum = 0.f;
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+        uint32_t wds[4];
+#pragma unroll
+        for (int jp = 0; jp < 4; ++jp) {
+            const int r = 8 * s2 + 2 * jp;
+            const uint32_t pk = pack_bf16x2(__builtin_amdgcn_exp2f(e[r] - mx), __builtin_amdgcn_exp2f(e[r + 1] - mx));
+            sum += bf16_lo(pk) + bf16_hi(pk);             // sum of the ROUNDED weights
+            wds[jp] = pk;
+        }
+        pop[s2] = u32x4{wds[0], wds[1], wds[2], wds[3]};
+    }
+    sum += __shfl_xor(sum, 32);
+    inv = sum > 0.f ? 1.f / sum : 0.f;
+}
+
+// One fibre's value update on a 64-feature chunk resident in LDS: rows at `fb + r * rs`.
+// Reads the rows as transposed operands, forms (P X)^T, scales by `inv`, rounds and writes
+// the rows back in place.  The rows belong to this wave alone while it runs.
+__device__ inline void update_fibre(char* lds, uint32_t fb, uint32_t rs, const u32x4 (&pop)[2], float inv, int lane) {
+    const int r32 = lane & 31, hf = lane >> 5;
+    const uint32_t trow = 4 * hf + ((lane & 15) >> 2);
+    const uint32_t tcol = (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+    f32x16 ot[kCB / 32];
+#pragma unroll
+    for (int t = 0; t < kCB / 32; ++t) {
+        ot[t] = f32x16{};
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            const char* a0 = lds + fb + (16 * s2 + trow) * rs + tcol + 64 * t;
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a0));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(a0 + 8 * rs));
+            const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+            ot[t] = mma(u32x4{l2.x, l2.y, h2.x, h2.y}, pop[s2], ot[t]);
+        }
+    }
+    lds_wave_sync();                                      // every lane has its operands before a row is overwritten
+#pragma unroll
+    for (int t = 0; t < kCB / 32; ++t)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            u32x2 v;
+            v.x = pack_bf16x2(ot[t][4 * q4] * inv, ot[t][4 * q4 + 1] * inv);
+            v.y = pack_bf16x2(ot[t][4 * q4 + 2] * inv, ot[t][4 * q4 + 3] * inv);
+            *reinterpret_cast<u32x2*>(lds + fb + r32 * rs + (32 * t + 8 * q4 + 4 * hf) * 2) = v;
+        }
+}
+
+__global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParams p) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int r32 = lane & 31, hf = lane >> 5;
+
+    // workgroup -> (key/value group gi, head of the group hg): the heads of one group are 8
+    // workgroup ids apart, i.e. on the same XCD when workgroup ids go round the 8 XCDs, and are
+    // dispatched one after the other there: they run at the same time and share their K rows
+    // through that XCD's L2.
+    const bool vin_is_o = (p.vin_heads == p.Hq);
+    const uint32_t span = 8u * (uint32_t)p.G;
+    const uint32_t blk = blockIdx.x / span, rem = blockIdx.x - blk * span;
+    const uint32_t hg = rem >> 3, gi = blk * 8u + (rem & 7u);
+    if (gi >= p.groups) return;                           // whole workgroup leaves together
+    const uint32_t g = gi % (uint32_t)p.Hkv;
+    const uint32_t sl = (gi / (uint32_t)p.Hkv) % p.slabs;
+    const uint32_t b = gi / ((uint32_t)p.Hkv * p.slabs);
+    const uint32_t h = g * (uint32_t)p.G + hg;
+    const uint32_t hv = vin_is_o ? h : g;
+    const int64_t tok0 = (int64_t)sl * kSlab;
+    const char* qb = reinterpret_cast<const char*>(p.q.p) + ((int64_t)b * p.q.sb + (int64_t)h * p.q.sh) * 2 + tok0 * p.q_row;
+    const char* kb = reinterpret_cast<const char*>(p.k.p) + ((int64_t)b * p.k.sb + (int64_t)g * p.k.sh) * 2 + tok0 * p.k_row;
+    const char* xb = reinterpret_cast<const char*>(p.vin.p) + ((int64_t)b * p.vin.sb + (int64_t)hv * p.vin.sh) * 2 + tok0 * p.v_row;
+    char* ob = reinterpret_cast<char*>(p.o.p) + ((int64_t)b * p.o.sb + (int64_t)h * p.o.sh) * 2 + tok0 * p.o_row;
+
+    // ===== phase A ==================================================================================
+    // Loads: 4 lanes per row (16-byte unit ua), 16 rows per pass, 8 passes = this wave's 128 tokens.
+    // Both halves of a 128-byte line of Q are requested together (the second waits in registers
+    // for the next chunk), so that no line is fetched twice; K, which the other heads of the
+    // group read as well, comes 64 bytes per chunk and finds its second half in L2.  The Q loads
+    // of the second line are issued in two halves, one after each chunk write of the first line,
+    // which keeps the bytes in flight even.
+    const int ua = lane & 3, ja = lane >> 2;
+    const uint32_t qoff = (uint32_t)(w * (kOwn * kN) + ja) * p.q_row + (uint32_t)(ua * 16);
+    const uint32_t koff = (uint32_t)(w * (kOwn * kN) + ja) * p.k_row + (uint32_t)(ua * 16);
+    u32x4 q0[8], q1[8], r0[8], r1[8], kreg[8];           // first / second halves of line 0 and of line 1; one chunk of K
+    auto load_q = [&](u32x4 (&lo)[8], u32x4 (&hi)[8], int line, int pp_begin, int pp_end) {
+#pragma unroll
+        for (int pp = pp_begin; pp < pp_end; ++pp) {
+            const char* row = qb + (size_t)(16u * pp) * p.q_row + line * 128;
+            lo[pp] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + qoff));
+            hi[pp] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + 64 + qoff));
+        }
+    };
+    auto load_k = [&](int c) {
+#pragma unroll
+        for (int pp = 0; pp < 8; ++pp)
+            kreg[pp] = *reinterpret_cast<const u32x4*>(kb + (size_t)(16u * pp) * p.k_row + c * kARow + koff);
+    };
+    load_q(q0, q1, 0, 0, 8);
+    load_k(0);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // LDS addresses (see the layout above): what depends on the lane or the wave sits in a few
+    // registers, the rest are instruction offsets
+    const uint32_t wr_a = (uint32_t)(w * kOwn * kABlock + ja * kARow + ((ua + (lane >> 3)) & 3) * 16);
+    uint32_t col_a[4], row_a[2];                          // column fibre j = 4 w + f, step s: col_a[(f >> 1) + 2 s] + f * 64
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) col_a[kk] = (uint32_t)(r32 * kABlock + w * (kOwn * kARow) + ((hf + 2 * w + kk) & 3) * 16);
+#pragma unroll
+    for (int s = 0; s < 2; ++s)                           // row fibre i = 4 w + f, step s: row_a[s] + f * kABlock
+        row_a[s] = (uint32_t)(w * kOwn * kABlock + r32 * kARow + ((hf + (r32 >> 1) + 2 * s) & 3) * 16);
+
+    f32x16 sc[kOwn], sr[kOwn];                            // S^T of the column fibres j = 4 w + f and the row fibres i = 4 w + f
+#pragma unroll
+    for (int f = 0; f < kOwn; ++f) { sc[f] = f32x16{}; sr[f] = f32x16{}; }
+    auto write_chunk = [&](const u32x4 (&qv)[8]) {
+#pragma unroll
+        for (int pp = 0; pp < 8; ++pp) {
+            char* dst = lds + wr_a + (pp >> 1) * kABlock + (pp & 1) * (16 * kARow);
+            *reinterpret_cast<u32x4*>(dst) = qv[pp];
+            *reinterpret_cast<u32x4*>(dst + kAK) = kreg[pp];
+        }
+    };
+    auto scores = [&]() {
+#pragma unroll
+        for (int f = 0; f < kOwn; ++f)
+#pragma unroll
+            for (int s = 0; s < kCA / 16; ++s) {
+                const char* ac = lds + col_a[((f >> 1) + 2 * s) & 3] + f * kARow;
+                const char* ar = lds + row_a[s] + f * kABlock;
+                sc[f] = mma(*reinterpret_cast<const u32x4*>(ac + kAK), *reinterpret_cast<const u32x4*>(ac), sc[f]);
+                sr[f] = mma(*reinterpret_cast<const u32x4*>(ar + kAK), *reinterpret_cast<const u32x4*>(ar), sr[f]);
+                __builtin_amdgcn_sched_barrier(0);        // keeps the operand reads from piling up in registers
+            }
+    };
+    static_assert(kD == 4 * kCA, "two 128-byte lines per row");
+    write_chunk(q0);                                      // chunk 0
+    load_k(1);
+    load_q(r0, r1, 1, 0, 4);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    scores();
+    __syncthreads();
+    write_chunk(q1);                                      // chunk 1
+    load_k(2);
+    load_q(r0, r1, 1, 4, 8);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    scores();
+    __syncthreads();
+    write_chunk(r0);                                      // chunk 2
+    load_k(3);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    scores();
+    __syncthreads();
+    write_chunk(r1);                                      // chunk 3
+
+    // value rows of the first phase-B chunk (8 lanes per row (unit ub), 8 rows per pass, 16 passes):
+    // half of them are requested here, the other half once the column tiles' accumulators are gone
+    const int ub = lane & 7;
+    const uint32_t tok_b = (uint32_t)(w * (kOwn * kN) + (lane >> 3));        // + 8 * pass
+    u32x4 xreg[16];
+    auto load_x = [&](int c, int pp_begin, int pp_end) {
+#pragma unroll
+        for (int pp = pp_begin; pp < pp_end; ++pp) {
+            const uint32_t t = tok_b + 8u * pp;
+            const u32x4* src = reinterpret_cast<const u32x4*>(xb + (t * p.v_row + (uint32_t)(c * (kCB * 2) + ub * 16)));
+            xreg[pp] = vin_is_o ? __builtin_nontemporal_load(src) : *src;   // a per-group V is read by every head of the group
+        }
+    };
+    load_x(0, 0, 8);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    scores();
+
+    // softmax of the 8 tiles
+    const float sl2 = p.scale * kLog2e;
+    u32x4 p1[kOwn][2], p2[kOwn][2];
+    float inv1[kOwn], inv2[kOwn];
+#pragma unroll
+    for (int f = 0; f < kOwn; ++f) softmax_tile(sc[f], r32, hf, p.causal, p.window1, p.mask1, sl2, p1[f], inv1[f]);
+    load_x(0, 8, 16);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int f = 0; f < kOwn; ++f) softmax_tile(sr[f], r32, hf, p.causal, p.window2, p.mask2, sl2, p2[f], inv2[f]);
+
+    // ===== phase B ==================================================================================
+    __syncthreads();                                      // phase A's LDS contents are dead
+#pragma unroll
+    for (int c = 0; c < kD / kCB; ++c) {
+        // this wave's rows (i in [4 w, 4 w + 4)) are its own at this point: no barrier before the write
+#pragma unroll
+        for (int pp = 0; pp < 16; ++pp) {
+            const uint32_t t = tok_b + 8u * pp;
+            *reinterpret_cast<u32x4*>(lds + ((t >> 5) * kBRowsPerI + (t & 31)) * kBPitch + ub * 16) = xreg[pp];
+        }
+        if (c + 1 < kD / kCB) { load_x(c + 1, 0, 16); __builtin_amdgcn_sched_barrier(0); }
+        __syncthreads();
+        // first hop: column fibres j = 4 w + f, rows i = 0..31 one slab row apart
+#pragma unroll
+        for (int f = 0; f < kOwn; ++f)
+            update_fibre(lds, (uint32_t)((w * kOwn + f) * kBPitch), (uint32_t)(kBRowsPerI * kBPitch), p1[f], inv1[f], lane);
+        __syncthreads();
+        // second hop: row fibres i = 4 w + f, rows j = 0..31 adjacent; then the rows go out
+#pragma unroll
+        for (int f = 0; f < kOwn; ++f) {
+            const uint32_t fb = (uint32_t)((w * kOwn + f) * kBRowsPerI * kBPitch);
+            update_fibre(lds, fb, (uint32_t)kBPitch, p2[f], inv2[f], lane);
+            lds_wave_sync();
+#pragma unroll
+            for (int pp = 0; pp < 4; ++pp) {
+                const uint32_t t = tok_b + (uint32_t)(f * kN + 8 * pp);       // token (i = 4 w + f, j = 8 pp + lane / 8)
+                const u32x4 v = *reinterpret_cast<const u32x4*>(lds + fb + (t & 31) * kBPitch + ub * 16);
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(ob + (t * p.o_row + (uint32_t)(c * (kCB * 2) + ub * 16))));
+            }
+        }
+        lds_wave_sync();                                  // the stores' LDS reads precede the next chunk's writes
+    }
+}
+
+bool pair_params(const HopParams& h1, const HopParams& h2, PairParams* pp) {
+    if (h1.n != kN || h2.n != kN || h1.D != kD || h2.stride != 1 || h1.stride != kN) return false;
+    const int64_t N = h1.fibres * h1.n;
+    if (h1.valid_len != N) return false;
+    if (!fits_u32(h1.q, kSlab) || !fits_u32(h1.k, kSlab) || !fits_u32(h1.vin, kSlab) || !fits_u32(h1.o, kSlab)) return false;
+    if (N % kSlab != 0 || h1.G < 1 || h1.G > 64) return false;
+    const int64_t slabs = N / kSlab;
+    const int64_t groups = (int64_t)h1.B * slabs * h1.Hkv;
+    if (groups > (int64_t)1 << 24) return false;
+    pp->q = h1.q; pp->k = h1.k; pp->vin = h1.vin; pp->o = h1.o;
+    pp->B = h1.B; pp->Hq = h1.Hq; pp->Hkv = h1.Hkv; pp->G = h1.G; pp->vin_heads = h1.vin_heads; pp->causal = h1.causal;
+    pp->scale = h1.scale;
+    pp->window1 = h1.window; pp->window2 = h2.window;
+    pp->mask1 = h1.mask; pp->mask2 = h2.mask;
+    pp->slabs = (uint32_t)slabs;
+    pp->groups = (uint32_t)groups;
+    pp->q_row = (uint32_t)(h1.q.st * 2); pp->k_row = (uint32_t)(h1.k.st * 2);
+    pp->v_row = (uint32_t)(h1.vin.st * 2); pp->o_row = (uint32_t)(h1.o.st * 2);
+    return true;
+}
+
+}  // namespace
+
+bool mfma_pair_supports(const HopParams& h1, const HopParams& h2, int dtype) {
+    PairParams pp;
+    return dtype == TA_BF16 && pair_params(h1, h2, &pp);
+}
+
+hipError_t launch_mfma_forward_pair(const HopParams& h1, const HopParams& h2, hipStream_t s) {
+    PairParams pp;
+    if (!pair_params(h1, h2, &pp)) return hipErrorInvalidValue;
+    // more than 64 KB of dynamic LDS has to be allowed once per device
+    static bool allowed[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidValue;
+    if (!allowed[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_fwd_pair_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+        allowed[dev] = true;
+    }
+    const uint32_t span = 8u * (uint32_t)pp.G;
+    const uint32_t grid = ((pp.groups + 7u) / 8u) * span;
+    hipLaunchKernelGGL(mfma_fwd_pair_kernel, dim3(grid), dim3(64 * kWaves), kLdsBytes, s, pp);
+    return hipGetLastError();
+}
+
+}  // namespace ta

@@ -21,6 +21,7 @@ EXPORTS = [
     "ta_plan_workspace_bytes", "ta_plan_backward_scratch_bytes", "ta_axis_attn_forward",
     "ta_axis_attn_backward", "ta_multihop_forward", "ta_multihop_backward", "ta_rope_apply", "ta_copy_bytes",
     "ta_status_string", "ta_last_error_detail", "ta_version",
+    "ta_axis_pair_attn_forward", "ta_plan_pair_kernel", "ta_plan_pair_bytes", "ta_plan_fused_position",
 ]
 
 
@@ -82,6 +83,14 @@ def load_library():
     lib.ta_plan_backward_scratch_bytes.restype = sz
     lib.ta_axis_attn_forward.argtypes = [vp, i, vp, vp, vp, i, vp, vp]
     lib.ta_axis_attn_forward.restype = i
+    lib.ta_axis_pair_attn_forward.argtypes = [vp, i, vp, vp, vp, i, vp, vp]
+    lib.ta_axis_pair_attn_forward.restype = i
+    lib.ta_plan_pair_kernel.argtypes = [vp, i, i]
+    lib.ta_plan_pair_kernel.restype = C.c_char_p
+    lib.ta_plan_pair_bytes.argtypes = [vp, i, i]
+    lib.ta_plan_pair_bytes.restype = dbl
+    lib.ta_plan_fused_position.argtypes = [vp]
+    lib.ta_plan_fused_position.restype = i
     lib.ta_axis_attn_backward.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp, vp, i, vp]
     lib.ta_axis_attn_backward.restype = i
     lib.ta_multihop_forward.argtypes = [vp, vp, vp, vp, vp, vp, sz, i, vp]
@@ -213,6 +222,16 @@ class Plan:
         s = load_library().ta_plan_hop_backward_kernel(self._h, axis, vin)
         return s.decode() if s is not None else None
 
+    def pair_kernel(self, axis: int, vin: int) -> Optional[str]:
+        s = load_library().ta_plan_pair_kernel(self._h, axis, vin)
+        return s.decode() if s is not None else None
+
+    def pair_bytes(self, axis: int, vin: int) -> float:
+        return load_library().ta_plan_pair_bytes(self._h, axis, vin)
+
+    def fused_position(self) -> int:
+        return load_library().ta_plan_fused_position(self._h)
+
     def hop_bytes(self, axis: int, vin: int, backward: bool = False, accumulate: bool = False) -> float:
         return load_library().ta_plan_hop_bytes(self._h, axis, vin, int(backward), int(accumulate))
 
@@ -229,6 +248,11 @@ class Plan:
 def ta_plan_create(batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dims: Sequence[int], dtype: int,
                    causal: bool, **kw) -> Plan:
     return Plan(make_desc(batch, n_q_heads, n_kv_heads, head_dim, dims, dtype, causal, **kw))
+
+
+def ta_axis_pair_attn_forward(plan: Plan, axis: int, q, k, v_in, vin: int, o_out, stream=None) -> None:
+    _check(load_library().ta_axis_pair_attn_forward(plan.handle, axis, _ptr(q), _ptr(k), _ptr(v_in), vin, _ptr(o_out),
+                                                    _stream(stream)))
 
 
 def ta_axis_attn_forward(plan: Plan, axis: int, q, k, v_in, vin: int, o_out, stream=None) -> None:

@@ -69,7 +69,13 @@ def test_cost_model_closed_forms():
     assert p.hop_bytes(1, ta.TA_VIN_O, True, True) / N == 55296
     assert p.hop_bytes(0, ta.TA_VIN_KV, True, True) / N == 43008
     o_bytes = B * N * Hq * D * 2
-    assert p.workspace_bytes(False) == 2 * o_bytes and p.workspace_bytes(True) == 2 * o_bytes
+    # 32 x 32 x 32 in bf16 at D = 128: the last two hops run fused in inference, so one intermediate O
+    assert p.fused_position() == 1 and p.pair_kernel(1, ta.TA_VIN_O) == "mfma_bf16_pair_n32"
+    assert p.pair_bytes(1, ta.TA_VIN_O) / N == 26624
+    assert p.workspace_bytes(False) == o_bytes and p.workspace_bytes(True) == 2 * o_bytes
+    pw = ta.ta_plan_create(B, Hq, Hkv, D, (32, 16, 64), ta.TA_BF16, True)
+    assert pw.fused_position() == -1 and pw.pair_kernel(1, ta.TA_VIN_O) == "unsupported"
+    assert pw.workspace_bytes(False) == 2 * o_bytes
     assert p.backward_scratch_bytes() == 2 * o_bytes
     p1 = ta.ta_plan_create(1, 1, 1, 64, (256,), ta.TA_F32, False)
     assert p1.workspace_bytes(False) == 0
