@@ -252,7 +252,8 @@ const char* ta_plan_hop_backward_kernel(const ta_plan_t* pl, int axis, int vin) 
     bp.dq = make_tensor(nullptr, pl->qs);
     bp.dk = make_tensor(nullptr, pl->kvs);
     bp.accumulate = 0;
-    if (ta::mfma_backward_supports(bp, pl->desc.dtype)) return "mfma_bf16_bwd_n32";
+    if (ta::mfma_backward_supports(bp, pl->desc.dtype))
+        return ta::mfma_backward_is_blocked(bp, pl->desc.dtype) ? "mfma_bf16_bwd_blocked" : "mfma_bf16_bwd_n32";
     return ta::generic_backward_supports(pl->dims[axis], pl->G, pl->desc.head_dim) ? "generic" : "unsupported";
 }
 

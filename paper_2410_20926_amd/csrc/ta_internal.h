@@ -78,6 +78,7 @@ hipError_t launch_mfma_forward_stream(const HopParams& p, hipStream_t s);
 bool       mfma_forward_supports(int32_t n, int32_t D, int dtype, int* kernel_id);
 bool       mfma_forward_layout_ok(const HopParams& p);   // strides and sizes fit the kernel's 32-bit row offsets
 bool       mfma_backward_supports(const BwdParams& bp, int dtype);
+bool       mfma_backward_is_blocked(const BwdParams& bp, int dtype);   // the variant for axes longer than one tile
 hipError_t launch_mfma_backward(const BwdParams& bp, hipStream_t s);
 // Fused pair of hops (axes h1 then h2 = the two innermost axes) in one kernel.
 bool       mfma_pair_supports(const HopParams& h1, const HopParams& h2, int dtype);

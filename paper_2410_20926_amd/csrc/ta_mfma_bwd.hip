@@ -347,6 +347,404 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
     if (w == nw - 1) store_tile<D>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.accumulate != 0, rows_valid, lane);
 }
 
+// ---------------------------------------------------------------------------------------
+// Axes longer than one tile (32 < n <= kStreamMaxN): the same derivative, walked in 32 x 32
+// blocks (query tile a, key tile c).  A wave is one query head of one fibre, the workgroup
+// the heads of a key/value head, as above.  Nothing but the tensors themselves is kept
+// between blocks: a block's operands are gathered again whenever it is visited (the fibre's
+// rows stay in L2), and the row statistics of the fibre live in LDS.
+//   for every query tile a:   sweep the key tiles once for the row statistics (running max,
+//                             sum and sum of P o dP), once more for dQ_a = sum_c dS_ac K_c
+//   for every key tile c:     sweep the query tiles for dX_c = sum_a P_ac^T G_a,
+//                             and again for dK_c = sum_a dS_ac^T Q_a
+// Blocks that the causal triangle or the band hides entirely are skipped.
+constexpr int kStreamMaxN = 1024;
+constexpr int kStreamMaxLds = 160 * 1024;              // LDS of one compute unit
+
+struct StreamBwdParams {
+    uint32_t q_row, k_row, v_row, o_row;   // token pitch in bytes of Q/dQ, K/dK, the value input and its gradient, dO
+    uint32_t fibres_lo, fibres_hi;         // gridDim.y; gridDim.z = B * fibres_hi
+    int32_t tiles;                         // ceil(n / 32)
+};
+
+// Keys 32 c .. 32 c + 31 that query row qr of the fibre may attend (bit = key), and query
+// rows 32 a .. 32 a + 31 that may attend key kr (bit = query row).
+__device__ inline uint32_t block_vis_keys(const HopParams& p, int qr, int c, int nreal) {
+    if (qr >= nreal) return 0u;
+    int lo, hi;
+    visible_range(qr, 0, p.n, p.causal, p.window, lo, hi);
+    hi = min(hi, nreal);
+    uint32_t v = range_mask(min(max(lo - kTile * c, 0), kTile), min(max(hi - kTile * c, 0), kTile));
+    if (p.mask) v &= p.mask[qr * p.mask_words + c];
+    return v;
+}
+__device__ inline uint32_t block_vis_rows(const HopParams& p, int kr, int a, int nreal) {
+    if (kr >= nreal) return 0u;
+    int lo, hi;
+    seen_range(kr, 0, p.n, p.causal, p.window, lo, hi);
+    hi = min(hi, nreal);
+    uint32_t v = range_mask(min(max(lo - kTile * a, 0), kTile), min(max(hi - kTile * a, 0), kTile));
+    if (p.mask) {
+        uint32_t col = 0;
+        for (int q = 0; q < kTile; ++q) {
+            const int qr = kTile * a + q;
+            if (qr < p.n) col |= ((p.mask[qr * p.mask_words + (kr >> 5)] >> (kr & 31)) & 1u) << q;
+        }
+        v &= col;
+    }
+    return v;
+}
+
+template <int D>
+__global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, StreamBwdParams sp) {
+    using G = BGeo<D>;
+    const HopParams& p = bp.hop;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nw = p.G;
+    const int g = blockIdx.x;
+    const int h = g * p.G + w;
+    const uint32_t zb = blockIdx.z / sp.fibres_hi;
+    const int64_t f = (int64_t)(blockIdx.z - zb * sp.fibres_hi) * sp.fibres_lo + blockIdx.y;
+    if (f >= p.fibres) return;                            // whole workgroup leaves together
+    const int b = (int)zb;
+    const bool vin_is_o = (p.vin_heads == p.Hq);
+    const int hv = vin_is_o ? h : g;
+    const int n = p.n, T = sp.tiles;
+    const uint32_t stride = (uint32_t)p.stride;
+    const uint32_t tok0 = (uint32_t)fibre_base_token(f, p.stride, n);
+    // rows of the fibre whose token is not padding form a prefix [0, nreal)
+    const uint32_t vl = (uint32_t)p.valid_len;
+    const int nreal = tok0 >= vl ? 0 : (int)min((uint32_t)n, (vl - tok0 + stride - 1) / stride);
+
+    const int wave_bytes = G::kBufBytes + kTile * 16 + 3 * kTile * T * 4;
+    float* red = reinterpret_cast<float*>(smem);
+    char* buf = smem + (nw > 1 ? G::kRedBytes : 0) + w * wave_bytes;
+    u32x4* rowoff = reinterpret_cast<u32x4*>(buf + G::kBufBytes);
+    float* stats = reinterpret_cast<float*>(buf + G::kBufBytes + kTile * 16);   // [tile][max | 1/sum | delta][32]
+
+    const char* qb = reinterpret_cast<const char*>(p.q.p) + ((int64_t)b * p.q.sb + (int64_t)h * p.q.sh) * 2;
+    const char* kb = reinterpret_cast<const char*>(p.k.p) + ((int64_t)b * p.k.sb + (int64_t)g * p.k.sh) * 2;
+    const char* xb = reinterpret_cast<const char*>(p.vin.p) + ((int64_t)b * p.vin.sb + (int64_t)hv * p.vin.sh) * 2;
+    const char* gb = reinterpret_cast<const char*>(bp.d_o.p) + ((int64_t)b * bp.d_o.sb + (int64_t)h * bp.d_o.sh) * 2;
+    char* dqb = reinterpret_cast<char*>(bp.dq.p) + ((int64_t)b * bp.dq.sb + (int64_t)h * bp.dq.sh) * 2;
+    char* dkb = reinterpret_cast<char*>(bp.dk.p) + ((int64_t)b * bp.dk.sb + (int64_t)g * bp.dk.sh) * 2;
+    char* dxb = reinterpret_cast<char*>(bp.d_vin.p) + ((int64_t)b * bp.d_vin.sb + (int64_t)hv * bp.d_vin.sh) * 2;
+
+    const int lrow = lane / G::kChunks, lcol = lane % G::kChunks;
+    const uint32_t lbyte = lcol * 16;
+    const int r32 = lane & 31, hf = lane >> 5;
+    char* stg = buf + lrow * G::kPitch + lbyte;
+    const char* oprd = buf + r32 * G::kPitch + hf * 16;
+    const char* trbase = buf + (4 * hf + ((lane & 15) >> 2)) * G::kPitch + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+    const float sl2 = p.scale * kLog2e;
+
+    // rows 32 t + .. of the fibre (clamped to the last one: padding rows of the last tile are
+    // masked in the softmax and never stored)
+    auto gather = [&](const char* base, uint32_t pitch, int t, u32x4 (&raw)[G::kPasses]) {
+#pragma unroll
+        for (int i = 0; i < G::kPasses; ++i) {
+            const uint32_t rr = (uint32_t)min(kTile * t + i * G::kRowsPerPass + lrow, n - 1);
+            raw[i] = *reinterpret_cast<const u32x4*>(base + ((tok0 + rr * stride) * pitch + lbyte));
+        }
+    };
+    auto set_rowoff = [&](int t) {                        // byte offsets of the rows of tile t for the epilogue helpers
+        lds_wave_sync();
+        if (lane < kTile) {
+            const uint32_t tok = tok0 + (uint32_t)min(kTile * t + lane, n - 1) * stride;
+            rowoff[lane] = u32x4{tok * sp.q_row, tok * sp.k_row, tok * sp.v_row, tok * sp.o_row};
+        }
+        lds_wave_sync();
+    };
+    // key tiles that some row of query tile a sees, and query tiles with a row that sees some key of tile c
+    auto key_tiles = [&](int a, int& cb, int& ce) {
+        int lo, hi, lo2, hi2;
+        visible_range(kTile * a, 0, n, p.causal, p.window, lo, hi);
+        visible_range(min(kTile * a + kTile - 1, n - 1), 0, n, p.causal, p.window, lo2, hi2);
+        cb = lo / kTile;
+        ce = (hi2 + kTile - 1) / kTile;
+    };
+    auto row_tiles = [&](int c, int& ab, int& ae) {
+        int lo, hi, lo2, hi2;
+        seen_range(kTile * c, 0, n, p.causal, p.window, lo, hi);
+        seen_range(min(kTile * c + kTile - 1, n - 1), 0, n, p.causal, p.window, lo2, hi2);
+        ab = lo / kTile;
+        ae = (hi2 + kTile - 1) / kTile;
+    };
+
+    // ===== query tiles: row statistics, then dQ =====================================================
+    for (int a = 0; a < T; ++a) {
+        u32x4 qop[G::kKSteps], gop[G::kKSteps];
+        {
+            u32x4 qraw[G::kPasses], graw[G::kPasses];
+            gather(qb, sp.q_row, a, qraw);
+            gather(gb, sp.o_row, a, graw);
+            lds_wave_sync();
+            stage_rows<D>(stg, qraw);
+            lds_wave_sync();
+            read_natural<D>(oprd, qop);
+            lds_wave_sync();
+            stage_rows<D>(stg, graw);
+            lds_wave_sync();
+            read_natural<D>(oprd, gop);
+            lds_wave_sync();
+        }
+        int cb, ce;
+        key_tiles(a, cb, ce);
+        const int qr = kTile * a + r32;                   // this lane's query row
+        // ---- sweep 1: running max m (log2 domain), sum l and sum of e * dP ------------------------
+        float m = -INFINITY, l = 0.f, dn = 0.f;
+        for (int c = cb; c < ce; ++c) {
+            u32x4 kraw[G::kPasses], xraw[G::kPasses], op[G::kKSteps];
+            gather(kb, sp.k_row, c, kraw);
+            gather(xb, sp.v_row, c, xraw);
+            stage_rows<D>(stg, kraw);
+            lds_wave_sync();
+            read_natural<D>(oprd, op);
+            lds_wave_sync();
+            f32x16 sT = {}, dpT = {};
+#pragma unroll
+            for (int s = 0; s < G::kKSteps; ++s) sT = mma(op[s], qop[s], sT);
+            stage_rows<D>(stg, xraw);
+            lds_wave_sync();
+            read_natural<D>(oprd, op);
+            lds_wave_sync();
+#pragma unroll
+            for (int s = 0; s < G::kKSteps; ++s) dpT = mma(op[s], gop[s], dpT);
+            const uint32_t vis = block_vis_keys(p, qr, c, nreal) >> (4 * hf);
+            float e[16], tmax = -INFINITY;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const bool ok = (vis >> (8 * (r / 4) + (r % 4))) & 1u;
+                e[r] = ok ? sT[r] * sl2 : -INFINITY;
+                tmax = fmaxf(tmax, e[r]);
+            }
+            tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+            const float mnew = fmaxf(m, tmax);
+            const float msafe = mnew == -INFINITY ? 0.f : mnew;
+            const float corr = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - msafe);
+            float ps = 0.f, pd = 0.f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float ev = __builtin_amdgcn_exp2f(e[r] - msafe);
+                ps += ev;
+                pd += ev * dpT[r];
+            }
+            ps += __shfl_xor(ps, 32);
+            pd += __shfl_xor(pd, 32);
+            l = l * corr + ps;
+            dn = dn * corr + pd;
+            m = mnew;
+        }
+        const float msafe = m == -INFINITY ? 0.f : m;
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        const float delta = dn * inv;
+        if (lane < kTile) {
+            stats[(3 * a + 0) * kTile + lane] = msafe;
+            stats[(3 * a + 1) * kTile + lane] = inv;
+            stats[(3 * a + 2) * kTile + lane] = delta;
+        }
+        // ---- sweep 2: dQ_a^T = sum_c K_c^T dS_ac^T ------------------------------------------------
+        f32x16 acc[G::kDTiles];
+#pragma unroll
+        for (int t = 0; t < G::kDTiles; ++t) acc[t] = f32x16{};
+        for (int c = cb; c < ce; ++c) {
+            u32x4 kraw[G::kPasses], xraw[G::kPasses], op[G::kKSteps], kT[G::kDTiles][2];
+            gather(xb, sp.v_row, c, xraw);
+            stage_rows<D>(stg, xraw);
+            gather(kb, sp.k_row, c, kraw);
+            lds_wave_sync();
+            read_natural<D>(oprd, op);
+            lds_wave_sync();
+            f32x16 sT = {}, dpT = {};
+#pragma unroll
+            for (int s = 0; s < G::kKSteps; ++s) dpT = mma(op[s], gop[s], dpT);
+            stage_rows<D>(stg, kraw);
+            lds_wave_sync();
+            read_natural<D>(oprd, op);
+#pragma unroll
+            for (int s = 0; s < G::kKSteps; ++s) sT = mma(op[s], qop[s], sT);
+            read_transposed<D>(trbase, kT);                // K^T last: it lives only until the products below
+            lds_wave_sync();
+            const uint32_t vis = block_vis_keys(p, qr, c, nreal) >> (4 * hf);
+            float e[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const bool ok = (vis >> (8 * (r / 4) + (r % 4))) & 1u;
+                const float pv = ok ? __builtin_amdgcn_exp2f(sT[r] * sl2 - msafe) * inv : 0.f;
+                e[r] = pv * (dpT[r] - delta);
+            }
+            u32x4 dsTop[2];
+            pack_rows(e, dsTop);
+#pragma unroll
+            for (int t = 0; t < G::kDTiles; ++t)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) acc[t] = mma(kT[t][s2], dsTop[s2], acc[t]);
+        }
+        set_rowoff(a);
+        u32x4 oldq[G::kDTiles * 2] = {};
+        if (bp.accumulate) prefetch_tile<D>(oldq, rowoff, 0, dqb, lane);
+        store_tile<D>(acc, p.scale, buf, rowoff, 0, dqb, oldq, bp.accumulate != 0, min(kTile, n - kTile * a), lane);
+    }
+    lds_wave_sync();
+
+    // ===== key tiles: dX, then dK ===================================================================
+    // P and dS of a block with one key per lane: lane = key row, registers = 16 of the 32 query rows
+    for (int c = 0; c < T; ++c) {
+        int ab, ae;
+        row_tiles(c, ab, ae);
+        const int kr = kTile * c + r32;                   // this lane's key row
+        u32x4 kop[G::kKSteps];
+        {
+            u32x4 kraw[G::kPasses];
+            gather(kb, sp.k_row, c, kraw);
+            lds_wave_sync();
+            stage_rows<D>(stg, kraw);
+            lds_wave_sync();
+            read_natural<D>(oprd, kop);
+            lds_wave_sync();
+        }
+        // ---- dX_c^T = sum_a G_a^T P_ac ---------------------------------------------------------------
+        f32x16 acc[G::kDTiles];
+#pragma unroll
+        for (int t = 0; t < G::kDTiles; ++t) acc[t] = f32x16{};
+        for (int a = ab; a < ae; ++a) {
+            u32x4 qraw[G::kPasses], graw[G::kPasses], op[G::kKSteps], gT[G::kDTiles][2];
+            gather(qb, sp.q_row, a, qraw);
+            stage_rows<D>(stg, qraw);
+            gather(gb, sp.o_row, a, graw);
+            lds_wave_sync();
+            read_natural<D>(oprd, op);
+            lds_wave_sync();
+            f32x16 sN = {};
+#pragma unroll
+            for (int s = 0; s < G::kKSteps; ++s) sN = mma(op[s], kop[s], sN);
+            stage_rows<D>(stg, graw);
+            lds_wave_sync();
+            read_transposed<D>(trbase, gT);
+            lds_wave_sync();
+            const uint32_t vis = block_vis_rows(p, kr, a, nreal) >> (4 * hf);
+            float pr[16];
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4 m4 = *reinterpret_cast<const f32x4*>(stats + (3 * a + 0) * kTile + 8 * q4 + 4 * hf);
+                const f32x4 i4 = *reinterpret_cast<const f32x4*>(stats + (3 * a + 1) * kTile + 8 * q4 + 4 * hf);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = 4 * q4 + j;
+                    const bool ok = (vis >> (8 * q4 + j)) & 1u;
+                    pr[r] = ok ? __builtin_amdgcn_exp2f(sN[r] * sl2 - m4[j]) * i4[j] : 0.f;
+                }
+            }
+            u32x4 pNop[2];
+            pack_rows(pr, pNop);
+#pragma unroll
+            for (int t = 0; t < G::kDTiles; ++t)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) acc[t] = mma(gT[t][s2], pNop[s2], acc[t]);
+        }
+        set_rowoff(c);
+        const int rows_c = min(kTile, n - kTile * c);
+        u32x4 none[G::kDTiles * 2] = {};
+        if (vin_is_o) {
+            store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, none, false, rows_c, lane);
+        } else {
+            chain_sum<D>(acc, red, w, nw, lane);
+            if (w == nw - 1) store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, none, false, rows_c, lane);
+        }
+        // ---- dK_c^T = sum_a Q_a^T dS_ac ---------------------------------------------------------------
+        u32x4 xop[G::kKSteps];
+        {
+            u32x4 xraw[G::kPasses];
+            gather(xb, sp.v_row, c, xraw);
+            lds_wave_sync();
+            stage_rows<D>(stg, xraw);
+            lds_wave_sync();
+            read_natural<D>(oprd, xop);
+            lds_wave_sync();
+        }
+#pragma unroll
+        for (int t = 0; t < G::kDTiles; ++t) acc[t] = f32x16{};
+        for (int a = ab; a < ae; ++a) {
+            u32x4 qraw[G::kPasses], graw[G::kPasses], op[G::kKSteps], qT[G::kDTiles][2];
+            gather(gb, sp.o_row, a, graw);
+            stage_rows<D>(stg, graw);
+            gather(qb, sp.q_row, a, qraw);
+            lds_wave_sync();
+            read_natural<D>(oprd, op);
+            lds_wave_sync();
+            f32x16 sN = {}, dpN = {};
+#pragma unroll
+            for (int s = 0; s < G::kKSteps; ++s) dpN = mma(op[s], xop[s], dpN);
+            stage_rows<D>(stg, qraw);
+            lds_wave_sync();
+            read_natural<D>(oprd, op);
+#pragma unroll
+            for (int s = 0; s < G::kKSteps; ++s) sN = mma(op[s], kop[s], sN);
+            read_transposed<D>(trbase, qT);
+            lds_wave_sync();
+            const uint32_t vis = block_vis_rows(p, kr, a, nreal) >> (4 * hf);
+            float ds[16];
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4 m4 = *reinterpret_cast<const f32x4*>(stats + (3 * a + 0) * kTile + 8 * q4 + 4 * hf);
+                const f32x4 i4 = *reinterpret_cast<const f32x4*>(stats + (3 * a + 1) * kTile + 8 * q4 + 4 * hf);
+                const f32x4 d4 = *reinterpret_cast<const f32x4*>(stats + (3 * a + 2) * kTile + 8 * q4 + 4 * hf);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = 4 * q4 + j;
+                    const bool ok = (vis >> (8 * q4 + j)) & 1u;
+                    const float pv = ok ? __builtin_amdgcn_exp2f(sN[r] * sl2 - m4[j]) * i4[j] : 0.f;
+                    ds[r] = pv * (dpN[r] - d4[j]);
+                }
+            }
+            u32x4 dsNop[2];
+            pack_rows(ds, dsNop);
+#pragma unroll
+            for (int t = 0; t < G::kDTiles; ++t)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) acc[t] = mma(qT[t][s2], dsNop[s2], acc[t]);
+        }
+        lds_wave_sync();
+        u32x4 oldk[G::kDTiles * 2] = {};
+        if (bp.accumulate && w == nw - 1) prefetch_tile<D>(oldk, rowoff, 1, dkb, lane);   // only the wave that ends up with the sum
+        chain_sum<D>(acc, red, w, nw, lane);
+        if (w == nw - 1) store_tile<D>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.accumulate != 0, rows_c, lane);
+        lds_wave_sync();
+    }
+}
+
+template <int D>
+hipError_t launch_stream(const BwdParams& bp, hipStream_t s) {
+    const HopParams& p = bp.hop;
+    StreamBwdParams sp;
+    sp.q_row = (uint32_t)(p.q.st * 2); sp.k_row = (uint32_t)(p.k.st * 2);
+    sp.v_row = (uint32_t)(p.vin.st * 2); sp.o_row = (uint32_t)(bp.d_o.st * 2);
+    sp.tiles = (p.n + kTile - 1) / kTile;
+    sp.fibres_lo = (uint32_t)(p.fibres < 32768 ? p.fibres : 32768);
+    sp.fibres_hi = (uint32_t)((p.fibres + sp.fibres_lo - 1) / sp.fibres_lo);
+    if ((int64_t)p.B * sp.fibres_hi > 65535) return hipErrorInvalidValue;
+    const size_t wave_bytes = (size_t)BGeo<D>::kBufBytes + kTile * 16 + (size_t)3 * kTile * sp.tiles * 4;
+    const size_t smem = (size_t)(p.G > 1 ? BGeo<D>::kRedBytes : 0) + (size_t)p.G * wave_bytes;
+    if (smem > kStreamMaxLds) return hipErrorInvalidValue;
+    if (smem > 64 * 1024) {                               // more than 64 KB of dynamic LDS has to be allowed once per device
+        static bool allowed[64] = {};
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 64) return hipErrorInvalidValue;
+        if (!allowed[dev]) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_bwd_stream_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize, kStreamMaxLds);
+            if (e != hipSuccess) return e;
+            allowed[dev] = true;
+        }
+    }
+    const dim3 grid((unsigned)p.Hkv, sp.fibres_lo, (unsigned)p.B * sp.fibres_hi);
+    hipLaunchKernelGGL((mfma_bwd_stream_kernel<D>), grid, dim3(64 * p.G), smem, s, bp, sp);
+    return hipGetLastError();
+}
+
 template <int D>
 hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
     const HopParams& p = bp.hop;
@@ -359,17 +757,29 @@ hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
 
 }  // namespace
 
-bool mfma_backward_supports(const BwdParams& bp, int dtype) {
+// 1: the one-tile kernel (n <= 32); 2: the blocked kernel (32 < n <= kStreamMaxN); 0: neither.
+static int backward_variant(const BwdParams& bp, int dtype) {
     const HopParams& p = bp.hop;
-    if (dtype != TA_BF16 || (p.D != 64 && p.D != 128) || p.n < 1 || p.n > kTile) return false;
-    if (p.G != 1 && p.G != 2 && p.G != 4 && p.G != 8) return false;
+    if (dtype != TA_BF16 || (p.D != 64 && p.D != 128) || p.n < 1 || p.n > kStreamMaxN) return 0;
+    if (p.G != 1 && p.G != 2 && p.G != 4 && p.G != 8) return 0;
     const int64_t N = p.fibres * p.n;
-    return N < ((int64_t)1 << 31) && p.B <= 65535 && fits_u32(p.q, N) && fits_u32(p.k, N) && fits_u32(p.vin, N) &&
-           fits_u32(bp.d_o, N) && fits_u32(bp.d_vin, N) && fits_u32(bp.dq, N) && fits_u32(bp.dk, N);
+    if (!(N < ((int64_t)1 << 31) && p.B <= 65535 && fits_u32(p.q, N) && fits_u32(p.k, N) && fits_u32(p.vin, N) &&
+          fits_u32(bp.d_o, N) && fits_u32(bp.d_vin, N) && fits_u32(bp.dq, N) && fits_u32(bp.dk, N))) return 0;
+    if (p.n <= kTile) return 1;
+    // the blocked kernel keeps three floats per row and head in LDS
+    const size_t tiles = (size_t)(p.n + kTile - 1) / kTile;
+    const size_t kbuf = p.D == 128 ? BGeo<128>::kBufBytes : BGeo<64>::kBufBytes;
+    const size_t red = p.G > 1 ? (p.D == 128 ? BGeo<128>::kRedBytes : BGeo<64>::kRedBytes) : 0;
+    return red + (size_t)p.G * (kbuf + kTile * 16 + 3 * kTile * tiles * 4) <= (size_t)kStreamMaxLds ? 2 : 0;
 }
 
+bool mfma_backward_supports(const BwdParams& bp, int dtype) { return backward_variant(bp, dtype) != 0; }
+bool mfma_backward_is_blocked(const BwdParams& bp, int dtype) { return backward_variant(bp, dtype) == 2; }
+
 hipError_t launch_mfma_backward(const BwdParams& bp, hipStream_t s) {
-    if (!mfma_backward_supports(bp, TA_BF16)) return hipErrorInvalidValue;
+    const int variant = backward_variant(bp, TA_BF16);
+    if (variant == 0) return hipErrorInvalidValue;
+    if (variant == 2) return bp.hop.D == 128 ? launch_stream<128>(bp, s) : launch_stream<64>(bp, s);
     HopParams hp = bp.hop;
     hp.o = bp.d_o;                                        // the table's fourth offset follows the O layout (dO)
     TileParams tp;

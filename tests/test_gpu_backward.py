@@ -45,7 +45,13 @@ CASES = [
     ((3, 20), 1, 2, 1, 256, True, "f32"),
     ((32, 16), 1, 4, 1, 128, True, "bf16"),
     ((16, 32, 4), 2, 4, 2, 128, True, "bf16"),
-    ((64, 8), 1, 2, 2, 64, False, "bf16"),           # n = 64 falls back to the generic kernel
+    ((64, 8), 1, 2, 2, 64, False, "bf16"),           # n = 64: the blocked kernel, two tiles
+    ((64, 4), 1, 4, 1, 128, True, "bf16"),           # the same, causal, a group of 4 heads (dK, dV summed over it)
+    ((3, 50), 2, 2, 1, 128, True, "bf16"),           # ragged second tile
+    ((100, 2), 1, 8, 1, 128, False, "bf16"),         # four tiles, 8 heads per group
+    ((2, 200), 1, 4, 2, 64, True, "bf16"),           # seven tiles
+    ((333,), 1, 2, 2, 128, True, "bf16"),            # one long axis: plain causal attention, 11 tiles
+    ((1024, 2), 1, 4, 1, 128, True, "bf16"),         # the longest axis the blocked kernel takes (more than 64 KB of LDS)
     ((3, 16, 8), 1, 2, 1, 128, True, "bf16"),        # packed fibres (2 and 4 per tile), 2 heads per group
     ((5, 7, 3), 2, 4, 4, 64, True, "bf16"),          # odd lengths: ragged tiles with padding rows
     ((32, 3), 1, 8, 2, 128, False, "bf16"),
@@ -162,6 +168,17 @@ def test_backward_strided_head_major_layout(dtype):
     torch.cuda.synchronize()
     for got, ref, name in ((dq, rq, "dq"), (dk, rk, "dk"), (dv, rv, "dv")):
         check_grad(to_host(got).transpose(0, 2, 1, 3), ref, dtype, name)
+
+
+def test_blocked_backward_is_chosen_for_long_bf16_axes():
+    plan = ta.ta_plan_create(1, 32, 8, 128, (64, 64, 32), ta.TA_BF16, True)
+    assert plan.hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_blocked"
+    assert plan.hop_backward_kernel(1, ta.TA_VIN_O) == "mfma_bf16_bwd_blocked"
+    assert plan.hop_backward_kernel(2, ta.TA_VIN_O) == "mfma_bf16_bwd_n32"
+    long_axis = ta.ta_plan_create(1, 8, 2, 128, (1024, 4), ta.TA_BF16, True)
+    assert long_axis.hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_blocked"
+    too_long = ta.ta_plan_create(1, 8, 2, 128, (2048, 2), ta.TA_BF16, True)
+    assert too_long.hop_backward_kernel(0, ta.TA_VIN_KV) == "unsupported"
 
 
 def test_backward_reports_unsupported_shapes():

@@ -224,11 +224,12 @@ def test_offsets_near_the_32_bit_limit():
     assert big.hop_kernel(2, 1) == "generic"
 
 
-def test_multihop_forward_under_graph_capture():
+@pytest.mark.parametrize("dims", [(16, 32, 8), (2, 32, 32)])      # every hop on its own; last two hops fused
+def test_multihop_forward_under_graph_capture(dims):
     """The library only enqueues kernels on the given stream (no allocation, no memset, no
     synchronisation), so a multi-hop forward can be captured into a HIP graph; every replay,
     with eager work and synchronisations in between, must reproduce the eager result."""
-    dims, B, Hq, Hkv, D = (16, 32, 8), 1, 8, 2, 128
+    B, Hq, Hkv, D = 1, 8, 2, 128
     N = int(np.prod(dims))
     plan = ta.ta_plan_create(B, Hq, Hkv, D, dims, ta.TA_BF16, True)
     gen = torch.Generator(device="cuda"); gen.manual_seed(5)
