@@ -119,11 +119,14 @@ def time_hops(torch, ta, plan, sets, w, steps):
         inter = [view(ws, j) for j in range(ws.numel() // ob)]    # as many inter-hop buffers as the plan asked for
         srcs = []
         cur, kind = v, ta.TA_VIN_KV
-        fused = -1 if w.backward else plan.fused_position()
+        fused = plan.fused_position()
         for pos in range(m):
             axis = plan.hop_axis(pos)
-            if pos == fused:
-                timed(("fwd2", pos, axis, kind), lambda: ta.ta_axis_pair_attn_forward(plan, axis, q, k, cur, kind, o))
+            if pos == fused:                             # a training step also gets the O between the two hops
+                mid = inter[pos] if w.backward else None
+                timed(("fwd2", pos, axis, kind), lambda: ta.ta_axis_pair_attn_forward(plan, axis, q, k, cur, kind, o, o_mid=mid))
+                srcs.append((cur, kind))
+                srcs.append((mid, ta.TA_VIN_O))
                 break
             dst = o if pos == m - 1 else (inter[pos] if w.backward else inter[pos % len(inter)])
             timed(("fwd", pos, axis, kind), lambda: ta.ta_axis_attn_forward(plan, axis, q, k, cur, kind, dst))
@@ -200,6 +203,8 @@ def measure(torch, ta, w, args, steps, warmup):
         bwd = d == "bwd"
         if d == "fwd2":
             nbytes = plan.pair_bytes(axis, kind)
+            if w.backward:                               # plus the write of the O between the two hops
+                nbytes += w.batch * w.seq_len * w.n_q_heads * w.head_dim * 2
             flops = plan.hop_flops(axis, False) + plan.hop_flops(axis + 1, False)
             name = plan.pair_kernel(axis, kind)
         else:

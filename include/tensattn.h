@@ -126,7 +126,7 @@ double ta_plan_hop_flops(const ta_plan_t* plan, int axis, int backward);
 
 /* Workspace for ta_multihop_forward, in bytes (0 when m == 1):
  * save_for_backward == 0: two ping-pong inter-hop O buffers (one when only one hop writes an
- *   intermediate O, none when none does: the last two hops may run fused, see below);
+ *   intermediate O, none when none does: fused, the last two hops keep theirs on chip);
  * save_for_backward != 0: m-1 retained inter-hop O buffers, O_1..O_{m-1}, in hop order.
  * Each buffer is a dense or o_strides-shaped O tensor rounded up to 256 bytes. */
 size_t ta_plan_workspace_bytes(const ta_plan_t* plan, int save_for_backward);
@@ -146,18 +146,20 @@ ta_status_t ta_axis_attn_forward(const ta_plan_t* plan, int axis,
 /* ---- two hops of Algorithm 1 in one launch ---------------------------------------------
  * The hop along `axis` followed by the hop along `axis + 1` (Eq. 4 twice with the same Q, K):
  * the same result as two ta_axis_attn_forward calls up to the rounding of the intermediate
- * O, which stays on chip.  Arguments as ta_axis_attn_forward.  Available when `axis + 1` is
- * the innermost axis, both axes have length 32, dtype is bf16, head_dim 128 and valid_len is
+ * O, which stays on chip.  Arguments as ta_axis_attn_forward; `o_mid` is NULL, or an O-shaped
+ * tensor that receives the output of the first of the two hops as well (what a backward
+ * pass needs); it must not overlap anything else.  Available when `axis + 1` is the
+ * innermost axis, both axes have length 32, dtype is bf16, head_dim 128 and valid_len is
  * unset; otherwise TA_ERR_UNSUPPORTED (ta_plan_pair_kernel tells beforehand). */
 ta_status_t ta_axis_pair_attn_forward(const ta_plan_t* plan, int axis,
                                       const void* q, const void* k, const void* v_in, int vin,
-                                      void* o_out, void* stream);
+                                      void* o_mid, void* o_out, void* stream);
 /* "mfma_bf16_pair_n32" or "unsupported"; NULL on error. */
 const char* ta_plan_pair_kernel(const ta_plan_t* plan, int axis, int vin);
 /* Algorithmic HBM bytes of the fused pair: Q, K, value input read once, O written once. */
 double      ta_plan_pair_bytes(const ta_plan_t* plan, int axis, int vin);
-/* Hop position at which ta_multihop_forward (save_for_backward == 0) switches to the fused
- * pair for the last two hops, or -1 when it runs every hop on its own. */
+/* Hop position at which ta_multihop_forward switches to the fused pair for the last two
+ * hops, or -1 when it runs every hop on its own. */
 int         ta_plan_fused_position(const ta_plan_t* plan);
 
 /* ---- per-axis attention, backward (the paper gives none: Sec. 3.2 only states that a

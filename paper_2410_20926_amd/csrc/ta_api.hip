@@ -338,13 +338,13 @@ ta_status_t ta_axis_attn_forward(const ta_plan_t* pl, int axis, const void* q, c
 }
 
 ta_status_t ta_axis_pair_attn_forward(const ta_plan_t* pl, int axis, const void* q, const void* k, const void* v_in,
-                                      int vin, void* o_out, void* stream) {
+                                      int vin, void* o_mid, void* o_out, void* stream) {
     g_detail[0] = 0;
     ta_status_t st = check_axis_vin(pl, axis, vin);
     if (st != TA_OK) return st;
     if (axis + 1 >= pl->order) return fail(TA_ERR_INVALID_ARG, "axis %d has no inner neighbour", axis);
     if (!q || !k || !v_in || !o_out) return fail(TA_ERR_NULL, "q, k, v_in or o_out is NULL");
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v_in) || !aligned16(o_out))
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v_in) || !aligned16(o_out) || !aligned16(o_mid))
         return fail(TA_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
     const ta_desc_t& d = pl->desc;
     const Range ro = span_of(o_out, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
@@ -354,11 +354,16 @@ ta_status_t ta_axis_pair_attn_forward(const ta_plan_t* pl, int axis, const void*
                                       : span_of(v_in, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
     if (overlaps(ro, rq) || overlaps(ro, rk) || overlaps(ro, rv))
         return fail(TA_ERR_ALIAS, "o_out overlaps an input");
+    if (o_mid) {
+        const Range rm = span_of(o_mid, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
+        if (overlaps(rm, rq) || overlaps(rm, rk) || overlaps(rm, rv) || overlaps(rm, ro))
+            return fail(TA_ERR_ALIAS, "o_mid overlaps an input or o_out");
+    }
     const ta::HopParams h1 = hop_params(pl, axis, q, k, v_in, vin, o_out);
     const ta::HopParams h2 = hop_params(pl, axis + 1, q, k, v_in, vin, o_out);
     if (!ta::mfma_pair_supports(h1, h2, d.dtype))
         return fail(TA_ERR_UNSUPPORTED, "no fused kernel for axes %d and %d of this plan (needs bf16, head_dim 128, the two innermost axes both of length 32, no padding)", axis, axis + 1);
-    hipError_t e = ta::launch_mfma_forward_pair(h1, h2, (hipStream_t)stream);
+    hipError_t e = ta::launch_mfma_forward_pair(h1, h2, o_mid, (hipStream_t)stream);
     if (e != hipSuccess) return fail(TA_ERR_DEVICE, "fused forward launch failed: %s", hipGetErrorString(e));
     return TA_OK;
 }
@@ -432,10 +437,11 @@ ta_status_t ta_multihop_forward(const ta_plan_t* pl, const void* q, const void* 
     char* ws = static_cast<char*>(workspace);
     const void* cur = v;
     int cur_kind = TA_VIN_KV;
-    const int fused = save_for_backward ? -1 : ta_plan_fused_position(pl);
+    const int fused = ta_plan_fused_position(pl);
     for (int pos = 0; pos < m; ++pos) {
-        if (pos == fused)                                  // the last two hops in one launch, no intermediate O
-            return ta_axis_pair_attn_forward(pl, pl->hop_axis[pos], q, k, cur, cur_kind, o, stream);
+        if (pos == fused)                                  // the last two hops in one launch; the O between them is only written for a backward
+            return ta_axis_pair_attn_forward(pl, pl->hop_axis[pos], q, k, cur, cur_kind,
+                                             save_for_backward ? ws + (size_t)pos * pl->o_buf_bytes : nullptr, o, stream);
         void* dst;
         if (pos == m - 1) dst = o;
         else if (save_for_backward) dst = ws + (size_t)pos * pl->o_buf_bytes;

@@ -82,7 +82,7 @@ bool       mfma_backward_is_blocked(const BwdParams& bp, int dtype);   // the va
 hipError_t launch_mfma_backward(const BwdParams& bp, hipStream_t s);
 // Fused pair of hops (axes h1 then h2 = the two innermost axes) in one kernel.
 bool       mfma_pair_supports(const HopParams& h1, const HopParams& h2, int dtype);
-hipError_t launch_mfma_forward_pair(const HopParams& h1, const HopParams& h2, hipStream_t s);
+hipError_t launch_mfma_forward_pair(const HopParams& h1, const HopParams& h2, void* o_mid, hipStream_t s);   // o_mid: nullptr or O-shaped, gets h1's output
 hipError_t launch_rope(const RopeParams& rp, int dtype, hipStream_t s);
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 

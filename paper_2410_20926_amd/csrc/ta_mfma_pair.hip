@@ -44,6 +44,7 @@ constexpr int kLdsBytes = (kABytes > kBBytes) ? kABytes : kBBytes;
 
 struct PairParams {
     Tensor q, k, vin, o;
+    void* mid;                               // nullptr, or an O-shaped tensor that receives the output of the first hop
     int32_t B, Hq, Hkv, G, vin_heads, causal;
     float scale;
     int32_t window1, window2;                // band widths on the outer / inner axis, 0 = none
@@ -128,6 +129,8 @@ __device__ inline void update_fibre(char* lds, uint32_t fb, uint32_t rs, const u
         }
 }
 
+// MID: the intermediate O (the first hop's output) is written out as well, for a backward pass.
+template <bool MID>
 __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int lane = threadIdx.x & 63;
@@ -153,6 +156,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
     const char* kb = reinterpret_cast<const char*>(p.k.p) + ((int64_t)b * p.k.sb + (int64_t)g * p.k.sh) * 2 + tok0 * p.k_row;
     const char* xb = reinterpret_cast<const char*>(p.vin.p) + ((int64_t)b * p.vin.sb + (int64_t)hv * p.vin.sh) * 2 + tok0 * p.v_row;
     char* ob = reinterpret_cast<char*>(p.o.p) + ((int64_t)b * p.o.sb + (int64_t)h * p.o.sh) * 2 + tok0 * p.o_row;
+    char* mb = reinterpret_cast<char*>(p.mid) + ((int64_t)b * p.o.sb + (int64_t)h * p.o.sh) * 2 + tok0 * p.o_row;
 
     // ===== phase A ==================================================================================
     // Loads: 4 lanes per row (16-byte unit ua), 16 rows per pass, 8 passes = this wave's 128 tokens.
@@ -288,6 +292,14 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
 #pragma unroll
         for (int f = 0; f < kOwn; ++f) {
             const uint32_t fb = (uint32_t)((w * kOwn + f) * kBRowsPerI * kBPitch);
+            if (MID) {
+#pragma unroll
+                for (int pp = 0; pp < 4; ++pp) {
+                    const uint32_t t = tok_b + (uint32_t)(f * kN + 8 * pp);
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(lds + fb + (t & 31) * kBPitch + ub * 16);
+                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(mb + (t * p.o_row + (uint32_t)(c * (kCB * 2) + ub * 16))));
+                }
+            }
             update_fibre(lds, fb, (uint32_t)kBPitch, p2[f], inv2[f], lane);
             lds_wave_sync();
 #pragma unroll
@@ -329,9 +341,10 @@ bool mfma_pair_supports(const HopParams& h1, const HopParams& h2, int dtype) {
     return dtype == TA_BF16 && pair_params(h1, h2, &pp);
 }
 
-hipError_t launch_mfma_forward_pair(const HopParams& h1, const HopParams& h2, hipStream_t s) {
+hipError_t launch_mfma_forward_pair(const HopParams& h1, const HopParams& h2, void* o_mid, hipStream_t s) {
     PairParams pp;
     if (!pair_params(h1, h2, &pp)) return hipErrorInvalidValue;
+    pp.mid = o_mid;
     // more than 64 KB of dynamic LDS has to be allowed once per device
     static bool allowed[64] = {};
     int dev = 0;
@@ -339,13 +352,15 @@ hipError_t launch_mfma_forward_pair(const HopParams& h1, const HopParams& h2, hi
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= 64) return hipErrorInvalidValue;
     if (!allowed[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_fwd_pair_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_fwd_pair_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_fwd_pair_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
         allowed[dev] = true;
     }
     const uint32_t span = 8u * (uint32_t)pp.G;
     const uint32_t grid = ((pp.groups + 7u) / 8u) * span;
-    hipLaunchKernelGGL(mfma_fwd_pair_kernel, dim3(grid), dim3(64 * kWaves), kLdsBytes, s, pp);
+    if (o_mid) hipLaunchKernelGGL(mfma_fwd_pair_kernel<true>, dim3(grid), dim3(64 * kWaves), kLdsBytes, s, pp);
+    else       hipLaunchKernelGGL(mfma_fwd_pair_kernel<false>, dim3(grid), dim3(64 * kWaves), kLdsBytes, s, pp);
     return hipGetLastError();
 }
 

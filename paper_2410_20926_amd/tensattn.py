@@ -83,7 +83,7 @@ def load_library():
     lib.ta_plan_backward_scratch_bytes.restype = sz
     lib.ta_axis_attn_forward.argtypes = [vp, i, vp, vp, vp, i, vp, vp]
     lib.ta_axis_attn_forward.restype = i
-    lib.ta_axis_pair_attn_forward.argtypes = [vp, i, vp, vp, vp, i, vp, vp]
+    lib.ta_axis_pair_attn_forward.argtypes = [vp, i, vp, vp, vp, i, vp, vp, vp]
     lib.ta_axis_pair_attn_forward.restype = i
     lib.ta_plan_pair_kernel.argtypes = [vp, i, i]
     lib.ta_plan_pair_kernel.restype = C.c_char_p
@@ -250,9 +250,9 @@ def ta_plan_create(batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, d
     return Plan(make_desc(batch, n_q_heads, n_kv_heads, head_dim, dims, dtype, causal, **kw))
 
 
-def ta_axis_pair_attn_forward(plan: Plan, axis: int, q, k, v_in, vin: int, o_out, stream=None) -> None:
-    _check(load_library().ta_axis_pair_attn_forward(plan.handle, axis, _ptr(q), _ptr(k), _ptr(v_in), vin, _ptr(o_out),
-                                                    _stream(stream)))
+def ta_axis_pair_attn_forward(plan: Plan, axis: int, q, k, v_in, vin: int, o_out, stream=None, o_mid=None) -> None:
+    _check(load_library().ta_axis_pair_attn_forward(plan.handle, axis, _ptr(q), _ptr(k), _ptr(v_in), vin, _ptr(o_mid),
+                                                    _ptr(o_out), _stream(stream)))
 
 
 def ta_axis_attn_forward(plan: Plan, axis: int, q, k, v_in, vin: int, o_out, stream=None) -> None:

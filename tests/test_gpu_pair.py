@@ -6,7 +6,8 @@ import pytest
 import torch
 
 import paper_2410_20926_amd as ta
-from gpu_util import TOL, multihop_forward, to_dev, to_host
+from gpu_util import TOL, multihop_backward, multihop_forward, to_dev, to_host
+from test_gpu_backward import check_grad
 from oracle import tensattn_oracle as orc
 from paper_2410_20926_amd.workloads import make_inputs, round_to_bf16
 
@@ -67,6 +68,13 @@ def test_pair_matches_oracle_and_the_two_single_hops(dims, B, Hq, Hkv, causal, v
     ta.ta_axis_attn_forward(plan, m - 1, dq, dk, mid, ta.TA_VIN_O, two)
     torch.cuda.synchronize()
     assert np.abs(got - to_host(two)).max() <= TOL["bf16"]
+    # with o_mid the launch also hands out the first hop's output, and o_out does not change
+    o2 = torch.full_like(o, float("nan"))
+    got_mid = torch.full_like(o, float("nan"))
+    ta.ta_axis_pair_attn_forward(plan, m - 2, dq, dk, dx, kind, o2, o_mid=got_mid)
+    torch.cuda.synchronize()
+    assert torch.equal(o2, o)
+    assert np.abs(to_host(got_mid) - to_host(mid)).max() <= 2.0 ** -8 * max(1.0, float(np.abs(to_host(mid)).max()))
 
 
 def test_pair_with_bands_and_tables():
@@ -90,16 +98,22 @@ def test_pair_with_bands_and_tables():
         assert err <= TOL["bf16"], f"causal={causal}: max-abs error {err:.3e}"
 
 
-def test_multihop_forward_uses_the_pair_only_without_saving():
+def test_multihop_forward_and_backward_with_the_pair():
     dims, B, Hq, Hkv, D = (4, 32, 32), 1, 8, 2, 128
     N = int(np.prod(dims))
-    q, k, v = make_inputs(B, N, Hq, Hkv, D, seed=8300, dtype="bf16")
+    q, k, v, d_o = make_inputs(B, N, Hq, Hkv, D, seed=8300, dtype="bf16", with_grad=True)
     ref = orc.tensorized_attention_forward(q, k, v, dims, True)
     fused, plan, _ = multihop_forward(q, k, v, dims, "bf16", True, save=False)
     assert plan.fused_position() == 1
     assert plan.workspace_bytes(False) == B * N * Hq * D * 2 and plan.workspace_bytes(True) == 2 * B * N * Hq * D * 2
-    saved, _, _ = multihop_forward(q, k, v, dims, "bf16", True, save=True)
-    assert np.abs(fused - ref).max() <= TOL["bf16"] and np.abs(saved - ref).max() <= TOL["bf16"]
+    saved, plan_s, dev = multihop_forward(q, k, v, dims, "bf16", True, save=True)
+    assert np.abs(fused - ref).max() <= TOL["bf16"] and np.array_equal(saved, fused)
+    # the saving forward wrote both intermediate O tensors: the backward that reads them matches the oracle
+    dq, dk, dv = multihop_backward(plan_s, dev, d_o, "bf16")
+    rq, rk, rv = orc.tensorized_attention_backward(q, k, v, d_o, dims, True)
+    check_grad(dq, rq, "bf16", "dq")
+    check_grad(dk, rk, "bf16", "dk")
+    check_grad(dv, rv, "bf16", "dv")
     # another hop order: the pair is not at the end, every hop runs on its own
     swapped, plan2, _ = multihop_forward(q, k, v, dims, "bf16", True, hop_order=(1, 0, 2))
     assert plan2.fused_position() == -1
