@@ -11,6 +11,8 @@
 namespace ta {
 namespace {
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 __device__ inline float lo_bf16(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ inline float hi_bf16(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 __device__ inline uint32_t to_bf16(float x) {
@@ -42,49 +44,60 @@ __device__ inline void pair_rotation(const RopeParams& rp, uint32_t tok, int f, 
     s = (float)sd;
 }
 
+// One work item = one 16-byte chunk position of one token: its rotations are computed once
+// and applied to that chunk of every head (the angles do not depend on the head, and their
+// double-precision sine and cosine cost far more than the memory traffic of one chunk).
 template <typename T>
 __global__ __launch_bounds__(256) void rope_kernel(RopeParams rp) {
     constexpr int E = 16 / sizeof(T);                     // features per 16-byte chunk
+    constexpr int P = E / 2;                              // rotary pairs per chunk
+    constexpr int kBatch = 8;                             // heads in flight per lane
     const int chunks = rp.D / E;                          // D is a multiple of 8
-    const uint64_t total = (uint64_t)rp.B * rp.N * rp.H * chunks;
+    const uint64_t total = (uint64_t)rp.B * rp.N * chunks;
     for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (uint64_t)gridDim.x * blockDim.x) {
         const int ch = (int)(i % chunks);
-        uint64_t r = i / chunks;
-        const int h = (int)(r % rp.H); r /= rp.H;
+        const uint64_t r = i / chunks;
         const uint32_t tok = (uint32_t)(r % rp.N);
         const int b = (int)(r / rp.N);
-        const int64_t off = (int64_t)b * rp.x.sb + (int64_t)tok * rp.x.st + (int64_t)h * rp.x.sh + ch * E;
-        const uint4 in = *reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(rp.x.p) + off);
-        uint4 out;
-        const uint32_t iw[4] = {in.x, in.y, in.z, in.w};
-        uint32_t ow[4];
-        if (sizeof(T) == 2) {
+        float c[P], s[P];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {                 // one pair per 32-bit word
-                float c, s;
-                pair_rotation(rp, tok, ch * E + 2 * k, c, s);
-                const float e = lo_bf16(iw[k]), o = hi_bf16(iw[k]);
-                ow[k] = to_bf16(e * c - o * s) | (to_bf16(e * s + o * c) << 16);
-            }
-        } else {
+        for (int k = 0; k < P; ++k) pair_rotation(rp, tok, ch * E + 2 * k, c[k], s[k]);
+        const int64_t off0 = (int64_t)b * rp.x.sb + (int64_t)tok * rp.x.st + ch * E;
+        for (int h0 = 0; h0 < rp.H; h0 += kBatch) {
+            u32x4 in[kBatch];
 #pragma unroll
-            for (int k = 0; k < 2; ++k) {                 // one pair per two words
-                float c, s;
-                pair_rotation(rp, tok, ch * E + 2 * k, c, s);
-                const float e = __uint_as_float(iw[2 * k]), o = __uint_as_float(iw[2 * k + 1]);
-                ow[2 * k] = __float_as_uint(e * c - o * s);
-                ow[2 * k + 1] = __float_as_uint(e * s + o * c);
+            for (int j = 0; j < kBatch; ++j)
+                if (h0 + j < rp.H) in[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(reinterpret_cast<const T*>(rp.x.p) + off0 + (int64_t)(h0 + j) * rp.x.sh));
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                if (h0 + j >= rp.H) continue;
+                const uint32_t iw[4] = {in[j].x, in[j].y, in[j].z, in[j].w};
+                uint32_t ow[4];
+                if (sizeof(T) == 2) {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {         // one pair per 32-bit word
+                        const float e = lo_bf16(iw[k]), o = hi_bf16(iw[k]);
+                        ow[k] = to_bf16(e * c[k % P] - o * s[k % P]) | (to_bf16(e * s[k % P] + o * c[k % P]) << 16);
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 2; ++k) {         // one pair per two words
+                        const float e = __uint_as_float(iw[2 * k]), o = __uint_as_float(iw[2 * k + 1]);
+                        ow[2 * k] = __float_as_uint(e * c[k] - o * s[k]);
+                        ow[2 * k + 1] = __float_as_uint(e * s[k] + o * c[k]);
+                    }
+                }
+                __builtin_nontemporal_store(u32x4{ow[0], ow[1], ow[2], ow[3]},
+                                            reinterpret_cast<u32x4*>(reinterpret_cast<T*>(rp.y.p) + off0 + (int64_t)(h0 + j) * rp.x.sh));
             }
         }
-        out = make_uint4(ow[0], ow[1], ow[2], ow[3]);
-        *reinterpret_cast<uint4*>(reinterpret_cast<T*>(rp.y.p) + off) = out;
     }
 }
 
 }  // namespace
 
 hipError_t launch_rope(const RopeParams& rp, int dtype, hipStream_t s) {
-    const uint64_t total = (uint64_t)rp.B * rp.N * rp.H * (rp.D / (dtype == TA_F32 ? 4 : 8));
+    const uint64_t total = (uint64_t)rp.B * rp.N * (rp.D / (dtype == TA_F32 ? 4 : 8));
     if (total == 0) return hipSuccess;
     uint64_t blocks = (total + 255) / 256;
     if (blocks > 256 * 64) blocks = 256 * 64;
