@@ -105,8 +105,8 @@ int64_t ta_plan_axis_stride(const ta_plan_t* plan, int axis); /* tokens between 
 int64_t ta_plan_axis_fibres(const ta_plan_t* plan, int axis); /* N / n_axis per (batch, head); -1 on error */
 int     ta_plan_hop_axis(const ta_plan_t* plan, int hop_position); /* axis run at position 0..m-1; -1 on error */
 /* Name of the kernel variant the plan chose for the forward hop on `axis` with value
- * input `vin` ("mfma_bf16_n32", "mfma_bf16_n64", their group-shared forms "..._shared" and, when the
- * value input is per key/value head, "..._shared_kv", "mfma_bf16_stream", "generic"); NULL on
+ * input `vin` ("mfma_bf16_n32", "mfma_bf16_n64", "mfma_bf16_stream", their group-shared forms
+ * "..._shared" and, when the value input is per key/value head, "..._shared_kv", "generic"); NULL on
  * error.  Static storage. */
 const char* ta_plan_hop_kernel(const ta_plan_t* plan, int axis, int vin);
 /* Same for the backward of that hop ("mfma_bf16_bwd_n32", "generic", or "unsupported" when

@@ -238,7 +238,7 @@ const char* ta_plan_hop_kernel(const ta_plan_t* pl, int axis, int vin) {
         // its instantiation that also shares the value tile (value input per key/value head) is "_kv"
         case ta::K_MFMA_BF16_N32: return pl->G % 4 != 0 ? "mfma_bf16_n32" : vin == TA_VIN_KV ? "mfma_bf16_n32_shared_kv" : "mfma_bf16_n32_shared";
         case ta::K_MFMA_BF16_N64: return pl->G % 4 != 0 ? "mfma_bf16_n64" : vin == TA_VIN_KV ? "mfma_bf16_n64_shared_kv" : "mfma_bf16_n64_shared";
-        case ta::K_MFMA_BF16_STREAM: return "mfma_bf16_stream";
+        case ta::K_MFMA_BF16_STREAM: return pl->G % 4 != 0 ? "mfma_bf16_stream" : vin == TA_VIN_KV ? "mfma_bf16_stream_shared_kv" : "mfma_bf16_stream_shared";
     }
     return nullptr;
 }

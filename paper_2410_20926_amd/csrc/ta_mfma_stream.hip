@@ -199,6 +199,217 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
     }
 }
 
+// Group-shared variant, for grouped-query heads with 4 (or a multiple of 4) query heads per
+// key/value head: the 4 waves of a workgroup are 4 heads of one group working on the same
+// query tile, so they walk the same key tiles.  Each wave fetches a quarter of every K tile
+// (and of every V tile when the value input is per key/value head, VS) into a workgroup-shared,
+// double-buffered LDS tile: K and V leave L2 once per workgroup instead of once per head, with
+// one barrier per key tile.
+template <int D, bool VS>
+__global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared_kernel(HopParams p, StreamParams sp) {
+    using G = Geo<D>;
+    constexpr int kBuf = kTile * G::kPitch;
+    constexpr int kMine = G::kPasses / kWavesPerBlock;    // passes of a shared tile this wave fetches
+    static_assert(G::kPasses % kWavesPerBlock == 0, "a tile splits evenly over the waves");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = blockIdx.x * kWavesPerBlock + w;
+    const uint32_t zb = blockIdx.z / sp.tiles_hi;
+    const uint32_t tt = (blockIdx.z - zb * sp.tiles_hi) * sp.tiles_lo + blockIdx.y;
+    if (tt >= sp.tiles) return;                           // whole workgroup leaves together (every head exists: 4 divides G)
+    const int b = (int)zb;
+    const int g = h / p.G;
+    const int hv = VS ? g : h;
+    const int n = p.n;
+    char* sK = smem;                                      // two K tiles
+    char* sV = smem + 2 * kBuf;                           // two V tiles (VS only)
+    char* buf = smem + (VS ? 4 : 2) * kBuf + w * kBuf;    // this wave's own transit tile
+
+    const uint32_t f = tt / sp.qtiles;
+    const int qt = (int)(sp.qtiles - 1 - (tt - f * sp.qtiles));
+    const uint32_t stride = (uint32_t)p.stride;
+    const uint32_t outer = f / stride;
+    const uint32_t tok0 = outer * stride * n + (f - outer * stride);
+
+    const char* qb = reinterpret_cast<const char*>(p.q.p) + ((int64_t)b * p.q.sb + (int64_t)h * p.q.sh) * 2 + tok0 * sp.q_row;
+    const char* kb = reinterpret_cast<const char*>(p.k.p) + ((int64_t)b * p.k.sb + (int64_t)g * p.k.sh) * 2 + tok0 * sp.k_row;
+    const char* vb = reinterpret_cast<const char*>(p.vin.p) + ((int64_t)b * p.vin.sb + (int64_t)hv * p.vin.sh) * 2 + tok0 * sp.v_row;
+    char* ob = reinterpret_cast<char*>(p.o.p) + ((int64_t)b * p.o.sb + (int64_t)h * p.o.sh) * 2 + tok0 * sp.o_row;
+
+    const int lrow = lane / G::kChunks, lcol = lane % G::kChunks;
+    const uint32_t lbyte = lcol * 16;
+    const int r32 = lane & 31, hf = lane >> 5;
+    const int ktiles = (n + kTile - 1) / kTile;
+    int jbeg = 0, jend = p.causal ? qt + 1 : ktiles;
+    if (p.window > 0) {
+        jbeg = max(0, qt * kTile - p.window + 1) / kTile;
+        jend = min(jend, (qt * kTile + kTile - 1 + p.window - 1) / kTile + 1);
+    }
+
+    u32x4 qreg[G::kPasses], kpart[kMine], vpart[VS ? kMine : 1], vreg[VS ? 1 : G::kPasses];
+    uint32_t ooff[G::kPasses];
+    auto load_shared = [&](int j) {                       // this wave's quarter of key tile j
+#pragma unroll
+        for (int i = 0; i < kMine; ++i) {
+            const uint32_t rk = (uint32_t)min(j * kTile + (w * kMine + i) * G::kRowsPerPass + lrow, n - 1);
+            kpart[i] = *reinterpret_cast<const u32x4*>(kb + (rk * sp.k_step + lbyte));
+            if (VS) vpart[i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
+        }
+    };
+    auto write_shared = [&](int slot) {
+#pragma unroll
+        for (int i = 0; i < kMine; ++i) {
+            const uint32_t at = (uint32_t)(slot * kBuf + ((w * kMine + i) * G::kRowsPerPass + lrow) * G::kPitch) + lbyte;
+            *reinterpret_cast<u32x4*>(sK + at) = kpart[i];
+            if (VS) *reinterpret_cast<u32x4*>(sV + at) = vpart[i];
+        }
+    };
+    auto load_own_v = [&](int j) {                        // a per-head value tile is this wave's alone
+#pragma unroll
+        for (int i = 0; i < (VS ? 0 : G::kPasses); ++i) {
+            const uint32_t rk = (uint32_t)min(j * kTile + i * G::kRowsPerPass + lrow, n - 1);
+            vreg[i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
+        }
+    };
+#pragma unroll
+    for (int i = 0; i < G::kPasses; ++i) {
+        const uint32_t rq = (uint32_t)min(qt * kTile + i * G::kRowsPerPass + lrow, n - 1);
+        qreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (rq * sp.q_step + lbyte)));
+        ooff[i] = rq * sp.o_step + lbyte;
+    }
+    load_shared(jbeg);
+    if (!VS) load_own_v(jbeg);
+    __builtin_amdgcn_sched_barrier(0);
+
+    char* stg = buf + lrow * G::kPitch + lbyte;
+    const uint32_t oprd = (uint32_t)(r32 * G::kPitch + hf * 16);
+    const uint32_t troff = (uint32_t)((4 * hf + ((lane & 15) >> 2)) * G::kPitch + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2);
+
+    u32x4 qop[G::kKSteps];
+    stage_rows<D>(stg, qreg);
+    lds_wave_sync();
+    read_natural<D>(buf + oprd, qop);
+    lds_wave_sync();
+    write_shared(0);
+
+    const uint32_t vl = (uint32_t)p.valid_len;
+    const int nreal = tok0 >= vl ? 0 : (int)min((uint32_t)n, (vl - tok0 + stride - 1) / stride);
+    const int qrow = qt * kTile + r32;
+    int klo = 0, khi = 0;
+    if (qrow < nreal) {
+        visible_range(qrow, 0, n, p.causal, p.window, klo, khi);
+        khi = min(khi, nreal);
+    }
+    const float sl2 = p.scale * kLog2e;
+    float m = -INFINITY, l = 0.f;
+    f32x16 ot[G::kDTiles];
+#pragma unroll
+    for (int t = 0; t < G::kDTiles; ++t) ot[t] = f32x16{};
+
+    for (int j = jbeg; j < jend; ++j) {
+        const int slot = (j - jbeg) & 1;
+        if (j + 1 < jend) load_shared(j + 1);             // lands while this tile is being used
+        __syncthreads();                                  // tile j is complete; nobody reads the other slot any more
+        u32x4 kop[G::kKSteps];
+        read_natural<D>(sK + slot * kBuf + oprd, kop);
+        f32x16 st = {};
+#pragma unroll
+        for (int s = 0; s < G::kKSteps; ++s) st = mma(kop[s], qop[s], st);
+
+        const uint32_t tw = qrow < nreal ? table_word(p, qrow, j) : 0u;
+        const uint32_t vis = (range_mask(min(max(klo - kTile * j, 0), kTile), min(max(khi - kTile * j, 0), kTile)) & tw) >> (4 * hf);
+        float e[16], tmax = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const bool ok = (vis >> (8 * (r / 4) + (r % 4))) & 1u;
+            e[r] = ok ? st[r] * sl2 : -INFINITY;
+            tmax = fmaxf(tmax, e[r]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float mnew = fmaxf(m, tmax);
+        const float msafe = mnew == -INFINITY ? 0.f : mnew;
+        const float corr = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - msafe);
+        m = mnew;
+        u32x4 pop[2];
+        float psum = 0.f;
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            uint32_t wds[4];
+#pragma unroll
+            for (int jp = 0; jp < 4; ++jp) {
+                const int r = 8 * s2 + 2 * jp;
+                const uint32_t pk = pack_bf16x2(__builtin_amdgcn_exp2f(e[r] - msafe), __builtin_amdgcn_exp2f(e[r + 1] - msafe));
+                psum += bf16_lo(pk) + bf16_hi(pk);        // sum of the ROUNDED weights
+                wds[jp] = pk;
+            }
+            pop[s2] = u32x4{wds[0], wds[1], wds[2], wds[3]};
+        }
+        psum += __shfl_xor(psum, 32);
+        l = l * corr + psum;
+
+        u32x4 vT[G::kDTiles][2];
+        if constexpr (VS) {
+            read_transposed<D>(sV + slot * kBuf + troff, vT);
+        } else {
+            stage_rows<D>(stg, vreg);
+            lds_wave_sync();
+            read_transposed<D>(buf + troff, vT);
+            lds_wave_sync();
+            if (j + 1 < jend) load_own_v(j + 1);
+        }
+#pragma unroll
+        for (int t = 0; t < G::kDTiles; ++t) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) ot[t][r] *= corr;
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) ot[t] = mma(vT[t][s2], pop[s2], ot[t]);
+        }
+        if (j + 1 < jend) write_shared(slot ^ 1);         // the other slot was last read before this iteration's barrier
+    }
+
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+    lds_wave_sync();
+#pragma unroll
+    for (int t = 0; t < G::kDTiles; ++t)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            u32x2 v;
+            v.x = pack_bf16x2(ot[t][4 * q4] * inv, ot[t][4 * q4 + 1] * inv);
+            v.y = pack_bf16x2(ot[t][4 * q4 + 2] * inv, ot[t][4 * q4 + 3] * inv);
+            *reinterpret_cast<u32x2*>(buf + r32 * G::kPitch + (32 * t + 8 * q4 + 4 * hf) * 2) = v;
+        }
+    lds_wave_sync();
+#pragma unroll
+    for (int i = 0; i < G::kPasses; ++i) {
+        const int row = qt * kTile + i * G::kRowsPerPass + lrow;
+        if (row < n) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(ob + ooff[i]));
+        }
+    }
+}
+
+template <int D, bool VS>
+hipError_t launch_shared(const HopParams& p, const StreamParams& sp, hipStream_t s) {
+    const size_t smem = (size_t)((VS ? 4 : 2) + kWavesPerBlock) * kTile * Geo<D>::kPitch;
+    const dim3 grid((unsigned)(p.Hq / kWavesPerBlock), sp.tiles_lo, (unsigned)p.B * sp.tiles_hi);
+    if (smem > 64 * 1024) {                               // more than 64 KB of dynamic LDS has to be allowed once per device
+        static bool allowed[64] = {};
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 64) return hipErrorInvalidValue;
+        if (!allowed[dev]) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_fwd_stream_shared_kernel<D, VS>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e != hipSuccess) return e;
+            allowed[dev] = true;
+        }
+    }
+    hipLaunchKernelGGL((mfma_fwd_stream_shared_kernel<D, VS>), grid, dim3(kWavesPerBlock * 64), smem, s, p, sp);
+    return hipGetLastError();
+}
+
 template <int D>
 hipError_t launch(const HopParams& p, const StreamParams& sp, hipStream_t s) {
     const size_t smem = (size_t)kWavesPerBlock * kTile * Geo<D>::kPitch;
@@ -227,6 +438,11 @@ hipError_t launch_mfma_forward_stream(const HopParams& p, hipStream_t s) {
     sp.k_step = (uint32_t)(p.stride * p.k.st * 2);
     sp.v_step = (uint32_t)(p.stride * p.vin.st * 2);
     sp.o_step = (uint32_t)(p.stride * p.o.st * 2);
+    if (p.G % kWavesPerBlock == 0) {                      // the 4 waves of a workgroup are 4 heads of one group
+        const bool vs = p.vin_heads != p.Hq;
+        if (p.D == 128) return vs ? launch_shared<128, true>(p, sp, s) : launch_shared<128, false>(p, sp, s);
+        return vs ? launch_shared<64, true>(p, sp, s) : launch_shared<64, false>(p, sp, s);
+    }
     return p.D == 128 ? launch<128>(p, sp, s) : launch<64>(p, sp, s);
 }
 

@@ -204,7 +204,7 @@ def test_offsets_near_the_32_bit_limit():
     from paper_2410_20926_amd.workloads import draw
     v = draw((1, N, Hkv, D), rng, 1.0, "bf16")
     plan = ta.ta_plan_create(1, Hq, Hkv, D, dims, ta.TA_BF16, True)
-    assert [plan.hop_kernel(a, 1) for a in range(3)] == ["mfma_bf16_stream", "mfma_bf16_n64_shared", "mfma_bf16_n64_shared"]
+    assert [plan.hop_kernel(a, 1) for a in range(3)] == ["mfma_bf16_stream_shared", "mfma_bf16_n64_shared", "mfma_bf16_n64_shared"]
     tq = torch.zeros(1, N, Hq, D, dtype=torch.bfloat16, device="cuda")
     tk = torch.zeros(1, N, Hkv, D, dtype=torch.bfloat16, device="cuda")
     tv = to_dev(v, "bf16")
