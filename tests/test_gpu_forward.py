@@ -102,11 +102,11 @@ def test_hop_order_and_scale_are_honoured():
     assert np.abs(other - ref).max() > 1e-3
 
 
-@pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_strided_head_major_layout(dtype):
+@pytest.mark.parametrize("dtype,dims", [("f32", (32, 6)), ("bf16", (32, 6)), ("bf16", (3, 32, 32))])   # the last: fused pair
+def test_strided_head_major_layout(dtype, dims):
     """Every tensor stored [B, H, N, D]; results must equal the dense call's."""
-    B, Hq, Hkv, D, dims = 2, 4, 2, 128, (32, 6)
-    N = 192
+    B, Hq, Hkv, D = 2, 4, 2, 128
+    N = int(np.prod(dims))
     q, k, v = make_inputs(B, N, Hq, Hkv, D, seed=9, dtype=dtype)
     ref = orc.tensorized_attention_forward(q, k, v, dims, True)
     sq = (Hq * N * D, D, N * D)
