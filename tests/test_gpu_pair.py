@@ -121,6 +121,18 @@ def test_multihop_forward_and_backward_with_the_pair():
     assert np.abs(swapped - ref2).max() <= TOL["bf16"]
 
 
+def test_order_two_needs_no_workspace_when_fused():
+    dims, B, Hq, Hkv, D = (32, 32), 2, 4, 1, 128
+    q, k, v = make_inputs(B, 1024, Hq, Hkv, D, seed=8400, dtype="bf16")
+    plan = ta.ta_plan_create(B, Hq, Hkv, D, dims, ta.TA_BF16, False)
+    assert plan.fused_position() == 0 and plan.workspace_bytes(False) == 0
+    o = torch.full((B, 1024, Hq, D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ta.ta_multihop_forward(plan, to_dev(q, "bf16"), to_dev(k, "bf16"), to_dev(v, "bf16"), o, None, 0, False)
+    torch.cuda.synchronize()
+    ref = orc.tensorized_attention_forward(q, k, v, dims, False)
+    assert np.abs(to_host(o) - ref).max() <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("kw", [dict(dims=(32, 16)), dict(dims=(32, 32, 2)), dict(dims=(32, 32), valid_len=1000),
                                 dict(dims=(32, 32), dtype=ta.TA_F32), dict(dims=(32, 32), D=64)])
 def test_pair_refuses_what_it_does_not_cover(kw):
