@@ -121,6 +121,19 @@ def test_multihop_forward_and_backward_with_the_pair():
     assert np.abs(swapped - ref2).max() <= TOL["bf16"]
 
 
+def test_pair_with_sharp_softmax():
+    """Logits with a standard deviation of 16: nearly one-hot attention rows, exercising the max subtraction."""
+    dims, B, Hq, Hkv, D = (2, 32, 32), 1, 4, 2, 128
+    N = int(np.prod(dims))
+    q, k, v = make_inputs(B, N, Hq, Hkv, D, seed=8500, dtype="bf16", qk_scale=4.0)
+    for causal in (False, True):
+        got, plan, _ = multihop_forward(q, k, v, dims, "bf16", causal)
+        assert plan.fused_position() == 1
+        ref = orc.tensorized_attention_forward(q, k, v, dims, causal)
+        assert np.isfinite(got).all()
+        assert np.abs(got - ref).max() <= TOL["bf16"]
+
+
 def test_order_two_needs_no_workspace_when_fused():
     dims, B, Hq, Hkv, D = (32, 32), 2, 4, 1, 128
     q, k, v = make_inputs(B, 1024, Hq, Hkv, D, seed=8400, dtype="bf16")
