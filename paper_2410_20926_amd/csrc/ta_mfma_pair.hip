@@ -1,6 +1,6 @@
 // Two consecutive hops of Algorithm 1 in one kernel: the hop along the second-innermost
 // tensor axis followed by the hop along the innermost one (Eq. 4 twice, with the same Q and
-// K), for 32 x 32 slabs, bf16, head width 128.  The intermediate value tensor of the pair
+// K), for 32 x 32 slabs, bf16, head width 128, with every per-axis mask of the single-hop kernels.  The intermediate value tensor of the pair
 // never leaves the chip, and Q, K, the value input and the output each cross HBM once.
 //
 // A slab is the 1,024 consecutive tokens (i, j), i on the outer of the two axes, j on the
@@ -53,6 +53,7 @@ struct PairParams {
     uint32_t slabs;                          // slabs per batch element
     uint32_t groups;                         // B * slabs * Hkv
     uint32_t q_row, k_row, v_row, o_row;     // token pitch of each tensor in bytes
+    int64_t valid_len;                       // tokens at or past it (per batch element) are padding; N when there is none
 };
 
 // Phase-A LDS layout.  Token (i, j)'s 64-byte chunk row of Q sits at i * kABlock + j * 64, that
@@ -64,11 +65,12 @@ struct PairParams {
 // Masked row softmax of one 32 x 32 score tile held as S^T (lane = query row, 16 keys per
 // lane, the other 16 in lane ^ 32).  Returns the rounded, un-normalised probabilities as
 // two B operands and 1 / (their row sum).
+// Positions at or past `nreal` of the fibre are padding: never a key, and a padded row sees nothing.
 __device__ inline void softmax_tile(const f32x16& st, int r32, int hf, int causal, int window, const uint32_t* table,
-                                    float sl2, u32x4 (&pop)[2], float& inv) {
+                                    int nreal, float sl2, u32x4 (&pop)[2], float& inv) {
     int lo, hi;
     visible_range(r32, 0, kN, causal, window, lo, hi);
-    uint32_t vis = range_mask(lo, hi);
+    uint32_t vis = r32 < nreal ? range_mask(lo, min(hi, nreal)) : 0u;
     if (table) vis &= table[r32];
     vis >>= 4 * hf;
     float e[16], mx = -INFINITY;
@@ -260,16 +262,23 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
     __syncthreads();
     scores();
 
-    // softmax of the 8 tiles
+    // softmax of the 8 tiles; `left` = real (unpadded) tokens from the slab's first token on
     const float sl2 = p.scale * kLog2e;
+    const int64_t left = p.valid_len - tok0;
     u32x4 p1[kOwn][2], p2[kOwn][2];
     float inv1[kOwn], inv2[kOwn];
 #pragma unroll
-    for (int f = 0; f < kOwn; ++f) softmax_tile(sc[f], r32, hf, p.causal, p.window1, p.mask1, sl2, p1[f], inv1[f]);
+    for (int f = 0; f < kOwn; ++f) {                      // column fibre j = 4 w + f: slab rows i with token 32 i + j < left
+        const int64_t room = left - (w * kOwn + f);
+        softmax_tile(sc[f], r32, hf, p.causal, p.window1, p.mask1, room <= 0 ? 0 : (int)min((int64_t)kN, (room + kN - 1) / kN), sl2, p1[f], inv1[f]);
+    }
     load_x(0, 8, 16);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int f = 0; f < kOwn; ++f) softmax_tile(sr[f], r32, hf, p.causal, p.window2, p.mask2, sl2, p2[f], inv2[f]);
+    for (int f = 0; f < kOwn; ++f) {                      // row fibre i = 4 w + f: columns j with token 32 i + j < left
+        const int64_t room = left - (int64_t)(w * kOwn + f) * kN;
+        softmax_tile(sr[f], r32, hf, p.causal, p.window2, p.mask2, room <= 0 ? 0 : (int)min((int64_t)kN, room), sl2, p2[f], inv2[f]);
+    }
 
     // ===== phase B ==================================================================================
     __syncthreads();                                      // phase A's LDS contents are dead
@@ -316,7 +325,6 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
 bool pair_params(const HopParams& h1, const HopParams& h2, PairParams* pp) {
     if (h1.n != kN || h2.n != kN || h1.D != kD || h2.stride != 1 || h1.stride != kN) return false;
     const int64_t N = h1.fibres * h1.n;
-    if (h1.valid_len != N) return false;
     if (!fits_u32(h1.q, kSlab) || !fits_u32(h1.k, kSlab) || !fits_u32(h1.vin, kSlab) || !fits_u32(h1.o, kSlab)) return false;
     if (N % kSlab != 0 || h1.G < 1 || h1.G > 64) return false;
     const int64_t slabs = N / kSlab;
@@ -327,6 +335,7 @@ bool pair_params(const HopParams& h1, const HopParams& h2, PairParams* pp) {
     pp->scale = h1.scale;
     pp->window1 = h1.window; pp->window2 = h2.window;
     pp->mask1 = h1.mask; pp->mask2 = h2.mask;
+    pp->valid_len = h1.valid_len;
     pp->slabs = (uint32_t)slabs;
     pp->groups = (uint32_t)groups;
     pp->q_row = (uint32_t)(h1.q.st * 2); pp->k_row = (uint32_t)(h1.k.st * 2);

@@ -146,7 +146,23 @@ def test_order_two_needs_no_workspace_when_fused():
     assert np.abs(to_host(o) - ref).max() <= TOL["bf16"]
 
 
-@pytest.mark.parametrize("kw", [dict(dims=(32, 16)), dict(dims=(32, 32, 2)), dict(dims=(32, 32), valid_len=1000),
+@pytest.mark.parametrize("valid_len", [2900, 2048 + 5, 1024, 37])
+@pytest.mark.parametrize("causal", [False, True])
+def test_pair_with_padding(valid_len, causal):
+    """Tokens at or past valid_len are padding: a slab cut in the middle of a row, at a row, a whole
+    padded slab, and a sequence of barely more than one row."""
+    dims, B, Hq, Hkv, D = (3, 32, 32), 2, 4, 2, 128
+    N = int(np.prod(dims))
+    q, k, v = make_inputs(B, N, Hq, Hkv, D, seed=8600 + valid_len, dtype="bf16")
+    got, plan, _ = multihop_forward(q, k, v, dims, "bf16", causal, valid_len=valid_len)
+    assert plan.fused_position() == 1
+    ref = orc.tensorized_attention_forward(q, k, v, dims, causal, valid_len=valid_len)
+    assert np.isfinite(got).all()
+    assert np.abs(got - ref).max() <= TOL["bf16"]
+    assert (got[:, valid_len:] == 0).all()
+
+
+@pytest.mark.parametrize("kw", [dict(dims=(32, 16)), dict(dims=(32, 32, 2)),
                                 dict(dims=(32, 32), dtype=ta.TA_F32), dict(dims=(32, 32), D=64)])
 def test_pair_refuses_what_it_does_not_cover(kw):
     dims = kw.pop("dims")
