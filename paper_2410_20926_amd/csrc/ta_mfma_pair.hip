@@ -160,6 +160,17 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
     char* ob = reinterpret_cast<char*>(p.o.p) + ((int64_t)b * p.o.sb + (int64_t)h * p.o.sh) * 2 + tok0 * p.o_row;
     char* mb = reinterpret_cast<char*>(p.mid) + ((int64_t)b * p.o.sb + (int64_t)h * p.o.sh) * 2 + tok0 * p.o_row;
 
+    if (p.valid_len <= tok0) {                            // the whole slab is padding: its outputs are zero, nothing is read
+#pragma unroll 4
+        for (int pp = 0; pp < kOwn * kN / 4; ++pp) {
+            const uint32_t t = (uint32_t)(w * (kOwn * kN) + pp * 4 + (lane >> 4));
+            const uint32_t off = t * p.o_row + (uint32_t)((lane & 15) * 16);
+            __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, reinterpret_cast<u32x4*>(ob + off));
+            if (MID) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, reinterpret_cast<u32x4*>(mb + off));
+        }
+        return;
+    }
+
     // ===== phase A ==================================================================================
     // Loads: 4 lanes per row (16-byte unit ua), 16 rows per pass, 8 passes = this wave's 128 tokens.
     // Both halves of a 128-byte line of Q are requested together (the second waits in registers

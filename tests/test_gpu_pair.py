@@ -160,6 +160,11 @@ def test_pair_with_padding(valid_len, causal):
     assert np.isfinite(got).all()
     assert np.abs(got - ref).max() <= TOL["bf16"]
     assert (got[:, valid_len:] == 0).all()
+    saved, plan_s, dev = multihop_forward(q, k, v, dims, "bf16", causal, save=True, valid_len=valid_len)
+    assert np.array_equal(saved, got)
+    o_bytes = B * N * Hq * D * 2
+    mid = dev["ws"][o_bytes:2 * o_bytes].view(torch.bfloat16).view(B, N, Hq, D)      # the O between the fused hops
+    assert (to_host(mid)[:, valid_len:] == 0).all() and np.isfinite(to_host(mid)).all()
 
 
 @pytest.mark.parametrize("kw", [dict(dims=(32, 16)), dict(dims=(32, 32, 2)),
