@@ -9,7 +9,7 @@ already live in HBM.  Prints ONE JSON line:
                       HIP-event timings of every hop launch (algorithmic bytes / time)
   cpu_baseline      : the CPU oracle, as it stands, timed on a bounded sample (whole
                       sequences of a few heads) on the host cores of this machine
-Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c4|c2|c5]
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c4|c2|c5|c6]
 """
 from __future__ import annotations
 
@@ -31,18 +31,18 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5", "c6"])
     ap.add_argument("--rotate", type=int, default=3, help="independent buffer sets cycled through, so that the "
                     "256 MB Infinity Cache cannot serve one step's re-reads from the previous step")
     ap.add_argument("--also", default=None, help="comma-separated further workloads measured in the same run and "
-                    "reported under other_workloads (default: c4,c5 next to c3, none otherwise)")
+                    "reported under other_workloads (default: c4,c5,c6 next to c3, none otherwise)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true", help="also launch the plain copy kernel on 1 GiB a few "
                     "times, so that a hardware-counter run of this command has a transfer of known size to scale by")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     args = ap.parse_args()
     if args.also is None:
-        args.also = "c4,c5" if args.workload == "c3" else ""
+        args.also = "c4,c5,c6" if args.workload == "c3" else ""
     return args
 
 

@@ -180,7 +180,13 @@ def test_config4_full_size_sampled_heads():
     assert plan.hop_kernel(0, 0) != "generic"
 
 
-@pytest.mark.parametrize("name,causal", [("c3", True), ("c3", False), ("c4", True)])
+def test_extrapolated_128k_shape_full_size_sampled_heads():
+    """128 x 32 x 32: a streamed first hop, then the fused pair."""
+    plan, _ = full_size_case("c6", [5, 30])
+    assert plan.hop_kernel(0, 0) == "mfma_bf16_stream_shared_kv" and plan.fused_position() == 1
+
+
+@pytest.mark.parametrize("name,causal", [("c3", True), ("c3", False), ("c4", True), ("c6", True)])
 def test_zero_queries_closed_form_at_full_size(name, causal):
     """Property that holds at any size and touches every fibre of every head."""
     w = WORKLOADS[name]
