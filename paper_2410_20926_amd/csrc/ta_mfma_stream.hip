@@ -10,6 +10,7 @@
 // transposed read (ds_read_b64_tr_b16) as the A operand, O^T = corr * O^T + V^T P^T.
 // The loads of tile j + 1 are issued as soon as tile j has left its registers.
 #include "ta_mfma_common.h"
+#include <type_traits>
 
 namespace ta {
 namespace {
@@ -247,23 +248,37 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
         jend = min(jend, (qt * kTile + kTile - 1 + p.window - 1) / kTile + 1);
     }
 
-    u32x4 qreg[G::kPasses], kpart[kMine], vpart[VS ? kMine : 1], vreg[VS ? 1 : G::kPasses];
+    // This wave's quarters of the next three key tiles travel in three register sets (tile t in
+    // set (t - jbeg) % 3): a tile is requested three steps before it is used, which covers the
+    // memory latency that one step of compute does not.
+    u32x4 qreg[G::kPasses], vreg[VS ? 1 : G::kPasses];
+    u32x4 kp[3][kMine], vp[3][VS ? kMine : 1];
     uint32_t ooff[G::kPasses];
-    auto load_shared = [&](int j) {                       // this wave's quarter of key tile j
+    // `set` is the same in every lane; the unrolled comparison turns it into scalar branches
+    // around code with fixed register names (no indexed registers)
+    auto load_shared = [&](int set, int j) {
 #pragma unroll
-        for (int i = 0; i < kMine; ++i) {
-            const uint32_t rk = (uint32_t)min(j * kTile + (w * kMine + i) * G::kRowsPerPass + lrow, n - 1);
-            kpart[i] = *reinterpret_cast<const u32x4*>(kb + (rk * sp.k_step + lbyte));
-            if (VS) vpart[i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
-        }
+        for (int sidx = 0; sidx < 3; ++sidx)
+            if (set == sidx) {
+#pragma unroll
+                for (int i = 0; i < kMine; ++i) {
+                    const uint32_t rk = (uint32_t)min(j * kTile + (w * kMine + i) * G::kRowsPerPass + lrow, n - 1);
+                    kp[sidx][i] = *reinterpret_cast<const u32x4*>(kb + (rk * sp.k_step + lbyte));
+                    if (VS) vp[sidx][i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
+                }
+            }
     };
-    auto write_shared = [&](int slot) {
+    auto write_shared = [&](int set, int slot) {
 #pragma unroll
-        for (int i = 0; i < kMine; ++i) {
-            const uint32_t at = (uint32_t)(slot * kBuf + ((w * kMine + i) * G::kRowsPerPass + lrow) * G::kPitch) + lbyte;
-            *reinterpret_cast<u32x4*>(sK + at) = kpart[i];
-            if (VS) *reinterpret_cast<u32x4*>(sV + at) = vpart[i];
-        }
+        for (int sidx = 0; sidx < 3; ++sidx)
+            if (set == sidx) {
+#pragma unroll
+                for (int i = 0; i < kMine; ++i) {
+                    const uint32_t at = (uint32_t)(slot * kBuf + ((w * kMine + i) * G::kRowsPerPass + lrow) * G::kPitch) + lbyte;
+                    *reinterpret_cast<u32x4*>(sK + at) = kp[sidx][i];
+                    if (VS) *reinterpret_cast<u32x4*>(sV + at) = vp[sidx][i];
+                }
+            }
     };
     auto load_own_v = [&](int j) {                        // a per-head value tile is this wave's alone
 #pragma unroll
@@ -278,7 +293,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
         qreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (rq * sp.q_step + lbyte)));
         ooff[i] = rq * sp.o_step + lbyte;
     }
-    load_shared(jbeg);
+    load_shared(0, jbeg);
+    if (jbeg + 1 < jend) load_shared(1, jbeg + 1);
+    if (jbeg + 2 < jend) load_shared(2, jbeg + 2);
     if (!VS) load_own_v(jbeg);
     __builtin_amdgcn_sched_barrier(0);
 
@@ -291,7 +308,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
     lds_wave_sync();
     read_natural<D>(buf + oprd, qop);
     lds_wave_sync();
-    write_shared(0);
+    write_shared(0, 0);
+    if (jbeg + 3 < jend) load_shared(0, jbeg + 3);
 
     const uint32_t vl = (uint32_t)p.valid_len;
     const int nreal = tok0 >= vl ? 0 : (int)min((uint32_t)n, (vl - tok0 + stride - 1) / stride);
@@ -307,9 +325,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
 #pragma unroll
     for (int t = 0; t < G::kDTiles; ++t) ot[t] = f32x16{};
 
-    for (int j = jbeg; j < jend; ++j) {
+    // one key tile; `next_set` (a constant at every call site) names the registers of tile j + 1
+    auto step = [&](int j, auto next_set_tag) {
+        constexpr int next_set = decltype(next_set_tag)::value;
         const int slot = (j - jbeg) & 1;
-        if (j + 1 < jend) load_shared(j + 1);             // lands while this tile is being used
         __syncthreads();                                  // tile j is complete; nobody reads the other slot any more
         u32x4 kop[G::kKSteps];
         read_natural<D>(sK + slot * kBuf + oprd, kop);
@@ -365,7 +384,15 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
 #pragma unroll
             for (int s2 = 0; s2 < 2; ++s2) ot[t] = mma(vT[t][s2], pop[s2], ot[t]);
         }
-        if (j + 1 < jend) write_shared(slot ^ 1);         // the other slot was last read before this iteration's barrier
+        if (j + 1 < jend) {                               // the other slot was last read before this iteration's barrier
+            write_shared(next_set, slot ^ 1);
+            if (j + 4 < jend) load_shared(next_set, j + 4);
+        }
+    };
+    for (int j = jbeg; j < jend; j += 3) {                // three steps per trip: the register sets get fixed names
+        step(j, std::integral_constant<int, 1>{});
+        if (j + 1 < jend) step(j + 1, std::integral_constant<int, 2>{});
+        if (j + 2 < jend) step(j + 2, std::integral_constant<int, 0>{});
     }
 
     const float inv = l > 0.f ? 1.f / l : 0.f;
