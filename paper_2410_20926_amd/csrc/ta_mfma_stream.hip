@@ -21,7 +21,8 @@ constexpr int kWavesPerBlock = 4;
 
 struct StreamParams {
     uint32_t qtiles;          // 32-row query tiles per fibre = ceil(n / 32)
-    uint32_t tiles;           // fibres * qtiles
+    uint32_t qchunk, qchunks; // chunked variant: query tiles per workgroup, workgroups per fibre
+    uint32_t tiles;           // units per (batch, head block): fibres * qtiles, or fibres * qchunks
     uint32_t tiles_lo, tiles_hi;
     uint32_t q_row, k_row, v_row, o_row;       // token pitch in bytes
     uint32_t q_step, k_step, v_step, o_step;   // bytes between neighbouring rows of a fibre (stride * token pitch)
@@ -417,6 +418,262 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
     }
 }
 
+// The group-shared variant for axes of up to 4 tiles (n <= 128), where one query tile is only
+// a few steps of work and a workgroup per query tile spends most of its life waiting for its
+// first rows.  Here a workgroup takes all query tiles of a fibre, the heaviest first, and
+// treats their (query tile, key tile) steps as ONE sequence: the quarters of a key tile are
+// requested three steps before the step that uses them and the rows of the next query tile while
+// the current one is being worked on, across query-tile boundaries, so that only the first
+// step of a workgroup waits for memory with nothing else to do.
+
+template <int D, bool VS>
+__global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunked_kernel(HopParams p, StreamParams sp) {
+    using G = Geo<D>;
+    constexpr int kBuf = kTile * G::kPitch;
+    constexpr int kMine = G::kPasses / kWavesPerBlock;    // passes of a shared tile this wave fetches
+    static_assert(G::kPasses % kWavesPerBlock == 0, "a tile splits evenly over the waves");
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = blockIdx.x * kWavesPerBlock + w;
+    const uint32_t zb = blockIdx.z / sp.tiles_hi;
+    const uint32_t tt = (blockIdx.z - zb * sp.tiles_hi) * sp.tiles_lo + blockIdx.y;
+    if (tt >= sp.tiles) return;                           // whole workgroup leaves together (every head exists: 4 divides G)
+    const int b = (int)zb;
+    const int g = h / p.G;
+    const int hv = VS ? g : h;
+    const int n = p.n;
+    char* sK = smem;                                      // two K tiles
+    char* sV = smem + 2 * kBuf;                           // two V tiles (VS only)
+    char* buf = smem + (VS ? 4 : 2) * kBuf + w * kBuf;    // this wave's own transit tile
+
+    // unit -> (fibre, chunk of query tiles); later (heavier, under the causal mask) chunks first
+    const uint32_t f = tt / sp.qchunks;
+    const int chunk = (int)(sp.qchunks - 1 - (tt - f * sp.qchunks));
+    const int ktiles = (n + kTile - 1) / kTile;
+    const int qt_hi = min((chunk + 1) * (int)sp.qchunk, ktiles) - 1, qt_lo = chunk * (int)sp.qchunk;   // query tiles qt_hi down to qt_lo
+    const uint32_t stride = (uint32_t)p.stride;
+    const uint32_t outer = f / stride;
+    const uint32_t tok0 = outer * stride * n + (f - outer * stride);
+
+    const char* qb = reinterpret_cast<const char*>(p.q.p) + ((int64_t)b * p.q.sb + (int64_t)h * p.q.sh) * 2 + tok0 * sp.q_row;
+    const char* kb = reinterpret_cast<const char*>(p.k.p) + ((int64_t)b * p.k.sb + (int64_t)g * p.k.sh) * 2 + tok0 * sp.k_row;
+    const char* vb = reinterpret_cast<const char*>(p.vin.p) + ((int64_t)b * p.vin.sb + (int64_t)hv * p.vin.sh) * 2 + tok0 * sp.v_row;
+    char* ob = reinterpret_cast<char*>(p.o.p) + ((int64_t)b * p.o.sb + (int64_t)h * p.o.sh) * 2 + tok0 * sp.o_row;
+
+    const int lrow = lane / G::kChunks, lcol = lane % G::kChunks;
+    const uint32_t lbyte = lcol * 16;
+    const int r32 = lane & 31, hf = lane >> 5;
+    // key tiles [jb, je) that some row of query tile qt can see (causal triangle, band)
+    auto key_tiles = [&](int qt, int& jb, int& je) {
+        jb = 0;
+        je = p.causal ? qt + 1 : ktiles;
+        if (p.window > 0) {
+            jb = max(0, qt * kTile - p.window + 1) / kTile;
+            je = min(je, (qt * kTile + kTile - 1 + p.window - 1) / kTile + 1);
+        }
+    };
+    // position in the sequence of steps: query tile qt (descending), key tile j (ascending)
+    struct Cursor { int qt, j, je; };
+    auto cursor_begin = [&](Cursor& c) { c.qt = qt_hi; key_tiles(c.qt, c.j, c.je); };
+    auto cursor_next = [&](Cursor& c) {                   // returns false past the last step
+        if (++c.j < c.je) return true;
+        if (--c.qt < qt_lo) return false;
+        key_tiles(c.qt, c.j, c.je);
+        return true;
+    };
+
+    // This wave's quarters of the next three key tiles travel in three register sets (the tile
+    // of step t in set t % 3).
+    u32x4 qreg[G::kPasses], vreg[VS ? 1 : G::kPasses];
+    u32x4 kp[3][kMine], vp[3][VS ? kMine : 1];
+    auto load_shared = [&](auto set_tag, int j) {
+        constexpr int set = decltype(set_tag)::value;
+#pragma unroll
+        for (int i = 0; i < kMine; ++i) {
+            const uint32_t rk = (uint32_t)min(j * kTile + (w * kMine + i) * G::kRowsPerPass + lrow, n - 1);
+            kp[set][i] = *reinterpret_cast<const u32x4*>(kb + (rk * sp.k_step + lbyte));
+            if (VS) vp[set][i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
+        }
+    };
+    auto write_shared = [&](auto set_tag, int slot) {
+        constexpr int set = decltype(set_tag)::value;
+#pragma unroll
+        for (int i = 0; i < kMine; ++i) {
+            const uint32_t at = (uint32_t)(slot * kBuf + ((w * kMine + i) * G::kRowsPerPass + lrow) * G::kPitch) + lbyte;
+            *reinterpret_cast<u32x4*>(sK + at) = kp[set][i];
+            if (VS) *reinterpret_cast<u32x4*>(sV + at) = vp[set][i];
+        }
+    };
+    auto load_own_v = [&](int j) {                        // a per-head value tile is this wave's alone
+#pragma unroll
+        for (int i = 0; i < (VS ? 0 : G::kPasses); ++i) {
+            const uint32_t rk = (uint32_t)min(j * kTile + i * G::kRowsPerPass + lrow, n - 1);
+            vreg[i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
+        }
+    };
+    auto load_q = [&](int qt) {
+#pragma unroll
+        for (int i = 0; i < G::kPasses; ++i) {
+            const uint32_t rq = (uint32_t)min(qt * kTile + i * G::kRowsPerPass + lrow, n - 1);
+            qreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (rq * sp.q_step + lbyte)));
+        }
+    };
+    using S0 = std::integral_constant<int, 0>;
+    using S1 = std::integral_constant<int, 1>;
+    using S2 = std::integral_constant<int, 2>;
+
+    Cursor cur, ahead;                                    // the step being worked on; the step whose tile is requested next
+    cursor_begin(cur);
+    ahead = cur;
+    bool more_ahead = true;
+    load_q(cur.qt);
+    load_shared(S0{}, ahead.j);
+    more_ahead = cursor_next(ahead);
+    if (more_ahead) { load_shared(S1{}, ahead.j); more_ahead = cursor_next(ahead); }
+    if (more_ahead) { load_shared(S2{}, ahead.j); more_ahead = cursor_next(ahead); }
+    if (!VS) load_own_v(cur.j);
+    __builtin_amdgcn_sched_barrier(0);
+
+    char* stg = buf + lrow * G::kPitch + lbyte;
+    const uint32_t oprd = (uint32_t)(r32 * G::kPitch + hf * 16);
+    const uint32_t troff = (uint32_t)((4 * hf + ((lane & 15) >> 2)) * G::kPitch + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2);
+    const uint32_t vl = (uint32_t)p.valid_len;
+    const int nreal = tok0 >= vl ? 0 : (int)min((uint32_t)n, (vl - tok0 + stride - 1) / stride);
+    const float sl2 = p.scale * kLog2e;
+
+    write_shared(S0{}, 0);
+    if (more_ahead) { load_shared(S0{}, ahead.j); more_ahead = cursor_next(ahead); }
+
+    // per query tile
+    u32x4 qop[G::kKSteps];
+    int klo = 0, khi = 0;
+    float m = -INFINITY, l = 0.f;
+    f32x16 ot[G::kDTiles];
+    int t = 0;                                            // step number: slot t & 1, register set t % 3
+    bool more = true, first_of_tile = true;
+
+    // one step; `next_set` (a constant at every call site) names the registers of the next step's tile
+    auto step = [&](auto next_set_tag) {
+        const int slot = t & 1;
+        const int qt = cur.qt, j = cur.j;
+        const int qrow = qt * kTile + r32;
+        if (first_of_tile) {
+            first_of_tile = false;
+            // first step of a query tile: its rows become the B operand, the next query tile's rows are requested
+            lds_wave_sync();
+            stage_rows<D>(stg, qreg);
+            lds_wave_sync();
+            read_natural<D>(buf + oprd, qop);
+            lds_wave_sync();
+            if (qt > qt_lo) load_q(qt - 1);
+            klo = 0; khi = 0;
+            if (qrow < nreal) {
+                visible_range(qrow, 0, n, p.causal, p.window, klo, khi);
+                khi = min(khi, nreal);
+            }
+            m = -INFINITY; l = 0.f;
+#pragma unroll
+            for (int tt2 = 0; tt2 < G::kDTiles; ++tt2) ot[tt2] = f32x16{};
+        }
+        __syncthreads();                                  // this step's tile is complete; nobody reads the other slot any more
+        u32x4 kop[G::kKSteps];
+        read_natural<D>(sK + slot * kBuf + oprd, kop);
+        f32x16 st = {};
+#pragma unroll
+        for (int s = 0; s < G::kKSteps; ++s) st = mma(kop[s], qop[s], st);
+
+        const uint32_t tw = qrow < nreal ? table_word(p, qrow, j) : 0u;
+        const uint32_t vis = (range_mask(min(max(klo - kTile * j, 0), kTile), min(max(khi - kTile * j, 0), kTile)) & tw) >> (4 * hf);
+        float e[16], tmax = -INFINITY;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const bool ok = (vis >> (8 * (r / 4) + (r % 4))) & 1u;
+            e[r] = ok ? st[r] * sl2 : -INFINITY;
+            tmax = fmaxf(tmax, e[r]);
+        }
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+        const float mnew = fmaxf(m, tmax);
+        const float msafe = mnew == -INFINITY ? 0.f : mnew;
+        const float corr = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - msafe);
+        m = mnew;
+        u32x4 pop[2];
+        float psum = 0.f;
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+            uint32_t wds[4];
+#pragma unroll
+            for (int jp = 0; jp < 4; ++jp) {
+                const int r = 8 * s2 + 2 * jp;
+                const uint32_t pk = pack_bf16x2(__builtin_amdgcn_exp2f(e[r] - msafe), __builtin_amdgcn_exp2f(e[r + 1] - msafe));
+                psum += bf16_lo(pk) + bf16_hi(pk);        // sum of the ROUNDED weights
+                wds[jp] = pk;
+            }
+            pop[s2] = u32x4{wds[0], wds[1], wds[2], wds[3]};
+        }
+        psum += __shfl_xor(psum, 32);
+        l = l * corr + psum;
+
+        // the next step (if any): needed below for the per-head value tile and for the end of this query tile
+        Cursor nxt = cur;
+        const bool has_next = cursor_next(nxt);
+        const bool last_of_tile = !has_next || nxt.qt != qt;
+
+        u32x4 vT[G::kDTiles][2];
+        if constexpr (VS) {
+            read_transposed<D>(sV + slot * kBuf + troff, vT);
+        } else {
+            stage_rows<D>(stg, vreg);
+            lds_wave_sync();
+            read_transposed<D>(buf + troff, vT);
+            lds_wave_sync();
+            if (has_next) load_own_v(nxt.j);
+        }
+#pragma unroll
+        for (int tt2 = 0; tt2 < G::kDTiles; ++tt2) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) ot[tt2][r] *= corr;
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) ot[tt2] = mma(vT[tt2][s2], pop[s2], ot[tt2]);
+        }
+        if (has_next) {                                   // the other slot was last read before this step's barrier
+            write_shared(next_set_tag, slot ^ 1);
+            if (more_ahead) { load_shared(next_set_tag, ahead.j); more_ahead = cursor_next(ahead); }
+        }
+        if (last_of_tile) {                               // normalise, round, transpose through the own tile, store
+            const float inv = l > 0.f ? 1.f / l : 0.f;
+            lds_wave_sync();
+#pragma unroll
+            for (int tt2 = 0; tt2 < G::kDTiles; ++tt2)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    u32x2 v;
+                    v.x = pack_bf16x2(ot[tt2][4 * q4] * inv, ot[tt2][4 * q4 + 1] * inv);
+                    v.y = pack_bf16x2(ot[tt2][4 * q4 + 2] * inv, ot[tt2][4 * q4 + 3] * inv);
+                    *reinterpret_cast<u32x2*>(buf + r32 * G::kPitch + (32 * tt2 + 8 * q4 + 4 * hf) * 2) = v;
+                }
+            lds_wave_sync();
+#pragma unroll
+            for (int i = 0; i < G::kPasses; ++i) {
+                const int row = qt * kTile + i * G::kRowsPerPass + lrow;
+                if (row < n) {
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
+                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(ob + ((uint32_t)row * sp.o_step + lbyte)));
+                }
+            }
+        }
+        if (last_of_tile) first_of_tile = true;
+        cur = nxt;
+        more = has_next;
+        ++t;
+    };
+    while (more) {                                        // three steps per trip: the register sets get fixed names
+        step(S1{});
+        if (more) step(S2{});
+        if (more) step(S0{});
+    }
+}
+
 template <int D, bool VS>
 hipError_t launch_shared(const HopParams& p, const StreamParams& sp, hipStream_t s) {
     const size_t smem = (size_t)((VS ? 4 : 2) + kWavesPerBlock) * kTile * Geo<D>::kPitch;
@@ -429,11 +686,13 @@ hipError_t launch_shared(const HopParams& p, const StreamParams& sp, hipStream_t
         if (dev < 0 || dev >= 64) return hipErrorInvalidValue;
         if (!allowed[dev]) {
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_fwd_stream_shared_kernel<D, VS>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_fwd_stream_chunked_kernel<D, VS>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
             if (e != hipSuccess) return e;
             allowed[dev] = true;
         }
     }
-    hipLaunchKernelGGL((mfma_fwd_stream_shared_kernel<D, VS>), grid, dim3(kWavesPerBlock * 64), smem, s, p, sp);
+    if (sp.qchunk > 1) hipLaunchKernelGGL((mfma_fwd_stream_chunked_kernel<D, VS>), grid, dim3(kWavesPerBlock * 64), smem, s, p, sp);
+    else               hipLaunchKernelGGL((mfma_fwd_stream_shared_kernel<D, VS>), grid, dim3(kWavesPerBlock * 64), smem, s, p, sp);
     return hipGetLastError();
 }
 
@@ -450,8 +709,11 @@ hipError_t launch(const HopParams& p, const StreamParams& sp, hipStream_t s) {
 hipError_t launch_mfma_forward_stream(const HopParams& p, hipStream_t s) {
     if (p.n < 1 || (p.D != 64 && p.D != 128) || !mfma_forward_layout_ok(p)) return hipErrorInvalidValue;
     StreamParams sp;
+    const bool shared = p.G % kWavesPerBlock == 0;        // the 4 waves of a workgroup are 4 heads of one group
     sp.qtiles = (uint32_t)((p.n + kTile - 1) / kTile);
-    const int64_t tiles = p.fibres * sp.qtiles;
+    sp.qchunk = (shared && sp.qtiles <= 4) ? sp.qtiles : 1u;   // short axes: one workgroup walks all query tiles of a fibre
+    sp.qchunks = (sp.qtiles + sp.qchunk - 1) / sp.qchunk;
+    const int64_t tiles = p.fibres * sp.qchunks;
     if (tiles <= 0 || tiles > 0x7fffffffLL) return hipErrorInvalidValue;
     sp.tiles = (uint32_t)tiles;
     sp.tiles_lo = (uint32_t)(tiles < 32768 ? tiles : 32768);
@@ -465,7 +727,7 @@ hipError_t launch_mfma_forward_stream(const HopParams& p, hipStream_t s) {
     sp.k_step = (uint32_t)(p.stride * p.k.st * 2);
     sp.v_step = (uint32_t)(p.stride * p.vin.st * 2);
     sp.o_step = (uint32_t)(p.stride * p.o.st * 2);
-    if (p.G % kWavesPerBlock == 0) {                      // the 4 waves of a workgroup are 4 heads of one group
+    if (shared) {
         const bool vs = p.vin_heads != p.Hq;
         if (p.D == 128) return vs ? launch_shared<128, true>(p, sp, s) : launch_shared<128, false>(p, sp, s);
         return vs ? launch_shared<64, true>(p, sp, s) : launch_shared<64, false>(p, sp, s);
