@@ -6,6 +6,7 @@ import json
 import os
 import re
 
+import numpy as np
 import pytest
 
 import paper_2410_20926_amd as ta
@@ -177,3 +178,24 @@ def test_missing_library_fails_loudly(monkeypatch):
     monkeypatch.setattr(binding, "_LIB_PATH", "/nonexistent/libtensattn.so")
     with pytest.raises(ImportError):
         ta.ta_plan_create(1, 1, 1, 64, (4,), ta.TA_F32, False)
+
+
+def test_pack_axis_mask_layout():
+    """Row a, word c // 32, bit c % 32 (the layout the descriptor's axis_mask documents)."""
+    rng = np.random.default_rng(5)
+    for n in (1, 5, 32, 33, 70):
+        m = rng.random((n, n)) < 0.5
+        words = ta.pack_axis_mask(m).view(np.uint32)
+        assert words.shape == (n, (n + 31) // 32)
+        for a in range(n):
+            for c in range(n):
+                assert ((int(words[a, c // 32]) >> (c % 32)) & 1) == int(m[a, c])
+        # bits past the last column are zero
+        if n % 32:
+            assert (words[:, -1] >> np.uint32(n % 32) == 0).all()
+
+
+def test_misaligned_axis_mask_is_rejected():
+    with pytest.raises(ta.TaError) as e:
+        ta.Plan(binding.make_desc(1, 2, 2, 64, (4, 4), ta.TA_F32, True, axis_masks=[6, None]))
+    assert e.value.name == "TA_ERR_INVALID_ARG"
