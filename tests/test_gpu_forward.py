@@ -56,6 +56,10 @@ CASES = [
     ((128, 4, 2), 1, 4, 1, 128, True, "bf16", 1.0),    # extrapolated first axis (Sec. 4.3), strided
     ((3, 97), 2, 2, 2, 64, True, "bf16", 1.0),
     ((257,), 1, 1, 1, 64, False, "bf16", 1.0),
+    ((97, 3), 2, 8, 2, 64, True, "bf16", 1.0),         # group-shared streaming, all query tiles in one workgroup, D = 64, ragged
+    ((2, 128), 1, 4, 1, 64, False, "bf16", 1.0),       # the same, non-causal, value input per head on the second hop
+    ((300, 2), 1, 8, 2, 64, True, "bf16", 1.0),        # group-shared streaming, one workgroup per query tile, D = 64
+    ((2, 161), 1, 4, 1, 128, False, "bf16", 1.0),
 ]
 
 
