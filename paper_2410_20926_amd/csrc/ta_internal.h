@@ -39,6 +39,10 @@ struct BwdParams {
     Tensor dq;               // Q layout
     Tensor dk;               // key/value layout
     int32_t accumulate;      // 0: overwrite dq, dk; 1: add
+    // set by the MFMA launcher: groups of more than 8 query heads are run 8 heads per launch
+    int32_t wg_heads;        // heads (= waves) per workgroup
+    int32_t head_base;       // first head of the group this launch covers
+    int32_t acc_k, acc_x;    // add to dk / to the group-summed d_vin (every launch after a group's first)
 };
 
 // Tensorized rotary position encoding of one [B, N, H, D] tensor (x -> y, same layout).

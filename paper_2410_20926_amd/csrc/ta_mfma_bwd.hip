@@ -7,7 +7,7 @@
 //     dS = P o (dP - rowsum(P o dP))
 //     dX = P^T G      dQ = dS K * scale      dK = dS^T Q * scale
 // One wavefront handles one (tile, query head); a workgroup is the G <= 8 query heads that
-// share a key/value head, so dK (and dX when the value input is V) are summed across the
+// share a key/value head (8 of them at a time when there are more), so dK (and dX when the value input is V) are summed across the
 // workgroup's waves in a fixed order through LDS: deterministic, no atomics.
 //
 // Layouts.  Every tensor tile goes ONCE into a row-major LDS transit buffer and is read
@@ -135,10 +135,10 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nw = p.G;
+    const int nw = bp.wg_heads;
 
     const int g = blockIdx.x;
-    const int h = g * p.G + w;
+    const int h = g * p.G + bp.head_base + w;
     const uint32_t zb = blockIdx.z / tp.tiles_hi;
     const uint32_t tt = (blockIdx.z - zb * tp.tiles_hi) * tp.tiles_lo + blockIdx.y;
     if (tt >= tp.tiles) return;                           // whole workgroup leaves together
@@ -329,12 +329,14 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
     if (vin_is_o) {
         store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, oldq, false, rows_valid, lane);
     } else {
+        u32x4 oldx[G::kDTiles * 2] = {};                  // the sum of the group's earlier heads, when it is run in several launches
+        if (bp.acc_x && w == nw - 1) prefetch_tile<D>(oldx, rowoff, 2, dxb, lane);
         chain_sum<D>(acc, red, w, nw, lane);
-        if (w == nw - 1) store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, oldq, false, rows_valid, lane);
+        if (w == nw - 1) store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, oldx, bp.acc_x != 0, rows_valid, lane);
     }
     // previous dK (accumulate): only the wave that ends up with the group's sum needs it
     u32x4 oldk[G::kDTiles * 2] = {};
-    if (bp.accumulate && w == nw - 1) prefetch_tile<D>(oldk, rowoff, 1, dkb, lane);
+    if (bp.acc_k && w == nw - 1) prefetch_tile<D>(oldk, rowoff, 1, dkb, lane);
 
     // ---- dK^T = Q^T dS : summed over the group ----------------------------------------------
 #pragma unroll
@@ -344,7 +346,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
         for (int s2 = 0; s2 < 2; ++s2) acc[t] = mma(qT[t][s2], dsNop[s2], acc[t]);
     }
     chain_sum<D>(acc, red, w, nw, lane);
-    if (w == nw - 1) store_tile<D>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.accumulate != 0, rows_valid, lane);
+    if (w == nw - 1) store_tile<D>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.acc_k != 0, rows_valid, lane);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -402,9 +404,9 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nw = p.G;
+    const int nw = bp.wg_heads;
     const int g = blockIdx.x;
-    const int h = g * p.G + w;
+    const int h = g * p.G + bp.head_base + w;
     const uint32_t zb = blockIdx.z / sp.fibres_hi;
     const int64_t f = (int64_t)(blockIdx.z - zb * sp.fibres_hi) * sp.fibres_lo + blockIdx.y;
     if (f >= p.fibres) return;                            // whole workgroup leaves together
@@ -650,8 +652,10 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
         if (vin_is_o) {
             store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, none, false, rows_c, lane);
         } else {
+            u32x4 oldx[G::kDTiles * 2] = {};
+            if (bp.acc_x && w == nw - 1) prefetch_tile<D>(oldx, rowoff, 2, dxb, lane);
             chain_sum<D>(acc, red, w, nw, lane);
-            if (w == nw - 1) store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, none, false, rows_c, lane);
+            if (w == nw - 1) store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, oldx, bp.acc_x != 0, rows_c, lane);
         }
         // ---- dK_c^T = sum_a Q_a^T dS_ac ---------------------------------------------------------------
         u32x4 xop[G::kKSteps];
@@ -708,9 +712,9 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
         }
         lds_wave_sync();
         u32x4 oldk[G::kDTiles * 2] = {};
-        if (bp.accumulate && w == nw - 1) prefetch_tile<D>(oldk, rowoff, 1, dkb, lane);   // only the wave that ends up with the sum
+        if (bp.acc_k && w == nw - 1) prefetch_tile<D>(oldk, rowoff, 1, dkb, lane);   // only the wave that ends up with the sum
         chain_sum<D>(acc, red, w, nw, lane);
-        if (w == nw - 1) store_tile<D>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.accumulate != 0, rows_c, lane);
+        if (w == nw - 1) store_tile<D>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.acc_k != 0, rows_c, lane);
         lds_wave_sync();
     }
 }
@@ -726,7 +730,7 @@ hipError_t launch_stream(const BwdParams& bp, hipStream_t s) {
     sp.fibres_hi = (uint32_t)((p.fibres + sp.fibres_lo - 1) / sp.fibres_lo);
     if ((int64_t)p.B * sp.fibres_hi > 65535) return hipErrorInvalidValue;
     const size_t wave_bytes = (size_t)BGeo<D>::kBufBytes + kTile * 16 + (size_t)3 * kTile * sp.tiles * 4;
-    const size_t smem = (size_t)(p.G > 1 ? BGeo<D>::kRedBytes : 0) + (size_t)p.G * wave_bytes;
+    const size_t smem = (size_t)(bp.wg_heads > 1 ? BGeo<D>::kRedBytes : 0) + (size_t)bp.wg_heads * wave_bytes;
     if (smem > kStreamMaxLds) return hipErrorInvalidValue;
     if (smem > 64 * 1024) {                               // more than 64 KB of dynamic LDS has to be allowed once per device
         static bool allowed[64] = {};
@@ -741,17 +745,17 @@ hipError_t launch_stream(const BwdParams& bp, hipStream_t s) {
         }
     }
     const dim3 grid((unsigned)p.Hkv, sp.fibres_lo, (unsigned)p.B * sp.fibres_hi);
-    hipLaunchKernelGGL((mfma_bwd_stream_kernel<D>), grid, dim3(64 * p.G), smem, s, bp, sp);
+    hipLaunchKernelGGL((mfma_bwd_stream_kernel<D>), grid, dim3(64 * bp.wg_heads), smem, s, bp, sp);
     return hipGetLastError();
 }
 
 template <int D>
 hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
     const HopParams& p = bp.hop;
-    const size_t smem = (size_t)(p.G > 1 ? BGeo<D>::kRedBytes : 0) + (size_t)p.G * BGeo<D>::kWaveBytes;
+    const size_t smem = (size_t)(bp.wg_heads > 1 ? BGeo<D>::kRedBytes : 0) + (size_t)bp.wg_heads * BGeo<D>::kWaveBytes;
     const dim3 grid((unsigned)p.Hkv, tp.tiles_lo, (unsigned)p.B * tp.tiles_hi);
-    if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true>), grid, dim3(64 * p.G), smem, s, bp, tp);
-    else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false>), grid, dim3(64 * p.G), smem, s, bp, tp);
+    if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true>), grid, dim3(64 * bp.wg_heads), smem, s, bp, tp);
+    else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false>), grid, dim3(64 * bp.wg_heads), smem, s, bp, tp);
     return hipGetLastError();
 }
 
@@ -761,7 +765,7 @@ hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
 static int backward_variant(const BwdParams& bp, int dtype) {
     const HopParams& p = bp.hop;
     if (dtype != TA_BF16 || (p.D != 64 && p.D != 128) || p.n < 1 || p.n > kStreamMaxN) return 0;
-    if (p.G != 1 && p.G != 2 && p.G != 4 && p.G != 8) return 0;
+    if (p.G != 1 && p.G != 2 && p.G != 4 && p.G % 8 != 0) return 0;   // groups of more than 8 heads run 8 heads per launch
     const int64_t N = p.fibres * p.n;
     if (!(N < ((int64_t)1 << 31) && p.B <= 65535 && fits_u32(p.q, N) && fits_u32(p.k, N) && fits_u32(p.vin, N) &&
           fits_u32(bp.d_o, N) && fits_u32(bp.d_vin, N) && fits_u32(bp.dq, N) && fits_u32(bp.dk, N))) return 0;
@@ -770,21 +774,36 @@ static int backward_variant(const BwdParams& bp, int dtype) {
     const size_t tiles = (size_t)(p.n + kTile - 1) / kTile;
     const size_t kbuf = p.D == 128 ? BGeo<128>::kBufBytes : BGeo<64>::kBufBytes;
     const size_t red = p.G > 1 ? (p.D == 128 ? BGeo<128>::kRedBytes : BGeo<64>::kRedBytes) : 0;
-    return red + (size_t)p.G * (kbuf + kTile * 16 + 3 * kTile * tiles * 4) <= (size_t)kStreamMaxLds ? 2 : 0;
+    const size_t wgh = p.G > 8 ? 8 : p.G;
+    return red + wgh * (kbuf + kTile * 16 + 3 * kTile * tiles * 4) <= (size_t)kStreamMaxLds ? 2 : 0;
 }
 
 bool mfma_backward_supports(const BwdParams& bp, int dtype) { return backward_variant(bp, dtype) != 0; }
 bool mfma_backward_is_blocked(const BwdParams& bp, int dtype) { return backward_variant(bp, dtype) == 2; }
 
-hipError_t launch_mfma_backward(const BwdParams& bp, hipStream_t s) {
-    const int variant = backward_variant(bp, TA_BF16);
+hipError_t launch_mfma_backward(const BwdParams& user, hipStream_t s) {
+    const int variant = backward_variant(user, TA_BF16);
     if (variant == 0) return hipErrorInvalidValue;
-    if (variant == 2) return bp.hop.D == 128 ? launch_stream<128>(bp, s) : launch_stream<64>(bp, s);
-    HopParams hp = bp.hop;
-    hp.o = bp.d_o;                                        // the table's fourth offset follows the O layout (dO)
+    HopParams hp = user.hop;
+    hp.o = user.d_o;                                      // the table's fourth offset follows the O layout (dO)
     TileParams tp;
-    if (!make_tile_params(hp, 1, &tp)) return hipErrorInvalidValue;
-    return bp.hop.D == 128 ? launch<128>(bp, tp, s) : launch<64>(bp, tp, s);
+    if (variant == 1 && !make_tile_params(hp, 1, &tp)) return hipErrorInvalidValue;
+    // A workgroup holds at most 8 heads.  A larger group goes 8 heads per launch, one launch after
+    // the other on the stream: each later launch adds its heads' share to dK (and to the group's
+    // dV), in a fixed order, so the result stays deterministic.
+    BwdParams bp = user;
+    const int G = user.hop.G;
+    bp.wg_heads = G > 8 ? 8 : G;
+    for (int base = 0; base < G; base += bp.wg_heads) {
+        bp.head_base = base;
+        bp.acc_k = base == 0 ? user.accumulate : 1;
+        bp.acc_x = base == 0 ? 0 : 1;
+        hipError_t e;
+        if (variant == 2) e = bp.hop.D == 128 ? launch_stream<128>(bp, s) : launch_stream<64>(bp, s);
+        else              e = bp.hop.D == 128 ? launch<128>(bp, tp, s) : launch<64>(bp, tp, s);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace ta

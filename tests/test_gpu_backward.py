@@ -56,7 +56,10 @@ CASES = [
     ((5, 7, 3), 2, 4, 4, 64, True, "bf16"),          # odd lengths: ragged tiles with padding rows
     ((32, 3), 1, 8, 2, 128, False, "bf16"),
     ((6, 32), 1, 8, 1, 64, True, "bf16"),            # 8 heads per group: workgroups of 8 waves
-    ((4, 16), 1, 16, 1, 128, True, "bf16"),          # 16 heads per group: generic fallback
+    ((4, 16), 1, 16, 1, 128, True, "bf16"),          # 16 heads per group: two launches of 8 heads, the second adds to dK, dV
+    ((8, 32), 2, 32, 1, 64, True, "bf16"),           # multi-query: 32 heads on one key/value head, four launches
+    ((64, 4), 1, 16, 1, 128, False, "bf16"),         # the blocked kernel with 16 heads per group
+    ((6, 5), 1, 12, 1, 64, True, "bf16"),            # 12 heads per group: no MFMA variant, generic kernel
     ((32, 8), 2, 16, 2, 128, False, "bf16"),         # 8 heads per group, full-width heads
 ]
 
