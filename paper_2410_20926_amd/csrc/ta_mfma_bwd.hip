@@ -127,18 +127,19 @@ __device__ inline void chain_sum(f32x16 (&acc)[Geo<D>::kDTiles], float* red, int
 }
 
 // blockDim.x = 64 * G (G = query heads per key/value head: 1, 2, 4 or 8); grid = (Hkv, tiles_lo, B * tiles_hi).
-// TABLE: the axis has a caller's bit table (a separate instantiation keeps the common case free of it).
-template <int D, bool TABLE>
+// TABLE: the axis has a caller's bit table; MULTI: the group has more than 8 heads and this launch
+// covers 8 of them (separate instantiations keep the common case free of both).
+template <int D, bool TABLE, bool MULTI>
 __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TileParams tp) {
     using G = BGeo<D>;
     const HopParams& p = bp.hop;
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nw = bp.wg_heads;
+    const int nw = MULTI ? bp.wg_heads : p.G;
 
     const int g = blockIdx.x;
-    const int h = g * p.G + bp.head_base + w;
+    const int h = g * p.G + (MULTI ? bp.head_base : 0) + w;
     const uint32_t zb = blockIdx.z / tp.tiles_hi;
     const uint32_t tt = (blockIdx.z - zb * tp.tiles_hi) * tp.tiles_lo + blockIdx.y;
     if (tt >= tp.tiles) return;                           // whole workgroup leaves together
@@ -329,14 +330,20 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
     if (vin_is_o) {
         store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, oldq, false, rows_valid, lane);
     } else {
-        u32x4 oldx[G::kDTiles * 2] = {};                  // the sum of the group's earlier heads, when it is run in several launches
-        if (bp.acc_x && w == nw - 1) prefetch_tile<D>(oldx, rowoff, 2, dxb, lane);
-        chain_sum<D>(acc, red, w, nw, lane);
-        if (w == nw - 1) store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, oldx, bp.acc_x != 0, rows_valid, lane);
+        if constexpr (MULTI) {
+            u32x4 oldx[G::kDTiles * 2] = {};              // the sum of the group's earlier heads
+            if (bp.acc_x && w == nw - 1) prefetch_tile<D>(oldx, rowoff, 2, dxb, lane);
+            chain_sum<D>(acc, red, w, nw, lane);
+            if (w == nw - 1) store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, oldx, bp.acc_x != 0, rows_valid, lane);
+        } else {
+            chain_sum<D>(acc, red, w, nw, lane);
+            if (w == nw - 1) store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, oldq, false, rows_valid, lane);
+        }
     }
     // previous dK (accumulate): only the wave that ends up with the group's sum needs it
     u32x4 oldk[G::kDTiles * 2] = {};
-    if (bp.acc_k && w == nw - 1) prefetch_tile<D>(oldk, rowoff, 1, dkb, lane);
+    const bool acc_k = MULTI ? bp.acc_k != 0 : bp.accumulate != 0;
+    if (acc_k && w == nw - 1) prefetch_tile<D>(oldk, rowoff, 1, dkb, lane);
 
     // ---- dK^T = Q^T dS : summed over the group ----------------------------------------------
 #pragma unroll
@@ -346,7 +353,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
         for (int s2 = 0; s2 < 2; ++s2) acc[t] = mma(qT[t][s2], dsNop[s2], acc[t]);
     }
     chain_sum<D>(acc, red, w, nw, lane);
-    if (w == nw - 1) store_tile<D>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.acc_k != 0, rows_valid, lane);
+    if (w == nw - 1) store_tile<D>(acc, p.scale, buf, rowoff, 1, dkb, oldk, acc_k, rows_valid, lane);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -754,8 +761,14 @@ hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
     const HopParams& p = bp.hop;
     const size_t smem = (size_t)(bp.wg_heads > 1 ? BGeo<D>::kRedBytes : 0) + (size_t)bp.wg_heads * BGeo<D>::kWaveBytes;
     const dim3 grid((unsigned)p.Hkv, tp.tiles_lo, (unsigned)p.B * tp.tiles_hi);
-    if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true>), grid, dim3(64 * bp.wg_heads), smem, s, bp, tp);
-    else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false>), grid, dim3(64 * bp.wg_heads), smem, s, bp, tp);
+    const dim3 block(64 * bp.wg_heads);
+    if (p.G > bp.wg_heads) {
+        if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true, true>), grid, block, smem, s, bp, tp);
+        else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false, true>), grid, block, smem, s, bp, tp);
+    } else {
+        if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true, false>), grid, block, smem, s, bp, tp);
+        else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false, false>), grid, block, smem, s, bp, tp);
+    }
     return hipGetLastError();
 }
 
