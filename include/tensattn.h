@@ -109,7 +109,8 @@ int     ta_plan_hop_axis(const ta_plan_t* plan, int hop_position); /* axis run a
  * "..._shared" and, when the value input is per key/value head, "..._shared_kv", "generic"); NULL on
  * error.  Static storage. */
 const char* ta_plan_hop_kernel(const ta_plan_t* plan, int axis, int vin);
-/* Same for the backward of that hop ("mfma_bf16_bwd_n32", "generic", or "unsupported" when
+/* Same for the backward of that hop ("mfma_bf16_bwd_n32", "mfma_bf16_bwd_blocked" for axes of 33 to
+ * 1024 positions, "generic", or "unsupported" when
  * ta_axis_attn_backward would return TA_ERR_UNSUPPORTED); NULL on error. */
 const char* ta_plan_hop_backward_kernel(const ta_plan_t* plan, int axis, int vin);
 
