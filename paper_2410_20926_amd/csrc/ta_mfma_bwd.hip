@@ -94,6 +94,36 @@ __device__ inline void store_tile(const f32x16 (&acc)[Geo<D>::kDTiles], float mu
     }
 }
 
+// The same without previous contents to add: the values are rounded to bf16 BEFORE the
+// transposition, which then moves half the bytes through LDS (one row-major bf16 tile).
+template <int D>
+__device__ inline void store_tile_plain(const f32x16 (&acc)[Geo<D>::kDTiles], float mult, char* buf, const u32x4* rowoff,
+                                        int which, char* gbase, int rows_valid, int lane) {
+    using G = BGeo<D>;
+    const int r32 = lane & 31, hf = lane >> 5;
+    const int lrow = lane / G::kChunks, lcol = lane % G::kChunks;
+#pragma unroll
+    for (int t = 0; t < G::kDTiles; ++t)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            u32x2 v;
+            v.x = pack_bf16x2(acc[t][4 * q4] * mult, acc[t][4 * q4 + 1] * mult);
+            v.y = pack_bf16x2(acc[t][4 * q4 + 2] * mult, acc[t][4 * q4 + 3] * mult);
+            *reinterpret_cast<u32x2*>(buf + r32 * G::kPitch + (32 * t + 8 * q4 + 4 * hf) * 2) = v;
+        }
+    lds_wave_sync();
+#pragma unroll
+    for (int i = 0; i < G::kPasses; ++i) {
+        const int row = i * G::kRowsPerPass + lrow;
+        if (row < rows_valid) {
+            const u32x4 v = *reinterpret_cast<const u32x4*>(buf + row * G::kPitch + lcol * 16);
+            const u32x4 off4 = rowoff[row];
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(gbase + ((which == 0 ? off4.x : which == 1 ? off4.y : off4.z) + lcol * 16)));
+        }
+    }
+    lds_wave_sync();
+}
+
 // Sum of acc over the workgroup's waves in wave order; the total ends in the LAST wave's
 // registers.  `red` is a workgroup-shared fp32 area in lane-major layout.
 template <int D>
@@ -328,7 +358,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
         for (int s2 = 0; s2 < 2; ++s2) acc[t] = mma(gT[t][s2], pNop[s2], acc[t]);
     }
     if (vin_is_o) {
-        store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, oldq, false, rows_valid, lane);
+        store_tile_plain<D>(acc, 1.f, buf, rowoff, 2, dxb, rows_valid, lane);
     } else {
         if constexpr (MULTI) {
             u32x4 oldx[G::kDTiles * 2] = {};              // the sum of the group's earlier heads
