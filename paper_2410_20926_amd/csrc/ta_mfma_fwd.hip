@@ -97,6 +97,16 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
     const uint32_t lbyte = lcol * 16;
     const int kt_end = (KT == 1) ? 1 : (p.causal ? qt + 1 : (n > kTile ? 2 : 1));   // key tiles this unit walks
 
+    if (((real_rows >> (qt * kTile)) & 0xffffffffull) == 0) {
+        // every query row of this unit is padding: zero rows out, nothing read
+#pragma unroll
+        for (int i = 0; i < G::kPasses; ++i) {
+            const int row = qt * kTile + i * G::kRowsPerPass + lrow;
+            if (row < rows_valid) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, reinterpret_cast<u32x4*>(ob + (rowoff[row].w + lbyte)));
+        }
+        return;
+    }
+
     // ---- 1. gather ---------------------------------------------------------------------
     // Lane (lrow, lcol) loads chunk lcol of rows i * kRowsPerPass + lrow of every tile.
     // Q, every K tile and the first V tile are requested here, before the first wait; a
@@ -368,6 +378,15 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
 
     const int lrow = lane / G::kChunks, lcol = lane % G::kChunks;
     const uint32_t lbyte = lcol * 16;
+    if (((real_rows >> (qt * kTile)) & 0xffffffffull) == 0) {
+        // every query row of this unit is padding (the same in all four waves): zero rows out, nothing read
+#pragma unroll
+        for (int i = 0; i < G::kPasses; ++i) {
+            const int row = qt * kTile + i * G::kRowsPerPass + lrow;
+            if (row < rows_valid) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, reinterpret_cast<u32x4*>(ob + (rowoff[row].w + lbyte)));
+        }
+        return;
+    }
     const int kt_end = (KT == 1) ? 1 : (p.causal ? qt + 1 : (n > kTile ? 2 : 1));
 
     // ---- gather: Q (private), this wave's quarter of every K tile, and V: its quarter of
