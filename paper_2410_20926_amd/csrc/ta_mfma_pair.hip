@@ -1,6 +1,6 @@
 // Two consecutive hops of Algorithm 1 in one kernel: the hop along the second-innermost
 // tensor axis followed by the hop along the innermost one (Eq. 4 twice, with the same Q and
-// K), for 32 x 32 slabs, bf16, head width 128, with every per-axis mask of the single-hop kernels.  The intermediate value tensor of the pair
+// K), for 32 x 32 slabs, bf16, head width 128 or 64, with every per-axis mask of the single-hop kernels.  The intermediate value tensor of the pair
 // never leaves the chip, and Q, K, the value input and the output each cross HBM once.
 //
 // A slab is the 1,024 consecutive tokens (i, j), i on the outer of the two axes, j on the
@@ -30,7 +30,6 @@ constexpr int kN = 32;                       // both axis lengths
 constexpr int kSlab = kN * kN;               // tokens per slab
 constexpr int kWaves = 8;                    // waves per workgroup; wave w owns i (and j) in [4 w, 4 w + 4)
 constexpr int kOwn = kN / kWaves;            // fibres of each kind per wave
-constexpr int kD = 128;
 constexpr int kCA = 32;                      // features per phase-A chunk (64 bytes of a row)
 constexpr int kCB = 64;                      // features per phase-B chunk (128 bytes of a row)
 constexpr int kARow = kCA * 2;               // bytes of one token's phase-A chunk row (half a 128-byte line)
@@ -132,7 +131,8 @@ __device__ inline void update_fibre(char* lds, uint32_t fb, uint32_t rs, const u
 }
 
 // MID: the intermediate O (the first hop's output) is written out as well, for a backward pass.
-template <bool MID>
+// kD: head width, 128 (two 128-byte lines per row, four score chunks, two value chunks) or 64.
+template <int kD, bool MID>
 __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int lane = threadIdx.x & 63;
@@ -161,10 +161,11 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
     char* mb = reinterpret_cast<char*>(p.mid) + ((int64_t)b * p.o.sb + (int64_t)h * p.o.sh) * 2 + tok0 * p.o_row;
 
     if (p.valid_len <= tok0) {                            // the whole slab is padding: its outputs are zero, nothing is read
+        constexpr int kLanesPerRow = kD / 8, kRowsPerPass = 64 / kLanesPerRow;
 #pragma unroll 4
-        for (int pp = 0; pp < kOwn * kN / 4; ++pp) {
-            const uint32_t t = (uint32_t)(w * (kOwn * kN) + pp * 4 + (lane >> 4));
-            const uint32_t off = t * p.o_row + (uint32_t)((lane & 15) * 16);
+        for (int pp = 0; pp < kOwn * kN / kRowsPerPass; ++pp) {
+            const uint32_t t = (uint32_t)(w * (kOwn * kN) + pp * kRowsPerPass + lane / kLanesPerRow);
+            const uint32_t off = t * p.o_row + (uint32_t)((lane % kLanesPerRow) * 16);
             __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, reinterpret_cast<u32x4*>(ob + off));
             if (MID) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, reinterpret_cast<u32x4*>(mb + off));
         }
@@ -232,28 +233,30 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
                 __builtin_amdgcn_sched_barrier(0);        // keeps the operand reads from piling up in registers
             }
     };
-    static_assert(kD == 4 * kCA, "two 128-byte lines per row");
+    static_assert(kD == 4 * kCA || kD == 2 * kCA, "one or two 128-byte lines per row");
     write_chunk(q0);                                      // chunk 0
     load_k(1);
-    load_q(r0, r1, 1, 0, 4);
+    if (kD == 4 * kCA) load_q(r0, r1, 1, 0, 4);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
     scores();
     __syncthreads();
     write_chunk(q1);                                      // chunk 1
-    load_k(2);
-    load_q(r0, r1, 1, 4, 8);
-    __builtin_amdgcn_sched_barrier(0);
-    __syncthreads();
-    scores();
-    __syncthreads();
-    write_chunk(r0);                                      // chunk 2
-    load_k(3);
-    __builtin_amdgcn_sched_barrier(0);
-    __syncthreads();
-    scores();
-    __syncthreads();
-    write_chunk(r1);                                      // chunk 3
+    if (kD == 4 * kCA) {
+        load_k(2);
+        load_q(r0, r1, 1, 4, 8);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        scores();
+        __syncthreads();
+        write_chunk(r0);                                  // chunk 2
+        load_k(3);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        scores();
+        __syncthreads();
+        write_chunk(r1);                                  // chunk 3
+    }
 
     // value rows of the first phase-B chunk (8 lanes per row (unit ub), 8 rows per pass, 16 passes):
     // half of them are requested here, the other half once the column tiles' accumulators are gone
@@ -334,7 +337,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
 }
 
 bool pair_params(const HopParams& h1, const HopParams& h2, PairParams* pp) {
-    if (h1.n != kN || h2.n != kN || h1.D != kD || h2.stride != 1 || h1.stride != kN) return false;
+    if (h1.n != kN || h2.n != kN || (h1.D != 128 && h1.D != 64) || h2.stride != 1 || h1.stride != kN) return false;
     const int64_t N = h1.fibres * h1.n;
     if (!fits_u32(h1.q, kSlab) || !fits_u32(h1.k, kSlab) || !fits_u32(h1.vin, kSlab) || !fits_u32(h1.o, kSlab)) return false;
     if (N % kSlab != 0 || h1.G < 1 || h1.G > 64) return false;
@@ -372,15 +375,24 @@ hipError_t launch_mfma_forward_pair(const HopParams& h1, const HopParams& h2, vo
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= 64) return hipErrorInvalidValue;
     if (!allowed[dev]) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_fwd_pair_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_fwd_pair_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e != hipSuccess) return e;
+        const void* kernels[4] = {reinterpret_cast<const void*>(mfma_fwd_pair_kernel<128, false>), reinterpret_cast<const void*>(mfma_fwd_pair_kernel<128, true>),
+                                  reinterpret_cast<const void*>(mfma_fwd_pair_kernel<64, false>), reinterpret_cast<const void*>(mfma_fwd_pair_kernel<64, true>)};
+        for (const void* kf : kernels) {
+            e = hipFuncSetAttribute(kf, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+            if (e != hipSuccess) return e;
+        }
         allowed[dev] = true;
     }
     const uint32_t span = 8u * (uint32_t)pp.G;
     const uint32_t grid = ((pp.groups + 7u) / 8u) * span;
-    if (o_mid) hipLaunchKernelGGL(mfma_fwd_pair_kernel<true>, dim3(grid), dim3(64 * kWaves), kLdsBytes, s, pp);
-    else       hipLaunchKernelGGL(mfma_fwd_pair_kernel<false>, dim3(grid), dim3(64 * kWaves), kLdsBytes, s, pp);
+    const dim3 block(64 * kWaves);
+    if (h1.D == 128) {
+        if (o_mid) hipLaunchKernelGGL((mfma_fwd_pair_kernel<128, true>), dim3(grid), block, kLdsBytes, s, pp);
+        else       hipLaunchKernelGGL((mfma_fwd_pair_kernel<128, false>), dim3(grid), block, kLdsBytes, s, pp);
+    } else {
+        if (o_mid) hipLaunchKernelGGL((mfma_fwd_pair_kernel<64, true>), dim3(grid), block, kLdsBytes, s, pp);
+        else       hipLaunchKernelGGL((mfma_fwd_pair_kernel<64, false>), dim3(grid), block, kLdsBytes, s, pp);
+    }
     return hipGetLastError();
 }
 

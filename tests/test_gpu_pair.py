@@ -167,8 +167,27 @@ def test_pair_with_padding(valid_len, causal):
     assert (to_host(mid)[:, valid_len:] == 0).all() and np.isfinite(to_host(mid)).all()
 
 
+@pytest.mark.parametrize("causal,valid_len", [(True, None), (False, None), (True, 1500)])
+def test_pair_at_head_width_64(causal, valid_len):
+    dims, B, Hq, Hkv, D = (2, 32, 32), 2, 8, 2, 64
+    N = int(np.prod(dims))
+    q, k, v, d_o = make_inputs(B, N, Hq, Hkv, D, seed=8700, dtype="bf16", qk_scale=0.125, with_grad=True)
+    kw = {} if valid_len is None else dict(valid_len=valid_len)
+    got, plan, _ = multihop_forward(q, k, v, dims, "bf16", causal, **kw)
+    assert plan.fused_position() == 1 and plan.pair_kernel(1, ta.TA_VIN_O) == "mfma_bf16_pair_n32"
+    ref = orc.tensorized_attention_forward(q, k, v, dims, causal, valid_len=valid_len)
+    assert np.isfinite(got).all() and np.abs(got - ref).max() <= TOL["bf16"]
+    saved, plan_s, dev = multihop_forward(q, k, v, dims, "bf16", causal, save=True, **kw)
+    assert np.array_equal(saved, got)
+    dq, dk, dv = multihop_backward(plan_s, dev, d_o, "bf16")
+    rq, rk, rv = orc.tensorized_attention_backward(q, k, v, d_o, dims, causal, valid_len=valid_len)
+    check_grad(dq, rq, "bf16", "dq")
+    check_grad(dk, rk, "bf16", "dk")
+    check_grad(dv, rv, "bf16", "dv")
+
+
 @pytest.mark.parametrize("kw", [dict(dims=(32, 16)), dict(dims=(32, 32, 2)),
-                                dict(dims=(32, 32), dtype=ta.TA_F32), dict(dims=(32, 32), D=64)])
+                                dict(dims=(32, 32), dtype=ta.TA_F32), dict(dims=(32, 32), D=256)])
 def test_pair_refuses_what_it_does_not_cover(kw):
     dims = kw.pop("dims")
     D = kw.pop("D", 128)
