@@ -51,12 +51,13 @@ Range span_of(const void* p, const int64_t s[3], int64_t B, int64_t N, int64_t H
 inline bool overlaps(Range a, Range b) { return a.lo < b.hi && b.lo < a.hi; }
 
 bool strides_ok(const int64_t s[3], int64_t B, int64_t N, int64_t H, int64_t D) {
-    // every stride positive, a multiple of 8 elements (16-byte rows), rows disjoint:
+    // every stride positive, a multiple of 8 elements (16-byte rows; of 2 when the head width itself
+    // is not a multiple of 8 and only the generic kernels, which read element by element, apply), rows disjoint:
     // sort the three (stride, extent) pairs and require stride_k >= extent_{k-1} * stride_{k-1}.
     int64_t st[3] = {s[0], s[1], s[2]};
     int64_t ex[3] = {B, N, H};
     for (int i = 0; i < 3; ++i)
-        if (st[i] <= 0 || (st[i] % 8) != 0) return false;
+        if (st[i] <= 0 || (st[i] % (D % 8 == 0 ? 8 : 2)) != 0) return false;
     for (int i = 0; i < 3; ++i)
         for (int j = i + 1; j < 3; ++j)
             if (st[j] < st[i]) { int64_t t = st[i]; st[i] = st[j]; st[j] = t; t = ex[i]; ex[i] = ex[j]; ex[j] = t; }
@@ -159,8 +160,8 @@ ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
         if (reinterpret_cast<uintptr_t>(d->axis_mask[i]) % 4 != 0) return fail(TA_ERR_INVALID_ARG, "axis_mask[%d] is not 4-byte aligned", i);
     if (d->valid_len < 0) return fail(TA_ERR_INVALID_ARG, "valid_len is negative");
     if (d->valid_len > N) return fail(TA_ERR_SHAPE, "valid_len %lld exceeds the sequence length %lld", (long long)d->valid_len, (long long)N);
-    if (d->head_dim % 8 != 0 || d->head_dim > 256)
-        return fail(TA_ERR_UNSUPPORTED, "head_dim %d: need a multiple of 8, at most 256", d->head_dim);
+    if (d->head_dim % 2 != 0 || d->head_dim > 256)
+        return fail(TA_ERR_UNSUPPORTED, "head_dim %d: need an even width, at most 256", d->head_dim);
 
     ta_plan* pl = new (std::nothrow) ta_plan;
     if (!pl) return fail(TA_ERR_INVALID_ARG, "out of host memory");
@@ -200,7 +201,7 @@ ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
     if (!strides_ok(pl->qs, d->batch, N, d->n_q_heads, D) || !strides_ok(pl->kvs, d->batch, N, d->n_kv_heads, D) ||
         !strides_ok(pl->os, d->batch, N, d->n_q_heads, D)) {
         delete pl;
-        return fail(TA_ERR_SHAPE, "strides must be positive multiples of 8 elements describing non-overlapping rows");
+        return fail(TA_ERR_SHAPE, "strides must be positive multiples of 8 elements (of 2 when head_dim is not a multiple of 8) describing non-overlapping rows");
     }
     pl->o_span = (d->batch - 1) * pl->os[0] + (N - 1) * pl->os[1] + (d->n_q_heads - 1) * pl->os[2] + D;
     pl->o_buf_bytes = (((size_t)pl->o_span * pl->elem) + 255) & ~(size_t)255;
@@ -498,6 +499,7 @@ ta_status_t ta_rope_apply(const ta_plan_t* pl, int which, int axis, float base, 
     if (!aligned16(x) || !aligned16(y)) return fail(TA_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
     if (pl->N >= ((int64_t)1 << 31)) return fail(TA_ERR_UNSUPPORTED, "sequence length %lld is too long for the encoding kernel", (long long)pl->N);
     const ta_desc_t& d = pl->desc;
+    if (d.head_dim % 8 != 0) return fail(TA_ERR_UNSUPPORTED, "the encoding kernel needs head_dim to be a multiple of 8, got %d", d.head_dim);
     const int64_t* st = which == 0 ? pl->qs : pl->kvs;
     const int H = which == 0 ? d.n_q_heads : d.n_kv_heads;
     if (x != y && overlaps(span_of(x, st, d.batch, pl->N, H, d.head_dim, pl->elem), span_of(y, st, d.batch, pl->N, H, d.head_dim, pl->elem)))

@@ -91,7 +91,7 @@ def test_cost_model_closed_forms():
     (dict(dims=(4, -3)), "TA_ERR_SHAPE"),
     (dict(n_q_heads=6, n_kv_heads=4), "TA_ERR_SHAPE"),
     (dict(batch=0), "TA_ERR_SHAPE"),
-    (dict(head_dim=100), "TA_ERR_UNSUPPORTED"),
+    (dict(head_dim=101), "TA_ERR_UNSUPPORTED"),
     (dict(head_dim=512), "TA_ERR_UNSUPPORTED"),
     (dict(dtype=7), "TA_ERR_INVALID_ARG"),
     (dict(hop_order=(0, 0)), "TA_ERR_INVALID_ARG"),
@@ -199,3 +199,9 @@ def test_misaligned_axis_mask_is_rejected():
     with pytest.raises(ta.TaError) as e:
         ta.Plan(binding.make_desc(1, 2, 2, 64, (4, 4), ta.TA_F32, True, axis_masks=[6, None]))
     assert e.value.name == "TA_ERR_INVALID_ARG"
+
+
+def test_head_widths_outside_the_matrix_core_kernels_use_the_generic_ones():
+    p = ta.ta_plan_create(1, 32, 32, 100, (32, 32), ta.TA_BF16, True)      # OpenLLaMA-3B geometry
+    assert p.hop_kernel(0, ta.TA_VIN_KV) == "generic" and p.hop_backward_kernel(1, ta.TA_VIN_O) == "generic"
+    assert p.fused_position() == -1

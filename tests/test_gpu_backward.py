@@ -60,6 +60,7 @@ CASES = [
     ((8, 32), 2, 32, 1, 64, True, "bf16"),           # multi-query: 32 heads on one key/value head, four launches
     ((64, 4), 1, 16, 1, 128, False, "bf16"),         # the blocked kernel with 16 heads per group
     ((6, 5), 1, 12, 1, 64, True, "bf16"),            # 12 heads per group: no MFMA variant, generic kernel
+    ((6, 9), 1, 4, 4, 100, True, "bf16"),            # head width 100: generic kernels
     ((32, 8), 2, 16, 2, 128, False, "bf16"),         # 8 heads per group, full-width heads
 ]
 

@@ -60,6 +60,8 @@ CASES = [
     ((2, 128), 1, 4, 1, 64, False, "bf16", 1.0),       # the same, non-causal, value input per head on the second hop
     ((300, 2), 1, 8, 2, 64, True, "bf16", 1.0),        # group-shared streaming, one workgroup per query tile, D = 64
     ((2, 161), 1, 4, 1, 128, False, "bf16", 1.0),
+    ((6, 9, 4), 1, 4, 4, 100, True, "bf16", 1.0),      # head width 100 (OpenLLaMA-3B's): generic kernels, 8-byte-granular rows
+    ((5, 12), 2, 2, 1, 36, False, "f32", 1.0),
 ]
 
 
