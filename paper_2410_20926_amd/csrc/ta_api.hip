@@ -51,13 +51,13 @@ Range span_of(const void* p, const int64_t s[3], int64_t B, int64_t N, int64_t H
 inline bool overlaps(Range a, Range b) { return a.lo < b.hi && b.lo < a.hi; }
 
 bool strides_ok(const int64_t s[3], int64_t B, int64_t N, int64_t H, int64_t D) {
-    // every stride positive, a multiple of 8 elements (16-byte rows; of 2 when the head width itself
-    // is not a multiple of 8 and only the generic kernels, which read element by element, apply), rows disjoint:
+    // every stride positive, a multiple of 8 elements (16-byte rows; of 4 when the head width is only a
+    // multiple of 4, whose rows the kernels read in 8-byte pieces; of 2 otherwise: generic kernels only), rows disjoint:
     // sort the three (stride, extent) pairs and require stride_k >= extent_{k-1} * stride_{k-1}.
     int64_t st[3] = {s[0], s[1], s[2]};
     int64_t ex[3] = {B, N, H};
     for (int i = 0; i < 3; ++i)
-        if (st[i] <= 0 || (st[i] % (D % 8 == 0 ? 8 : 2)) != 0) return false;
+        if (st[i] <= 0 || (st[i] % (D % 8 == 0 ? 8 : D % 4 == 0 ? 4 : 2)) != 0) return false;
     for (int i = 0; i < 3; ++i)
         for (int j = i + 1; j < 3; ++j)
             if (st[j] < st[i]) { int64_t t = st[i]; st[i] = st[j]; st[j] = t; t = ex[i]; ex[i] = ex[j]; ex[j] = t; }
@@ -201,7 +201,7 @@ ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
     if (!strides_ok(pl->qs, d->batch, N, d->n_q_heads, D) || !strides_ok(pl->kvs, d->batch, N, d->n_kv_heads, D) ||
         !strides_ok(pl->os, d->batch, N, d->n_q_heads, D)) {
         delete pl;
-        return fail(TA_ERR_SHAPE, "strides must be positive multiples of 8 elements (of 2 when head_dim is not a multiple of 8) describing non-overlapping rows");
+        return fail(TA_ERR_SHAPE, "strides must be positive multiples of 8 elements (of 4 or 2 when head_dim is only a multiple of 4 or 2) describing non-overlapping rows");
     }
     pl->o_span = (d->batch - 1) * pl->os[0] + (N - 1) * pl->os[1] + (d->n_q_heads - 1) * pl->os[2] + D;
     pl->o_buf_bytes = (((size_t)pl->o_span * pl->elem) + 255) & ~(size_t)255;

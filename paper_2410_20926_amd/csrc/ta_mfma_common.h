@@ -38,6 +38,35 @@ __device__ inline f32x16 mma(const u32x4 a, const u32x4 b, const f32x16 c) {   /
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
+// One lane's 16-byte chunk (8 features starting at byte `lbyte` of the row at `base + rowoff`).  NARROW:
+// the row holds only `dbytes` bytes (a head width that is a multiple of 4 but not of 8 features,
+// or simply narrower than the tile): the chunk is read as two 8-byte halves, each only if it
+// lies inside the row, and what lies outside is zero, so that the tile's extra features are
+// zero in every operand.  Rows are then only 8-byte aligned, which the 8-byte accesses respect.
+template <bool NARROW, bool NT>
+__device__ inline u32x4 load_chunk(const char* base, uint32_t rowoff, uint32_t lbyte, uint32_t dbytes) {
+    if constexpr (!NARROW) {
+        const u32x4* a = reinterpret_cast<const u32x4*>(base + (rowoff + lbyte));
+        return NT ? __builtin_nontemporal_load(a) : *a;
+    } else {
+        u32x2 lo = {0u, 0u}, hi = {0u, 0u};
+        const u32x2* a = reinterpret_cast<const u32x2*>(base + (rowoff + lbyte));
+        if (lbyte + 8 <= dbytes) lo = NT ? __builtin_nontemporal_load(a) : *a;
+        if (lbyte + 16 <= dbytes) hi = NT ? __builtin_nontemporal_load(a + 1) : a[1];
+        return u32x4{lo.x, lo.y, hi.x, hi.y};
+    }
+}
+template <bool NARROW>
+__device__ inline void store_chunk(char* base, uint32_t rowoff, uint32_t lbyte, uint32_t dbytes, const u32x4 v) {
+    if constexpr (!NARROW) {
+        __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(base + (rowoff + lbyte)));
+    } else {
+        u32x2* a = reinterpret_cast<u32x2*>(base + (rowoff + lbyte));
+        if (lbyte + 8 <= dbytes) __builtin_nontemporal_store(u32x2{v.x, v.y}, a);
+        if (lbyte + 16 <= dbytes) __builtin_nontemporal_store(u32x2{v.z, v.w}, a + 1);
+    }
+}
+
 template <int D>
 struct Geo {
     static constexpr int kChunks = D / 8;                 // 16-byte chunks per row

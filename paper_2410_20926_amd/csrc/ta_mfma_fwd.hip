@@ -32,7 +32,8 @@ using namespace mfma;
 constexpr int kWavesPerBlock = 4;
 
 // KT = number of 32-key tiles a unit may walk (1: n <= 32, 2: n <= 64).
-template <int D, int KT>
+// NARROW: the head is narrower than the D-wide tile (p.D features of 2 bytes per row); see load_chunk.
+template <int D, int KT, bool NARROW>
 __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopParams p, TileParams tp) {
     using G = Geo<D>;
     constexpr int kRows = kTile * KT;                     // rows of the unit's fibre set that have a table entry
@@ -95,6 +96,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
     const int lrow = lane / G::kChunks;                   // row within a pass
     const int lcol = lane % G::kChunks;                   // 16-byte chunk within the row
     const uint32_t lbyte = lcol * 16;
+    const uint32_t dbytes = (uint32_t)p.D * 2;           // bytes of a row (less than the tile's when NARROW)
     const int kt_end = (KT == 1) ? 1 : (p.causal ? qt + 1 : (n > kTile ? 2 : 1));   // key tiles this unit walks
 
     if (((real_rows >> (qt * kTile)) & 0xffffffffull) == 0) {
@@ -102,7 +104,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
 #pragma unroll
         for (int i = 0; i < G::kPasses; ++i) {
             const int row = qt * kTile + i * G::kRowsPerPass + lrow;
-            if (row < rows_valid) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, reinterpret_cast<u32x4*>(ob + (rowoff[row].w + lbyte)));
+            if (row < rows_valid) store_chunk<NARROW>(ob, rowoff[row].w, lbyte, dbytes, u32x4{0u, 0u, 0u, 0u});
         }
         return;
     }
@@ -123,14 +125,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
 #pragma unroll
             for (int i = 0; i < G::kPasses; ++i) {
                 const u32x4 off = rowoff[j * kTile + i * G::kRowsPerPass + lrow];
-                kreg[j][i] = k_once ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + (off.y + lbyte)))
-                                    : *reinterpret_cast<const u32x4*>(kb + (off.y + lbyte));
-                voff[j][i] = off.z + lbyte;
-                if (j == 0) vreg[j][i] = v_once ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + voff[j][i]))
-                                                : *reinterpret_cast<const u32x4*>(vb + voff[j][i]);
+                kreg[j][i] = k_once ? load_chunk<NARROW, true>(kb, off.y, lbyte, dbytes) : load_chunk<NARROW, false>(kb, off.y, lbyte, dbytes);
+                voff[j][i] = off.z;
+                if (j == 0) vreg[j][i] = v_once ? load_chunk<NARROW, true>(vb, voff[j][i], lbyte, dbytes) : load_chunk<NARROW, false>(vb, voff[j][i], lbyte, dbytes);
                 if (KT == 1) {
-                    qreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (off.x + lbyte)));
-                    ooff[i] = off.w + lbyte;
+                    qreg[i] = load_chunk<NARROW, true>(qb, off.x, lbyte, dbytes);
+                    ooff[i] = off.w;
                 }
             }
         }
@@ -139,8 +139,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
 #pragma unroll
         for (int i = 0; i < G::kPasses; ++i) {
             const u32x4 off = rowoff[qt * kTile + i * G::kRowsPerPass + lrow];
-            qreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (off.x + lbyte)));
-            ooff[i] = off.w + lbyte;
+            qreg[i] = load_chunk<NARROW, true>(qb, off.x, lbyte, dbytes);
+            ooff[i] = off.w;
         }
     }
     __builtin_amdgcn_sched_barrier(0);                    // keep these loads ahead of the first wait
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
             lds_wave_sync();
             if (KT > 1 && j == 0 && kt_end > 1) {         // K tile 0 is out of its registers: request V tile 1
 #pragma unroll
-                for (int i = 0; i < G::kPasses; ++i) vreg[1][i] = *reinterpret_cast<const u32x4*>(vb + voff[1][i]);
+                for (int i = 0; i < G::kPasses; ++i) vreg[1][i] = load_chunk<NARROW, false>(vb, voff[1][i], lbyte, dbytes);
                 __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
         const int row = qt * kTile + i * G::kRowsPerPass + lrow;
         if (row < rows_valid) {
             const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(ob + ooff[i]));
+            store_chunk<NARROW>(ob, ooff[i], lbyte, dbytes, v);
         }
     }
 }
@@ -311,7 +311,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
 // (a previous O) still goes through the wave's private transit tile.
 // VS: the value input is shared too (first hop).  Then the private tile only carries Q in and O
 // out, one lane per row, and is used in two halves of 16 rows to halve its LDS footprint.
-template <int D, int KT, bool VS>
+template <int D, int KT, bool VS, bool NARROW>
 __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel(HopParams p, TileParams tp) {
     using G = Geo<D>;
     constexpr int kRows = kTile * KT;
@@ -378,12 +378,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
 
     const int lrow = lane / G::kChunks, lcol = lane % G::kChunks;
     const uint32_t lbyte = lcol * 16;
+    const uint32_t dbytes = (uint32_t)p.D * 2;           // bytes of a row (less than the tile's when NARROW)
     if (((real_rows >> (qt * kTile)) & 0xffffffffull) == 0) {
         // every query row of this unit is padding (the same in all four waves): zero rows out, nothing read
 #pragma unroll
         for (int i = 0; i < G::kPasses; ++i) {
             const int row = qt * kTile + i * G::kRowsPerPass + lrow;
-            if (row < rows_valid) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, reinterpret_cast<u32x4*>(ob + (rowoff[row].w + lbyte)));
+            if (row < rows_valid) store_chunk<NARROW>(ob, rowoff[row].w, lbyte, dbytes, u32x4{0u, 0u, 0u, 0u});
         }
         return;
     }
@@ -396,8 +397,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
 #pragma unroll
     for (int i = 0; i < G::kPasses; ++i) {
         const u32x4 off = rowoff[qt * kTile + i * G::kRowsPerPass + lrow];
-        qreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (off.x + lbyte)));
-        ooff[i] = off.w + lbyte;
+        qreg[i] = load_chunk<NARROW, true>(qb, off.x, lbyte, dbytes);
+        ooff[i] = off.w;
     }
 #pragma unroll
     for (int j = 0; j < KT; ++j) {
@@ -405,15 +406,15 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
 #pragma unroll
             for (int i = 0; i < kShare; ++i) {
                 const u32x4 off = rowoff[j * kTile + (w * kShare + i) * G::kRowsPerPass + lrow];
-                ksh[j][i] = *reinterpret_cast<const u32x4*>(kb + (off.y + lbyte));
-                if (v_shared) vsh[j][i] = *reinterpret_cast<const u32x4*>(vb + (off.z + lbyte));
+                ksh[j][i] = load_chunk<NARROW, false>(kb, off.y, lbyte, dbytes);
+                if (v_shared) vsh[j][i] = load_chunk<NARROW, false>(vb, off.z, lbyte, dbytes);
             }
             if (!v_shared) {
 #pragma unroll
                 for (int i = 0; i < G::kPasses; ++i) {
                     const u32x4 off = rowoff[j * kTile + i * G::kRowsPerPass + lrow];
-                    vreg[j][i] = (KT == 1) ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vb + (off.z + lbyte)))
-                                           : *reinterpret_cast<const u32x4*>(vb + (off.z + lbyte));   // with two query tiles a value tile is read twice: keep it cached
+                    vreg[j][i] = (KT == 1) ? load_chunk<NARROW, true>(vb, off.z, lbyte, dbytes)
+                                           : load_chunk<NARROW, false>(vb, off.z, lbyte, dbytes);   // with two query tiles a value tile is read twice: keep it cached
                 }
             }
         }
@@ -551,29 +552,29 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
             const int row = qt * kTile + (hs * kHalfPasses + i) * G::kRowsPerPass + lrow;
             if (row < rows_valid) {
                 const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
-                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(ob + ooff[hs * kHalfPasses + i]));
+                store_chunk<NARROW>(ob, ooff[hs * kHalfPasses + i], lbyte, dbytes, v);
             }
         }
         lds_wave_sync();
     }
 }
 
-template <int D, int KT>
+template <int D, int KT, bool NARROW>
 hipError_t launch_shared(const HopParams& p, const TileParams& tp, hipStream_t s) {
     const size_t tile = (size_t)kTile * Geo<D>::kPitch;
     const bool vs = p.vin_heads != p.Hq;
     const size_t smem = (vs ? 2 : 1) * KT * tile + (size_t)kTile * KT * 16 + kWavesPerBlock * (vs ? tile / 2 : tile);
     const dim3 grid((unsigned)(p.Hq / kWavesPerBlock), tp.tiles_lo, (unsigned)p.B * tp.tiles_hi);
-    if (vs) hipLaunchKernelGGL((mfma_fwd_shared_kernel<D, KT, true>), grid, dim3(kWavesPerBlock * 64), smem, s, p, tp);
-    else hipLaunchKernelGGL((mfma_fwd_shared_kernel<D, KT, false>), grid, dim3(kWavesPerBlock * 64), smem, s, p, tp);
+    if (vs) hipLaunchKernelGGL((mfma_fwd_shared_kernel<D, KT, true, NARROW>), grid, dim3(kWavesPerBlock * 64), smem, s, p, tp);
+    else hipLaunchKernelGGL((mfma_fwd_shared_kernel<D, KT, false, NARROW>), grid, dim3(kWavesPerBlock * 64), smem, s, p, tp);
     return hipGetLastError();
 }
 
-template <int D, int KT>
+template <int D, int KT, bool NARROW>
 hipError_t launch(const HopParams& p, const TileParams& tp, hipStream_t s) {
     const size_t smem = (size_t)kWavesPerBlock * (Geo<D>::kBufBytes + kTile * KT * 16);
     const dim3 grid((unsigned)((p.Hq + kWavesPerBlock - 1) / kWavesPerBlock), tp.tiles_lo, (unsigned)p.B * tp.tiles_hi);
-    hipLaunchKernelGGL((mfma_fwd_kernel<D, KT>), grid, dim3(kWavesPerBlock * 64), smem, s, p, tp);
+    hipLaunchKernelGGL((mfma_fwd_kernel<D, KT, NARROW>), grid, dim3(kWavesPerBlock * 64), smem, s, p, tp);
     return hipGetLastError();
 }
 
@@ -587,28 +588,37 @@ bool mfma_forward_layout_ok(const HopParams& p) {
 
 bool mfma_forward_supports(int32_t n, int32_t D, int dtype, int* kernel_id) {
     int kid = K_GENERIC;
-    if (dtype == TA_BF16 && (D == 64 || D == 128) && n >= 1) {
+    // head widths 64 and 128 fill a tile; any other multiple of 4 up to 128 rides in the next wider
+    // tile with its extra features zero (one- and two-tile kernels only)
+    const bool full = D == 64 || D == 128, narrow = !full && D % 4 == 0 && D >= 8 && D < 128;
+    if (dtype == TA_BF16 && n >= 1 && (full || narrow)) {
         if (n <= 32) kid = K_MFMA_BF16_N32;
         else if (n <= 64) kid = K_MFMA_BF16_N64;
-        else kid = K_MFMA_BF16_STREAM;
+        else if (full) kid = K_MFMA_BF16_STREAM;
     }
     if (kernel_id) *kernel_id = kid;
     return kid != K_GENERIC;
 }
 
+namespace {
+template <int D, bool NARROW>
+hipError_t launch_width(const HopParams& p, const TileParams& tp, int KT, hipStream_t s) {
+    if (p.G % kWavesPerBlock == 0)                     // 4 query heads of a workgroup share their key/value head
+        return KT == 1 ? launch_shared<D, 1, NARROW>(p, tp, s) : launch_shared<D, 2, NARROW>(p, tp, s);
+    return KT == 1 ? launch<D, 1, NARROW>(p, tp, s) : launch<D, 2, NARROW>(p, tp, s);
+}
+}  // namespace
+
 hipError_t launch_mfma_forward(const HopParams& p, int kernel_id, hipStream_t s) {
     if (kernel_id == K_MFMA_BF16_STREAM) return launch_mfma_forward_stream(p, s);
     const int KT = kernel_id == K_MFMA_BF16_N32 ? 1 : (kernel_id == K_MFMA_BF16_N64 ? 2 : 0);
-    if (KT == 0 || p.n < 1 || p.n > kTile * KT || (p.D != 64 && p.D != 128) || !mfma_forward_layout_ok(p))
+    if (KT == 0 || p.n < 1 || p.n > kTile * KT || p.D < 8 || p.D > 128 || p.D % 4 != 0 || !mfma_forward_layout_ok(p))
         return hipErrorInvalidValue;
     TileParams tp;
     if (!make_tile_params(p, KT, &tp)) return hipErrorInvalidValue;
-    if (p.G % kWavesPerBlock == 0) {                   // 4 query heads of a workgroup share their key/value head
-        if (p.D == 128) return KT == 1 ? launch_shared<128, 1>(p, tp, s) : launch_shared<128, 2>(p, tp, s);
-        return KT == 1 ? launch_shared<64, 1>(p, tp, s) : launch_shared<64, 2>(p, tp, s);
-    }
-    if (p.D == 128) return KT == 1 ? launch<128, 1>(p, tp, s) : launch<128, 2>(p, tp, s);
-    return KT == 1 ? launch<64, 1>(p, tp, s) : launch<64, 2>(p, tp, s);
+    if (p.D == 128) return launch_width<128, false>(p, tp, KT, s);
+    if (p.D == 64) return launch_width<64, false>(p, tp, KT, s);
+    return p.D > 64 ? launch_width<128, true>(p, tp, KT, s) : launch_width<64, true>(p, tp, KT, s);
 }
 
 }  // namespace ta

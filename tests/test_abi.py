@@ -201,7 +201,11 @@ def test_misaligned_axis_mask_is_rejected():
     assert e.value.name == "TA_ERR_INVALID_ARG"
 
 
-def test_head_widths_outside_the_matrix_core_kernels_use_the_generic_ones():
-    p = ta.ta_plan_create(1, 32, 32, 100, (32, 32), ta.TA_BF16, True)      # OpenLLaMA-3B geometry
-    assert p.hop_kernel(0, ta.TA_VIN_KV) == "generic" and p.hop_backward_kernel(1, ta.TA_VIN_O) == "generic"
-    assert p.fused_position() == -1
+def test_kernels_for_other_head_widths():
+    p = ta.ta_plan_create(1, 32, 32, 100, (32, 32), ta.TA_BF16, True)      # OpenLLaMA-3B geometry: a multiple of 4
+    assert p.hop_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_n32" and p.hop_kernel(1, ta.TA_VIN_O) == "mfma_bf16_n32"
+    assert p.fused_position() == -1 and p.hop_backward_kernel(1, ta.TA_VIN_O) == "generic"
+    long_axis = ta.ta_plan_create(1, 8, 2, 96, (128, 4), ta.TA_BF16, True)
+    assert long_axis.hop_kernel(0, ta.TA_VIN_KV) == "generic"             # the streaming kernels take full tiles only
+    odd = ta.ta_plan_create(1, 4, 4, 90, (16, 16), ta.TA_BF16, True)       # even, not a multiple of 4
+    assert odd.hop_kernel(0, ta.TA_VIN_KV) == "generic"

@@ -60,7 +60,11 @@ CASES = [
     ((2, 128), 1, 4, 1, 64, False, "bf16", 1.0),       # the same, non-causal, value input per head on the second hop
     ((300, 2), 1, 8, 2, 64, True, "bf16", 1.0),        # group-shared streaming, one workgroup per query tile, D = 64
     ((2, 161), 1, 4, 1, 128, False, "bf16", 1.0),
-    ((6, 9, 4), 1, 4, 4, 100, True, "bf16", 1.0),      # head width 100 (OpenLLaMA-3B's): generic kernels, 8-byte-granular rows
+    ((6, 9, 4), 1, 4, 4, 100, True, "bf16", 1.0),      # head width 100 (OpenLLaMA-3B's): 8-byte-granular rows in 128-wide tiles
+    ((32, 32), 2, 8, 2, 100, True, "bf16", 1.0),       # the same with grouped-query heads (group-shared kernel)
+    ((48, 5), 1, 4, 1, 96, False, "bf16", 1.0),        # two-tile kernels, width 96
+    ((7, 64), 1, 3, 3, 40, True, "bf16", 1.0),         # width 40 in 64-wide tiles
+    ((10, 6), 1, 2, 2, 90, True, "bf16", 1.0),         # even but not a multiple of 4: generic kernels
     ((5, 12), 2, 2, 1, 36, False, "f32", 1.0),
 ]
 
