@@ -44,22 +44,31 @@ __device__ inline uint32_t tile_out_offset(const u32x4* rowoff, int which, int h
 
 // Requests the current contents of an output tile (for accumulate = 1) long before the
 // epilogue needs them, in the epilogue's mapping.
-template <int D>
-__device__ inline void prefetch_tile(u32x4 (&old)[Geo<D>::kDTiles * 2], const u32x4* rowoff, int which, const char* gbase, int lane) {
+// NARROW (here and below): rows hold only `dbytes` bytes and are 8-byte aligned; see load_chunk.
+template <int D, bool NARROW = false>
+__device__ inline void prefetch_tile(u32x4 (&old)[Geo<D>::kDTiles * 2], const u32x4* rowoff, int which, const char* gbase, int lane,
+                                     uint32_t dbytes = 0) {
 #pragma unroll
     for (int half = 0; half < Geo<D>::kDTiles / 2; ++half)
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            old[half * 4 + i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gbase + tile_out_offset<D>(rowoff, which, half, i, lane)));
+        for (int i = 0; i < 4; ++i) {
+            if constexpr (NARROW) {
+                const uint32_t fbyte = (uint32_t)(half * 64 + (lane & 7) * 8) * 2;
+                old[half * 4 + i] = load_chunk<true, true>(gbase, tile_out_offset<D>(rowoff, which, half, i, lane) - fbyte, fbyte, dbytes);
+            } else {
+                old[half * 4 + i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gbase + tile_out_offset<D>(rowoff, which, half, i, lane)));
+            }
+        }
 }
 
 // acc[t][r] holds (row = lane % 32, feature 32 t + 8 (r/4) + 4 hf + r % 4).  Multiplies by
 // `mult`, optionally adds the tensor's previous contents (`old`, from prefetch_tile), rounds
 // to bf16 and stores the rows with 16-byte stores; the transposition goes through LDS in
 // fp32, 64 features at a time.
-template <int D>
+template <int D, bool NARROW = false>
 __device__ inline void store_tile(const f32x16 (&acc)[Geo<D>::kDTiles], float mult, char* buf, const u32x4* rowoff,
-                                  int which, char* gbase, const u32x4 (&old)[Geo<D>::kDTiles * 2], bool add_old, int rows_valid, int lane) {
+                                  int which, char* gbase, const u32x4 (&old)[Geo<D>::kDTiles * 2], bool add_old, int rows_valid, int lane,
+                                  uint32_t dbytes = 0) {
     using G = BGeo<D>;
     const int r32 = lane & 31, hf = lane >> 5;
 #pragma unroll
@@ -85,9 +94,13 @@ __device__ inline void store_tile(const f32x16 (&acc)[Geo<D>::kDTiles], float mu
 #pragma unroll
                     for (int e = 0; e < 4; ++e) { y[2 * e] += bf16_lo(o[e]); y[2 * e + 1] += bf16_hi(o[e]); }
                 }
-                __builtin_nontemporal_store(
-                    u32x4{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])},
-                    reinterpret_cast<u32x4*>(gbase + tile_out_offset<D>(rowoff, which, half, i, lane)));
+                const u32x4 packed = u32x4{pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]), pack_bf16x2(y[6], y[7])};
+                if constexpr (NARROW) {
+                    const uint32_t fbyte = (uint32_t)(half * 64 + (lane & 7) * 8) * 2;
+                    store_chunk<true>(gbase, tile_out_offset<D>(rowoff, which, half, i, lane) - fbyte, fbyte, dbytes, packed);
+                } else {
+                    __builtin_nontemporal_store(packed, reinterpret_cast<u32x4*>(gbase + tile_out_offset<D>(rowoff, which, half, i, lane)));
+                }
             }
         }
         lds_wave_sync();
@@ -96,9 +109,9 @@ __device__ inline void store_tile(const f32x16 (&acc)[Geo<D>::kDTiles], float mu
 
 // The same without previous contents to add: the values are rounded to bf16 BEFORE the
 // transposition, which then moves half the bytes through LDS (one row-major bf16 tile).
-template <int D>
+template <int D, bool NARROW = false>
 __device__ inline void store_tile_plain(const f32x16 (&acc)[Geo<D>::kDTiles], float mult, char* buf, const u32x4* rowoff,
-                                        int which, char* gbase, int rows_valid, int lane) {
+                                        int which, char* gbase, int rows_valid, int lane, uint32_t dbytes = 0) {
     using G = BGeo<D>;
     const int r32 = lane & 31, hf = lane >> 5;
     const int lrow = lane / G::kChunks, lcol = lane % G::kChunks;
@@ -118,7 +131,8 @@ __device__ inline void store_tile_plain(const f32x16 (&acc)[Geo<D>::kDTiles], fl
         if (row < rows_valid) {
             const u32x4 v = *reinterpret_cast<const u32x4*>(buf + row * G::kPitch + lcol * 16);
             const u32x4 off4 = rowoff[row];
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(gbase + ((which == 0 ? off4.x : which == 1 ? off4.y : off4.z) + lcol * 16)));
+            if constexpr (NARROW) store_chunk<true>(gbase, which == 0 ? off4.x : which == 1 ? off4.y : off4.z, (uint32_t)lcol * 16, dbytes, v);
+            else __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(gbase + ((which == 0 ? off4.x : which == 1 ? off4.y : off4.z) + lcol * 16)));
         }
     }
     lds_wave_sync();
@@ -159,7 +173,7 @@ __device__ inline void chain_sum(f32x16 (&acc)[Geo<D>::kDTiles], float* red, int
 // blockDim.x = 64 * G (G = query heads per key/value head: 1, 2, 4 or 8); grid = (Hkv, tiles_lo, B * tiles_hi).
 // TABLE: the axis has a caller's bit table; MULTI: the group has more than 8 heads and this launch
 // covers 8 of them (separate instantiations keep the common case free of both).
-template <int D, bool TABLE, bool MULTI>
+template <int D, bool TABLE, bool MULTI, bool NARROW>
 __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TileParams tp) {
     using G = BGeo<D>;
     const HopParams& p = bp.hop;
@@ -213,6 +227,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
 
     const int lrow = lane / G::kChunks, lcol = lane % G::kChunks;
     const uint32_t lbyte = lcol * 16;
+    const uint32_t dbytes = (uint32_t)p.D * 2;            // bytes of a row (less than the tile's when NARROW)
     const int r32 = lane & 31, hf = lane >> 5;
 
     // ---- gather Q, K, X, G rows: every load is issued before the first wait ------------
@@ -221,11 +236,10 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
     for (int i = 0; i < G::kPasses; ++i) {
         const u32x4 off = rowoff[i * G::kRowsPerPass + lrow];
         // Rows read by this wave alone are streamed; rows every wave of the group reads stay cached.
-        qraw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (off.x + lbyte)));
-        kraw[i] = *reinterpret_cast<const u32x4*>(kb + (off.y + lbyte));
-        xraw[i] = vin_is_o ? __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xb + (off.z + lbyte)))
-                           : *reinterpret_cast<const u32x4*>(xb + (off.z + lbyte));
-        graw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gb + (off.w + lbyte)));
+        qraw[i] = load_chunk<NARROW, true>(qb, off.x, lbyte, dbytes);
+        kraw[i] = load_chunk<NARROW, false>(kb, off.y, lbyte, dbytes);
+        xraw[i] = vin_is_o ? load_chunk<NARROW, true>(xb, off.z, lbyte, dbytes) : load_chunk<NARROW, false>(xb, off.z, lbyte, dbytes);
+        graw[i] = load_chunk<NARROW, true>(gb, off.w, lbyte, dbytes);
     }
     __builtin_amdgcn_sched_barrier(0);
 
@@ -275,7 +289,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
 
     // previous dQ (accumulate): requested now, consumed after the dQ products
     u32x4 oldq[G::kDTiles * 2] = {};
-    if (bp.accumulate) prefetch_tile<D>(oldq, rowoff, 0, dqb, lane);
+    if (bp.accumulate) prefetch_tile<D, NARROW>(oldq, rowoff, 0, dqb, lane, dbytes);
 
     // ---- softmax and dS, one query row per lane -------------------------------------------
     const float sl2 = p.scale * kLog2e;
@@ -348,7 +362,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) acc[t] = mma(kT[t][s2], dsTop[s2], acc[t]);
     }
-    store_tile<D>(acc, p.scale, buf, rowoff, 0, dqb, oldq, bp.accumulate != 0, rows_valid, lane);
+    store_tile<D, NARROW>(acc, p.scale, buf, rowoff, 0, dqb, oldq, bp.accumulate != 0, rows_valid, lane, dbytes);
 
     // ---- dX^T = G^T P : per head, or summed over the group when the value input is V ------
 #pragma unroll
@@ -358,22 +372,22 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
         for (int s2 = 0; s2 < 2; ++s2) acc[t] = mma(gT[t][s2], pNop[s2], acc[t]);
     }
     if (vin_is_o) {
-        store_tile_plain<D>(acc, 1.f, buf, rowoff, 2, dxb, rows_valid, lane);
+        store_tile_plain<D, NARROW>(acc, 1.f, buf, rowoff, 2, dxb, rows_valid, lane, dbytes);
     } else {
         if constexpr (MULTI) {
             u32x4 oldx[G::kDTiles * 2] = {};              // the sum of the group's earlier heads
-            if (bp.acc_x && w == nw - 1) prefetch_tile<D>(oldx, rowoff, 2, dxb, lane);
+            if (bp.acc_x && w == nw - 1) prefetch_tile<D, NARROW>(oldx, rowoff, 2, dxb, lane, dbytes);
             chain_sum<D>(acc, red, w, nw, lane);
-            if (w == nw - 1) store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, oldx, bp.acc_x != 0, rows_valid, lane);
+            if (w == nw - 1) store_tile<D, NARROW>(acc, 1.f, buf, rowoff, 2, dxb, oldx, bp.acc_x != 0, rows_valid, lane, dbytes);
         } else {
             chain_sum<D>(acc, red, w, nw, lane);
-            if (w == nw - 1) store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, oldq, false, rows_valid, lane);
+            if (w == nw - 1) store_tile<D, NARROW>(acc, 1.f, buf, rowoff, 2, dxb, oldq, false, rows_valid, lane, dbytes);
         }
     }
     // previous dK (accumulate): only the wave that ends up with the group's sum needs it
     u32x4 oldk[G::kDTiles * 2] = {};
     const bool acc_k = MULTI ? bp.acc_k != 0 : bp.accumulate != 0;
-    if (acc_k && w == nw - 1) prefetch_tile<D>(oldk, rowoff, 1, dkb, lane);
+    if (acc_k && w == nw - 1) prefetch_tile<D, NARROW>(oldk, rowoff, 1, dkb, lane, dbytes);
 
     // ---- dK^T = Q^T dS : summed over the group ----------------------------------------------
 #pragma unroll
@@ -383,7 +397,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
         for (int s2 = 0; s2 < 2; ++s2) acc[t] = mma(qT[t][s2], dsNop[s2], acc[t]);
     }
     chain_sum<D>(acc, red, w, nw, lane);
-    if (w == nw - 1) store_tile<D>(acc, p.scale, buf, rowoff, 1, dkb, oldk, acc_k, rows_valid, lane);
+    if (w == nw - 1) store_tile<D, NARROW>(acc, p.scale, buf, rowoff, 1, dkb, oldk, acc_k, rows_valid, lane, dbytes);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -786,18 +800,20 @@ hipError_t launch_stream(const BwdParams& bp, hipStream_t s) {
     return hipGetLastError();
 }
 
-template <int D>
+template <int D, bool NARROW>
 hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
     const HopParams& p = bp.hop;
     const size_t smem = (size_t)(bp.wg_heads > 1 ? BGeo<D>::kRedBytes : 0) + (size_t)bp.wg_heads * BGeo<D>::kWaveBytes;
     const dim3 grid((unsigned)p.Hkv, tp.tiles_lo, (unsigned)p.B * tp.tiles_hi);
     const dim3 block(64 * bp.wg_heads);
-    if (p.G > bp.wg_heads) {
-        if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true, true>), grid, block, smem, s, bp, tp);
-        else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false, true>), grid, block, smem, s, bp, tp);
+    if (NARROW) {                                         // narrow heads: the plain instantiation only (no table, groups of up to 8)
+        hipLaunchKernelGGL((mfma_bwd_kernel<D, false, false, true>), grid, block, smem, s, bp, tp);
+    } else if (p.G > bp.wg_heads) {
+        if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true, true, false>), grid, block, smem, s, bp, tp);
+        else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false, true, false>), grid, block, smem, s, bp, tp);
     } else {
-        if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true, false>), grid, block, smem, s, bp, tp);
-        else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false, false>), grid, block, smem, s, bp, tp);
+        if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true, false, false>), grid, block, smem, s, bp, tp);
+        else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false, false, false>), grid, block, smem, s, bp, tp);
     }
     return hipGetLastError();
 }
@@ -807,7 +823,10 @@ hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
 // 1: the one-tile kernel (n <= 32); 2: the blocked kernel (32 < n <= kStreamMaxN); 0: neither.
 static int backward_variant(const BwdParams& bp, int dtype) {
     const HopParams& p = bp.hop;
-    if (dtype != TA_BF16 || (p.D != 64 && p.D != 128) || p.n < 1 || p.n > kStreamMaxN) return 0;
+    const bool full = p.D == 64 || p.D == 128;
+    // other widths that are multiples of 4 ride in the next wider tile: one-tile kernel, no table, groups of up to 8
+    const bool narrow = !full && p.D % 4 == 0 && p.D >= 8 && p.D < 128 && p.n <= kTile && !p.mask && p.G <= 8;
+    if (dtype != TA_BF16 || !(full || narrow) || p.n < 1 || p.n > kStreamMaxN) return 0;
     if (p.G != 1 && p.G != 2 && p.G != 4 && p.G % 8 != 0) return 0;   // groups of more than 8 heads run 8 heads per launch
     const int64_t N = p.fibres * p.n;
     if (!(N < ((int64_t)1 << 31) && p.B <= 65535 && fits_u32(p.q, N) && fits_u32(p.k, N) && fits_u32(p.vin, N) &&
@@ -843,7 +862,9 @@ hipError_t launch_mfma_backward(const BwdParams& user, hipStream_t s) {
         bp.acc_x = base == 0 ? 0 : 1;
         hipError_t e;
         if (variant == 2) e = bp.hop.D == 128 ? launch_stream<128>(bp, s) : launch_stream<64>(bp, s);
-        else              e = bp.hop.D == 128 ? launch<128>(bp, tp, s) : launch<64>(bp, tp, s);
+        else if (bp.hop.D == 128) e = launch<128, false>(bp, tp, s);
+        else if (bp.hop.D == 64)  e = launch<64, false>(bp, tp, s);
+        else                      e = bp.hop.D > 64 ? launch<128, true>(bp, tp, s) : launch<64, true>(bp, tp, s);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;

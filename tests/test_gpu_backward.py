@@ -60,7 +60,10 @@ CASES = [
     ((8, 32), 2, 32, 1, 64, True, "bf16"),           # multi-query: 32 heads on one key/value head, four launches
     ((64, 4), 1, 16, 1, 128, False, "bf16"),         # the blocked kernel with 16 heads per group
     ((6, 5), 1, 12, 1, 64, True, "bf16"),            # 12 heads per group: no MFMA variant, generic kernel
-    ((6, 9), 1, 4, 4, 100, True, "bf16"),            # head width 100: generic kernels
+    ((6, 9), 1, 4, 4, 100, True, "bf16"),            # head width 100: 8-byte-granular rows in 128-wide tiles
+    ((32, 4, 8), 2, 8, 2, 96, True, "bf16"),         # width 96, groups of 4 heads, three hops (dQ, dK accumulate)
+    ((16, 32), 1, 2, 2, 40, False, "bf16"),          # width 40 in 64-wide tiles
+    ((40, 3), 1, 2, 2, 100, True, "bf16"),           # width 100 on an axis of two tiles: MFMA forward, generic backward
     ((32, 8), 2, 16, 2, 128, False, "bf16"),         # 8 heads per group, full-width heads
 ]
 
