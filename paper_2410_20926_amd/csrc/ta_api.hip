@@ -132,7 +132,7 @@ const char* ta_last_error_detail(void) { return g_detail; }
 
 void ta_version(int* major, int* minor) {
     if (major) *major = 0;
-    if (minor) *minor = 3;
+    if (minor) *minor = 4;
 }
 
 ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {

@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_status_strings():
-    assert ta.ta_version() == (0, 3)
+    assert ta.ta_version() == (0, 4)
     lib = ta.load_library()
     assert lib.ta_status_string(0) == b"TA_OK"
     assert lib.ta_status_string(5) == b"TA_ERR_ALIAS"
