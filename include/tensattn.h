@@ -152,7 +152,8 @@ ta_status_t ta_axis_attn_forward(const ta_plan_t* plan, int axis,
  * O, which stays on chip.  Arguments as ta_axis_attn_forward; `o_mid` is NULL, or an O-shaped
  * tensor that receives the output of the first of the two hops as well (what a backward
  * pass needs); it must not overlap anything else.  Available when `axis + 1` is the
- * innermost axis, both axes have length 32, dtype is bf16 and head_dim 128 or 64; otherwise
+ * innermost axis, both axes have length 32, dtype is bf16 and head_dim a multiple of 4 up to 128;
+ * otherwise
  * TA_ERR_UNSUPPORTED (ta_plan_pair_kernel tells beforehand). */
 ta_status_t ta_axis_pair_attn_forward(const ta_plan_t* plan, int axis,
                                       const void* q, const void* k, const void* v_in, int vin,

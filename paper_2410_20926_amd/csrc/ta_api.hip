@@ -363,7 +363,7 @@ ta_status_t ta_axis_pair_attn_forward(const ta_plan_t* pl, int axis, const void*
     const ta::HopParams h1 = hop_params(pl, axis, q, k, v_in, vin, o_out);
     const ta::HopParams h2 = hop_params(pl, axis + 1, q, k, v_in, vin, o_out);
     if (!ta::mfma_pair_supports(h1, h2, d.dtype))
-        return fail(TA_ERR_UNSUPPORTED, "no fused kernel for axes %d and %d of this plan (needs bf16, head_dim 128 or 64 and the two innermost axes, both of length 32)", axis, axis + 1);
+        return fail(TA_ERR_UNSUPPORTED, "no fused kernel for axes %d and %d of this plan (needs bf16, head_dim a multiple of 4 up to 128 and the two innermost axes, both of length 32)", axis, axis + 1);
     hipError_t e = ta::launch_mfma_forward_pair(h1, h2, o_mid, (hipStream_t)stream);
     if (e != hipSuccess) return fail(TA_ERR_DEVICE, "fused forward launch failed: %s", hipGetErrorString(e));
     return TA_OK;

@@ -53,6 +53,7 @@ struct PairParams {
     uint32_t groups;                         // B * slabs * Hkv
     uint32_t q_row, k_row, v_row, o_row;     // token pitch of each tensor in bytes
     int64_t valid_len;                       // tokens at or past it (per batch element) are padding; N when there is none
+    uint32_t dbytes;                         // bytes of a row (2 * head width)
 };
 
 // Phase-A LDS layout.  Token (i, j)'s 64-byte chunk row of Q sits at i * kABlock + j * 64, that
@@ -60,6 +61,23 @@ struct PairParams {
 // unit u is at position (u + j / 2) mod 4.  Consecutive j (a row fibre) then alternate between
 // the halves of a 128-byte line and walk through the units; consecutive i (a column fibre) are
 // an odd number of units apart: both access patterns cover all banks.
+
+// Narrow heads (rows of `dbytes` < 2 kD bytes, 8-byte aligned): the 16-byte chunk at `addr`, which
+// starts `at` bytes into its row, as two 8-byte pieces, each only if it lies inside the row; what
+// lies outside reads as zero and is not written.
+template <bool NT>
+__device__ inline u32x4 narrow_load(const char* addr, uint32_t at, uint32_t dbytes) {
+    u32x2 lo = {0u, 0u}, hi = {0u, 0u};
+    const u32x2* a = reinterpret_cast<const u32x2*>(addr);
+    if (at + 8 <= dbytes) lo = NT ? __builtin_nontemporal_load(a) : *a;
+    if (at + 16 <= dbytes) hi = NT ? __builtin_nontemporal_load(a + 1) : a[1];
+    return u32x4{lo.x, lo.y, hi.x, hi.y};
+}
+__device__ inline void narrow_store(char* addr, uint32_t at, uint32_t dbytes, const u32x4 v) {
+    u32x2* a = reinterpret_cast<u32x2*>(addr);
+    if (at + 8 <= dbytes) __builtin_nontemporal_store(u32x2{v.x, v.y}, a);
+    if (at + 16 <= dbytes) __builtin_nontemporal_store(u32x2{v.z, v.w}, a + 1);
+}
 
 // Masked row softmax of one 32 x 32 score tile held as S^T (lane = query row, 16 keys per
 // lane, the other 16 in lane ^ 32).  Returns the rounded, un-normalised probabilities as
@@ -131,8 +149,10 @@ __device__ inline void update_fibre(char* lds, uint32_t fb, uint32_t rs, const u
 }
 
 // MID: the intermediate O (the first hop's output) is written out as well, for a backward pass.
-// kD: head width, 128 (two 128-byte lines per row, four score chunks, two value chunks) or 64.
-template <int kD, bool MID>
+// kD: tile width, 128 (two 128-byte lines per row, four score chunks, two value chunks) or 64.
+// NARROW: the head is narrower than the tile (p.dbytes bytes per row, a multiple of 8); the tile's
+// extra features are zero.
+template <int kD, bool MID, bool NARROW>
 __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int lane = threadIdx.x & 63;
@@ -166,8 +186,13 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
         for (int pp = 0; pp < kOwn * kN / kRowsPerPass; ++pp) {
             const uint32_t t = (uint32_t)(w * (kOwn * kN) + pp * kRowsPerPass + lane / kLanesPerRow);
             const uint32_t off = t * p.o_row + (uint32_t)((lane % kLanesPerRow) * 16);
-            __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, reinterpret_cast<u32x4*>(ob + off));
-            if (MID) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, reinterpret_cast<u32x4*>(mb + off));
+            if constexpr (NARROW) {
+                narrow_store(ob + off, (uint32_t)((lane % kLanesPerRow) * 16), p.dbytes, u32x4{0u, 0u, 0u, 0u});
+                if (MID) narrow_store(mb + off, (uint32_t)((lane % kLanesPerRow) * 16), p.dbytes, u32x4{0u, 0u, 0u, 0u});
+            } else {
+                __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, reinterpret_cast<u32x4*>(ob + off));
+                if (MID) __builtin_nontemporal_store(u32x4{0u, 0u, 0u, 0u}, reinterpret_cast<u32x4*>(mb + off));
+            }
         }
         return;
     }
@@ -187,14 +212,20 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
 #pragma unroll
         for (int pp = pp_begin; pp < pp_end; ++pp) {
             const char* row = qb + (size_t)(16u * pp) * p.q_row + line * 128;
-            lo[pp] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + qoff));
-            hi[pp] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + 64 + qoff));
+            if constexpr (NARROW) {
+                lo[pp] = narrow_load<true>(row + qoff, (uint32_t)(line * 128 + ua * 16), p.dbytes);
+                hi[pp] = narrow_load<true>(row + 64 + qoff, (uint32_t)(line * 128 + 64 + ua * 16), p.dbytes);
+            } else {
+                lo[pp] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + qoff));
+                hi[pp] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(row + 64 + qoff));
+            }
         }
     };
     auto load_k = [&](int c) {
 #pragma unroll
         for (int pp = 0; pp < 8; ++pp)
-            kreg[pp] = *reinterpret_cast<const u32x4*>(kb + (size_t)(16u * pp) * p.k_row + c * kARow + koff);
+            if constexpr (NARROW) kreg[pp] = narrow_load<false>(kb + (size_t)(16u * pp) * p.k_row + c * kARow + koff, (uint32_t)(c * kARow + ua * 16), p.dbytes);
+            else kreg[pp] = *reinterpret_cast<const u32x4*>(kb + (size_t)(16u * pp) * p.k_row + c * kARow + koff);
     };
     load_q(q0, q1, 0, 0, 8);
     load_k(0);
@@ -268,7 +299,12 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
         for (int pp = pp_begin; pp < pp_end; ++pp) {
             const uint32_t t = tok_b + 8u * pp;
             const u32x4* src = reinterpret_cast<const u32x4*>(xb + (t * p.v_row + (uint32_t)(c * (kCB * 2) + ub * 16)));
-            xreg[pp] = vin_is_o ? __builtin_nontemporal_load(src) : *src;   // a per-group V is read by every head of the group
+            if constexpr (NARROW) {
+                const uint32_t at = (uint32_t)(c * (kCB * 2) + ub * 16);
+                xreg[pp] = vin_is_o ? narrow_load<true>(reinterpret_cast<const char*>(src), at, p.dbytes) : narrow_load<false>(reinterpret_cast<const char*>(src), at, p.dbytes);
+            } else {
+                xreg[pp] = vin_is_o ? __builtin_nontemporal_load(src) : *src;   // a per-group V is read by every head of the group
+            }
         }
     };
     load_x(0, 0, 8);
@@ -320,7 +356,8 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
                 for (int pp = 0; pp < 4; ++pp) {
                     const uint32_t t = tok_b + (uint32_t)(f * kN + 8 * pp);
                     const u32x4 v = *reinterpret_cast<const u32x4*>(lds + fb + (t & 31) * kBPitch + ub * 16);
-                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(mb + (t * p.o_row + (uint32_t)(c * (kCB * 2) + ub * 16))));
+                    if constexpr (NARROW) narrow_store(mb + (t * p.o_row + (uint32_t)(c * (kCB * 2) + ub * 16)), (uint32_t)(c * (kCB * 2) + ub * 16), p.dbytes, v);
+                    else __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(mb + (t * p.o_row + (uint32_t)(c * (kCB * 2) + ub * 16))));
                 }
             }
             update_fibre(lds, fb, (uint32_t)kBPitch, p2[f], inv2[f], lane);
@@ -329,7 +366,8 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
             for (int pp = 0; pp < 4; ++pp) {
                 const uint32_t t = tok_b + (uint32_t)(f * kN + 8 * pp);       // token (i = 4 w + f, j = 8 pp + lane / 8)
                 const u32x4 v = *reinterpret_cast<const u32x4*>(lds + fb + (t & 31) * kBPitch + ub * 16);
-                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(ob + (t * p.o_row + (uint32_t)(c * (kCB * 2) + ub * 16))));
+                if constexpr (NARROW) narrow_store(ob + (t * p.o_row + (uint32_t)(c * (kCB * 2) + ub * 16)), (uint32_t)(c * (kCB * 2) + ub * 16), p.dbytes, v);
+                else __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(ob + (t * p.o_row + (uint32_t)(c * (kCB * 2) + ub * 16))));
             }
         }
         lds_wave_sync();                                  // the stores' LDS reads precede the next chunk's writes
@@ -337,7 +375,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
 }
 
 bool pair_params(const HopParams& h1, const HopParams& h2, PairParams* pp) {
-    if (h1.n != kN || h2.n != kN || (h1.D != 128 && h1.D != 64) || h2.stride != 1 || h1.stride != kN) return false;
+    if (h1.n != kN || h2.n != kN || h1.D < 8 || h1.D > 128 || h1.D % 4 != 0 || h2.stride != 1 || h1.stride != kN) return false;
     const int64_t N = h1.fibres * h1.n;
     if (!fits_u32(h1.q, kSlab) || !fits_u32(h1.k, kSlab) || !fits_u32(h1.vin, kSlab) || !fits_u32(h1.o, kSlab)) return false;
     if (N % kSlab != 0 || h1.G < 1 || h1.G > 64) return false;
@@ -350,6 +388,7 @@ bool pair_params(const HopParams& h1, const HopParams& h2, PairParams* pp) {
     pp->window1 = h1.window; pp->window2 = h2.window;
     pp->mask1 = h1.mask; pp->mask2 = h2.mask;
     pp->valid_len = h1.valid_len;
+    pp->dbytes = (uint32_t)h1.D * 2;
     pp->slabs = (uint32_t)slabs;
     pp->groups = (uint32_t)groups;
     pp->q_row = (uint32_t)(h1.q.st * 2); pp->k_row = (uint32_t)(h1.k.st * 2);
@@ -369,31 +408,27 @@ hipError_t launch_mfma_forward_pair(const HopParams& h1, const HopParams& h2, vo
     if (!pair_params(h1, h2, &pp)) return hipErrorInvalidValue;
     pp.mid = o_mid;
     // more than 64 KB of dynamic LDS has to be allowed once per device
-    static bool allowed[64] = {};
+    static bool allowed[64][8] = {};
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     if (dev < 0 || dev >= 64) return hipErrorInvalidValue;
-    if (!allowed[dev]) {
-        const void* kernels[4] = {reinterpret_cast<const void*>(mfma_fwd_pair_kernel<128, false>), reinterpret_cast<const void*>(mfma_fwd_pair_kernel<128, true>),
-                                  reinterpret_cast<const void*>(mfma_fwd_pair_kernel<64, false>), reinterpret_cast<const void*>(mfma_fwd_pair_kernel<64, true>)};
-        for (const void* kf : kernels) {
-            e = hipFuncSetAttribute(kf, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-            if (e != hipSuccess) return e;
-        }
-        allowed[dev] = true;
+    const bool wide = h1.D > 64, narrow = h1.D != 64 && h1.D != 128, mid = o_mid != nullptr;
+    const void* kf;
+    if (wide) kf = narrow ? (mid ? (const void*)mfma_fwd_pair_kernel<128, true, true> : (const void*)mfma_fwd_pair_kernel<128, false, true>)
+                          : (mid ? (const void*)mfma_fwd_pair_kernel<128, true, false> : (const void*)mfma_fwd_pair_kernel<128, false, false>);
+    else      kf = narrow ? (mid ? (const void*)mfma_fwd_pair_kernel<64, true, true> : (const void*)mfma_fwd_pair_kernel<64, false, true>)
+                          : (mid ? (const void*)mfma_fwd_pair_kernel<64, true, false> : (const void*)mfma_fwd_pair_kernel<64, false, false>);
+    const int which = (wide ? 4 : 0) + (narrow ? 2 : 0) + (mid ? 1 : 0);
+    if (!allowed[dev][which]) {                           // per device and instantiation
+        e = hipFuncSetAttribute(kf, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+        allowed[dev][which] = true;
     }
     const uint32_t span = 8u * (uint32_t)pp.G;
     const uint32_t grid = ((pp.groups + 7u) / 8u) * span;
-    const dim3 block(64 * kWaves);
-    if (h1.D == 128) {
-        if (o_mid) hipLaunchKernelGGL((mfma_fwd_pair_kernel<128, true>), dim3(grid), block, kLdsBytes, s, pp);
-        else       hipLaunchKernelGGL((mfma_fwd_pair_kernel<128, false>), dim3(grid), block, kLdsBytes, s, pp);
-    } else {
-        if (o_mid) hipLaunchKernelGGL((mfma_fwd_pair_kernel<64, true>), dim3(grid), block, kLdsBytes, s, pp);
-        else       hipLaunchKernelGGL((mfma_fwd_pair_kernel<64, false>), dim3(grid), block, kLdsBytes, s, pp);
-    }
-    return hipGetLastError();
+    void* args[1] = {&pp};
+    return hipLaunchKernel(kf, dim3(grid), dim3(64 * kWaves), args, kLdsBytes, s);
 }
 
 }  // namespace ta

@@ -204,7 +204,8 @@ def test_misaligned_axis_mask_is_rejected():
 def test_kernels_for_other_head_widths():
     p = ta.ta_plan_create(1, 32, 32, 100, (32, 32), ta.TA_BF16, True)      # OpenLLaMA-3B geometry: a multiple of 4
     assert p.hop_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_n32" and p.hop_kernel(1, ta.TA_VIN_O) == "mfma_bf16_n32"
-    assert p.fused_position() == -1 and p.hop_backward_kernel(1, ta.TA_VIN_O) == "mfma_bf16_bwd_n32"
+    assert p.fused_position() == 0 and p.pair_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_pair_n32"
+    assert p.hop_backward_kernel(1, ta.TA_VIN_O) == "mfma_bf16_bwd_n32"
     two_tiles = ta.ta_plan_create(1, 32, 32, 100, (64, 16), ta.TA_BF16, True)
     assert two_tiles.hop_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_n64" and two_tiles.hop_backward_kernel(0, ta.TA_VIN_KV) == "generic"
     long_axis = ta.ta_plan_create(1, 8, 2, 96, (128, 4), ta.TA_BF16, True)

@@ -167,9 +167,11 @@ def test_pair_with_padding(valid_len, causal):
     assert (to_host(mid)[:, valid_len:] == 0).all() and np.isfinite(to_host(mid)).all()
 
 
-@pytest.mark.parametrize("causal,valid_len", [(True, None), (False, None), (True, 1500)])
-def test_pair_at_head_width_64(causal, valid_len):
-    dims, B, Hq, Hkv, D = (2, 32, 32), 2, 8, 2, 64
+@pytest.mark.parametrize("causal,valid_len,Hq,Hkv,D", [(True, None, 8, 2, 64), (False, None, 8, 2, 64), (True, 1500, 8, 2, 64),
+                                                     (True, None, 4, 4, 100),      # OpenLLaMA-3B's head width, in 128-wide tiles
+                                                     (False, 1900, 8, 2, 96), (True, None, 4, 1, 40)])
+def test_pair_at_other_head_widths(causal, valid_len, Hq, Hkv, D):
+    dims, B = (2, 32, 32), 2
     N = int(np.prod(dims))
     q, k, v, d_o = make_inputs(B, N, Hq, Hkv, D, seed=8700, dtype="bf16", qk_scale=0.125, with_grad=True)
     kw = {} if valid_len is None else dict(valid_len=valid_len)
