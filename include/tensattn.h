@@ -97,8 +97,7 @@ typedef struct ta_plan ta_plan_t;     /* opaque, immutable, host-only, shareable
  * inconsistent, valid_len > N -> TA_ERR_SHAPE; bad dtype / hop_order / negative window or
  * valid_len, misaligned axis_mask -> TA_ERR_INVALID_ARG; a shape no
  * kernel covers (head_dim odd or above 256) -> TA_ERR_UNSUPPORTED.  The matrix-core kernels take
- * head_dim 64 and 128 everywhere and any other multiple of 4 up to 128 on axes of up to 64 positions
- * (backward: up to 32); the rest runs on the generic kernels. */
+ * head_dim 64 and 128 and any other multiple of 4 up to 128; the rest runs on the generic kernels. */
 ta_status_t ta_plan_create(const ta_desc_t* desc, ta_plan_t** out_plan);
 void        ta_plan_destroy(ta_plan_t* plan);                 /* NULL-safe */
 

@@ -448,7 +448,8 @@ __device__ inline uint32_t block_vis_rows(const HopParams& p, int kr, int a, int
     return v;
 }
 
-template <int D>
+// NARROW: the head is narrower than the D-wide tile; see load_chunk.
+template <int D, bool NARROW>
 __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, StreamBwdParams sp) {
     using G = BGeo<D>;
     const HopParams& p = bp.hop;
@@ -487,6 +488,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
 
     const int lrow = lane / G::kChunks, lcol = lane % G::kChunks;
     const uint32_t lbyte = lcol * 16;
+    const uint32_t dbytes = (uint32_t)p.D * 2;            // bytes of a row (less than the tile's when NARROW)
     const int r32 = lane & 31, hf = lane >> 5;
     char* stg = buf + lrow * G::kPitch + lbyte;
     const char* oprd = buf + r32 * G::kPitch + hf * 16;
@@ -499,7 +501,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
 #pragma unroll
         for (int i = 0; i < G::kPasses; ++i) {
             const uint32_t rr = (uint32_t)min(kTile * t + i * G::kRowsPerPass + lrow, n - 1);
-            raw[i] = *reinterpret_cast<const u32x4*>(base + ((tok0 + rr * stride) * pitch + lbyte));
+            raw[i] = load_chunk<NARROW, false>(base, (tok0 + rr * stride) * pitch, lbyte, dbytes);
         }
     };
     auto set_rowoff = [&](int t) {                        // byte offsets of the rows of tile t for the epilogue helpers
@@ -637,8 +639,8 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
         }
         set_rowoff(a);
         u32x4 oldq[G::kDTiles * 2] = {};
-        if (bp.accumulate) prefetch_tile<D>(oldq, rowoff, 0, dqb, lane);
-        store_tile<D>(acc, p.scale, buf, rowoff, 0, dqb, oldq, bp.accumulate != 0, min(kTile, n - kTile * a), lane);
+        if (bp.accumulate) prefetch_tile<D, NARROW>(oldq, rowoff, 0, dqb, lane, dbytes);
+        store_tile<D, NARROW>(acc, p.scale, buf, rowoff, 0, dqb, oldq, bp.accumulate != 0, min(kTile, n - kTile * a), lane, dbytes);
     }
     lds_wave_sync();
 
@@ -701,12 +703,12 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
         const int rows_c = min(kTile, n - kTile * c);
         u32x4 none[G::kDTiles * 2] = {};
         if (vin_is_o) {
-            store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, none, false, rows_c, lane);
+            store_tile<D, NARROW>(acc, 1.f, buf, rowoff, 2, dxb, none, false, rows_c, lane, dbytes);
         } else {
             u32x4 oldx[G::kDTiles * 2] = {};
-            if (bp.acc_x && w == nw - 1) prefetch_tile<D>(oldx, rowoff, 2, dxb, lane);
+            if (bp.acc_x && w == nw - 1) prefetch_tile<D, NARROW>(oldx, rowoff, 2, dxb, lane, dbytes);
             chain_sum<D>(acc, red, w, nw, lane);
-            if (w == nw - 1) store_tile<D>(acc, 1.f, buf, rowoff, 2, dxb, oldx, bp.acc_x != 0, rows_c, lane);
+            if (w == nw - 1) store_tile<D, NARROW>(acc, 1.f, buf, rowoff, 2, dxb, oldx, bp.acc_x != 0, rows_c, lane, dbytes);
         }
         // ---- dK_c^T = sum_a Q_a^T dS_ac ---------------------------------------------------------------
         u32x4 xop[G::kKSteps];
@@ -763,14 +765,14 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
         }
         lds_wave_sync();
         u32x4 oldk[G::kDTiles * 2] = {};
-        if (bp.acc_k && w == nw - 1) prefetch_tile<D>(oldk, rowoff, 1, dkb, lane);   // only the wave that ends up with the sum
+        if (bp.acc_k && w == nw - 1) prefetch_tile<D, NARROW>(oldk, rowoff, 1, dkb, lane, dbytes);   // only the wave that ends up with the sum
         chain_sum<D>(acc, red, w, nw, lane);
-        if (w == nw - 1) store_tile<D>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.acc_k != 0, rows_c, lane);
+        if (w == nw - 1) store_tile<D, NARROW>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.acc_k != 0, rows_c, lane, dbytes);
         lds_wave_sync();
     }
 }
 
-template <int D>
+template <int D, bool NARROW>
 hipError_t launch_stream(const BwdParams& bp, hipStream_t s) {
     const HopParams& p = bp.hop;
     StreamBwdParams sp;
@@ -790,13 +792,13 @@ hipError_t launch_stream(const BwdParams& bp, hipStream_t s) {
         if (e != hipSuccess) return e;
         if (dev < 0 || dev >= 64) return hipErrorInvalidValue;
         if (!allowed[dev]) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_bwd_stream_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize, kStreamMaxLds);
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_bwd_stream_kernel<D, NARROW>), hipFuncAttributeMaxDynamicSharedMemorySize, kStreamMaxLds);
             if (e != hipSuccess) return e;
             allowed[dev] = true;
         }
     }
     const dim3 grid((unsigned)p.Hkv, sp.fibres_lo, (unsigned)p.B * sp.fibres_hi);
-    hipLaunchKernelGGL((mfma_bwd_stream_kernel<D>), grid, dim3(64 * bp.wg_heads), smem, s, bp, sp);
+    hipLaunchKernelGGL((mfma_bwd_stream_kernel<D, NARROW>), grid, dim3(64 * bp.wg_heads), smem, s, bp, sp);
     return hipGetLastError();
 }
 
@@ -824,8 +826,8 @@ hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
 static int backward_variant(const BwdParams& bp, int dtype) {
     const HopParams& p = bp.hop;
     const bool full = p.D == 64 || p.D == 128;
-    // other widths that are multiples of 4 ride in the next wider tile: one-tile kernel, no table, groups of up to 8
-    const bool narrow = !full && p.D % 4 == 0 && p.D >= 8 && p.D < 128 && p.n <= kTile && !p.mask && p.G <= 8;
+    // other widths that are multiples of 4 ride in the next wider tile (the one-tile kernel: without a table, groups of up to 8)
+    const bool narrow = !full && p.D % 4 == 0 && p.D >= 8 && p.D < 128 && (p.n > kTile || (!p.mask && p.G <= 8));
     if (dtype != TA_BF16 || !(full || narrow) || p.n < 1 || p.n > kStreamMaxN) return 0;
     if (p.G != 1 && p.G != 2 && p.G != 4 && p.G % 8 != 0) return 0;   // groups of more than 8 heads run 8 heads per launch
     const int64_t N = p.fibres * p.n;
@@ -834,8 +836,8 @@ static int backward_variant(const BwdParams& bp, int dtype) {
     if (p.n <= kTile) return 1;
     // the blocked kernel keeps three floats per row and head in LDS
     const size_t tiles = (size_t)(p.n + kTile - 1) / kTile;
-    const size_t kbuf = p.D == 128 ? BGeo<128>::kBufBytes : BGeo<64>::kBufBytes;
-    const size_t red = p.G > 1 ? (p.D == 128 ? BGeo<128>::kRedBytes : BGeo<64>::kRedBytes) : 0;
+    const size_t kbuf = p.D > 64 ? BGeo<128>::kBufBytes : BGeo<64>::kBufBytes;
+    const size_t red = p.G > 1 ? (p.D > 64 ? BGeo<128>::kRedBytes : BGeo<64>::kRedBytes) : 0;
     const size_t wgh = p.G > 8 ? 8 : p.G;
     return red + wgh * (kbuf + kTile * 16 + 3 * kTile * tiles * 4) <= (size_t)kStreamMaxLds ? 2 : 0;
 }
@@ -861,7 +863,8 @@ hipError_t launch_mfma_backward(const BwdParams& user, hipStream_t s) {
         bp.acc_k = base == 0 ? user.accumulate : 1;
         bp.acc_x = base == 0 ? 0 : 1;
         hipError_t e;
-        if (variant == 2) e = bp.hop.D == 128 ? launch_stream<128>(bp, s) : launch_stream<64>(bp, s);
+        if (variant == 2) e = bp.hop.D == 128 ? launch_stream<128, false>(bp, s) : bp.hop.D == 64 ? launch_stream<64, false>(bp, s)
+                            : bp.hop.D > 64 ? launch_stream<128, true>(bp, s) : launch_stream<64, true>(bp, s);
         else if (bp.hop.D == 128) e = launch<128, false>(bp, tp, s);
         else if (bp.hop.D == 64)  e = launch<64, false>(bp, tp, s);
         else                      e = bp.hop.D > 64 ? launch<128, true>(bp, tp, s) : launch<64, true>(bp, tp, s);

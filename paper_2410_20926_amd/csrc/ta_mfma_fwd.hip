@@ -589,12 +589,12 @@ bool mfma_forward_layout_ok(const HopParams& p) {
 bool mfma_forward_supports(int32_t n, int32_t D, int dtype, int* kernel_id) {
     int kid = K_GENERIC;
     // head widths 64 and 128 fill a tile; any other multiple of 4 up to 128 rides in the next wider
-    // tile with its extra features zero (one- and two-tile kernels only)
+    // tile with its extra features zero
     const bool full = D == 64 || D == 128, narrow = !full && D % 4 == 0 && D >= 8 && D < 128;
     if (dtype == TA_BF16 && n >= 1 && (full || narrow)) {
         if (n <= 32) kid = K_MFMA_BF16_N32;
         else if (n <= 64) kid = K_MFMA_BF16_N64;
-        else if (full) kid = K_MFMA_BF16_STREAM;
+        else kid = K_MFMA_BF16_STREAM;
     }
     if (kernel_id) *kernel_id = kid;
     return kid != K_GENERIC;

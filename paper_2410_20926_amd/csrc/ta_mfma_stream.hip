@@ -28,7 +28,8 @@ struct StreamParams {
     uint32_t q_step, k_step, v_step, o_step;   // bytes between neighbouring rows of a fibre (stride * token pitch)
 };
 
-template <int D>
+// NARROW (all three kernels): the head is narrower than the D-wide tile; see load_chunk.
+template <int D, bool NARROW>
 __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel(HopParams p, StreamParams sp) {
     using G = Geo<D>;
     constexpr int kBuf = kTile * G::kPitch;
@@ -59,6 +60,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
 
     const int lrow = lane / G::kChunks, lcol = lane % G::kChunks;
     const uint32_t lbyte = lcol * 16;
+    const uint32_t dbytes = (uint32_t)p.D * 2;            // bytes of a row (less than the tile's when NARROW)
     const int r32 = lane & 31, hf = lane >> 5;
     const int ktiles = (n + kTile - 1) / kTile;
     // key tiles that any row of this query tile can see (causal triangle, band)
@@ -75,9 +77,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
     for (int i = 0; i < G::kPasses; ++i) {
         const uint32_t rq = (uint32_t)min(qt * kTile + i * G::kRowsPerPass + lrow, n - 1);
         const uint32_t rk = (uint32_t)min(jbeg * kTile + i * G::kRowsPerPass + lrow, n - 1);
-        qreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (rq * sp.q_step + lbyte)));   // read by this wave alone
-        kreg[i] = *reinterpret_cast<const u32x4*>(kb + (rk * sp.k_step + lbyte));
-        vreg[i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
+        qreg[i] = load_chunk<NARROW, true>(qb, rq * sp.q_step, lbyte, dbytes);   // read by this wave alone
+        kreg[i] = load_chunk<NARROW, false>(kb, rk * sp.k_step, lbyte, dbytes);
+        vreg[i] = load_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
         ooff[i] = rq * sp.o_step + lbyte;
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -118,7 +120,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
 #pragma unroll
             for (int i = 0; i < G::kPasses; ++i) {
                 const uint32_t rk = (uint32_t)min((j + 1) * kTile + i * G::kRowsPerPass + lrow, n - 1);
-                kreg[i] = *reinterpret_cast<const u32x4*>(kb + (rk * sp.k_step + lbyte));
+                kreg[i] = load_chunk<NARROW, false>(kb, rk * sp.k_step, lbyte, dbytes);
             }
         }
         f32x16 st = {};
@@ -167,7 +169,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
 #pragma unroll
             for (int i = 0; i < G::kPasses; ++i) {
                 const uint32_t rk = (uint32_t)min((j + 1) * kTile + i * G::kRowsPerPass + lrow, n - 1);
-                vreg[i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
+                vreg[i] = load_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
             }
         }
 #pragma unroll
@@ -196,7 +198,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
         const int row = qt * kTile + i * G::kRowsPerPass + lrow;
         if (row < n) {
             const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(ob + ooff[i]));
+            store_chunk<NARROW>(ob, ooff[i] - lbyte, lbyte, dbytes, v);
         }
     }
 }
@@ -207,7 +209,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
 // (and of every V tile when the value input is per key/value head, VS) into a workgroup-shared,
 // double-buffered LDS tile: K and V leave L2 once per workgroup instead of once per head, with
 // one barrier per key tile.
-template <int D, bool VS>
+template <int D, bool VS, bool NARROW>
 __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared_kernel(HopParams p, StreamParams sp) {
     using G = Geo<D>;
     constexpr int kBuf = kTile * G::kPitch;
@@ -241,6 +243,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
 
     const int lrow = lane / G::kChunks, lcol = lane % G::kChunks;
     const uint32_t lbyte = lcol * 16;
+    const uint32_t dbytes = (uint32_t)p.D * 2;            // bytes of a row (less than the tile's when NARROW)
     const int r32 = lane & 31, hf = lane >> 5;
     const int ktiles = (n + kTile - 1) / kTile;
     int jbeg = 0, jend = p.causal ? qt + 1 : ktiles;
@@ -264,8 +267,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
 #pragma unroll
                 for (int i = 0; i < kMine; ++i) {
                     const uint32_t rk = (uint32_t)min(j * kTile + (w * kMine + i) * G::kRowsPerPass + lrow, n - 1);
-                    kp[sidx][i] = *reinterpret_cast<const u32x4*>(kb + (rk * sp.k_step + lbyte));
-                    if (VS) vp[sidx][i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
+                    kp[sidx][i] = load_chunk<NARROW, false>(kb, rk * sp.k_step, lbyte, dbytes);
+                    if (VS) vp[sidx][i] = load_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
                 }
             }
     };
@@ -285,13 +288,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
 #pragma unroll
         for (int i = 0; i < (VS ? 0 : G::kPasses); ++i) {
             const uint32_t rk = (uint32_t)min(j * kTile + i * G::kRowsPerPass + lrow, n - 1);
-            vreg[i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
+            vreg[i] = load_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
         }
     };
 #pragma unroll
     for (int i = 0; i < G::kPasses; ++i) {
         const uint32_t rq = (uint32_t)min(qt * kTile + i * G::kRowsPerPass + lrow, n - 1);
-        qreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (rq * sp.q_step + lbyte)));
+        qreg[i] = load_chunk<NARROW, true>(qb, rq * sp.q_step, lbyte, dbytes);
         ooff[i] = rq * sp.o_step + lbyte;
     }
     load_shared(0, jbeg);
@@ -413,7 +416,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
         const int row = qt * kTile + i * G::kRowsPerPass + lrow;
         if (row < n) {
             const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
-            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(ob + ooff[i]));
+            store_chunk<NARROW>(ob, ooff[i] - lbyte, lbyte, dbytes, v);
         }
     }
 }
@@ -426,7 +429,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
 // the current one is being worked on, across query-tile boundaries, so that only the first
 // step of a workgroup waits for memory with nothing else to do.
 
-template <int D, bool VS>
+template <int D, bool VS, bool NARROW>
 __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunked_kernel(HopParams p, StreamParams sp) {
     using G = Geo<D>;
     constexpr int kBuf = kTile * G::kPitch;
@@ -463,6 +466,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunke
 
     const int lrow = lane / G::kChunks, lcol = lane % G::kChunks;
     const uint32_t lbyte = lcol * 16;
+    const uint32_t dbytes = (uint32_t)p.D * 2;            // bytes of a row (less than the tile's when NARROW)
     const int r32 = lane & 31, hf = lane >> 5;
     // key tiles [jb, je) that some row of query tile qt can see (causal triangle, band)
     auto key_tiles = [&](int qt, int& jb, int& je) {
@@ -492,8 +496,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunke
 #pragma unroll
         for (int i = 0; i < kMine; ++i) {
             const uint32_t rk = (uint32_t)min(j * kTile + (w * kMine + i) * G::kRowsPerPass + lrow, n - 1);
-            kp[set][i] = *reinterpret_cast<const u32x4*>(kb + (rk * sp.k_step + lbyte));
-            if (VS) vp[set][i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
+            kp[set][i] = load_chunk<NARROW, false>(kb, rk * sp.k_step, lbyte, dbytes);
+            if (VS) vp[set][i] = load_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
         }
     };
     auto write_shared = [&](auto set_tag, int slot) {
@@ -509,14 +513,14 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunke
 #pragma unroll
         for (int i = 0; i < (VS ? 0 : G::kPasses); ++i) {
             const uint32_t rk = (uint32_t)min(j * kTile + i * G::kRowsPerPass + lrow, n - 1);
-            vreg[i] = *reinterpret_cast<const u32x4*>(vb + (rk * sp.v_step + lbyte));
+            vreg[i] = load_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
         }
     };
     auto load_q = [&](int qt) {
 #pragma unroll
         for (int i = 0; i < G::kPasses; ++i) {
             const uint32_t rq = (uint32_t)min(qt * kTile + i * G::kRowsPerPass + lrow, n - 1);
-            qreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (rq * sp.q_step + lbyte)));
+            qreg[i] = load_chunk<NARROW, true>(qb, rq * sp.q_step, lbyte, dbytes);
         }
     };
     using S0 = std::integral_constant<int, 0>;
@@ -658,7 +662,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunke
                 const int row = qt * kTile + i * G::kRowsPerPass + lrow;
                 if (row < n) {
                     const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
-                    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(ob + ((uint32_t)row * sp.o_step + lbyte)));
+                    store_chunk<NARROW>(ob, (uint32_t)row * sp.o_step, lbyte, dbytes, v);
                 }
             }
         }
@@ -674,7 +678,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunke
     }
 }
 
-template <int D, bool VS>
+template <int D, bool VS, bool NARROW>
 hipError_t launch_shared(const HopParams& p, const StreamParams& sp, hipStream_t s) {
     const size_t smem = (size_t)((VS ? 4 : 2) + kWavesPerBlock) * kTile * Geo<D>::kPitch;
     const dim3 grid((unsigned)(p.Hq / kWavesPerBlock), sp.tiles_lo, (unsigned)p.B * sp.tiles_hi);
@@ -685,29 +689,29 @@ hipError_t launch_shared(const HopParams& p, const StreamParams& sp, hipStream_t
         if (e != hipSuccess) return e;
         if (dev < 0 || dev >= 64) return hipErrorInvalidValue;
         if (!allowed[dev]) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_fwd_stream_shared_kernel<D, VS>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-            if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_fwd_stream_chunked_kernel<D, VS>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_fwd_stream_shared_kernel<D, VS, NARROW>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_fwd_stream_chunked_kernel<D, VS, NARROW>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
             if (e != hipSuccess) return e;
             allowed[dev] = true;
         }
     }
-    if (sp.qchunk > 1) hipLaunchKernelGGL((mfma_fwd_stream_chunked_kernel<D, VS>), grid, dim3(kWavesPerBlock * 64), smem, s, p, sp);
-    else               hipLaunchKernelGGL((mfma_fwd_stream_shared_kernel<D, VS>), grid, dim3(kWavesPerBlock * 64), smem, s, p, sp);
+    if (sp.qchunk > 1) hipLaunchKernelGGL((mfma_fwd_stream_chunked_kernel<D, VS, NARROW>), grid, dim3(kWavesPerBlock * 64), smem, s, p, sp);
+    else               hipLaunchKernelGGL((mfma_fwd_stream_shared_kernel<D, VS, NARROW>), grid, dim3(kWavesPerBlock * 64), smem, s, p, sp);
     return hipGetLastError();
 }
 
-template <int D>
+template <int D, bool NARROW>
 hipError_t launch(const HopParams& p, const StreamParams& sp, hipStream_t s) {
     const size_t smem = (size_t)kWavesPerBlock * kTile * Geo<D>::kPitch;
     const dim3 grid((unsigned)((p.Hq + kWavesPerBlock - 1) / kWavesPerBlock), sp.tiles_lo, (unsigned)p.B * sp.tiles_hi);
-    hipLaunchKernelGGL((mfma_fwd_stream_kernel<D>), grid, dim3(kWavesPerBlock * 64), smem, s, p, sp);
+    hipLaunchKernelGGL((mfma_fwd_stream_kernel<D, NARROW>), grid, dim3(kWavesPerBlock * 64), smem, s, p, sp);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_mfma_forward_stream(const HopParams& p, hipStream_t s) {
-    if (p.n < 1 || (p.D != 64 && p.D != 128) || !mfma_forward_layout_ok(p)) return hipErrorInvalidValue;
+    if (p.n < 1 || p.D < 8 || p.D > 128 || p.D % 4 != 0 || !mfma_forward_layout_ok(p)) return hipErrorInvalidValue;
     StreamParams sp;
     const bool shared = p.G % kWavesPerBlock == 0;        // the 4 waves of a workgroup are 4 heads of one group
     sp.qtiles = (uint32_t)((p.n + kTile - 1) / kTile);
@@ -727,12 +731,11 @@ hipError_t launch_mfma_forward_stream(const HopParams& p, hipStream_t s) {
     sp.k_step = (uint32_t)(p.stride * p.k.st * 2);
     sp.v_step = (uint32_t)(p.stride * p.vin.st * 2);
     sp.o_step = (uint32_t)(p.stride * p.o.st * 2);
-    if (shared) {
-        const bool vs = p.vin_heads != p.Hq;
-        if (p.D == 128) return vs ? launch_shared<128, true>(p, sp, s) : launch_shared<128, false>(p, sp, s);
-        return vs ? launch_shared<64, true>(p, sp, s) : launch_shared<64, false>(p, sp, s);
-    }
-    return p.D == 128 ? launch<128>(p, sp, s) : launch<64>(p, sp, s);
+    const bool vs = p.vin_heads != p.Hq;
+    if (p.D == 128) return shared ? (vs ? launch_shared<128, true, false>(p, sp, s) : launch_shared<128, false, false>(p, sp, s)) : launch<128, false>(p, sp, s);
+    if (p.D == 64) return shared ? (vs ? launch_shared<64, true, false>(p, sp, s) : launch_shared<64, false, false>(p, sp, s)) : launch<64, false>(p, sp, s);
+    if (p.D > 64) return shared ? (vs ? launch_shared<128, true, true>(p, sp, s) : launch_shared<128, false, true>(p, sp, s)) : launch<128, true>(p, sp, s);
+    return shared ? (vs ? launch_shared<64, true, true>(p, sp, s) : launch_shared<64, false, true>(p, sp, s)) : launch<64, true>(p, sp, s);
 }
 
 }  // namespace ta

@@ -207,8 +207,9 @@ def test_kernels_for_other_head_widths():
     assert p.fused_position() == 0 and p.pair_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_pair_n32"
     assert p.hop_backward_kernel(1, ta.TA_VIN_O) == "mfma_bf16_bwd_n32"
     two_tiles = ta.ta_plan_create(1, 32, 32, 100, (64, 16), ta.TA_BF16, True)
-    assert two_tiles.hop_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_n64" and two_tiles.hop_backward_kernel(0, ta.TA_VIN_KV) == "generic"
+    assert two_tiles.hop_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_n64"
+    assert two_tiles.hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_blocked"
     long_axis = ta.ta_plan_create(1, 8, 2, 96, (128, 4), ta.TA_BF16, True)
-    assert long_axis.hop_kernel(0, ta.TA_VIN_KV) == "generic"             # the streaming kernels take full tiles only
+    assert long_axis.hop_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_stream_shared_kv"
     odd = ta.ta_plan_create(1, 4, 4, 90, (16, 16), ta.TA_BF16, True)       # even, not a multiple of 4
     assert odd.hop_kernel(0, ta.TA_VIN_KV) == "generic"

@@ -63,7 +63,8 @@ CASES = [
     ((6, 9), 1, 4, 4, 100, True, "bf16"),            # head width 100: 8-byte-granular rows in 128-wide tiles
     ((32, 4, 8), 2, 8, 2, 96, True, "bf16"),         # width 96, groups of 4 heads, three hops (dQ, dK accumulate)
     ((16, 32), 1, 2, 2, 40, False, "bf16"),          # width 40 in 64-wide tiles
-    ((40, 3), 1, 2, 2, 100, True, "bf16"),           # width 100 on an axis of two tiles: MFMA forward, generic backward
+    ((40, 3), 1, 2, 2, 100, True, "bf16"),           # width 100 on an axis of two tiles: the blocked kernel
+    ((3, 90), 1, 4, 1, 96, False, "bf16"),           # width 96, three tiles, a group of 4 heads
     ((32, 8), 2, 16, 2, 128, False, "bf16"),         # 8 heads per group, full-width heads
 ]
 

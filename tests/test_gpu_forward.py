@@ -65,6 +65,9 @@ CASES = [
     ((48, 5), 1, 4, 1, 96, False, "bf16", 1.0),        # two-tile kernels, width 96
     ((7, 64), 1, 3, 3, 40, True, "bf16", 1.0),         # width 40 in 64-wide tiles
     ((10, 6), 1, 2, 2, 90, True, "bf16", 1.0),         # even but not a multiple of 4: generic kernels
+    ((130, 2), 1, 3, 3, 100, True, "bf16", 1.0),       # width 100 on the streaming kernels: per head,
+    ((100, 4), 2, 8, 2, 96, True, "bf16", 1.0),        # group-shared with all query tiles in one workgroup,
+    ((2, 300), 1, 4, 1, 40, False, "bf16", 1.0),       # and group-shared with one workgroup per query tile
     ((5, 12), 2, 2, 1, 36, False, "f32", 1.0),
 ]
 
