@@ -829,7 +829,7 @@ static int backward_variant(const BwdParams& bp, int dtype) {
     // other widths that are multiples of 4 ride in the next wider tile (the one-tile kernel: without a table, groups of up to 8)
     const bool narrow = !full && p.D % 4 == 0 && p.D >= 8 && p.D < 128 && (p.n > kTile || (!p.mask && p.G <= 8));
     if (dtype != TA_BF16 || !(full || narrow) || p.n < 1 || p.n > kStreamMaxN) return 0;
-    if (p.G != 1 && p.G != 2 && p.G != 4 && p.G % 8 != 0) return 0;   // groups of more than 8 heads run 8 heads per launch
+    if (p.G < 1 || p.G > 256) return 0;                              // groups of more than 8 heads run 8 heads per launch
     const int64_t N = p.fibres * p.n;
     if (!(N < ((int64_t)1 << 31) && p.B <= 65535 && fits_u32(p.q, N) && fits_u32(p.k, N) && fits_u32(p.vin, N) &&
           fits_u32(bp.d_o, N) && fits_u32(bp.d_vin, N) && fits_u32(bp.dq, N) && fits_u32(bp.dk, N))) return 0;
@@ -857,8 +857,8 @@ hipError_t launch_mfma_backward(const BwdParams& user, hipStream_t s) {
     // dV), in a fixed order, so the result stays deterministic.
     BwdParams bp = user;
     const int G = user.hop.G;
-    bp.wg_heads = G > 8 ? 8 : G;
-    for (int base = 0; base < G; base += bp.wg_heads) {
+    for (int base = 0; base < G; base += 8) {
+        bp.wg_heads = G - base > 8 ? 8 : G - base;
         bp.head_base = base;
         bp.acc_k = base == 0 ? user.accumulate : 1;
         bp.acc_x = base == 0 ? 0 : 1;

@@ -59,7 +59,9 @@ CASES = [
     ((4, 16), 1, 16, 1, 128, True, "bf16"),          # 16 heads per group: two launches of 8 heads, the second adds to dK, dV
     ((8, 32), 2, 32, 1, 64, True, "bf16"),           # multi-query: 32 heads on one key/value head, four launches
     ((64, 4), 1, 16, 1, 128, False, "bf16"),         # the blocked kernel with 16 heads per group
-    ((6, 5), 1, 12, 1, 64, True, "bf16"),            # 12 heads per group: no MFMA variant, generic kernel
+    ((6, 5), 1, 12, 1, 64, True, "bf16"),            # 12 heads per group: a launch of 8 and one of 4
+    ((8, 16), 1, 7, 1, 128, True, "bf16"),           # 7 heads per group (28 query / 4 key-value heads is a real geometry)
+    ((5, 40), 2, 6, 2, 128, False, "bf16"),          # 3 heads per group, blocked kernel on the second axis
     ((6, 9), 1, 4, 4, 100, True, "bf16"),            # head width 100: 8-byte-granular rows in 128-wide tiles
     ((32, 4, 8), 2, 8, 2, 96, True, "bf16"),         # width 96, groups of 4 heads, three hops (dQ, dK accumulate)
     ((16, 32), 1, 2, 2, 40, False, "bf16"),          # width 40 in 64-wide tiles
