@@ -40,6 +40,7 @@ PAIR_CASES = [
     ((2, 32, 32), 1, 3, 3, False, "o"),          # 6 workgroup groups: the last block of 8 is partly empty
     ((5, 32, 32), 1, 16, 2, True, "o"),          # 8 heads per key/value head
     ((2, 2, 32, 32), 1, 4, 2, True, "o"),
+    ((3, 32, 32), 1, 14, 2, True, "o"),          # 7 heads per key/value head
 ]
 
 
