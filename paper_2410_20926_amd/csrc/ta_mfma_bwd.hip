@@ -808,14 +808,12 @@ hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
     const size_t smem = (size_t)(bp.wg_heads > 1 ? BGeo<D>::kRedBytes : 0) + (size_t)bp.wg_heads * BGeo<D>::kWaveBytes;
     const dim3 grid((unsigned)p.Hkv, tp.tiles_lo, (unsigned)p.B * tp.tiles_hi);
     const dim3 block(64 * bp.wg_heads);
-    if (NARROW) {                                         // narrow heads: the plain instantiation only (no table, groups of up to 8)
-        hipLaunchKernelGGL((mfma_bwd_kernel<D, false, false, true>), grid, block, smem, s, bp, tp);
-    } else if (p.G > bp.wg_heads) {
-        if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true, true, false>), grid, block, smem, s, bp, tp);
-        else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false, true, false>), grid, block, smem, s, bp, tp);
+    if (p.G > bp.wg_heads) {
+        if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true, true, NARROW>), grid, block, smem, s, bp, tp);
+        else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false, true, NARROW>), grid, block, smem, s, bp, tp);
     } else {
-        if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true, false, false>), grid, block, smem, s, bp, tp);
-        else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false, false, false>), grid, block, smem, s, bp, tp);
+        if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true, false, NARROW>), grid, block, smem, s, bp, tp);
+        else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false, false, NARROW>), grid, block, smem, s, bp, tp);
     }
     return hipGetLastError();
 }
@@ -826,8 +824,8 @@ hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
 static int backward_variant(const BwdParams& bp, int dtype) {
     const HopParams& p = bp.hop;
     const bool full = p.D == 64 || p.D == 128;
-    // other widths that are multiples of 4 ride in the next wider tile (the one-tile kernel: without a table, groups of up to 8)
-    const bool narrow = !full && p.D % 4 == 0 && p.D >= 8 && p.D < 128 && (p.n > kTile || (!p.mask && p.G <= 8));
+    // other widths that are multiples of 4 ride in the next wider tile
+    const bool narrow = !full && p.D % 4 == 0 && p.D >= 8 && p.D < 128;
     if (dtype != TA_BF16 || !(full || narrow) || p.n < 1 || p.n > kStreamMaxN) return 0;
     if (p.G < 1 || p.G > 256) return 0;                              // groups of more than 8 heads run 8 heads per launch
     const int64_t N = p.fibres * p.n;

@@ -85,6 +85,7 @@ TABLE_CASES = [
     ((128, 3), 1, 4, 1, 128, True, "bf16", (0,), None, 300),              # streaming kernel, chunked over the query tiles
     ((2, 100), 1, 8, 2, 128, False, "bf16", (1,), (0, 70), None),
     ((2, 32, 32), 1, 4, 1, 128, True, "bf16", (1, 2), (0, 12, 0), 1900),  # the fused pair with tables on both of its axes
+    ((4, 32, 8), 1, 24, 2, 100, True, "bf16", (0, 1, 2), None, None),     # head width 100, 12 heads per group, tables everywhere
 ]
 
 
