@@ -20,8 +20,11 @@
  *    the slowest (Sec. 4.3: with {32,32,32} one more step on the first axis is 1,024
  *    more tokens).  Axes are numbered from 0 here.
  *  - Grouped-query heads: query head h uses key/value head h / (n_q_heads / n_kv_heads).
- *  - Every call returns a ta_status_t; nothing aborts, throws or prints.  On error
- *    nothing has been enqueued.  ta_last_error_detail() gives a thread-local message.
+ *  - Every call returns a ta_status_t; nothing aborts, throws or prints.  Every check of a
+ *    call (arguments, aliasing, kernel availability and launch geometry of EVERY hop it runs)
+ *    happens before its first launch: on any status but TA_ERR_DEVICE nothing has been
+ *    enqueued.  TA_ERR_DEVICE means HIP itself refused a launch; hops before it may have
+ *    been enqueued.  ta_last_error_detail() gives a thread-local message.
  *    Kernel faults that happen asynchronously surface at the caller's next
  *    synchronisation, as with any HIP launch.
  */
@@ -45,7 +48,8 @@ typedef enum {
     TA_ERR_UNSUPPORTED = 4,   /* valid request this build has no kernel for */
     TA_ERR_ALIAS = 5,         /* an output overlaps an input */
     TA_ERR_WORKSPACE = 6,     /* workspace too small */
-    TA_ERR_DEVICE = 7         /* HIP reported a launch error */
+    TA_ERR_DEVICE = 7,        /* HIP reported a launch error */
+    TA_ERR_NOMEM = 8          /* host memory for a plan could not be allocated */
 } ta_status_t;
 
 typedef enum { TA_F32 = 0, TA_BF16 = 1 } ta_dtype_t;

@@ -6,6 +6,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 
 #include "ta_internal.h"
@@ -23,10 +24,16 @@ struct ta_plan {
     int64_t qs[3], kvs[3], os[3];    // resolved element strides (batch, token, head)
     int64_t o_span;              // elements from the first to one past the last element of an O tensor
     size_t o_buf_bytes;          // bytes of one inter-hop O buffer, rounded up to 256
-    int kernel_id[TA_MAX_ORDER][2];  // forward kernel per (axis, vin)
+    // decisions per (axis, value-input kind), made once in ta_plan_create so that no call
+    // can fail on geometry after an earlier hop has been enqueued
+    int kernel_id[TA_MAX_ORDER][2];  // forward kernel (ta::KernelId), or ta::K_NONE when no kernel's grid fits
+    int bwd_id[TA_MAX_ORDER][2];     // backward variant (BwdId)
+    bool pair[TA_MAX_ORDER][2];      // the fused pair (axis, axis + 1) is available
 };
 
 namespace {
+
+enum BwdId : int { BWD_NONE = 0, BWD_MFMA_N32 = 1, BWD_MFMA_BLOCKED = 2, BWD_GENERIC = 3 };
 
 thread_local char g_detail[256] = "";
 
@@ -103,6 +110,83 @@ ta::HopParams hop_params(const ta_plan* pl, int axis, const void* q, const void*
     return hp;
 }
 
+ta::BwdParams bwd_params(const ta_plan* pl, int axis, const void* q, const void* k, const void* vin, int vin_kind,
+                         const void* d_o, void* d_vin, void* dq, void* dk, int accumulate) {
+    ta::BwdParams bp;
+    bp.hop = hop_params(pl, axis, q, k, vin, vin_kind, nullptr);
+    bp.d_o = make_tensor(d_o, pl->os);
+    bp.d_vin = make_tensor(d_vin, vin_kind == TA_VIN_KV ? pl->kvs : pl->os);
+    bp.dq = make_tensor(dq, pl->qs);
+    bp.dk = make_tensor(dk, pl->kvs);
+    bp.accumulate = accumulate;
+    bp.wg_heads = 0; bp.head_base = 0; bp.acc_k = 0; bp.acc_x = 0;
+    return bp;
+}
+
+// Byte ranges of the plan's tensor kinds.
+Range q_span(const ta_plan* pl, const void* p) {
+    return span_of(p, pl->qs, pl->desc.batch, pl->N, pl->desc.n_q_heads, pl->desc.head_dim, pl->elem);
+}
+Range kv_span(const ta_plan* pl, const void* p) {
+    return span_of(p, pl->kvs, pl->desc.batch, pl->N, pl->desc.n_kv_heads, pl->desc.head_dim, pl->elem);
+}
+Range o_span(const ta_plan* pl, const void* p) {
+    return span_of(p, pl->os, pl->desc.batch, pl->N, pl->desc.n_q_heads, pl->desc.head_dim, pl->elem);
+}
+Range vin_span(const ta_plan* pl, const void* p, int vin) { return vin == TA_VIN_KV ? kv_span(pl, p) : o_span(pl, p); }
+
+const char* forward_kernel_name(const ta_plan* pl, int axis, int vin) {
+    switch (pl->kernel_id[axis][vin]) {
+        case ta::K_NONE: return "unsupported";
+        case ta::K_GENERIC: return "generic";
+        // with 4 (or a multiple of 4) query heads per key/value head the group-shared variant runs;
+        // its instantiation that also shares the value tile (value input per key/value head) is "_kv"
+        case ta::K_MFMA_BF16_N32: return pl->G % 4 != 0 ? "mfma_bf16_n32" : vin == TA_VIN_KV ? "mfma_bf16_n32_shared_kv" : "mfma_bf16_n32_shared";
+        case ta::K_MFMA_BF16_N64: return pl->G % 4 != 0 ? "mfma_bf16_n64" : vin == TA_VIN_KV ? "mfma_bf16_n64_shared_kv" : "mfma_bf16_n64_shared";
+        case ta::K_MFMA_BF16_STREAM: return pl->G % 4 != 0 ? "mfma_bf16_stream" : vin == TA_VIN_KV ? "mfma_bf16_stream_shared_kv" : "mfma_bf16_stream_shared";
+    }
+    return nullptr;
+}
+
+// The enqueue steps proper.  Arguments have been validated by the caller; the only failure left
+// is HIP refusing the launch.
+ta_status_t enqueue_forward(const ta_plan* pl, int axis, const void* q, const void* k, const void* v_in, int vin,
+                            void* o_out, hipStream_t stream) {
+    const ta::HopParams hp = hop_params(pl, axis, q, k, v_in, vin, o_out);
+    const int kid = pl->kernel_id[axis][vin];
+    const hipError_t e = kid == ta::K_GENERIC ? ta::launch_generic_forward(hp, pl->desc.dtype, stream)
+                                              : ta::launch_mfma_forward(hp, kid, stream);
+    if (e != hipSuccess) return fail(TA_ERR_DEVICE, "forward launch failed (axis %d): %s", axis, hipGetErrorString(e));
+    return TA_OK;
+}
+
+ta_status_t enqueue_pair(const ta_plan* pl, int axis, const void* q, const void* k, const void* v_in, int vin,
+                         void* o_mid, void* o_out, hipStream_t stream) {
+    const ta::HopParams h1 = hop_params(pl, axis, q, k, v_in, vin, o_out);
+    const ta::HopParams h2 = hop_params(pl, axis + 1, q, k, v_in, vin, o_out);
+    const hipError_t e = ta::launch_mfma_forward_pair(h1, h2, o_mid, stream);
+    if (e != hipSuccess) return fail(TA_ERR_DEVICE, "fused forward launch failed (axes %d, %d): %s", axis, axis + 1, hipGetErrorString(e));
+    return TA_OK;
+}
+
+ta_status_t enqueue_backward(const ta_plan* pl, int axis, const void* q, const void* k, const void* v_in, int vin,
+                             const void* d_o, void* d_v_in, void* dq, void* dk, int accumulate, hipStream_t stream) {
+    const ta::BwdParams bp = bwd_params(pl, axis, q, k, v_in, vin, d_o, d_v_in, dq, dk, accumulate);
+    const int id = pl->bwd_id[axis][vin];
+    const hipError_t e = id == BWD_GENERIC ? ta::launch_generic_backward(bp, pl->desc.dtype, stream)
+                                           : ta::launch_mfma_backward(bp, stream);
+    if (e != hipSuccess) return fail(TA_ERR_DEVICE, "backward launch failed (axis %d): %s", axis, hipGetErrorString(e));
+    return TA_OK;
+}
+
+ta_status_t unsupported_forward(const ta_plan* pl, int axis) {
+    return fail(TA_ERR_UNSUPPORTED, "forward: no kernel's launch grid fits axis %d (length %d) of this plan", axis, pl->dims[axis]);
+}
+ta_status_t unsupported_backward(const ta_plan* pl, int axis) {
+    return fail(TA_ERR_UNSUPPORTED, "backward: axis %d of length %d with %d heads per group exceeds every kernel's limit",
+                axis, pl->dims[axis], pl->G);
+}
+
 ta_status_t check_axis_vin(const ta_plan* pl, int axis, int vin) {
     if (!pl) return fail(TA_ERR_NULL, "plan is NULL");
     if (axis < 0 || axis >= pl->order) return fail(TA_ERR_INVALID_ARG, "axis %d out of range [0, %d)", axis, pl->order);
@@ -124,6 +208,7 @@ const char* ta_status_string(ta_status_t st) {
         case TA_ERR_ALIAS: return "TA_ERR_ALIAS";
         case TA_ERR_WORKSPACE: return "TA_ERR_WORKSPACE";
         case TA_ERR_DEVICE: return "TA_ERR_DEVICE";
+        case TA_ERR_NOMEM: return "TA_ERR_NOMEM";
     }
     return "TA_ERR_?";
 }
@@ -132,7 +217,7 @@ const char* ta_last_error_detail(void) { return g_detail; }
 
 void ta_version(int* major, int* minor) {
     if (major) *major = 0;
-    if (minor) *minor = 4;
+    if (minor) *minor = 5;
 }
 
 ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
@@ -150,10 +235,9 @@ ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
     int64_t N = 1;
     for (int i = 0; i < d->order; ++i) {
         if (d->dims[i] < 1) return fail(TA_ERR_SHAPE, "dims[%d] = %d < 1", i, d->dims[i]);
-        if (N > (int64_t)1 << 40) return fail(TA_ERR_SHAPE, "sequence length overflows");
+        if ((int64_t)d->dims[i] > ((int64_t)1 << 40) / N) return fail(TA_ERR_SHAPE, "sequence length exceeds 2^40 tokens");
         N *= d->dims[i];
     }
-    if (N > (int64_t)1 << 40) return fail(TA_ERR_SHAPE, "sequence length overflows");
     for (int i = 0; i < d->order; ++i)
         if (d->window[i] < 0) return fail(TA_ERR_INVALID_ARG, "window[%d] = %d is negative", i, d->window[i]);
     for (int i = 0; i < d->order; ++i)
@@ -164,7 +248,7 @@ ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
         return fail(TA_ERR_UNSUPPORTED, "head_dim %d: need an even width, at most 256", d->head_dim);
 
     ta_plan* pl = new (std::nothrow) ta_plan;
-    if (!pl) return fail(TA_ERR_INVALID_ARG, "out of host memory");
+    if (!pl) return fail(TA_ERR_NOMEM, "out of host memory");
     memset(pl, 0, sizeof(*pl));
     pl->desc = *d;
     pl->order = d->order;
@@ -206,13 +290,25 @@ ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
     pl->o_span = (d->batch - 1) * pl->os[0] + (N - 1) * pl->os[1] + (d->n_q_heads - 1) * pl->os[2] + D;
     pl->o_buf_bytes = (((size_t)pl->o_span * pl->elem) + 255) & ~(size_t)255;
 
+    // every per-hop decision is taken here, against the launchers' own feasibility predicates
     for (int i = 0; i < d->order; ++i)
         for (int vin = 0; vin < 2; ++vin) {
+            const ta::HopParams hp = hop_params(pl, i, nullptr, nullptr, nullptr, vin, nullptr);
             int kid = ta::K_GENERIC;
             ta::mfma_forward_supports(pl->dims[i], d->head_dim, d->dtype, &kid);
-            if (kid != ta::K_GENERIC && !ta::mfma_forward_layout_ok(hop_params(pl, i, nullptr, nullptr, nullptr, vin, nullptr)))
-                kid = ta::K_GENERIC;
+            if (kid != ta::K_GENERIC && !ta::mfma_forward_feasible(hp, kid)) kid = ta::K_GENERIC;
+            if (kid == ta::K_GENERIC && !ta::generic_forward_supports(hp)) kid = ta::K_NONE;
             pl->kernel_id[i][vin] = kid;
+            const ta::BwdParams bp = bwd_params(pl, i, nullptr, nullptr, nullptr, vin, nullptr, nullptr, nullptr, nullptr, 0);
+            if (ta::mfma_backward_supports(bp, d->dtype))
+                pl->bwd_id[i][vin] = ta::mfma_backward_is_blocked(bp, d->dtype) ? BWD_MFMA_BLOCKED : BWD_MFMA_N32;
+            else
+                pl->bwd_id[i][vin] = ta::generic_backward_supports(hp) ? BWD_GENERIC : BWD_NONE;
+            pl->pair[i][vin] = false;
+            if (i + 1 < d->order) {
+                const ta::HopParams h2 = hop_params(pl, i + 1, nullptr, nullptr, nullptr, vin, nullptr);
+                pl->pair[i][vin] = ta::mfma_pair_supports(hp, h2, d->dtype);
+            }
         }
     *out = pl;
     return TA_OK;
@@ -232,37 +328,21 @@ int ta_plan_hop_axis(const ta_plan_t* pl, int pos) {
 }
 const char* ta_plan_hop_kernel(const ta_plan_t* pl, int axis, int vin) {
     if (!pl || axis < 0 || axis >= pl->order || (vin != 0 && vin != 1)) return nullptr;
-    switch (pl->kernel_id[axis][vin]) {
-        case ta::K_GENERIC: return "generic";
-        case ta::K_MFMA_BF16_N16: return "mfma_bf16_n16";
-        // with 4 (or a multiple of 4) query heads per key/value head the group-shared variant runs;
-        // its instantiation that also shares the value tile (value input per key/value head) is "_kv"
-        case ta::K_MFMA_BF16_N32: return pl->G % 4 != 0 ? "mfma_bf16_n32" : vin == TA_VIN_KV ? "mfma_bf16_n32_shared_kv" : "mfma_bf16_n32_shared";
-        case ta::K_MFMA_BF16_N64: return pl->G % 4 != 0 ? "mfma_bf16_n64" : vin == TA_VIN_KV ? "mfma_bf16_n64_shared_kv" : "mfma_bf16_n64_shared";
-        case ta::K_MFMA_BF16_STREAM: return pl->G % 4 != 0 ? "mfma_bf16_stream" : vin == TA_VIN_KV ? "mfma_bf16_stream_shared_kv" : "mfma_bf16_stream_shared";
-    }
-    return nullptr;
+    return forward_kernel_name(pl, axis, vin);
 }
 
 const char* ta_plan_hop_backward_kernel(const ta_plan_t* pl, int axis, int vin) {
     if (!pl || axis < 0 || axis >= pl->order || (vin != 0 && vin != 1)) return nullptr;
-    ta::BwdParams bp;
-    bp.hop = hop_params(pl, axis, nullptr, nullptr, nullptr, vin, nullptr);
-    bp.d_o = make_tensor(nullptr, pl->os);
-    bp.d_vin = make_tensor(nullptr, vin == TA_VIN_KV ? pl->kvs : pl->os);
-    bp.dq = make_tensor(nullptr, pl->qs);
-    bp.dk = make_tensor(nullptr, pl->kvs);
-    bp.accumulate = 0;
-    if (ta::mfma_backward_supports(bp, pl->desc.dtype))
-        return ta::mfma_backward_is_blocked(bp, pl->desc.dtype) ? "mfma_bf16_bwd_blocked" : "mfma_bf16_bwd_n32";
-    return ta::generic_backward_supports(pl->dims[axis], pl->G, pl->desc.head_dim) ? "generic" : "unsupported";
+    switch (pl->bwd_id[axis][vin]) {
+        case BWD_MFMA_N32: return "mfma_bf16_bwd_n32";
+        case BWD_MFMA_BLOCKED: return "mfma_bf16_bwd_blocked";
+        case BWD_GENERIC: return "generic";
+    }
+    return "unsupported";
 }
 
 static bool pair_ok(const ta_plan* pl, int axis, int vin) {
-    if (axis < 0 || axis + 1 >= pl->order) return false;
-    const ta::HopParams h1 = hop_params(pl, axis, nullptr, nullptr, nullptr, vin, nullptr);
-    const ta::HopParams h2 = hop_params(pl, axis + 1, nullptr, nullptr, nullptr, vin, nullptr);
-    return ta::mfma_pair_supports(h1, h2, pl->desc.dtype);
+    return axis >= 0 && axis + 1 < pl->order && pl->pair[axis][vin];
 }
 
 const char* ta_plan_pair_kernel(const ta_plan_t* pl, int axis, int vin) {
@@ -321,21 +401,11 @@ ta_status_t ta_axis_attn_forward(const ta_plan_t* pl, int axis, const void* q, c
     if (!q || !k || !v_in || !o_out) return fail(TA_ERR_NULL, "q, k, v_in or o_out is NULL");
     if (!aligned16(q) || !aligned16(k) || !aligned16(v_in) || !aligned16(o_out))
         return fail(TA_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
-    const ta_desc_t& d = pl->desc;
-    const Range ro = span_of(o_out, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
-    const Range rq = span_of(q, pl->qs, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
-    const Range rk = span_of(k, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem);
-    const Range rv = vin == TA_VIN_KV ? span_of(v_in, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem)
-                                      : span_of(v_in, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
-    if (overlaps(ro, rq) || overlaps(ro, rk) || overlaps(ro, rv))
+    const Range ro = o_span(pl, o_out);
+    if (overlaps(ro, q_span(pl, q)) || overlaps(ro, kv_span(pl, k)) || overlaps(ro, vin_span(pl, v_in, vin)))
         return fail(TA_ERR_ALIAS, "o_out overlaps an input");
-
-    const ta::HopParams hp = hop_params(pl, axis, q, k, v_in, vin, o_out);
-    const int kid = pl->kernel_id[axis][vin];
-    hipError_t e = kid == ta::K_GENERIC ? ta::launch_generic_forward(hp, d.dtype, (hipStream_t)stream)
-                                        : ta::launch_mfma_forward(hp, kid, (hipStream_t)stream);
-    if (e != hipSuccess) return fail(TA_ERR_DEVICE, "forward launch failed: %s", hipGetErrorString(e));
-    return TA_OK;
+    if (pl->kernel_id[axis][vin] == ta::K_NONE) return unsupported_forward(pl, axis);
+    return enqueue_forward(pl, axis, q, k, v_in, vin, o_out, (hipStream_t)stream);
 }
 
 ta_status_t ta_axis_pair_attn_forward(const ta_plan_t* pl, int axis, const void* q, const void* k, const void* v_in,
@@ -347,26 +417,17 @@ ta_status_t ta_axis_pair_attn_forward(const ta_plan_t* pl, int axis, const void*
     if (!q || !k || !v_in || !o_out) return fail(TA_ERR_NULL, "q, k, v_in or o_out is NULL");
     if (!aligned16(q) || !aligned16(k) || !aligned16(v_in) || !aligned16(o_out) || !aligned16(o_mid))
         return fail(TA_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
-    const ta_desc_t& d = pl->desc;
-    const Range ro = span_of(o_out, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
-    const Range rq = span_of(q, pl->qs, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
-    const Range rk = span_of(k, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem);
-    const Range rv = vin == TA_VIN_KV ? span_of(v_in, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem)
-                                      : span_of(v_in, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
+    const Range ro = o_span(pl, o_out), rq = q_span(pl, q), rk = kv_span(pl, k), rv = vin_span(pl, v_in, vin);
     if (overlaps(ro, rq) || overlaps(ro, rk) || overlaps(ro, rv))
         return fail(TA_ERR_ALIAS, "o_out overlaps an input");
     if (o_mid) {
-        const Range rm = span_of(o_mid, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem);
+        const Range rm = o_span(pl, o_mid);
         if (overlaps(rm, rq) || overlaps(rm, rk) || overlaps(rm, rv) || overlaps(rm, ro))
             return fail(TA_ERR_ALIAS, "o_mid overlaps an input or o_out");
     }
-    const ta::HopParams h1 = hop_params(pl, axis, q, k, v_in, vin, o_out);
-    const ta::HopParams h2 = hop_params(pl, axis + 1, q, k, v_in, vin, o_out);
-    if (!ta::mfma_pair_supports(h1, h2, d.dtype))
+    if (!pair_ok(pl, axis, vin))
         return fail(TA_ERR_UNSUPPORTED, "no fused kernel for axes %d and %d of this plan (needs bf16, head_dim a multiple of 4 up to 128 and the two innermost axes, both of length 32)", axis, axis + 1);
-    hipError_t e = ta::launch_mfma_forward_pair(h1, h2, o_mid, (hipStream_t)stream);
-    if (e != hipSuccess) return fail(TA_ERR_DEVICE, "fused forward launch failed: %s", hipGetErrorString(e));
-    return TA_OK;
+    return enqueue_pair(pl, axis, q, k, v_in, vin, o_mid, o_out, (hipStream_t)stream);
 }
 
 ta_status_t ta_axis_attn_backward(const ta_plan_t* pl, int axis, const void* q, const void* k, const void* v_in,
@@ -380,39 +441,60 @@ ta_status_t ta_axis_attn_backward(const ta_plan_t* pl, int axis, const void* q, 
     const void* ptrs[7] = {q, k, v_in, d_o, d_v_in, dq, dk};
     for (const void* p : ptrs)
         if (!aligned16(p)) return fail(TA_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
-    const ta_desc_t& d = pl->desc;
-    const int64_t* vs = vin == TA_VIN_KV ? pl->kvs : pl->os;
-    const int vh = vin == TA_VIN_KV ? d.n_kv_heads : d.n_q_heads;
-    const Range in[4] = {span_of(q, pl->qs, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem),
-                         span_of(k, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem),
-                         span_of(v_in, vs, d.batch, pl->N, vh, d.head_dim, pl->elem),
-                         span_of(d_o, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem)};
-    const Range outr[3] = {span_of(d_v_in, vs, d.batch, pl->N, vh, d.head_dim, pl->elem),
-                           span_of(dq, pl->qs, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem),
-                           span_of(dk, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem)};
+    const Range in[4] = {q_span(pl, q), kv_span(pl, k), vin_span(pl, v_in, vin), o_span(pl, d_o)};
+    const Range outr[3] = {vin_span(pl, d_v_in, vin), q_span(pl, dq), kv_span(pl, dk)};
     for (int i = 0; i < 3; ++i) {
         for (int j = 0; j < 4; ++j)
             if (overlaps(outr[i], in[j])) return fail(TA_ERR_ALIAS, "a gradient output overlaps an input");
         for (int j = i + 1; j < 3; ++j)
             if (overlaps(outr[i], outr[j])) return fail(TA_ERR_ALIAS, "gradient outputs overlap each other");
     }
-    ta::BwdParams bp;
-    bp.hop = hop_params(pl, axis, q, k, v_in, vin, nullptr);
-    bp.d_o = make_tensor(d_o, pl->os);
-    bp.d_vin = make_tensor(d_v_in, vs);
-    bp.dq = make_tensor(dq, pl->qs);
-    bp.dk = make_tensor(dk, pl->kvs);
-    bp.accumulate = accumulate;
-    hipError_t e;
-    if (ta::mfma_backward_supports(bp, d.dtype)) {
-        e = ta::launch_mfma_backward(bp, (hipStream_t)stream);
-    } else {
-        if (!ta::generic_backward_supports(pl->dims[axis], pl->G, d.head_dim))
-            return fail(TA_ERR_UNSUPPORTED, "backward: axis length %d with %d heads per group exceeds the kernel's limit",
-                        pl->dims[axis], pl->G);
-        e = ta::launch_generic_backward(bp, d.dtype, (hipStream_t)stream);
+    if (pl->bwd_id[axis][vin] == BWD_NONE) return unsupported_backward(pl, axis);
+    return enqueue_backward(pl, axis, q, k, v_in, vin, d_o, d_v_in, dq, dk, accumulate, (hipStream_t)stream);
+}
+
+// Everything ta_multihop_forward checks, shared with its no-allocation form: all of it happens
+// before the first launch.
+static ta_status_t check_multihop_forward(const ta_plan* pl, const void* q, const void* k, const void* v, void* o,
+                                          const void* workspace, size_t workspace_bytes, size_t need) {
+    if (!q || !k || !v || !o) return fail(TA_ERR_NULL, "q, k, v or o is NULL");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o))
+        return fail(TA_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
+    const Range ro = o_span(pl, o), rq = q_span(pl, q), rk = kv_span(pl, k), rv = kv_span(pl, v);
+    if (overlaps(ro, rq) || overlaps(ro, rk) || overlaps(ro, rv)) return fail(TA_ERR_ALIAS, "o overlaps an input");
+    if (need > 0) {
+        if (!workspace) return fail(TA_ERR_NULL, "workspace is NULL but %zu bytes are needed", need);
+        if (workspace_bytes < need) return fail(TA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
+        if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return fail(TA_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+        const Range rw = {reinterpret_cast<uintptr_t>(workspace), reinterpret_cast<uintptr_t>(workspace) + need};
+        if (overlaps(rw, rq) || overlaps(rw, rk) || overlaps(rw, rv) || overlaps(rw, ro))
+            return fail(TA_ERR_ALIAS, "workspace overlaps a tensor");
     }
-    if (e != hipSuccess) return fail(TA_ERR_DEVICE, "backward launch failed: %s", hipGetErrorString(e));
+    const int fused = ta_plan_fused_position(pl);
+    for (int pos = 0; pos < pl->order && pos != fused; ++pos)
+        if (pl->kernel_id[pl->hop_axis[pos]][pos == 0 ? TA_VIN_KV : TA_VIN_O] == ta::K_NONE) return unsupported_forward(pl, pl->hop_axis[pos]);
+    return TA_OK;
+}
+
+static ta_status_t run_multihop_forward(const ta_plan* pl, const void* q, const void* k, const void* v, void* o,
+                                        char* ws, int save_for_backward, hipStream_t stream) {
+    const int m = pl->order;
+    const void* cur = v;
+    int cur_kind = TA_VIN_KV;
+    const int fused = ta_plan_fused_position(pl);
+    for (int pos = 0; pos < m; ++pos) {
+        if (pos == fused)                                  // the last two hops in one launch; the O between them is only written for a backward
+            return enqueue_pair(pl, pl->hop_axis[pos], q, k, cur, cur_kind,
+                                save_for_backward ? ws + (size_t)pos * pl->o_buf_bytes : nullptr, o, stream);
+        void* dst;
+        if (pos == m - 1) dst = o;
+        else if (save_for_backward) dst = ws + (size_t)pos * pl->o_buf_bytes;
+        else dst = ws + (size_t)(pos & 1) * pl->o_buf_bytes;
+        ta_status_t st = enqueue_forward(pl, pl->hop_axis[pos], q, k, cur, cur_kind, dst, stream);
+        if (st != TA_OK) return st;
+        cur = dst;
+        cur_kind = TA_VIN_O;
+    }
     return TA_OK;
 }
 
@@ -420,39 +502,10 @@ ta_status_t ta_multihop_forward(const ta_plan_t* pl, const void* q, const void* 
                                 void* workspace, size_t workspace_bytes, int save_for_backward, void* stream) {
     g_detail[0] = 0;
     if (!pl) return fail(TA_ERR_NULL, "plan is NULL");
-    if (!q || !k || !v || !o) return fail(TA_ERR_NULL, "q, k, v or o is NULL");
     const size_t need = ta_plan_workspace_bytes(pl, save_for_backward);
-    if (need > 0) {
-        if (!workspace) return fail(TA_ERR_NULL, "workspace is NULL but %zu bytes are needed", need);
-        if (workspace_bytes < need) return fail(TA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need);
-        if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return fail(TA_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
-        const ta_desc_t& d = pl->desc;
-        const Range rw = {reinterpret_cast<uintptr_t>(workspace), reinterpret_cast<uintptr_t>(workspace) + need};
-        if (overlaps(rw, span_of(q, pl->qs, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem)) ||
-            overlaps(rw, span_of(k, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem)) ||
-            overlaps(rw, span_of(v, pl->kvs, d.batch, pl->N, d.n_kv_heads, d.head_dim, pl->elem)) ||
-            overlaps(rw, span_of(o, pl->os, d.batch, pl->N, d.n_q_heads, d.head_dim, pl->elem)))
-            return fail(TA_ERR_ALIAS, "workspace overlaps a tensor");
-    }
-    const int m = pl->order;
-    char* ws = static_cast<char*>(workspace);
-    const void* cur = v;
-    int cur_kind = TA_VIN_KV;
-    const int fused = ta_plan_fused_position(pl);
-    for (int pos = 0; pos < m; ++pos) {
-        if (pos == fused)                                  // the last two hops in one launch; the O between them is only written for a backward
-            return ta_axis_pair_attn_forward(pl, pl->hop_axis[pos], q, k, cur, cur_kind,
-                                             save_for_backward ? ws + (size_t)pos * pl->o_buf_bytes : nullptr, o, stream);
-        void* dst;
-        if (pos == m - 1) dst = o;
-        else if (save_for_backward) dst = ws + (size_t)pos * pl->o_buf_bytes;
-        else dst = ws + (size_t)(pos & 1) * pl->o_buf_bytes;
-        ta_status_t st = ta_axis_attn_forward(pl, pl->hop_axis[pos], q, k, cur, cur_kind, dst, stream);
-        if (st != TA_OK) return st;
-        cur = dst;
-        cur_kind = TA_VIN_O;
-    }
-    return TA_OK;
+    const ta_status_t st = check_multihop_forward(pl, q, k, v, o, workspace, workspace_bytes, need);
+    if (st != TA_OK) return st;
+    return run_multihop_forward(pl, q, k, v, o, static_cast<char*>(workspace), save_for_backward, (hipStream_t)stream);
 }
 
 ta_status_t ta_multihop_backward(const ta_plan_t* pl, const void* q, const void* k, const void* v, const void* d_o,
@@ -461,18 +514,43 @@ ta_status_t ta_multihop_backward(const ta_plan_t* pl, const void* q, const void*
     g_detail[0] = 0;
     if (!pl) return fail(TA_ERR_NULL, "plan is NULL");
     if (!q || !k || !v || !d_o || !dq || !dk || !dv) return fail(TA_ERR_NULL, "a tensor pointer is NULL");
+    const void* ptrs[7] = {q, k, v, d_o, dq, dk, dv};
+    for (const void* p : ptrs)
+        if (!aligned16(p)) return fail(TA_ERR_INVALID_ARG, "device pointers must be 16-byte aligned");
     const int m = pl->order;
     const size_t need_ws = ta_plan_workspace_bytes(pl, 1);
+    const size_t need_sc = m > 1 ? ta_plan_backward_scratch_bytes(pl) : 0;
     if (need_ws > 0) {
         if (!workspace) return fail(TA_ERR_NULL, "workspace is NULL");
         if (workspace_bytes < need_ws) return fail(TA_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", workspace_bytes, need_ws);
+        if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return fail(TA_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
     }
-    if (m > 1) {
-        const size_t need_sc = ta_plan_backward_scratch_bytes(pl);
+    if (need_sc > 0) {
         if (!scratch) return fail(TA_ERR_NULL, "scratch is NULL");
         if (scratch_bytes < need_sc) return fail(TA_ERR_WORKSPACE, "scratch has %zu bytes, %zu needed", scratch_bytes, need_sc);
         if ((reinterpret_cast<uintptr_t>(scratch) & 255u) != 0) return fail(TA_ERR_INVALID_ARG, "scratch must be 256-byte aligned");
     }
+    // no output may overlap an input, the saved tensors, the scratch or another output
+    const Range in[4] = {q_span(pl, q), kv_span(pl, k), kv_span(pl, v), o_span(pl, d_o)};
+    const Range outr[3] = {q_span(pl, dq), kv_span(pl, dk), kv_span(pl, dv)};
+    const uintptr_t wlo = reinterpret_cast<uintptr_t>(workspace), slo = reinterpret_cast<uintptr_t>(scratch);
+    const Range rw = {wlo, wlo + need_ws}, rs = {slo, slo + need_sc};
+    for (int i = 0; i < 3; ++i) {
+        for (int j = 0; j < 4; ++j)
+            if (overlaps(outr[i], in[j])) return fail(TA_ERR_ALIAS, "a gradient output overlaps an input");
+        for (int j = i + 1; j < 3; ++j)
+            if (overlaps(outr[i], outr[j])) return fail(TA_ERR_ALIAS, "gradient outputs overlap each other");
+        if (need_ws > 0 && overlaps(outr[i], rw)) return fail(TA_ERR_ALIAS, "a gradient output overlaps the workspace");
+        if (need_sc > 0 && overlaps(outr[i], rs)) return fail(TA_ERR_ALIAS, "a gradient output overlaps the scratch");
+    }
+    if (need_sc > 0) {
+        for (int j = 0; j < 4; ++j)
+            if (overlaps(rs, in[j])) return fail(TA_ERR_ALIAS, "scratch overlaps an input");
+        if (need_ws > 0 && overlaps(rs, rw)) return fail(TA_ERR_ALIAS, "scratch overlaps the workspace");
+    }
+    for (int pos = 0; pos < m; ++pos)
+        if (pl->bwd_id[pl->hop_axis[pos]][pos == 0 ? TA_VIN_KV : TA_VIN_O] == BWD_NONE) return unsupported_backward(pl, pl->hop_axis[pos]);
+
     const char* ws = static_cast<const char*>(workspace);
     char* sc = static_cast<char*>(scratch);
     const void* grad = d_o;
@@ -480,8 +558,8 @@ ta_status_t ta_multihop_backward(const ta_plan_t* pl, const void* q, const void*
         const void* x = pos == 0 ? v : ws + (size_t)(pos - 1) * pl->o_buf_bytes;
         const int kind = pos == 0 ? TA_VIN_KV : TA_VIN_O;
         void* gprev = pos == 0 ? dv : sc + (size_t)(pos & 1) * pl->o_buf_bytes;
-        ta_status_t st = ta_axis_attn_backward(pl, pl->hop_axis[pos], q, k, x, kind, grad, gprev, dq, dk,
-                                               pos == m - 1 ? 0 : 1, stream);
+        ta_status_t st = enqueue_backward(pl, pl->hop_axis[pos], q, k, x, kind, grad, gprev, dq, dk, pos == m - 1 ? 0 : 1,
+                                          (hipStream_t)stream);
         if (st != TA_OK) return st;
         grad = gprev;
     }
@@ -530,3 +608,24 @@ ta_status_t ta_copy_bytes(const void* src, void* dst, size_t bytes, void* stream
 }
 
 }  // extern "C"
+
+namespace ta {
+
+hipError_t allow_dynamic_lds(const void* kernel, int bytes) {
+    struct Entry { int dev; const void* kernel; int bytes; };
+    static std::mutex mu;
+    static Entry done[256];
+    static int n_done = 0;
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lock(mu);
+    for (int i = 0; i < n_done; ++i)
+        if (done[i].dev == dev && done[i].kernel == kernel && done[i].bytes >= bytes) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e != hipSuccess) return e;
+    if (n_done < 256) done[n_done++] = Entry{dev, kernel, bytes};   // a full table only costs repeated (idempotent) calls
+    return hipSuccess;
+}
+
+}  // namespace ta

@@ -386,7 +386,14 @@ inline int tile_rows(int D) { return D <= 128 ? 32 : 16; }
 
 }  // namespace
 
+bool generic_forward_supports(const HopParams& p) {
+    const int64_t qblocks = (p.n + kQB - 1) / kQB;
+    const int64_t per_seq = p.fibres * qblocks;
+    return per_seq > 0 && per_seq <= 0x7fffffffLL / ((int64_t)p.B * p.Hq);
+}
+
 hipError_t launch_generic_forward(const HopParams& p, int dtype, hipStream_t s) {
+    if (!generic_forward_supports(p)) return hipErrorInvalidValue;
     const int TK = tile_rows(p.D);
     const int qblocks = (p.n + kQB - 1) / kQB;
     const int64_t blocks = (int64_t)p.B * p.Hq * p.fibres * qblocks;
@@ -404,12 +411,13 @@ static size_t backward_smem(int32_t n, int32_t G, int32_t D) {
     return sizeof(float) * ((size_t)3 * G * n + (size_t)2 * TK * (D + 1) + (size_t)kWaves * 2 * D);
 }
 
-bool generic_backward_supports(int32_t n, int32_t G, int32_t D) {
-    return backward_smem(n, G, D) <= 64 * 1024;
+bool generic_backward_supports(const HopParams& p) {
+    return backward_smem(p.n, p.G, p.D) <= 64 * 1024 && p.fibres > 0 && p.fibres <= 0x7fffffffLL / ((int64_t)p.B * p.Hkv);
 }
 
 hipError_t launch_generic_backward(const BwdParams& bp, int dtype, hipStream_t s) {
     const HopParams& p = bp.hop;
+    if (!generic_backward_supports(p)) return hipErrorInvalidValue;
     const int TK = tile_rows(p.D);
     const int64_t blocks = (int64_t)p.B * p.Hkv * p.fibres;
     const size_t smem = backward_smem(p.n, p.G, p.D);

@@ -65,22 +65,27 @@ __host__ __device__ inline int64_t fibre_base_token(int64_t f, int64_t stride, i
 }
 
 enum KernelId : int {
+    K_NONE = -1,             // no kernel's launch geometry fits the shape
     K_GENERIC = 0,
-    K_MFMA_BF16_N16 = 1,
     K_MFMA_BF16_N32 = 2,
     K_MFMA_BF16_N64 = 3,
     K_MFMA_BF16_STREAM = 4,
 };
 
-// Launchers.  Each checks nothing: the API layer has validated shapes against what
-// the kernel assumes.  Each returns the hipError_t of the launch.
+// Launchers and their feasibility predicates.  The API layer asks the predicates once, when the
+// plan is made, and only launches what they accepted; a launcher repeats its own geometry checks
+// and returns hipErrorInvalidValue rather than launch a grid its kernel does not fit.  Each
+// launcher returns the hipError_t of the launch.
 hipError_t launch_generic_forward(const HopParams& p, int dtype, hipStream_t s);
 hipError_t launch_generic_backward(const BwdParams& p, int dtype, hipStream_t s);
-bool       generic_backward_supports(int32_t n, int32_t G, int32_t D);
+bool       generic_forward_supports(const HopParams& p);
+bool       generic_backward_supports(const HopParams& p);   // the row statistics fit LDS and the grid fits
 hipError_t launch_mfma_forward(const HopParams& p, int kernel_id, hipStream_t s);
 hipError_t launch_mfma_forward_stream(const HopParams& p, hipStream_t s);
 bool       mfma_forward_supports(int32_t n, int32_t D, int dtype, int* kernel_id);
 bool       mfma_forward_layout_ok(const HopParams& p);   // strides and sizes fit the kernel's 32-bit row offsets
+bool       mfma_forward_feasible(const HopParams& p, int kernel_id);   // layout_ok and the launch grid fits
+bool       mfma_forward_stream_feasible(const HopParams& p);
 bool       mfma_backward_supports(const BwdParams& bp, int dtype);
 bool       mfma_backward_is_blocked(const BwdParams& bp, int dtype);   // the variant for axes longer than one tile
 hipError_t launch_mfma_backward(const BwdParams& bp, hipStream_t s);
@@ -88,6 +93,9 @@ hipError_t launch_mfma_backward(const BwdParams& bp, hipStream_t s);
 bool       mfma_pair_supports(const HopParams& h1, const HopParams& h2, int dtype);
 hipError_t launch_mfma_forward_pair(const HopParams& h1, const HopParams& h2, void* o_mid, hipStream_t s);   // o_mid: nullptr or O-shaped, gets h1's output
 hipError_t launch_rope(const RopeParams& rp, int dtype, hipStream_t s);
+// Allows `kernel` to be launched with up to `bytes` of dynamic LDS (more than 64 KB has to be
+// allowed once per device and kernel).  Remembers what it has set; callable from any thread.
+hipError_t allow_dynamic_lds(const void* kernel, int bytes);
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 
 }  // namespace ta

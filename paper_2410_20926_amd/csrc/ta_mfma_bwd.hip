@@ -785,17 +785,9 @@ hipError_t launch_stream(const BwdParams& bp, hipStream_t s) {
     const size_t wave_bytes = (size_t)BGeo<D>::kBufBytes + kTile * 16 + (size_t)3 * kTile * sp.tiles * 4;
     const size_t smem = (size_t)(bp.wg_heads > 1 ? BGeo<D>::kRedBytes : 0) + (size_t)bp.wg_heads * wave_bytes;
     if (smem > kStreamMaxLds) return hipErrorInvalidValue;
-    if (smem > 64 * 1024) {                               // more than 64 KB of dynamic LDS has to be allowed once per device
-        static bool allowed[64] = {};
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
+    if (smem > 64 * 1024) {
+        const hipError_t e = allow_dynamic_lds(reinterpret_cast<const void*>(mfma_bwd_stream_kernel<D, NARROW>), kStreamMaxLds);
         if (e != hipSuccess) return e;
-        if (dev < 0 || dev >= 64) return hipErrorInvalidValue;
-        if (!allowed[dev]) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_bwd_stream_kernel<D, NARROW>), hipFuncAttributeMaxDynamicSharedMemorySize, kStreamMaxLds);
-            if (e != hipSuccess) return e;
-            allowed[dev] = true;
-        }
     }
     const dim3 grid((unsigned)p.Hkv, sp.fibres_lo, (unsigned)p.B * sp.fibres_hi);
     hipLaunchKernelGGL((mfma_bwd_stream_kernel<D, NARROW>), grid, dim3(64 * bp.wg_heads), smem, s, bp, sp);
@@ -831,7 +823,16 @@ static int backward_variant(const BwdParams& bp, int dtype) {
     const int64_t N = p.fibres * p.n;
     if (!(N < ((int64_t)1 << 31) && p.B <= 65535 && fits_u32(p.q, N) && fits_u32(p.k, N) && fits_u32(p.vin, N) &&
           fits_u32(bp.d_o, N) && fits_u32(bp.d_vin, N) && fits_u32(bp.dq, N) && fits_u32(bp.dk, N))) return 0;
-    if (p.n <= kTile) return 1;
+    if (p.n <= kTile) {
+        TileParams tp;
+        HopParams hp = p;
+        hp.o = bp.d_o;
+        return make_tile_params(hp, 1, &tp) ? 1 : 0;
+    }
+    {   // the blocked kernel's grid: (Hkv, fibres_lo, B * fibres_hi)
+        const int64_t lo = p.fibres < 32768 ? p.fibres : 32768;
+        if (p.fibres <= 0 || (int64_t)p.B * ((p.fibres + lo - 1) / lo) > 65535) return 0;
+    }
     // the blocked kernel keeps three floats per row and head in LDS
     const size_t tiles = (size_t)(p.n + kTile - 1) / kTile;
     const size_t kbuf = p.D > 64 ? BGeo<128>::kBufBytes : BGeo<64>::kBufBytes;

@@ -609,11 +609,18 @@ hipError_t launch_width(const HopParams& p, const TileParams& tp, int KT, hipStr
 }
 }  // namespace
 
+bool mfma_forward_feasible(const HopParams& p, int kernel_id) {
+    if (kernel_id == K_MFMA_BF16_STREAM) return mfma_forward_stream_feasible(p);
+    const int KT = kernel_id == K_MFMA_BF16_N32 ? 1 : (kernel_id == K_MFMA_BF16_N64 ? 2 : 0);
+    if (KT == 0 || p.n < 1 || p.n > kTile * KT || p.D < 8 || p.D > 128 || p.D % 4 != 0 || !mfma_forward_layout_ok(p)) return false;
+    TileParams tp;
+    return make_tile_params(p, KT, &tp);
+}
+
 hipError_t launch_mfma_forward(const HopParams& p, int kernel_id, hipStream_t s) {
     if (kernel_id == K_MFMA_BF16_STREAM) return launch_mfma_forward_stream(p, s);
-    const int KT = kernel_id == K_MFMA_BF16_N32 ? 1 : (kernel_id == K_MFMA_BF16_N64 ? 2 : 0);
-    if (KT == 0 || p.n < 1 || p.n > kTile * KT || p.D < 8 || p.D > 128 || p.D % 4 != 0 || !mfma_forward_layout_ok(p))
-        return hipErrorInvalidValue;
+    if (!mfma_forward_feasible(p, kernel_id)) return hipErrorInvalidValue;
+    const int KT = kernel_id == K_MFMA_BF16_N32 ? 1 : 2;
     TileParams tp;
     if (!make_tile_params(p, KT, &tp)) return hipErrorInvalidValue;
     if (p.D == 128) return launch_width<128, false>(p, tp, KT, s);

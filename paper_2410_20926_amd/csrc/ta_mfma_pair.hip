@@ -407,24 +407,14 @@ hipError_t launch_mfma_forward_pair(const HopParams& h1, const HopParams& h2, vo
     PairParams pp;
     if (!pair_params(h1, h2, &pp)) return hipErrorInvalidValue;
     pp.mid = o_mid;
-    // more than 64 KB of dynamic LDS has to be allowed once per device
-    static bool allowed[64][8] = {};
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    if (dev < 0 || dev >= 64) return hipErrorInvalidValue;
     const bool wide = h1.D > 64, narrow = h1.D != 64 && h1.D != 128, mid = o_mid != nullptr;
     const void* kf;
     if (wide) kf = narrow ? (mid ? (const void*)mfma_fwd_pair_kernel<128, true, true> : (const void*)mfma_fwd_pair_kernel<128, false, true>)
                           : (mid ? (const void*)mfma_fwd_pair_kernel<128, true, false> : (const void*)mfma_fwd_pair_kernel<128, false, false>);
     else      kf = narrow ? (mid ? (const void*)mfma_fwd_pair_kernel<64, true, true> : (const void*)mfma_fwd_pair_kernel<64, false, true>)
                           : (mid ? (const void*)mfma_fwd_pair_kernel<64, true, false> : (const void*)mfma_fwd_pair_kernel<64, false, false>);
-    const int which = (wide ? 4 : 0) + (narrow ? 2 : 0) + (mid ? 1 : 0);
-    if (!allowed[dev][which]) {                           // per device and instantiation
-        e = hipFuncSetAttribute(kf, hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
-        if (e != hipSuccess) return e;
-        allowed[dev][which] = true;
-    }
+    const hipError_t e = allow_dynamic_lds(kf, kLdsBytes);
+    if (e != hipSuccess) return e;
     const uint32_t span = 8u * (uint32_t)pp.G;
     const uint32_t grid = ((pp.groups + 7u) / 8u) * span;
     void* args[1] = {&pp};

@@ -682,18 +682,11 @@ template <int D, bool VS, bool NARROW>
 hipError_t launch_shared(const HopParams& p, const StreamParams& sp, hipStream_t s) {
     const size_t smem = (size_t)((VS ? 4 : 2) + kWavesPerBlock) * kTile * Geo<D>::kPitch;
     const dim3 grid((unsigned)(p.Hq / kWavesPerBlock), sp.tiles_lo, (unsigned)p.B * sp.tiles_hi);
-    if (smem > 64 * 1024) {                               // more than 64 KB of dynamic LDS has to be allowed once per device
-        static bool allowed[64] = {};
-        int dev = 0;
-        hipError_t e = hipGetDevice(&dev);
+    if (smem > 64 * 1024) {
+        const void* kf = sp.qchunk > 1 ? reinterpret_cast<const void*>(mfma_fwd_stream_chunked_kernel<D, VS, NARROW>)
+                                       : reinterpret_cast<const void*>(mfma_fwd_stream_shared_kernel<D, VS, NARROW>);
+        const hipError_t e = allow_dynamic_lds(kf, (int)smem);
         if (e != hipSuccess) return e;
-        if (dev < 0 || dev >= 64) return hipErrorInvalidValue;
-        if (!allowed[dev]) {
-            e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_fwd_stream_shared_kernel<D, VS, NARROW>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-            if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(mfma_fwd_stream_chunked_kernel<D, VS, NARROW>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-            if (e != hipSuccess) return e;
-            allowed[dev] = true;
-        }
     }
     if (sp.qchunk > 1) hipLaunchKernelGGL((mfma_fwd_stream_chunked_kernel<D, VS, NARROW>), grid, dim3(kWavesPerBlock * 64), smem, s, p, sp);
     else               hipLaunchKernelGGL((mfma_fwd_stream_shared_kernel<D, VS, NARROW>), grid, dim3(kWavesPerBlock * 64), smem, s, p, sp);
@@ -710,19 +703,20 @@ hipError_t launch(const HopParams& p, const StreamParams& sp, hipStream_t s) {
 
 }  // namespace
 
-hipError_t launch_mfma_forward_stream(const HopParams& p, hipStream_t s) {
-    if (p.n < 1 || p.D < 8 || p.D > 128 || p.D % 4 != 0 || !mfma_forward_layout_ok(p)) return hipErrorInvalidValue;
-    StreamParams sp;
+// Launch geometry of the streaming kernels; false when the shape or the grid does not fit.
+static bool stream_params(const HopParams& p, StreamParams* spp) {
+    if (p.n < 1 || p.D < 8 || p.D > 128 || p.D % 4 != 0 || !mfma_forward_layout_ok(p)) return false;
+    StreamParams& sp = *spp;
     const bool shared = p.G % kWavesPerBlock == 0;        // the 4 waves of a workgroup are 4 heads of one group
     sp.qtiles = (uint32_t)((p.n + kTile - 1) / kTile);
     sp.qchunk = (shared && sp.qtiles <= 4) ? sp.qtiles : 1u;   // short axes: one workgroup walks all query tiles of a fibre
     sp.qchunks = (sp.qtiles + sp.qchunk - 1) / sp.qchunk;
     const int64_t tiles = p.fibres * sp.qchunks;
-    if (tiles <= 0 || tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (tiles <= 0 || tiles > 0x7fffffffLL) return false;
     sp.tiles = (uint32_t)tiles;
     sp.tiles_lo = (uint32_t)(tiles < 32768 ? tiles : 32768);
     sp.tiles_hi = (uint32_t)((tiles + sp.tiles_lo - 1) / sp.tiles_lo);
-    if ((int64_t)p.B * sp.tiles_hi > 65535) return hipErrorInvalidValue;
+    if ((int64_t)p.B * sp.tiles_hi > 65535) return false;
     sp.q_row = (uint32_t)(p.q.st * 2);
     sp.k_row = (uint32_t)(p.k.st * 2);
     sp.v_row = (uint32_t)(p.vin.st * 2);
@@ -731,6 +725,18 @@ hipError_t launch_mfma_forward_stream(const HopParams& p, hipStream_t s) {
     sp.k_step = (uint32_t)(p.stride * p.k.st * 2);
     sp.v_step = (uint32_t)(p.stride * p.vin.st * 2);
     sp.o_step = (uint32_t)(p.stride * p.o.st * 2);
+    return true;
+}
+
+bool mfma_forward_stream_feasible(const HopParams& p) {
+    StreamParams sp;
+    return stream_params(p, &sp);
+}
+
+hipError_t launch_mfma_forward_stream(const HopParams& p, hipStream_t s) {
+    StreamParams sp;
+    if (!stream_params(p, &sp)) return hipErrorInvalidValue;
+    const bool shared = p.G % kWavesPerBlock == 0;
     const bool vs = p.vin_heads != p.Hq;
     if (p.D == 128) return shared ? (vs ? launch_shared<128, true, false>(p, sp, s) : launch_shared<128, false, false>(p, sp, s)) : launch<128, false>(p, sp, s);
     if (p.D == 64) return shared ? (vs ? launch_shared<64, true, false>(p, sp, s) : launch_shared<64, false, false>(p, sp, s)) : launch<64, false>(p, sp, s);

@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_status_strings():
-    assert ta.ta_version() == (0, 4)
+    assert ta.ta_version() == (0, 5)
     lib = ta.load_library()
     assert lib.ta_status_string(0) == b"TA_OK"
     assert lib.ta_status_string(5) == b"TA_ERR_ALIAS"
@@ -171,6 +171,68 @@ def test_entry_points_reject_bad_arguments_without_launching():
     assert status(ta.ta_rope_apply, p, 1, 0, Q, O, -3.0, False, S) == "TA_ERR_INVALID_ARG"
     assert status(ta.ta_copy_bytes, Q, K, 24, S) == "TA_ERR_INVALID_ARG"
     assert status(ta.ta_copy_bytes, None, K, 32, S) == "TA_ERR_NULL"
+
+
+def test_multihop_calls_validate_every_hop_before_the_first_launch():
+    """Nothing may be enqueued when a call is going to fail: aliasing, alignment and the
+    availability of a kernel for EVERY hop are checked up front.  There is no GPU here, so a
+    call that got as far as a launch would come back as TA_ERR_DEVICE instead."""
+    def status(fn, *a, **k):
+        with pytest.raises(ta.TaError) as ei:
+            fn(*a, **k)
+        return ei.value.name
+
+    S = 0xdead0
+    Q, K, V, O, W, G = 0x10000000, 0x20000000, 0x30000000, 0x40000000, 0x50000000, 0x60000000
+    DQ, DK, DV, SC = 0x70000000, 0x80000000, 0x90000000, 0xa0000000
+    p = ta.ta_plan_create(1, 2, 1, 64, (4, 3), ta.TA_F32, True)
+    big = 1 << 20
+    # the output of the LAST hop overlaps an input: found before the first hop is enqueued
+    assert status(ta.ta_multihop_forward, p, Q, K, V, Q + 64, W, big, False, S) == "TA_ERR_ALIAS"
+    assert status(ta.ta_multihop_forward, p, Q, K, V, V, W, big, False, S) == "TA_ERR_ALIAS"
+    assert status(ta.ta_multihop_forward, p, Q, K + 8, V, O, W, big, False, S) == "TA_ERR_INVALID_ARG"
+    # backward: scratch and workspace are range-checked against every tensor and each other
+    assert status(ta.ta_multihop_backward, p, Q, K, V, G, W, big, DQ, DK, DV, W, big, S) == "TA_ERR_ALIAS"
+    assert status(ta.ta_multihop_backward, p, Q, K, V, G, W, big, DQ, DK, DV, DQ, big, S) == "TA_ERR_ALIAS"
+    assert status(ta.ta_multihop_backward, p, Q, K, V, G, W, big, DQ, DK, DV, Q, big, S) == "TA_ERR_ALIAS"
+    assert status(ta.ta_multihop_backward, p, Q, K, V, G, W, big, W, DK, DV, SC, big, S) == "TA_ERR_ALIAS"
+    assert status(ta.ta_multihop_backward, p, Q, K, V, G, W, big, DQ, DQ, DV, SC, big, S) == "TA_ERR_ALIAS"
+    assert status(ta.ta_multihop_backward, p, Q, K, V, G, W, big, DQ, DK, K, SC, big, S) == "TA_ERR_ALIAS"
+    assert status(ta.ta_multihop_backward, p, Q, K, V, G, W, big, DQ, DK, DV, SC + 16, big, S) == "TA_ERR_INVALID_ARG"
+    assert status(ta.ta_multihop_backward, p, Q, K, V, G, W, big, DQ + 2, DK, DV, SC, big, S) == "TA_ERR_INVALID_ARG"
+    # an fp32 axis too long for the backward's row statistics: the hop over axis 1 runs first in
+    # the backward and is fine, the hop over axis 0 is not; the call must refuse before either
+    long_axis = ta.ta_plan_create(1, 8, 1, 64, (4096, 2), ta.TA_F32, True)
+    assert long_axis.hop_backward_kernel(1, ta.TA_VIN_O) == "generic"
+    assert long_axis.hop_backward_kernel(0, ta.TA_VIN_KV) == "unsupported"
+    huge = 1 << 28
+    A = [i << 32 for i in range(1, 12)]
+    assert status(ta.ta_multihop_backward, long_axis, A[0], A[1], A[2], A[3], A[4], huge, A[5], A[6], A[7], A[8], huge, S) == "TA_ERR_UNSUPPORTED"
+
+
+def test_launch_geometry_is_settled_when_the_plan_is_made():
+    """Whether a kernel's launch grid fits is decided by ta_plan_create, not at launch time."""
+    ok = ta.ta_plan_create(32767, 1, 1, 64, (32769, 16), ta.TA_BF16, True)
+    assert ok.hop_kernel(1, ta.TA_VIN_KV) == "mfma_bf16_n32" and ok.hop_backward_kernel(1, ta.TA_VIN_KV) == "mfma_bf16_bwd_n32"
+    # 32,769 tiles need 2 grid rows per batch element: with 32,768 batch elements no grid holds the job, neither
+    # the matrix-core kernel's nor the generic kernel's, and the plan says so (it used to surface as a failed launch)
+    more = ta.ta_plan_create(32768, 1, 1, 64, (32769, 32), ta.TA_BF16, True)
+    assert more.hop_kernel(1, ta.TA_VIN_KV) == "unsupported"
+    assert more.hop_backward_kernel(1, ta.TA_VIN_KV) == "generic"        # one workgroup per fibre and group: that grid fits
+    assert more.pair_kernel(0, ta.TA_VIN_KV) == "unsupported"
+    none = ta.ta_plan_create(65535, 8, 1, 64, (32769, 32), ta.TA_BF16, True)         # more workgroups than any grid here holds
+    assert none.hop_kernel(1, ta.TA_VIN_KV) == "unsupported"
+    with pytest.raises(ta.TaError) as e:
+        ta.ta_axis_attn_forward(none, 1, 1 << 50, 2 << 50, 3 << 50, ta.TA_VIN_KV, 4 << 50, 0xdead0)
+    assert e.value.name == "TA_ERR_UNSUPPORTED"
+
+
+def test_sequence_length_overflow_is_caught_before_multiplying():
+    for dims in ((1 << 30, 1 << 30), (1 << 20, 1 << 20, 1 << 20), (2147483647, 2147483647, 2147483647, 2147483647)):
+        with pytest.raises(ta.TaError) as e:
+            ta.ta_plan_create(1, 1, 1, 64, dims, ta.TA_F32, False)
+        assert e.value.name == "TA_ERR_SHAPE"
+    assert ta.load_library().ta_status_string(8) == b"TA_ERR_NOMEM"
 
 
 def test_missing_library_fails_loudly(monkeypatch):
