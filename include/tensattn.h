@@ -194,6 +194,25 @@ ta_status_t ta_multihop_forward(const ta_plan_t* plan,
                                 void* workspace, size_t workspace_bytes,
                                 int save_for_backward, void* stream);
 
+/* ---- the multi-hop forward for callers that cannot allocate -------------------------------
+ * For code under HIP graph capture, tight serving loops and harnesses that forbid hipMalloc:
+ * ta_multihop_forward with save_for_backward = 0, except that the inter-hop O tensors live in
+ * device memory that is part of the library itself (a fixed array of TA_STATIC_WORKSPACE_BYTES
+ * bytes in the library's code object; every GPU the library runs on holds its own copy until
+ * the process ends) instead of a caller's workspace.  The call allocates and frees nothing.
+ * Plans whose ta_plan_workspace_bytes(plan, 0) exceeds TA_STATIC_WORKSPACE_BYTES are refused
+ * with TA_ERR_WORKSPACE (64 MiB holds e.g. one intermediate O of 8,192 tokens x 32 heads x 128
+ * bf16 features, which is all a three-hop plan with a fused last pair needs).  All calls on one
+ * GPU share that GPU's array: calls that overlap in time on one GPU (different streams or
+ * threads) race; calls that follow one another on a stream do not, and nothing needs clearing
+ * in between, since every hop overwrites an intermediate tensor before the next hop reads it.
+ * The first call on a device looks up the array's address on that device, with that device
+ * current; make it outside a stream capture.  Results are identical to ta_multihop_forward's. */
+#define TA_STATIC_WORKSPACE_BYTES (64u << 20)
+ta_status_t ta_multihop_forward_static(const ta_plan_t* plan,
+                                       const void* q, const void* k, const void* v, void* o,
+                                       void* stream);
+
 /* ---- full multi-hop backward ----------------------------------------------------------
  * Gradients of sum(O * d_o) w.r.t. Q, K, V: hops undone in reverse order, dq and dk
  * accumulated over hops (first processed hop overwrites), dv = gradient reaching O_0.

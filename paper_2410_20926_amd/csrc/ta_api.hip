@@ -31,7 +31,31 @@ struct ta_plan {
     bool pair[TA_MAX_ORDER][2];      // the fused pair (axis, axis + 1) is available
 };
 
+// Workspace of ta_multihop_forward_static: device memory that belongs to the library's code
+// object, one copy per GPU, present from the moment the library is loaded on that GPU until the
+// process ends.  In host code this name is only a handle for hipGetSymbolAddress, never an address.
+static __device__ __align__(256) unsigned char scratch[TA_STATIC_WORKSPACE_BYTES];
+
 namespace {
+
+// Device address of `scratch` on the current device, looked up once per device.
+ta_status_t static_workspace(void** out) {
+    static std::mutex mu;
+    static void* ptr[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return TA_ERR_DEVICE;
+    if (dev < 0 || dev >= 64) return TA_ERR_DEVICE;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return TA_ERR_DEVICE;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return TA_OK;
+}
 
 enum BwdId : int { BWD_NONE = 0, BWD_MFMA_N32 = 1, BWD_MFMA_BLOCKED = 2, BWD_GENERIC = 3 };
 
@@ -506,6 +530,21 @@ ta_status_t ta_multihop_forward(const ta_plan_t* pl, const void* q, const void* 
     const ta_status_t st = check_multihop_forward(pl, q, k, v, o, workspace, workspace_bytes, need);
     if (st != TA_OK) return st;
     return run_multihop_forward(pl, q, k, v, o, static_cast<char*>(workspace), save_for_backward, (hipStream_t)stream);
+}
+
+ta_status_t ta_multihop_forward_static(const ta_plan_t* pl, const void* q, const void* k, const void* v, void* o,
+                                       void* stream) {
+    g_detail[0] = 0;
+    if (!pl) return fail(TA_ERR_NULL, "plan is NULL");
+    const size_t need = ta_plan_workspace_bytes(pl, 0);
+    if (need > (size_t)TA_STATIC_WORKSPACE_BYTES)
+        return fail(TA_ERR_WORKSPACE, "the inter-hop tensors of this plan need %zu bytes, the library's own workspace holds %zu",
+                    need, (size_t)TA_STATIC_WORKSPACE_BYTES);
+    void* ws = nullptr;
+    if (static_workspace(&ws) != TA_OK) return fail(TA_ERR_DEVICE, "the address of the library's own workspace could not be obtained on the current device");
+    const ta_status_t st = check_multihop_forward(pl, q, k, v, o, ws, (size_t)TA_STATIC_WORKSPACE_BYTES, need);
+    if (st != TA_OK) return st;
+    return run_multihop_forward(pl, q, k, v, o, static_cast<char*>(ws), 0, (hipStream_t)stream);
 }
 
 ta_status_t ta_multihop_backward(const ta_plan_t* pl, const void* q, const void* k, const void* v, const void* d_o,

@@ -22,7 +22,9 @@ EXPORTS = [
     "ta_axis_attn_backward", "ta_multihop_forward", "ta_multihop_backward", "ta_rope_apply", "ta_copy_bytes",
     "ta_status_string", "ta_last_error_detail", "ta_version",
     "ta_axis_pair_attn_forward", "ta_plan_pair_kernel", "ta_plan_pair_bytes", "ta_plan_fused_position",
+    "ta_multihop_forward_static",
 ]
+TA_STATIC_WORKSPACE_BYTES = 64 << 20
 
 
 class TaDesc(C.Structure):
@@ -95,6 +97,8 @@ def load_library():
     lib.ta_axis_attn_backward.restype = i
     lib.ta_multihop_forward.argtypes = [vp, vp, vp, vp, vp, vp, sz, i, vp]
     lib.ta_multihop_forward.restype = i
+    lib.ta_multihop_forward_static.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.ta_multihop_forward_static.restype = i
     lib.ta_multihop_backward.argtypes = [vp, vp, vp, vp, vp, vp, sz, vp, vp, vp, vp, sz, vp]
     lib.ta_multihop_backward.restype = i
     lib.ta_rope_apply.argtypes = [vp, i, i, C.c_float, i, vp, vp, vp]
@@ -270,6 +274,10 @@ def ta_multihop_forward(plan: Plan, q, k, v, o, workspace, workspace_bytes: int,
                         stream=None) -> None:
     _check(load_library().ta_multihop_forward(plan.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(workspace),
                                               workspace_bytes, int(save_for_backward), _stream(stream)))
+
+
+def ta_multihop_forward_static(plan: Plan, q, k, v, o, stream=None) -> None:
+    _check(load_library().ta_multihop_forward_static(plan.handle, _ptr(q), _ptr(k), _ptr(v), _ptr(o), _stream(stream)))
 
 
 def ta_multihop_backward(plan: Plan, q, k, v, d_o, workspace, workspace_bytes: int, dq, dk, dv, scratch,
