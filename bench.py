@@ -35,14 +35,14 @@ def parse_args():
     ap.add_argument("--rotate", type=int, default=3, help="independent buffer sets cycled through, so that the "
                     "256 MB Infinity Cache cannot serve one step's re-reads from the previous step")
     ap.add_argument("--also", default=None, help="comma-separated further workloads measured in the same run and "
-                    "reported under other_workloads (default: c4,c5,c6 next to c3, none otherwise)")
+                    "reported under other_workloads (default: c2,c4,c5,c6 next to c3, none otherwise)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true", help="also launch the plain copy kernel on 1 GiB a few "
                     "times, so that a hardware-counter run of this command has a transfer of known size to scale by")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     args = ap.parse_args()
     if args.also is None:
-        args.also = "c4,c5,c6" if args.workload == "c3" else ""
+        args.also = "c2,c4,c5,c6" if args.workload == "c3" else ""
     return args
 
 
@@ -151,36 +151,78 @@ def plan_o_bytes(plan, w):
     return (n + 255) // 256 * 256
 
 
-def cpu_baseline(w, target_seconds):
-    """The oracle, untuned, on whole sequences of a few query heads of the same workload
-    (heads are independent, so tokens/s of the full job = N*B / (t_per_head * H_q))."""
-    import numpy as np
+def _cpu_worker(job):
+    """One worker process of the CPU baseline: `passes` whole single-head passes of the oracle.
+    Returns (wall seconds, CPU seconds) of the timed passes."""
+    name, worker, passes = job
     from oracle import tensattn_oracle as orc
-    from paper_2410_20926_amd.workloads import make_inputs
-    q, k, v, d_o = make_inputs(1, w.seq_len, 1, 1, w.head_dim, w.seed, "bf16", w.qk_prescale, with_grad=True)
-    heads = 0
-    c0 = time.process_time()
-    t0 = time.perf_counter()
-    while True:
+    from paper_2410_20926_amd.workloads import WORKLOADS, make_inputs
+    w = WORKLOADS[name]
+    q, k, v, d_o = make_inputs(1, w.seq_len, 1, 1, w.head_dim, w.seed + worker, "bf16", w.qk_prescale, with_grad=True)
+
+    def one_head():
         if w.backward:                                  # the oracle's backward runs its own forward first
             orc.tensorized_attention_backward(q, k, v, d_o, w.dims, w.causal)
         else:
             orc.tensorized_attention_forward(q, k, v, w.dims, w.causal)
-        heads += 1
-        el = time.perf_counter() - t0
-        if el + el / heads > target_seconds:
-            break
-    wall = time.perf_counter() - t0
-    cpu = time.process_time() - c0
-    per_head = wall / heads
-    tokens_per_s = w.batch * w.seq_len / (per_head * w.batch * w.n_q_heads)
+
+    one_head()                                          # first touch of the code and the arrays, untimed
+    c0, t0 = time.process_time(), time.perf_counter()
+    for _ in range(passes):
+        one_head()
+    return time.perf_counter() - t0, time.process_time() - c0
+
+
+def cpu_baseline(w, target_seconds):
+    """The oracle, untuned, on whole sequences of single query heads of the same workload, on
+    ALL host cores of this process: one worker process per core (heads are independent; the
+    oracle's NumPy code holds the interpreter lock most of the time, so threads would not
+    scale), each running the same number of single-head passes.  tokens/s of the full job =
+    B * N / (wall time per head-pass * B * H_q).  Must run before this process touches the GPU:
+    the workers are fresh interpreters started by multiprocessing's spawn method."""
+    import multiprocessing as mp
+    host_cores = len(os.sched_getaffinity(0))
+    ctx = mp.get_context("spawn")
+    with ctx.Pool(host_cores) as pool:
+        t_one = pool.map(_cpu_worker, [(w.name, 0, 1)])[0][0]                 # sizes the sample
+        passes = max(1, int(target_seconds / max(2.0 * t_one, 1e-3)))            # passes slow down when all cores are busy
+        t0 = time.perf_counter()
+        res = pool.map(_cpu_worker, [(w.name, i, passes) for i in range(host_cores)], chunksize=1)
+        wall_all = time.perf_counter() - t0
+    wall = max(r[0] for r in res)                                                # timed part of the slowest worker
+    cpu = sum(r[1] for r in res)
+    heads = passes * host_cores
+    tokens_per_s = w.batch * w.seq_len / (wall / heads * w.batch * w.n_q_heads)
     return {
         "value": tokens_per_s, "unit": "tokens/s", "cores": max(1, int(round(cpu / wall))),
-        "host_cores": len(os.sched_getaffinity(0)), "kind": "oracle",
+        "host_cores": host_cores, "kind": "oracle",
         "sample": f"{heads} single-head passes of {w.name} (all {w.seq_len} tokens, all hops"
                   f"{', forward + backward' if w.backward else ''}; the job has "
-                  f"{w.batch * w.n_q_heads} such heads), {wall:.1f} s wall; scaled by heads",
+                  f"{w.batch * w.n_q_heads} such heads), {passes} on each of {host_cores} worker processes, {wall:.1f} s wall "
+                  f"({wall_all:.1f} s with process start-up), {cpu:.1f} s CPU; one pass on an otherwise idle machine takes "
+                  f"{t_one * 1e3:.0f} ms; scaled by heads",
     }
+
+
+def full_attention_reference(torch, ta, workloads):
+    """Plain causal attention (tensor order 1: one hop over the whole sequence, the library's
+    streaming kernel) on the same GPU at the two sequence lengths, and the tensorized / full time
+    ratio next to the paper's whole-model figures for the same lengths (Table 3, Llama-8B row:
+    context only, another machine and a whole model)."""
+    from paper_2410_20926_amd.workloads import Workload
+    out = {}
+    for name, paper_ratio in (("c3", 0.25), ("c4", 0.09)):
+        w, tens_ms = workloads[name]
+        full = Workload(f"{name}_order1", w.index, "bf16", w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, (w.seq_len,), True, w.qk_prescale)
+        plan, sets, wsb, scb = make_sets(torch, full, 1)
+        steps = 5 if w.seq_len <= 32768 else 3
+        wall = time_steps(torch, ta, plan, sets, wsb, scb, False, steps, 1)
+        ms = wall / steps * 1e3
+        out[f"N={w.seq_len}"] = {"full_attention_ms": round(ms, 3), "tensorized_ms": round(tens_ms, 4), "kernel": plan.hop_kernel(0, 0),
+                                 "tensorized_over_full": round(tens_ms / ms, 5), "paper_table3_llama8b_whole_model": paper_ratio}
+        del sets
+        torch.cuda.empty_cache()
+    return out
 
 
 def measure(torch, ta, w, args, steps, warmup):
@@ -226,14 +268,16 @@ def measure(torch, ta, w, args, steps, warmup):
     achieved = nb / sec / 1e9
     # HBM bytes per launch from the hardware counters of an earlier rocprofv3 --pmc run of this
     # command (FETCH_SIZE and WRITE_SIZE, scaled by the copy kernel; see profiles/), when one is stored
-    traffic = None
+    traffic, traffic_source = None, None
     tpath = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
     if os.path.exists(tpath):
         rec = json.load(open(tpath)).get(dom)
         if rec:
             traffic = rec["fetch_bytes_per_launch"] + rec["write_bytes_per_launch"]
+            traffic_source = (f"stored: profiles/traffic_{w.name}.json, written by `python -m paper_2410_20926_amd.counters` from the "
+                              f"rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs listed in profiles/tensattn_{w.name}.txt (not measured in this run)")
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_source,
                 "avg_launch_us": round(sec / launches * 1e6, 2), "algorithmic_bytes_per_launch": nb / launches,
                 "launches_timed": launches, "per_hop": hops}
 
@@ -254,9 +298,11 @@ def main():
         print("bench.py: this build measures one GPU only (every box here has one); run with --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+    from paper_2410_20926_amd.workloads import WORKLOADS
+    # the CPU baseline runs first: its worker processes must exist before this process initialises the GPU
+    cpu = None if args.no_cpu_baseline else cpu_baseline(WORKLOADS[args.workload], args.cpu_seconds)
     import torch
     import paper_2410_20926_amd as ta
-    from paper_2410_20926_amd.workloads import WORKLOADS
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
@@ -264,9 +310,11 @@ def main():
     w = WORKLOADS[args.workload]
     tokens_per_s, ms_per_step, roofline = measure(torch, ta, w, args, args.steps, args.warmup)
     others = {}
+    step_ms = {args.workload: ms_per_step}
     for name in [x for x in args.also.split(",") if x and x != args.workload]:
         ow = WORKLOADS[name]
         tps, ms, rf = measure(torch, ta, ow, args, max(5, args.steps // 2), max(2, args.warmup // 2))
+        step_ms[name] = ms
         others[name] = {"tokens_per_s": tps, "ms_per_step": ms, "workload": describe(ow),
                         "roofline_kernel": rf["kernel"], "roofline_GBps": rf["achieved"], "roofline_frac": rf["frac"],
                         "per_hop": [{k_: h_[k_] for k_ in ("pass", "hop", "n", "kernel", "us", "GBps", "frac_of_8TBps")}
@@ -301,8 +349,10 @@ def main():
     }
     if others:
         out["other_workloads"] = others
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, args.cpu_seconds)
+    if "c3" in step_ms and "c4" in step_ms:
+        out["full_attention_same_gpu"] = full_attention_reference(torch, ta, {n_: (WORKLOADS[n_], step_ms[n_]) for n_ in ("c3", "c4")})
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out), flush=True)
 
 

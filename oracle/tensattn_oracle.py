@@ -221,7 +221,8 @@ def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
                                   hop_order: Optional[Sequence[int]] = None,
                                   window: Optional[Sequence[int]] = None,
                                   valid_len: Optional[int] = None,
-                                  axis_masks: Optional[Sequence[Optional[np.ndarray]]] = None):
+                                  axis_masks: Optional[Sequence[Optional[np.ndarray]]] = None,
+                                  trace: Optional[dict] = None):
     """Gradient of L = sum(O * d_o) through Algorithm 1 w.r.t. q, k, v.
 
     Hops are undone in reverse.  For one hop on one fibre with rows Qs, Ks,
@@ -232,7 +233,12 @@ def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
         dS     = A o (dA - rowsum(A o dA))
         dQs   += dS Ks * scale ;  dKs += dS^T Qs * scale
     The gradient reaching O_0 is dV; dK and dV of a key/value head are the sums
-    over the query heads that share it.  Returns (dq, dk, dv) in float64."""
+    over the query heads that share it.  Returns (dq, dk, dv) in float64.
+
+    `trace`, when a dict is given, receives the separate terms of those sums and changes
+    nothing else: "dq_hops"[pos] and "dk_hops"[pos] ([B, N, H_q, D] each, per QUERY head) are
+    what the hop executed at position pos adds to dq and dk, "dv_heads" [B, N, H_q, Dv] is the
+    gradient reaching O_0 per query head (the tests build error bounds from them)."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
@@ -250,6 +256,10 @@ def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
     dq = np.zeros_like(q)
     dk = np.zeros_like(k)
     dv = np.zeros_like(v)
+    if trace is not None:
+        trace["dq_hops"] = [np.zeros_like(q) for _ in order]
+        trace["dk_hops"] = [np.zeros_like(q) for _ in order]
+        trace["dv_heads"] = np.zeros((B, N, Hq, v.shape[3]))
     for b in range(B):
         for h in range(Hq):
             g = h // G
@@ -270,8 +280,13 @@ def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
                 dKi = np.matmul(np.swapaxes(dS, -1, -2), Qi) * scale
                 dq[b, :, h, :] += np.moveaxis(dQi, -2, axis).reshape(N, D)
                 dk[b, :, g, :] += np.moveaxis(dKi, -2, axis).reshape(N, D)
+                if trace is not None:
+                    trace["dq_hops"][pos][b, :, h, :] = np.moveaxis(dQi, -2, axis).reshape(N, D)
+                    trace["dk_hops"][pos][b, :, h, :] = np.moveaxis(dKi, -2, axis).reshape(N, D)
                 grad = np.moveaxis(dX, -2, axis).reshape(N, v.shape[3])
             dv[b, :, g, :] += grad
+            if trace is not None:
+                trace["dv_heads"][b, :, h, :] = grad
     return dq, dk, dv
 
 

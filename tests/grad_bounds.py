@@ -49,3 +49,67 @@ def gradient_magnitudes(q, k, v, d_o, dims, causal, scale=None, hop_order=None, 
                 ga = np.moveaxis(np.matmul(np.swapaxes(A, -1, -2), Gi), -2, ax).reshape(N, v.shape[3])
             Mv[b, :, g, :] += ga
     return Mq, Mk, Mv
+
+
+HALF_ULP_BF16 = 2.0 ** -8          # largest relative error of one rounding to bfloat16 (8 significant bits)
+
+
+def backward_reference_and_tolerance(q, k, v, d_o, dims, causal, dtype, launch_heads=8, scale=None, hop_order=None, **mask_kw):
+    """The oracle's (dq, dk, dv) and, for each, a per-element tolerance for the HIP path.
+
+    bf16:  tol = 2e-2 + 2^-8 * R, where R sums the absolute values of every quantity that the path
+    stores in bf16 on the way to that element:
+      dq  its running sum after each processed hop (hops are undone last to first; each adds
+          its share to the stored dq and rounds), the last of which is the result itself;
+      dk  the same, per launch: a launch covers up to `launch_heads` query heads of a group,
+          sums them in fp32, adds the stored dk and rounds;
+      dv  the group sum per launch, plus (m - 1) times the magnitude sum of the gradient chain
+          (gradient_magnitudes), for the m - 1 inter-hop gradients stored in bf16.
+    The absolute 2e-2 is the forward's bound and covers the roundings of matrix-core operands
+    (attention weights, dS, the saved inter-hop O).
+    fp32:  tol = 1e-5 + 2^-20 * M with M from gradient_magnitudes (fp32 sums of up to n_i * D terms)."""
+    trace = {}
+    ref = orc.tensorized_attention_backward(q, k, v, d_o, dims, causal, scale, hop_order, trace=trace, **mask_kw)
+    Mq, Mk, Mv = gradient_magnitudes(q, k, v, d_o, dims, causal, scale, hop_order, **mask_kw)
+    if dtype == "f32":
+        return ref, tuple(1e-5 + 2.0 ** -20 * m for m in (Mq, Mk, Mv))
+    B, N, Hq, D = np.asarray(q).shape
+    Hkv = np.asarray(k).shape[2]
+    G = Hq // Hkv
+    m = len(dims)
+    Rq, Rk, Rv = np.zeros_like(ref[0]), np.zeros_like(ref[1]), (m - 1) * Mv
+    run_q = np.zeros_like(ref[0])
+    run_k = np.zeros_like(ref[1])
+    for pos in range(m - 1, -1, -1):
+        run_q = run_q + trace["dq_hops"][pos]
+        Rq += np.abs(run_q)
+        for base in range(0, G, launch_heads):
+            hs = np.arange(base, min(base + launch_heads, G))
+            run_k = run_k + trace["dk_hops"][pos].reshape(B, N, Hkv, G, D)[:, :, :, hs].sum(3)
+            Rk += np.abs(run_k)
+    run_v = np.zeros_like(ref[2])
+    for base in range(0, G, launch_heads):
+        hs = np.arange(base, min(base + launch_heads, G))
+        run_v = run_v + trace["dv_heads"].reshape(B, N, Hkv, G, -1)[:, :, :, hs].sum(3)
+        Rv = Rv + np.abs(run_v)
+    return ref, (2e-2 + HALF_ULP_BF16 * Rq, 2e-2 + HALF_ULP_BF16 * Rk, 2e-2 + HALF_ULP_BF16 * Rv)
+
+
+def check_gradient(got, ref, tol, what, report=None):
+    """Element-wise |got - ref| <= tol; returns (and optionally records) the largest error / tolerance."""
+    assert np.isfinite(got).all(), f"{what}: non-finite gradient"
+    err = np.abs(got - ref)
+    ratio = float((err / tol).max())
+    line = (f"{what}: max|err| {err.max():.3e}, max|ref| {np.abs(ref).max():.3e}, "
+            f"largest error / tolerance {ratio:.3f}")
+    print(line)
+    if report is not None:
+        report.append(line)
+    assert ratio <= 1.0, line
+    return ratio
+
+
+def check_backward(got, q, k, v, d_o, dims, causal, dtype, what="", **oracle_kw):
+    """(dq, dk, dv) of the HIP path against the oracle, element by element, to the tolerance above."""
+    ref, tol = backward_reference_and_tolerance(q, k, v, d_o, dims, causal, dtype, **oracle_kw)
+    return max(check_gradient(g_, r_, t_, f"{what} {name}".strip()) for g_, r_, t_, name in zip(got, ref, tol, ("dq", "dk", "dv")))

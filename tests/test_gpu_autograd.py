@@ -8,7 +8,7 @@ from gpu_util import TOL, to_dev, to_host
 from oracle import tensattn_oracle as orc
 from paper_2410_20926_amd.autograd import tensorized_attention
 from paper_2410_20926_amd.workloads import make_inputs
-from test_gpu_backward import check_grad
+from grad_bounds import check_backward
 
 pytestmark = pytest.mark.gpu
 
@@ -25,10 +25,7 @@ def test_autograd_matches_oracle(dims, B, Hq, Hkv, D, causal, dtype):
     o = tensorized_attention(tq, tk, tv, dims, causal)
     assert np.abs(to_host(o) - orc.tensorized_attention_forward(q, k, v, dims, causal)).max() <= TOL[dtype]
     o.backward(to_dev(d_o, dtype))
-    rq, rk, rv = orc.tensorized_attention_backward(q, k, v, d_o, dims, causal)
-    check_grad(to_host(tq.grad), rq, dtype, "dq")
-    check_grad(to_host(tk.grad), rk, dtype, "dk")
-    check_grad(to_host(tv.grad), rv, dtype, "dv")
+    check_backward((to_host(tq.grad), to_host(tk.grad), to_host(tv.grad)), q, k, v, d_o, dims, causal, dtype)
 
 
 def test_autograd_without_grad_keeps_nothing():

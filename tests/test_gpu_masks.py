@@ -9,7 +9,7 @@ import paper_2410_20926_amd as ta
 from gpu_util import TOL, multihop_backward, multihop_forward
 from oracle import tensattn_oracle as orc
 from paper_2410_20926_amd.workloads import make_inputs
-from test_gpu_backward import check_grad
+from grad_bounds import check_backward
 
 pytestmark = pytest.mark.gpu
 
@@ -60,10 +60,7 @@ def test_masked_backward_matches_oracle(dims, B, Hq, Hkv, D, causal, dtype, wind
         kw["valid_len"] = valid_len
     _, plan, dev = multihop_forward(q, k, v, dims, dtype, causal, save=True, **kw)
     dq, dk, dv = multihop_backward(plan, dev, d_o, dtype)
-    rq, rk, rv = orc.tensorized_attention_backward(q, k, v, d_o, dims, causal, window=window, valid_len=valid_len)
-    check_grad(dq, rq, dtype, "dq")
-    check_grad(dk, rk, dtype, "dk")
-    check_grad(dv, rv, dtype, "dv")
+    check_backward((dq, dk, dv), q, k, v, d_o, dims, causal, dtype, window=window, valid_len=valid_len)
     if valid_len is not None:
         assert (dq[:, valid_len:] == 0).all() and (dk[:, valid_len:] == 0).all() and (dv[:, valid_len:] == 0).all()
 
@@ -138,11 +135,7 @@ def test_table_backward_matches_oracle(dims, B, Hq, Hkv, D, causal, dtype, axes,
         kw["valid_len"] = valid_len
     _, plan, devt = multihop_forward(q, k, v, dims, dtype, causal, save=True, **kw)
     dq, dk, dv = multihop_backward(plan, devt, d_o, dtype)
-    rq, rk, rv = orc.tensorized_attention_backward(q, k, v, d_o, dims, causal, window=window, valid_len=valid_len,
-                                                   axis_masks=host)
-    check_grad(dq, rq, dtype, "dq")
-    check_grad(dk, rk, dtype, "dk")
-    check_grad(dv, rv, dtype, "dv")
+    check_backward((dq, dk, dv), q, k, v, d_o, dims, causal, dtype, window=window, valid_len=valid_len, axis_masks=host)
 
 
 def test_table_spelling_causal_is_bit_identical_to_the_causal_flag():

@@ -7,7 +7,7 @@ import torch
 
 import paper_2410_20926_amd as ta
 from gpu_util import TOL, multihop_backward, multihop_forward, to_dev, to_host
-from test_gpu_backward import check_grad
+from grad_bounds import check_backward
 from oracle import tensattn_oracle as orc
 from paper_2410_20926_amd.workloads import make_inputs, round_to_bf16
 
@@ -111,10 +111,7 @@ def test_multihop_forward_and_backward_with_the_pair():
     assert np.abs(fused - ref).max() <= TOL["bf16"] and np.array_equal(saved, fused)
     # the saving forward wrote both intermediate O tensors: the backward that reads them matches the oracle
     dq, dk, dv = multihop_backward(plan_s, dev, d_o, "bf16")
-    rq, rk, rv = orc.tensorized_attention_backward(q, k, v, d_o, dims, True)
-    check_grad(dq, rq, "bf16", "dq")
-    check_grad(dk, rk, "bf16", "dk")
-    check_grad(dv, rv, "bf16", "dv")
+    check_backward((dq, dk, dv), q, k, v, d_o, dims, True, "bf16")
     # another hop order: the pair is not at the end, every hop runs on its own
     swapped, plan2, _ = multihop_forward(q, k, v, dims, "bf16", True, hop_order=(1, 0, 2))
     assert plan2.fused_position() == -1
@@ -183,10 +180,7 @@ def test_pair_at_other_head_widths(causal, valid_len, Hq, Hkv, D):
     saved, plan_s, dev = multihop_forward(q, k, v, dims, "bf16", causal, save=True, **kw)
     assert np.array_equal(saved, got)
     dq, dk, dv = multihop_backward(plan_s, dev, d_o, "bf16")
-    rq, rk, rv = orc.tensorized_attention_backward(q, k, v, d_o, dims, causal, valid_len=valid_len)
-    check_grad(dq, rq, "bf16", "dq")
-    check_grad(dk, rk, "bf16", "dk")
-    check_grad(dv, rv, "bf16", "dv")
+    check_backward((dq, dk, dv), q, k, v, d_o, dims, causal, "bf16", valid_len=valid_len)
 
 
 @pytest.mark.parametrize("kw", [dict(dims=(32, 16)), dict(dims=(32, 32, 2)),

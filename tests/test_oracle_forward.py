@@ -142,7 +142,7 @@ def test_separable_scores_give_numpy_kron(causal):
     got = orc.tensorized_attention_forward(q[None, :, None], k[None, :, None], v[None, :, None],
                                            dims, causal, scale=scale)[0, :, 0]
     np.testing.assert_allclose(got, W @ v, rtol=0, atol=1e-12)
-    # the paper's "irrelevant to the order of updating" holds here
+    # the order of the hops does not matter here (Sec. 3.1 claims it in general)
     for order in [(2, 1, 0), (1, 0, 2)]:
         alt = orc.tensorized_attention_forward(q[None, :, None], k[None, :, None],
                                                v[None, :, None], dims, causal, scale=scale,
@@ -289,13 +289,44 @@ def test_grouped_query_equals_repeated_kv():
 
 # --- complexity model (App. C.2 with the fibre count restored) ------------------------------
 
-def test_flop_count_matches_closed_form():
+def test_flop_count_of_an_instrumented_hop_matches_the_cost_models():
+    """Counts the multiplications and additions of Eq. 4 while executing it with scalar loops (one
+    fibre at a time: n x n scores of D products each, then n x n weights applied to D features),
+    checks the loop's result against the oracle, and compares the count with the closed form
+    4 N n_i D per head and hop (App. C.2's table with the fibre count N / n_i restored) and with
+    the library's own cost model, which the benchmark reports."""
+    import paper_2410_20926_amd as ta
     dims, D = (4, 3, 5), 8
     N = int(np.prod(dims))
+    rng = np.random.default_rng(7)
+    q, k, x = rng.standard_normal((N, D)), rng.standard_normal((N, D)), rng.standard_normal((N, D))
+    strides = orc.axis_strides(dims)
+    plan = ta.ta_plan_create(1, 1, 1, D, dims, ta.TA_F32, False)
     total = 0
-    for n in dims:
-        fibres = N // n
-        total += fibres * (2 * n * n * D + 2 * n * n * D)
+    for axis, n in enumerate(dims):
+        flops = 0
+        out = np.zeros_like(x)
+        for f in range(N // n):
+            outer, inner = divmod(f, strides[axis])
+            rows = [outer * strides[axis] * n + inner + a * strides[axis] for a in range(n)]
+            s = np.zeros((n, n))
+            for a in range(n):
+                for c in range(n):
+                    acc = 0.0
+                    for e in range(D):
+                        acc += q[rows[a], e] * k[rows[c], e]
+                        flops += 2
+                    s[a, c] = acc / np.sqrt(D)
+            p = np.exp(s - s.max(1, keepdims=True))
+            p /= p.sum(1, keepdims=True)
+            for a in range(n):
+                for c in range(n):
+                    for e in range(D):
+                        out[rows[a], e] += p[a, c] * x[rows[c], e]
+                        flops += 2
+        np.testing.assert_allclose(out, orc.axis_attention(q, k, x, dims, axis, 1 / np.sqrt(D), False), rtol=0, atol=1e-12)
+        assert flops == 4 * N * n * D == plan.hop_flops(axis)
+        total += flops
     assert total == 4 * N * D * sum(dims)
     fact = json.load(open(GOLDEN))["tensor3_parameter_count"]
     assert fact["rank"] * sum(n * n for n in fact["dims"]) == fact["parameters"]
