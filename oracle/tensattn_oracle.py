@@ -30,7 +30,11 @@ Readings taken where the paper is silent:
     c <= a when causal) and padding (tokens at or past `valid_len` are never attended
     to; their own rows see nothing and come out as zero), and an explicit n_i x n_i
     boolean table per axis (`axis_masks`), all of them intersected; a row left with no
-    visible key comes out as zero.
+    visible key comes out as zero.  `valid_len` may also be one length per batch element
+    (Eq. 3's M_i is one table per fibre: sequences of different lengths in one batch);
+  - tensorized positional encoding inside the hops (Sec. 3.2), `rope_base`: the hop along
+    axis i scores with Q and K rotated by their coordinate on that axis (`tensorized_rope`
+    with axis = i), so that its attention depends on j_i - k_i; the value path is untouched.
 
 Parity pins (tests/test_oracle_*.py): d=1 against a library attention
 routine, row sums, brute-force N x N Kronecker-form operator built with scalar
@@ -160,14 +164,24 @@ def _hop_order(m: int, hop_order: Optional[Sequence[int]]) -> list:
     return order
 
 
+def _per_batch(valid_len, B: int) -> list:
+    """valid_len as a list of B entries (None = no padding)."""
+    if valid_len is None or np.isscalar(valid_len):
+        return [valid_len] * B
+    out = [int(x) for x in valid_len]
+    assert len(out) == B, "one valid_len per batch element"
+    return out
+
+
 def tensorized_attention_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
                                  dims: Sequence[int], causal: bool,
                                  scale: Optional[float] = None,
                                  hop_order: Optional[Sequence[int]] = None,
                                  return_intermediates: bool = False,
                                  window: Optional[Sequence[int]] = None,
-                                 valid_len: Optional[int] = None,
-                                 axis_masks: Optional[Sequence[Optional[np.ndarray]]] = None):
+                                 valid_len=None,
+                                 axis_masks: Optional[Sequence[Optional[np.ndarray]]] = None,
+                                 rope_base: Optional[float] = None):
     """Algorithm 1.
 
     q: [B, N, H_q, D]; k, v: [B, N, H_kv, D] (H_q a multiple of H_kv);
@@ -175,7 +189,10 @@ def tensorized_attention_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
     `return_intermediates` also returns the list [O_0, O_1, ..., O_m] (O_0 is V
     expanded to H_q heads, O_j the value tensor after the j-th executed hop)
     and the list of attention tensors A per executed hop, each of shape
-    [B, H_q] + batch dims + [n, n]."""
+    [B, H_q] + batch dims + [n, n].
+    `valid_len`: None, one length for every batch element, or a sequence of B lengths.
+    `rope_base`: None, or the base of the per-axis rotary encoding applied to Q and K inside
+    every hop (the hop along axis i uses tensorized_rope(., dims, axis=i, base))."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
@@ -192,15 +209,21 @@ def tensorized_attention_forward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
     window = [0] * len(dims) if window is None else [int(x) for x in window]
     axis_masks = [None] * len(dims) if axis_masks is None else list(axis_masks)
 
+    valid_lens = _per_batch(valid_len, B)
+    # the Q and K every hop scores with: as given, or rotated by the coordinate on the hop's axis
+    q_hop = {axis: q if rope_base is None else tensorized_rope(q, dims, axis, rope_base) for axis in order}
+    k_hop = {axis: k if rope_base is None else tensorized_rope(k, dims, axis, rope_base) for axis in order}
+
     o = np.empty((B, N, Hq, v.shape[3]), dtype=np.float64)
     inter = [np.repeat(v, G, axis=2)] + [np.empty_like(o) for _ in order]
     probs = [None] * len(order)
     for b in range(B):
+        valid_len = valid_lens[b]
         for h in range(Hq):
             g = h // G
-            qh, kh = q[b, :, h, :], k[b, :, g, :]
             oh = v[b, :, g, :]                      # Initialise O = V
             for pos, axis in enumerate(order):
+                qh, kh = q_hop[axis][b, :, h, :], k_hop[axis][b, :, g, :]
                 if return_intermediates:
                     oh, A = axis_attention(qh, kh, oh, dims, axis, scale, causal, True, window[axis], valid_len, axis_masks[axis])
                     if probs[pos] is None:
@@ -220,9 +243,10 @@ def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
                                   causal: bool, scale: Optional[float] = None,
                                   hop_order: Optional[Sequence[int]] = None,
                                   window: Optional[Sequence[int]] = None,
-                                  valid_len: Optional[int] = None,
+                                  valid_len=None,
                                   axis_masks: Optional[Sequence[Optional[np.ndarray]]] = None,
-                                  trace: Optional[dict] = None):
+                                  trace: Optional[dict] = None,
+                                  rope_base: Optional[float] = None):
     """Gradient of L = sum(O * d_o) through Algorithm 1 w.r.t. q, k, v.
 
     Hops are undone in reverse.  For one hop on one fibre with rows Qs, Ks,
@@ -234,6 +258,9 @@ def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
         dQs   += dS Ks * scale ;  dKs += dS^T Qs * scale
     The gradient reaching O_0 is dV; dK and dV of a key/value head are the sums
     over the query heads that share it.  Returns (dq, dk, dv) in float64.
+    With `rope_base` the hop scores with rotated Q and K (see the forward): Qs, Ks above are the
+    rotated rows, and the hop's dQs, dKs are rotated back (the rotation's transpose is its
+    inverse) before they are added to dq, dk.
 
     `trace`, when a dict is given, receives the separate terms of those sums and changes
     nothing else: "dq_hops"[pos] and "dk_hops"[pos] ([B, N, H_q, D] each, per QUERY head) are
@@ -251,7 +278,15 @@ def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
         scale = 1.0 / math.sqrt(D)
     order = _hop_order(len(dims), hop_order)
     _, inter, probs = tensorized_attention_forward(
-        q, k, v, dims, causal, scale, order, return_intermediates=True, window=window, valid_len=valid_len, axis_masks=axis_masks)
+        q, k, v, dims, causal, scale, order, return_intermediates=True, window=window, valid_len=valid_len, axis_masks=axis_masks,
+        rope_base=rope_base)
+    q_hop = {axis: q if rope_base is None else tensorized_rope(q, dims, axis, rope_base) for axis in order}
+    k_hop = {axis: k if rope_base is None else tensorized_rope(k, dims, axis, rope_base) for axis in order}
+
+    def unrotate(x, axis):                      # [N, D] gradient w.r.t. rotated rows -> w.r.t. the rows as given
+        if rope_base is None:
+            return x
+        return tensorized_rope(x[None, :, None, :], dims, axis, rope_base, inverse=True)[0, :, 0, :]
 
     dq = np.zeros_like(q)
     dk = np.zeros_like(k)
@@ -271,18 +306,20 @@ def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
                 shape_v = dims + [v.shape[3]]
                 Gi = np.moveaxis(grad.reshape(shape_v), axis, -2)
                 Xi = np.moveaxis(inter[pos][b, :, h, :].reshape(shape_v), axis, -2)
-                Qi = np.moveaxis(q[b, :, h, :].reshape(shape_d), axis, -2)
-                Ki = np.moveaxis(k[b, :, g, :].reshape(shape_d), axis, -2)
+                Qi = np.moveaxis(q_hop[axis][b, :, h, :].reshape(shape_d), axis, -2)
+                Ki = np.moveaxis(k_hop[axis][b, :, g, :].reshape(shape_d), axis, -2)
                 dA = np.matmul(Gi, np.swapaxes(Xi, -1, -2))
                 dX = np.matmul(np.swapaxes(A, -1, -2), Gi)
                 dS = A * (dA - np.sum(A * dA, axis=-1, keepdims=True))
                 dQi = np.matmul(dS, Ki) * scale
                 dKi = np.matmul(np.swapaxes(dS, -1, -2), Qi) * scale
-                dq[b, :, h, :] += np.moveaxis(dQi, -2, axis).reshape(N, D)
-                dk[b, :, g, :] += np.moveaxis(dKi, -2, axis).reshape(N, D)
+                dq_hop = unrotate(np.moveaxis(dQi, -2, axis).reshape(N, D), axis)
+                dk_hop = unrotate(np.moveaxis(dKi, -2, axis).reshape(N, D), axis)
+                dq[b, :, h, :] += dq_hop
+                dk[b, :, g, :] += dk_hop
                 if trace is not None:
-                    trace["dq_hops"][pos][b, :, h, :] = np.moveaxis(dQi, -2, axis).reshape(N, D)
-                    trace["dk_hops"][pos][b, :, h, :] = np.moveaxis(dKi, -2, axis).reshape(N, D)
+                    trace["dq_hops"][pos][b, :, h, :] = dq_hop
+                    trace["dk_hops"][pos][b, :, h, :] = dk_hop
                 grad = np.moveaxis(dX, -2, axis).reshape(N, v.shape[3])
             dv[b, :, g, :] += grad
             if trace is not None:

@@ -211,3 +211,26 @@ def test_explicit_mask_backward_matches_finite_differences(causal):
             flat[i] = old
             fd = (fp - fm) / 2e-5
             assert abs(fd - g.reshape(-1)[i]) <= 1e-6 * max(1e-3, abs(fd)) + 1e-9
+
+
+def test_valid_len_per_batch_element():
+    """One length per batch element (Eq. 3's M_i is a table per fibre; sequences of different lengths in
+    a batch are its everyday case): every batch element behaves as if run alone with its own length,
+    checked against the scalar-loop operator, forward and (dV = W^T dO) backward; length 0 = all padding."""
+    import bruteforce as bf
+    dims, D = (3, 2, 2), 4
+    N = 12
+    rng = np.random.default_rng(91)
+    lens = [12, 7, 0, 1]
+    B = len(lens)
+    q, k, v, d_o = (rng.standard_normal((B, N, 1, D)) for _ in range(4))
+    for causal in (False, True):
+        got = orc.tensorized_attention_forward(q, k, v, dims, causal, scale=0.7, valid_len=lens)
+        dq, dk, dv = orc.tensorized_attention_backward(q, k, v, d_o, dims, causal, scale=0.7, valid_len=lens)
+        for b, L in enumerate(lens):
+            W = np.array(bf.operator_by_products(q[b, :, 0].tolist(), k[b, :, 0].tolist(), dims, 0.7, causal, valid_len=L))
+            np.testing.assert_allclose(got[b, :, 0], W @ v[b, :, 0], rtol=0, atol=1e-12)
+            np.testing.assert_allclose(dv[b, :, 0], W.T @ d_o[b, :, 0], rtol=0, atol=1e-12)
+            assert (got[b, L:] == 0).all() and (dq[b, L:] == 0).all() and (dk[b, L:] == 0).all() and (dv[b, L:] == 0).all()
+            alone = orc.tensorized_attention_forward(q[b:b + 1], k[b:b + 1], v[b:b + 1], dims, causal, scale=0.7, valid_len=L)
+            np.testing.assert_array_equal(alone[0], got[b])
