@@ -89,6 +89,26 @@ typedef struct ta_desc_t {
                                          batch element).  4-byte aligned, caller-owned, read-only, and must
                                          stay valid and unchanged while the plan is in use; entries at or
                                          beyond `order` are ignored. */
+    const int64_t* valid_lens;        /* DEVICE pointer to B lengths, or NULL.  Eq. 3's M_i is one table per fibre;
+                                         this is its everyday case, sequences of different lengths in one batch:
+                                         batch element b is padded from token valid_lens[b] on (values are clamped
+                                         to 0..N; 0 = the whole element is padding; combined with valid_len by
+                                         taking the smaller).  8-byte aligned, caller-owned, read when a kernel
+                                         runs: it may change between calls, not while one is in flight. */
+    /* Tensorized positional encoding inside the hops (Sec. 3.2: a token's position is the vector of its
+     * tensor coordinates, and the rotary encoding is applied per axis).  With rope = 1 the hop along axis i
+     * scores with Q and K rotated by their coordinate j_i on that axis - feature pair (2p, 2p+1) turned by
+     * j_i * rope_base^(-2p / head_dim) radians - so that its attention depends on j_i - k_i; the kernels turn
+     * the rows between the global load and the matrix cores, and the backward turns dQ and dK back: no
+     * encoded copy of Q or K ever exists in memory.  Values are not encoded.  Pairs are INTERLEAVED
+     * neighbours; a model whose rotary pairs are (p, p + head_dim/2) gets the same scores by permuting the
+     * columns of its query and key projections once (scores are invariant under a common feature
+     * permutation).  Which features take which axis is not in the paper: this per-hop form is a reading.
+     * The matrix-core kernels take it for axes of up to 4,096 positions (fp32 angles); longer axes, and
+     * fp32 tensors, run on the generic kernels (double-precision angles).  The fused pair of hops is not
+     * used with it. */
+    int32_t rope;                     /* 0 or 1 */
+    float   rope_base;                /* the base; 0 means 10000 */
 } ta_desc_t;
 
 typedef struct ta_plan ta_plan_t;     /* opaque, immutable, host-only, shareable between threads */

@@ -265,7 +265,9 @@ def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
     `trace`, when a dict is given, receives the separate terms of those sums and changes
     nothing else: "dq_hops"[pos] and "dk_hops"[pos] ([B, N, H_q, D] each, per QUERY head) are
     what the hop executed at position pos adds to dq and dk, "dv_heads" [B, N, H_q, Dv] is the
-    gradient reaching O_0 per query head (the tests build error bounds from them)."""
+    gradient reaching O_0 per query head, and "dq_sq", "dk_sq" ([B, N, H_q, D]) are the sums of
+    the SQUARES of the individual products dS[a,c] K[c,x] scale and dS[a,c] Q[a,x] scale that
+    make up dq and dk over all hops (the tests build error bounds from all of them)."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
@@ -295,6 +297,8 @@ def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
         trace["dq_hops"] = [np.zeros_like(q) for _ in order]
         trace["dk_hops"] = [np.zeros_like(q) for _ in order]
         trace["dv_heads"] = np.zeros((B, N, Hq, v.shape[3]))
+        trace["dq_sq"] = np.zeros_like(q)
+        trace["dk_sq"] = np.zeros_like(q)
     for b in range(B):
         for h in range(Hq):
             g = h // G
@@ -320,6 +324,8 @@ def tensorized_attention_backward(q: np.ndarray, k: np.ndarray, v: np.ndarray,
                 if trace is not None:
                     trace["dq_hops"][pos][b, :, h, :] = dq_hop
                     trace["dk_hops"][pos][b, :, h, :] = dk_hop
+                    trace["dq_sq"][b, :, h, :] += np.moveaxis(np.matmul(dS ** 2, Ki ** 2) * scale ** 2, -2, axis).reshape(N, D)
+                    trace["dk_sq"][b, :, h, :] += np.moveaxis(np.matmul(np.swapaxes(dS, -1, -2) ** 2, Qi ** 2) * scale ** 2, -2, axis).reshape(N, D)
                 grad = np.moveaxis(dX, -2, axis).reshape(N, v.shape[3])
             dv[b, :, g, :] += grad
             if trace is not None:

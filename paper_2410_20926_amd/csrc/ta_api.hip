@@ -131,6 +131,14 @@ ta::HopParams hop_params(const ta_plan* pl, int axis, const void* q, const void*
     hp.valid_len = pl->desc.valid_len > 0 ? pl->desc.valid_len : pl->N;
     hp.mask = static_cast<const uint32_t*>(pl->desc.axis_mask[axis]);
     hp.mask_words = (pl->dims[axis] + 31) / 32;
+    hp.valid_lens = pl->desc.valid_lens;
+    hp.N = pl->N;
+    hp.rope = pl->desc.rope;
+    // pair p of a row at position a turns by a * base^(-2p/D) radians = a * exp2(c0 * p + c1) revolutions
+    const double log2_base = log2(pl->desc.rope_base > 0.f ? (double)pl->desc.rope_base : 10000.0);
+    hp.rope_log2_base = (float)log2_base;
+    hp.rope_c0 = (float)(-2.0 * log2_base / (double)pl->desc.head_dim);
+    hp.rope_c1 = (float)(-log2(2.0 * M_PI));
     return hp;
 }
 
@@ -266,6 +274,9 @@ ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
         if (d->window[i] < 0) return fail(TA_ERR_INVALID_ARG, "window[%d] = %d is negative", i, d->window[i]);
     for (int i = 0; i < d->order; ++i)
         if (reinterpret_cast<uintptr_t>(d->axis_mask[i]) % 4 != 0) return fail(TA_ERR_INVALID_ARG, "axis_mask[%d] is not 4-byte aligned", i);
+    if (reinterpret_cast<uintptr_t>(d->valid_lens) % 8 != 0) return fail(TA_ERR_INVALID_ARG, "valid_lens is not 8-byte aligned");
+    if (d->rope != 0 && d->rope != 1) return fail(TA_ERR_INVALID_ARG, "rope must be 0 or 1");
+    if (!(d->rope_base >= 0.f) || isinf(d->rope_base)) return fail(TA_ERR_INVALID_ARG, "rope_base must be finite and >= 0");
     if (d->valid_len < 0) return fail(TA_ERR_INVALID_ARG, "valid_len is negative");
     if (d->valid_len > N) return fail(TA_ERR_SHAPE, "valid_len %lld exceeds the sequence length %lld", (long long)d->valid_len, (long long)N);
     if (d->head_dim % 2 != 0 || d->head_dim > 256)

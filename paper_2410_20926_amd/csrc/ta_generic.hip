@@ -50,16 +50,51 @@ __device__ inline T* row_ptr_w(const Tensor& t, int64_t b, int64_t tok, int64_t 
     return reinterpret_cast<T*>(t.p) + b * t.sb + tok * t.st + h * t.sh;
 }
 
+// Rotary encoding inside a hop (Sec. 3.2, per-axis positions): sine and cosine of the angle by
+// which feature pair (2 pr, 2 pr + 1) of a row at position a on the hop's axis is turned,
+// a * base^(-2 pr / D), formed in double precision.
+__device__ inline void rope_angle(const HopParams& p, int a, int pr, double* sn, double* cs) {
+    const double ang = (double)a * exp2(-(2.0 * pr / (double)p.D) * (double)p.rope_log2_base);
+    sincos(ang, sn, cs);
+}
+
+// Element d of a row of Q or K at position a: as stored, or turned when the hop encodes positions.
+template <typename T>
+__device__ inline float enc_load(const HopParams& p, bool rope, const T* row, int d, int a) {
+    const float x = to_f32(row[d]);
+    if (!rope) return x;
+    const float y = to_f32(row[d ^ 1]);                // the other feature of the pair
+    double sn, cs;
+    rope_angle(p, a, d >> 1, &sn, &cs);
+    return (float)((d & 1) ? (double)y * sn + (double)x * cs : (double)x * cs - (double)y * sn);
+}
+
+// A gradient element with respect to a turned row, taken back to the row as stored (the turn's
+// transpose): `x` is this lane's element d, the pair's other element sits in lane ^ 1.  Every
+// lane of the wave must call it.
+__device__ inline float enc_grad(const HopParams& p, float x, int d, int a) {
+    if (!p.rope) return x;
+    const float y = __shfl_xor(x, 1);
+    double sn, cs;
+    rope_angle(p, a, d >> 1, &sn, &cs);
+    return (float)((d & 1) ? (double)x * cs - (double)y * sn : (double)x * cs + (double)y * sn);
+}
+
 // Copy `rows` rows of D elements (row r at token tok0 + (r0 + r) * stride) into an LDS
-// tile of pitch `pitch` floats; rows at or past n are zero-filled.
+// tile of pitch `pitch` floats; rows at or past n are zero-filled.  With `rope` (a hop that
+// encodes positions, Q and K tiles) every row is turned by its position r0 + r on the axis.
 template <typename T>
 __device__ inline void load_tile(float* tile, int pitch, int rows, int r0, const Tensor& t,
-                                 int64_t b, int64_t tok0, int64_t stride, int64_t h, int n, int D) {
+                                 int64_t b, int64_t tok0, int64_t stride, int64_t h, int n, int D,
+                                 const HopParams* rope = nullptr) {
     for (int idx = threadIdx.x; idx < rows * D; idx += kThreads) {
         const int r = idx / D, d = idx - r * D;
         const int a = r0 + r;
         float x = 0.f;
-        if (a < n) x = to_f32(row_ptr<T>(t, b, tok0 + (int64_t)a * stride, h)[d]);
+        if (a < n) {
+            const T* row = row_ptr<T>(t, b, tok0 + (int64_t)a * stride, h);
+            x = rope ? enc_load<T>(*rope, true, row, d, a) : to_f32(row[d]);
+        }
         tile[r * pitch + d] = x;
     }
 }
@@ -94,13 +129,15 @@ __global__ __launch_bounds__(kThreads) void generic_forward_kernel(HopParams p, 
     const int g = h / p.G;
     const int hv = (p.vin_heads == p.Hq) ? h : g;
     const int64_t tok0 = fibre_base_token(f, p.stride, n);
+    p.valid_len = hop_valid_len(p, b);                  // this batch element's padding length
+    const HopParams* enc = p.rope ? &p : nullptr;       // the hop turns Q and K rows by their position
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int c_l = lane & 31, hh = lane >> 5;
     const int ncol = (D + 63) / 64;
     const int dh = D / 2;
 
-    load_tile<T>(Qs, D, kQB, qb * kQB, p.q, b, tok0, p.stride, h, n, D);
+    load_tile<T>(Qs, D, kQB, qb * kQB, p.q, b, tok0, p.stride, h, n, D, enc);
 
     float m[4], l[4], acc[4][4];
 #pragma unroll
@@ -113,7 +150,7 @@ __global__ __launch_bounds__(kThreads) void generic_forward_kernel(HopParams p, 
     const int kend = p.causal ? a_last + 1 : n;         // keys past the block's last row are masked
     for (int k0 = 0; k0 < kend; k0 += TK) {
         __syncthreads();
-        load_tile<T>(Ks, D + 1, TK, k0, p.k, b, tok0, p.stride, g, n, D);
+        load_tile<T>(Ks, D + 1, TK, k0, p.k, b, tok0, p.stride, g, n, D, enc);
         load_tile<T>(Vs, D, TK, k0, p.vin, b, tok0, p.stride, hv, n, D);
         __syncthreads();
 #pragma unroll
@@ -174,7 +211,7 @@ __global__ __launch_bounds__(kThreads) void generic_forward_kernel(HopParams p, 
 template <typename T>
 __global__ __launch_bounds__(kThreads) void generic_backward_kernel(BwdParams bp, int TK) {
     extern __shared__ float smem[];
-    const HopParams& p = bp.hop;
+    HopParams& p = bp.hop;
     const int D = p.D, n = p.n, G = p.G;
     const int pitch = D + 1;
     float* st_m = smem;                     // [G][n] row max
@@ -190,6 +227,8 @@ __global__ __launch_bounds__(kThreads) void generic_backward_kernel(BwdParams bp
     const int b = (int)(bid / p.Hkv);
     const int64_t tok0 = fibre_base_token(f, p.stride, n);
     const bool vin_is_o = (p.vin_heads == p.Hq);
+    p.valid_len = hop_valid_len(p, b);                  // this batch element's padding length
+    const HopParams* enc = p.rope ? &p : nullptr;       // the hop turns Q and K rows by their position
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int c_l = lane & 31, hh = lane >> 5;
@@ -208,14 +247,14 @@ __global__ __launch_bounds__(kThreads) void generic_backward_kernel(BwdParams bp
             if (active) {
                 const T* qrow = row_ptr<T>(p.q, b, tok0 + (int64_t)a * p.stride, h);
                 const T* grow = row_ptr<T>(bp.d_o, b, tok0 + (int64_t)a * p.stride, h);
-                for (int d = lane; d < D; d += 64) { r0[d] = to_f32(qrow[d]); r1[d] = to_f32(grow[d]); }
+                for (int d = lane; d < D; d += 64) { r0[d] = enc_load<T>(p, p.rope != 0, qrow, d, a); r1[d] = to_f32(grow[d]); }
             }
             float m = -INFINITY, l = 0.f, acc[4] = {0.f, 0.f, 0.f, 0.f};
             const int kend = p.causal ? min(n, rb * kWaves + kWaves) : n;
             // pass 1: statistics and the row of O
             for (int k0 = 0; k0 < kend; k0 += TK) {
                 __syncthreads();
-                load_tile<T>(tA, pitch, TK, k0, p.k, b, tok0, p.stride, g, n, D);
+                load_tile<T>(tA, pitch, TK, k0, p.k, b, tok0, p.stride, g, n, D, enc);
                 load_tile<T>(tB, pitch, TK, k0, p.vin, b, tok0, p.stride, hv, n, D);
                 __syncthreads();
                 if (!active) continue;
@@ -260,7 +299,7 @@ __global__ __launch_bounds__(kThreads) void generic_backward_kernel(BwdParams bp
             float dqa[4] = {0.f, 0.f, 0.f, 0.f};
             for (int k0 = 0; k0 < kend; k0 += TK) {
                 __syncthreads();
-                load_tile<T>(tA, pitch, TK, k0, p.k, b, tok0, p.stride, g, n, D);
+                load_tile<T>(tA, pitch, TK, k0, p.k, b, tok0, p.stride, g, n, D, enc);
                 load_tile<T>(tB, pitch, TK, k0, p.vin, b, tok0, p.stride, hv, n, D);
                 __syncthreads();
                 if (!active) continue;
@@ -290,8 +329,8 @@ __global__ __launch_bounds__(kThreads) void generic_backward_kernel(BwdParams bp
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int col = lane + 64 * j;
+                    float x = enc_grad(p, dqa[j] * p.scale, col, a);   // back to the row as stored (all lanes take part)
                     if (col < D) {
-                        float x = dqa[j] * p.scale;
                         if (bp.accumulate) x += to_f32(dqrow[col]);
                         from_f32(dqrow + col, x);
                     }
@@ -312,13 +351,13 @@ __global__ __launch_bounds__(kThreads) void generic_backward_kernel(BwdParams bp
             if (active) {
                 const T* krow = row_ptr<T>(p.k, b, tok0 + (int64_t)c * p.stride, g);
                 const T* xrow = row_ptr<T>(p.vin, b, tok0 + (int64_t)c * p.stride, hv);
-                for (int d = lane; d < D; d += 64) { r0[d] = to_f32(krow[d]); r1[d] = to_f32(xrow[d]); }
+                for (int d = lane; d < D; d += 64) { r0[d] = enc_load<T>(p, p.rope != 0, krow, d, c); r1[d] = to_f32(xrow[d]); }
             }
             if (vin_is_o) { accX[0] = accX[1] = accX[2] = accX[3] = 0.f; }
             const int qstart = p.causal ? (kb * kWaves / TK) * TK : 0;   // rows before the block's first key see none of its keys
             for (int q0 = qstart; q0 < n; q0 += TK) {
                 __syncthreads();
-                load_tile<T>(tA, pitch, TK, q0, p.q, b, tok0, p.stride, h, n, D);
+                load_tile<T>(tA, pitch, TK, q0, p.q, b, tok0, p.stride, h, n, D, enc);
                 load_tile<T>(tB, pitch, TK, q0, bp.d_o, b, tok0, p.stride, h, n, D);
                 __syncthreads();
                 if (!active) continue;
@@ -364,8 +403,8 @@ __global__ __launch_bounds__(kThreads) void generic_backward_kernel(BwdParams bp
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const int col = lane + 64 * j;
+                float x = enc_grad(p, accK[j] * p.scale, col, c);     // back to the row as stored (all lanes take part)
                 if (col < D) {
-                    float x = accK[j] * p.scale;
                     if (bp.accumulate) x += to_f32(dkrow[col]);
                     from_f32(dkrow + col, x);
                 }

@@ -30,7 +30,25 @@ struct HopParams {
     int64_t valid_len;       // tokens at or past it are padding; equals N when there is none
     const uint32_t* mask;    // device table of this axis (n rows of mask_words words, bit c of row a = visible) or nullptr
     int32_t mask_words;      // ceil(n / 32)
+    const int64_t* valid_lens;   // device, one padding length per batch element (clamped to [0, N], combined with valid_len), or nullptr
+    int64_t N;               // tokens per batch element
+    // Rotary encoding inside the hop: Q and K rows are turned by their position a on this axis before
+    // the scores, feature pair (2p, 2p+1) by a * base^(-2p/D) radians.
+    int32_t rope;            // 0: off
+    float rope_c0, rope_c1;  // that angle in REVOLUTIONS is a * exp2(rope_c0 * p + rope_c1)
+    float rope_log2_base;    // log2(base), for kernels that form the angle in double precision
 };
+
+// Padding length of batch element b: min(valid_len, valid_lens[b]) clamped to [0, N].
+__device__ inline int64_t hop_valid_len(const HopParams& p, int b) {
+    int64_t v = p.valid_len;
+    if (p.valid_lens) {
+        const int64_t x = p.valid_lens[b];
+        v = x < v ? x : v;
+        v = v < 0 ? 0 : v;
+    }
+    return v;
+}
 
 struct BwdParams {
     HopParams hop;           // hop.o is unused

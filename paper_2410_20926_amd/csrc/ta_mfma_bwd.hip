@@ -65,10 +65,29 @@ __device__ inline void prefetch_tile(u32x4 (&old)[Geo<D>::kDTiles * 2], const u3
 // `mult`, optionally adds the tensor's previous contents (`old`, from prefetch_tile), rounds
 // to bf16 and stores the rows with 16-byte stores; the transposition goes through LDS in
 // fp32, 64 features at a time.
-template <int D, bool NARROW = false>
+// No rotation of the stored rows.
+struct NoRope {
+    static constexpr bool on = false;
+    __device__ float pos(int) const { return 0.f; }
+    __device__ const HopParams* hop() const { return nullptr; }
+};
+// The rows are gradients with respect to rotary-encoded rows: tile row r sits at position pos(r) on the
+// hop's axis and is turned back (the encoding's transpose) before anything is added to it.
+template <typename PosFn>
+struct UnRope {
+    static constexpr bool on = true;
+    const HopParams* p;
+    PosFn fn;
+    __device__ float pos(int r) const { return fn(r); }
+    __device__ const HopParams* hop() const { return p; }
+};
+template <typename PosFn>
+__device__ inline UnRope<PosFn> unrope(const HopParams* p, PosFn fn) { return UnRope<PosFn>{p, fn}; }
+
+template <int D, bool NARROW = false, typename Enc = NoRope>
 __device__ inline void store_tile(const f32x16 (&acc)[Geo<D>::kDTiles], float mult, char* buf, const u32x4* rowoff,
                                   int which, char* gbase, const u32x4 (&old)[Geo<D>::kDTiles * 2], bool add_old, int rows_valid, int lane,
-                                  uint32_t dbytes = 0) {
+                                  uint32_t dbytes = 0, const Enc enc = Enc{}) {
     using G = BGeo<D>;
     const int r32 = lane & 31, hf = lane >> 5;
 #pragma unroll
@@ -89,6 +108,14 @@ __device__ inline void store_tile(const f32x16 (&acc)[Geo<D>::kDTiles], float mu
             const f32x4 x1 = *reinterpret_cast<const f32x4*>(buf + row * G::kFPitch + cc * 32 + 16);
             if (row < rows_valid) {
                 float y[8] = {x0[0], x0[1], x0[2], x0[3], x1[0], x1[1], x1[2], x1[3]};
+                if constexpr (Enc::on) {
+                    if (enc.hop()->rope) {
+                        float rev[4], c[4], sn[4];
+                        rope_rates(*enc.hop(), half * 8 + cc, rev);
+                        rope_sincos(enc.pos(row), rev, c, sn);
+                        rope_apply_f32<true>(y, c, sn);
+                    }
+                }
                 if (add_old) {
                     const u32x4 o = old[half * 4 + i];
 #pragma unroll
@@ -211,7 +238,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
             const uint32_t outer = f / stride;
             const uint32_t tok = outer * stride * n + (f - outer * stride) + a * stride;
             rowoff[lane] = u32x4{tok * tp.q_row, tok * tp.k_row, tok * tp.v_row, tok * tp.o_row};
-            real = lane < rows_valid && tok < (uint32_t)p.valid_len;
+            real = lane < rows_valid && tok < (uint32_t)hop_valid_len(p, b);
         }
         real_rows = (uint32_t)__ballot(real);
     }
@@ -242,6 +269,25 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
         graw[i] = load_chunk<NARROW, true>(gb, off.w, lbyte, dbytes);
     }
     __builtin_amdgcn_sched_barrier(0);
+
+    // rotary encoding: Q and K rows are turned by their position on the axis before anything uses them;
+    // dQ and dK below are gradients with respect to the turned rows and are turned back when stored
+    auto row_pos = [&](int row) -> float {
+        const int rc = min(row, rows_valid - 1);
+        return (float)(rc - (int)((rc + 0.5f) * tp.inv_n) * n);
+    };
+    if (p.rope) {
+        float rev[4];
+        rope_rates(p, lcol, rev);
+#pragma unroll
+        for (int i = 0; i < G::kPasses; ++i) {
+            float c[4], sn[4];
+            rope_sincos(row_pos(i * G::kRowsPerPass + lrow), rev, c, sn);
+            qraw[i] = rope_apply(qraw[i], c, sn);
+            kraw[i] = rope_apply(kraw[i], c, sn);
+        }
+    }
+    const auto enc = unrope(&p, row_pos);
 
     char* stg = buf + lrow * G::kPitch + lbyte;                              // row-major staging (this lane's chunk)
     const char* oprd = buf + r32 * G::kPitch + hf * 16;                      // natural operand reads
@@ -362,7 +408,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) acc[t] = mma(kT[t][s2], dsTop[s2], acc[t]);
     }
-    store_tile<D, NARROW>(acc, p.scale, buf, rowoff, 0, dqb, oldq, bp.accumulate != 0, rows_valid, lane, dbytes);
+    store_tile<D, NARROW>(acc, p.scale, buf, rowoff, 0, dqb, oldq, bp.accumulate != 0, rows_valid, lane, dbytes, enc);
 
     // ---- dX^T = G^T P : per head, or summed over the group when the value input is V ------
 #pragma unroll
@@ -397,7 +443,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
         for (int s2 = 0; s2 < 2; ++s2) acc[t] = mma(qT[t][s2], dsNop[s2], acc[t]);
     }
     chain_sum<D>(acc, red, w, nw, lane);
-    if (w == nw - 1) store_tile<D, NARROW>(acc, p.scale, buf, rowoff, 1, dkb, oldk, acc_k, rows_valid, lane, dbytes);
+    if (w == nw - 1) store_tile<D, NARROW>(acc, p.scale, buf, rowoff, 1, dkb, oldk, acc_k, rows_valid, lane, dbytes, enc);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -469,7 +515,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
     const uint32_t stride = (uint32_t)p.stride;
     const uint32_t tok0 = (uint32_t)fibre_base_token(f, p.stride, n);
     // rows of the fibre whose token is not padding form a prefix [0, nreal)
-    const uint32_t vl = (uint32_t)p.valid_len;
+    const uint32_t vl = (uint32_t)hop_valid_len(p, b);
     const int nreal = tok0 >= vl ? 0 : (int)min((uint32_t)n, (vl - tok0 + stride - 1) / stride);
 
     const int wave_bytes = G::kBufBytes + kTile * 16 + 3 * kTile * T * 4;
@@ -504,6 +550,15 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
             raw[i] = load_chunk<NARROW, false>(base, (tok0 + rr * stride) * pitch, lbyte, dbytes);
         }
     };
+    // rotary encoding: every gathered Q or K tile is turned, row by row, by its position on the axis
+    float rev[4];
+    if (p.rope) rope_rates(p, lcol, rev);
+    auto encode = [&](int t, u32x4 (&raw)[G::kPasses]) {
+        if (p.rope) {
+#pragma unroll
+            for (int i = 0; i < G::kPasses; ++i) raw[i] = rope_chunk(raw[i], (float)min(kTile * t + i * G::kRowsPerPass + lrow, n - 1), rev);
+        }
+    };
     auto set_rowoff = [&](int t) {                        // byte offsets of the rows of tile t for the epilogue helpers
         lds_wave_sync();
         if (lane < kTile) {
@@ -536,6 +591,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
             gather(qb, sp.q_row, a, qraw);
             gather(gb, sp.o_row, a, graw);
             lds_wave_sync();
+            encode(a, qraw);
             stage_rows<D>(stg, qraw);
             lds_wave_sync();
             read_natural<D>(oprd, qop);
@@ -554,6 +610,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
             u32x4 kraw[G::kPasses], xraw[G::kPasses], op[G::kKSteps];
             gather(kb, sp.k_row, c, kraw);
             gather(xb, sp.v_row, c, xraw);
+            encode(c, kraw);
             stage_rows<D>(stg, kraw);
             lds_wave_sync();
             read_natural<D>(oprd, op);
@@ -615,6 +672,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
             f32x16 sT = {}, dpT = {};
 #pragma unroll
             for (int s = 0; s < G::kKSteps; ++s) dpT = mma(op[s], gop[s], dpT);
+            encode(c, kraw);
             stage_rows<D>(stg, kraw);
             lds_wave_sync();
             read_natural<D>(oprd, op);
@@ -640,7 +698,8 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
         set_rowoff(a);
         u32x4 oldq[G::kDTiles * 2] = {};
         if (bp.accumulate) prefetch_tile<D, NARROW>(oldq, rowoff, 0, dqb, lane, dbytes);
-        store_tile<D, NARROW>(acc, p.scale, buf, rowoff, 0, dqb, oldq, bp.accumulate != 0, min(kTile, n - kTile * a), lane, dbytes);
+        store_tile<D, NARROW>(acc, p.scale, buf, rowoff, 0, dqb, oldq, bp.accumulate != 0, min(kTile, n - kTile * a), lane, dbytes,
+                              unrope(&p, [&](int r) { return (float)(kTile * a + r); }));
     }
     lds_wave_sync();
 
@@ -655,6 +714,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
             u32x4 kraw[G::kPasses];
             gather(kb, sp.k_row, c, kraw);
             lds_wave_sync();
+            encode(c, kraw);
             stage_rows<D>(stg, kraw);
             lds_wave_sync();
             read_natural<D>(oprd, kop);
@@ -667,6 +727,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
         for (int a = ab; a < ae; ++a) {
             u32x4 qraw[G::kPasses], graw[G::kPasses], op[G::kKSteps], gT[G::kDTiles][2];
             gather(qb, sp.q_row, a, qraw);
+            encode(a, qraw);
             stage_rows<D>(stg, qraw);
             gather(gb, sp.o_row, a, graw);
             lds_wave_sync();
@@ -734,6 +795,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
             f32x16 sN = {}, dpN = {};
 #pragma unroll
             for (int s = 0; s < G::kKSteps; ++s) dpN = mma(op[s], xop[s], dpN);
+            encode(a, qraw);
             stage_rows<D>(stg, qraw);
             lds_wave_sync();
             read_natural<D>(oprd, op);
@@ -767,7 +829,8 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
         u32x4 oldk[G::kDTiles * 2] = {};
         if (bp.acc_k && w == nw - 1) prefetch_tile<D, NARROW>(oldk, rowoff, 1, dkb, lane, dbytes);   // only the wave that ends up with the sum
         chain_sum<D>(acc, red, w, nw, lane);
-        if (w == nw - 1) store_tile<D, NARROW>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.acc_k != 0, rows_c, lane, dbytes);
+        if (w == nw - 1) store_tile<D, NARROW>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.acc_k != 0, rows_c, lane, dbytes,
+                                               unrope(&p, [&](int r) { return (float)(kTile * c + r); }));
         lds_wave_sync();
     }
 }

@@ -67,6 +67,51 @@ __device__ inline void store_chunk(char* base, uint32_t rowoff, uint32_t lbyte, 
     }
 }
 
+// ---- rotary encoding of a lane's 16-byte chunk (Sec. 3.2: per-axis positions) ----------------------
+// A chunk is 4 interleaved feature pairs (2p, 2p+1), p = 4 * chunk + e.  rope_rates gives the turn of
+// each of the lane's pairs per position step, in revolutions; rope_chunk turns the chunk of a row at
+// position `pos` (by the negative angle when INVERSE: the transpose, what a gradient needs).  fp32
+// throughout; the hardware sine and cosine take revolutions, reduced to [0, 1) first.
+__device__ inline void rope_rates(const HopParams& p, int chunk, float (&rev)[4]) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) rev[e] = __builtin_amdgcn_exp2f(p.rope_c0 * (float)(4 * chunk + e) + p.rope_c1);
+}
+__device__ inline void rope_sincos(float pos, const float (&rev)[4], float (&c)[4], float (&s)[4]) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float t = __builtin_amdgcn_fractf(pos * rev[e]);
+        s[e] = __builtin_amdgcn_sinf(t);
+        c[e] = __builtin_amdgcn_cosf(t);
+    }
+}
+template <bool INVERSE = false>
+__device__ inline u32x4 rope_apply(const u32x4 x, const float (&c)[4], const float (&s)[4]) {
+    u32x4 y;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float lo = bf16_lo(x[e]), hi = bf16_hi(x[e]);
+        const float sn = INVERSE ? -s[e] : s[e];
+        y[e] = pack_bf16x2(lo * c[e] - hi * sn, lo * sn + hi * c[e]);
+    }
+    return y;
+}
+__device__ inline u32x4 rope_chunk(const u32x4 x, float pos, const float (&rev)[4]) {
+    float c[4], s[4];
+    rope_sincos(pos, rev, c, s);
+    return rope_apply(x, c, s);
+}
+// The same on 8 fp32 values (4 pairs) in registers, e.g. a gradient row chunk before it is rounded.
+template <bool INVERSE>
+__device__ inline void rope_apply_f32(float (&y)[8], const float (&c)[4], const float (&s)[4]) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const float lo = y[2 * e], hi = y[2 * e + 1];
+        const float sn = INVERSE ? -s[e] : s[e];
+        y[2 * e] = lo * c[e] - hi * sn;
+        y[2 * e + 1] = lo * sn + hi * c[e];
+    }
+}
+
 template <int D>
 struct Geo {
     static constexpr int kChunks = D / 8;                 // 16-byte chunks per row

@@ -73,6 +73,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
     uint64_t real_rows;                                   // bit r: table row r exists and its token is not padding
     {
         const uint32_t stride = (uint32_t)p.stride;
+        const uint32_t vl = (uint32_t)hop_valid_len(p, b);
         bool real = false;
         if (lane < kRows) {
             const int rc = min(lane, rows_valid - 1);
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
             const uint32_t outer = f / stride;
             const uint32_t tok = outer * stride * n + (f - outer * stride) + a * stride;
             rowoff[lane] = u32x4{tok * tp.q_row, tok * tp.k_row, tok * tp.v_row, tok * tp.o_row};
-            real = lane < rows_valid && tok < (uint32_t)p.valid_len;
+            real = lane < rows_valid && tok < vl;
         }
         real_rows = __ballot(real);
     }
@@ -145,6 +146,23 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
     }
     __builtin_amdgcn_sched_barrier(0);                    // keep these loads ahead of the first wait
 
+    // ---- rotary encoding of the gathered Q and K rows, by their position on the axis -----
+    float rev[4];
+    auto row_pos = [&](int row) -> float {                // position on the axis of row `row` of the fibre set
+        if (KT == 1) { const int rc = min(row, rows_valid - 1); return (float)(rc - (int)((rc + 0.5f) * tp.inv_n) * n); }
+        return (float)min(row, n - 1);
+    };
+    if (p.rope) {
+        rope_rates(p, lcol, rev);
+#pragma unroll
+        for (int i = 0; i < G::kPasses; ++i) {
+            float c[4], sn[4];
+            rope_sincos(row_pos(qt * kTile + i * G::kRowsPerPass + lrow), rev, c, sn);
+            qreg[i] = rope_apply(qreg[i], c, sn);
+            if (KT == 1) kreg[0][i] = rope_apply(kreg[0][i], c, sn);     // one tile: K's rows are Q's rows
+        }
+    }
+
     const int r32 = lane & 31;                            // tile row this lane owns in operands
     const int hf = lane >> 5;                             // which 8-wide half of a 16-wide MFMA step
     const char* oprd = buf + r32 * G::kPitch + hf * 16;   // operand read base
@@ -168,6 +186,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
         st[j] = f32x16{};
         if (j < kt_end) {
             u32x4 kop[G::kKSteps];
+            if (KT > 1 && p.rope) {
+#pragma unroll
+                for (int i = 0; i < G::kPasses; ++i) kreg[j][i] = rope_chunk(kreg[j][i], row_pos(j * kTile + i * G::kRowsPerPass + lrow), rev);
+            }
 #pragma unroll
             for (int i = 0; i < G::kPasses; ++i)
                 *reinterpret_cast<u32x4*>(stg + i * G::kRowsPerPass * G::kPitch) = kreg[j][i];
@@ -356,6 +378,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
     uint64_t real_rows;                                   // bit r: table row r exists and its token is not padding
     {
         const uint32_t stride = (uint32_t)p.stride;
+        const uint32_t vl = (uint32_t)hop_valid_len(p, b);
         bool real = false;
         if (lane < kRows) {
             const int rc = min(lane, rows_valid - 1);
@@ -365,7 +388,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
             const uint32_t outer = f / stride;
             const uint32_t tok = outer * stride * n + (f - outer * stride) + a * stride;
             rowoff[lane] = u32x4{tok * tp.q_row, tok * tp.k_row, tok * tp.v_row, tok * tp.o_row};
-            real = lane < rows_valid && tok < (uint32_t)p.valid_len;
+            real = lane < rows_valid && tok < vl;
         }
         real_rows = __ballot(real);
     }
@@ -420,6 +443,26 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
         }
     }
     __builtin_amdgcn_sched_barrier(0);
+
+    // ---- rotary encoding of the gathered rows, by their position on the axis: Q (private) and this
+    //      wave's quarter of every K tile, before they enter LDS ---------------------------------
+    if (p.rope) {
+        float rev[4];
+        rope_rates(p, lcol, rev);
+        auto row_pos = [&](int row) -> float {
+            if (KT == 1) { const int rc = min(row, rows_valid - 1); return (float)(rc - (int)((rc + 0.5f) * tp.inv_n) * n); }
+            return (float)min(row, n - 1);
+        };
+#pragma unroll
+        for (int i = 0; i < G::kPasses; ++i) qreg[i] = rope_chunk(qreg[i], row_pos(qt * kTile + i * G::kRowsPerPass + lrow), rev);
+#pragma unroll
+        for (int j = 0; j < KT; ++j)
+            if (j < kt_end) {
+#pragma unroll
+                for (int i = 0; i < kShare; ++i)
+                    ksh[j][i] = rope_chunk(ksh[j][i], row_pos(j * kTile + (w * kShare + i) * G::kRowsPerPass + lrow), rev);
+            }
+    }
 
     const int r32 = lane & 31, hf = lane >> 5;
     char* stg = buf + lrow * G::kPitch + lbyte;
@@ -582,6 +625,7 @@ hipError_t launch(const HopParams& p, const TileParams& tp, hipStream_t s) {
 
 bool mfma_forward_layout_ok(const HopParams& p) {
     const int64_t N = p.fibres * p.n;
+    if (p.rope && p.n > 4096) return false;             // fp32 angles: positions beyond that lose too much of the turn
     return N < ((int64_t)1 << 31) && p.B <= 65535 && fits_u32(p.q, N) && fits_u32(p.k, N) && fits_u32(p.vin, N) &&
            fits_u32(p.o, N);
 }

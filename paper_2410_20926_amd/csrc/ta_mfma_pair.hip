@@ -53,6 +53,7 @@ struct PairParams {
     uint32_t groups;                         // B * slabs * Hkv
     uint32_t q_row, k_row, v_row, o_row;     // token pitch of each tensor in bytes
     int64_t valid_len;                       // tokens at or past it (per batch element) are padding; N when there is none
+    const int64_t* valid_lens;               // device: one such length per batch element (combined with valid_len), or nullptr
     uint32_t dbytes;                         // bytes of a row (2 * head width)
 };
 
@@ -180,7 +181,12 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
     char* ob = reinterpret_cast<char*>(p.o.p) + ((int64_t)b * p.o.sb + (int64_t)h * p.o.sh) * 2 + tok0 * p.o_row;
     char* mb = reinterpret_cast<char*>(p.mid) + ((int64_t)b * p.o.sb + (int64_t)h * p.o.sh) * 2 + tok0 * p.o_row;
 
-    if (p.valid_len <= tok0) {                            // the whole slab is padding: its outputs are zero, nothing is read
+    int64_t valid_len = p.valid_len;                      // this batch element's padding length
+    if (p.valid_lens) {
+        const int64_t x = p.valid_lens[b];
+        valid_len = x < valid_len ? (x < 0 ? 0 : x) : valid_len;
+    }
+    if (valid_len <= tok0) {                              // the whole slab is padding: its outputs are zero, nothing is read
         constexpr int kLanesPerRow = kD / 8, kRowsPerPass = 64 / kLanesPerRow;
 #pragma unroll 4
         for (int pp = 0; pp < kOwn * kN / kRowsPerPass; ++pp) {
@@ -314,7 +320,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
 
     // softmax of the 8 tiles; `left` = real (unpadded) tokens from the slab's first token on
     const float sl2 = p.scale * kLog2e;
-    const int64_t left = p.valid_len - tok0;
+    const int64_t left = valid_len - tok0;
     u32x4 p1[kOwn][2], p2[kOwn][2];
     float inv1[kOwn], inv2[kOwn];
 #pragma unroll
@@ -375,6 +381,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
 }
 
 bool pair_params(const HopParams& h1, const HopParams& h2, PairParams* pp) {
+    if (h1.rope) return false;                            // the fused kernel scores with Q and K as given
     if (h1.n != kN || h2.n != kN || h1.D < 8 || h1.D > 128 || h1.D % 4 != 0 || h2.stride != 1 || h1.stride != kN) return false;
     const int64_t N = h1.fibres * h1.n;
     if (!fits_u32(h1.q, kSlab) || !fits_u32(h1.k, kSlab) || !fits_u32(h1.vin, kSlab) || !fits_u32(h1.o, kSlab)) return false;
@@ -388,6 +395,7 @@ bool pair_params(const HopParams& h1, const HopParams& h2, PairParams* pp) {
     pp->window1 = h1.window; pp->window2 = h2.window;
     pp->mask1 = h1.mask; pp->mask2 = h2.mask;
     pp->valid_len = h1.valid_len;
+    pp->valid_lens = h1.valid_lens;
     pp->dbytes = (uint32_t)h1.D * 2;
     pp->slabs = (uint32_t)slabs;
     pp->groups = (uint32_t)groups;

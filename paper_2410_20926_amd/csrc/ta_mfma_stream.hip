@@ -88,6 +88,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
     const char* oprd = buf + r32 * G::kPitch + hf * 16;
     const char* trbase = buf + (4 * hf + ((lane & 15) >> 2)) * G::kPitch + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
 
+    // rotary encoding: Q here, every K tile just before it enters LDS, each row by its position on the axis
+    float rev[4];
+    if (p.rope) {
+        rope_rates(p, lcol, rev);
+#pragma unroll
+        for (int i = 0; i < G::kPasses; ++i) qreg[i] = rope_chunk(qreg[i], (float)min(qt * kTile + i * G::kRowsPerPass + lrow, n - 1), rev);
+    }
     u32x4 qop[G::kKSteps];
     stage_rows<D>(stg, qreg);
     lds_wave_sync();
@@ -95,7 +102,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
     lds_wave_sync();
 
     // rows of the fibre whose token is not padding form a prefix [0, nreal)
-    const uint32_t vl = (uint32_t)p.valid_len;
+    const uint32_t vl = (uint32_t)hop_valid_len(p, b);
     const int nreal = tok0 >= vl ? 0 : (int)min((uint32_t)n, (vl - tok0 + stride - 1) / stride);
     const int qrow = qt * kTile + r32;                    // this lane's query row in the fibre
     int klo = 0, khi = 0;                                 // it sees keys [klo, khi)
@@ -112,6 +119,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
     for (int j = jbeg; j < jend; ++j) {
         // ---- K tile j: LDS transit, then request tile j + 1 into the same registers ------
         u32x4 kop[G::kKSteps];
+        if (p.rope) {
+#pragma unroll
+            for (int i = 0; i < G::kPasses; ++i) kreg[i] = rope_chunk(kreg[i], (float)min(j * kTile + i * G::kRowsPerPass + lrow, n - 1), rev);
+        }
         stage_rows<D>(stg, kreg);
         lds_wave_sync();
         read_natural<D>(oprd, kop);
@@ -272,14 +283,17 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
                 }
             }
     };
-    auto write_shared = [&](int set, int slot) {
+    float rev[4];                                         // rotary encoding: turn rates of this lane's four feature pairs
+    if (p.rope) rope_rates(p, lcol, rev);
+    auto write_shared = [&](int set, int slot, int j) {    // j: the key tile the registers hold (its rows' positions, for the encoding)
 #pragma unroll
         for (int sidx = 0; sidx < 3; ++sidx)
             if (set == sidx) {
 #pragma unroll
                 for (int i = 0; i < kMine; ++i) {
                     const uint32_t at = (uint32_t)(slot * kBuf + ((w * kMine + i) * G::kRowsPerPass + lrow) * G::kPitch) + lbyte;
-                    *reinterpret_cast<u32x4*>(sK + at) = kp[sidx][i];
+                    const u32x4 kv = p.rope ? rope_chunk(kp[sidx][i], (float)min(j * kTile + (w * kMine + i) * G::kRowsPerPass + lrow, n - 1), rev) : kp[sidx][i];
+                    *reinterpret_cast<u32x4*>(sK + at) = kv;
                     if (VS) *reinterpret_cast<u32x4*>(sV + at) = vp[sidx][i];
                 }
             }
@@ -307,15 +321,19 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
     const uint32_t oprd = (uint32_t)(r32 * G::kPitch + hf * 16);
     const uint32_t troff = (uint32_t)((4 * hf + ((lane & 15) >> 2)) * G::kPitch + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2);
 
+    if (p.rope) {
+#pragma unroll
+        for (int i = 0; i < G::kPasses; ++i) qreg[i] = rope_chunk(qreg[i], (float)min(qt * kTile + i * G::kRowsPerPass + lrow, n - 1), rev);
+    }
     u32x4 qop[G::kKSteps];
     stage_rows<D>(stg, qreg);
     lds_wave_sync();
     read_natural<D>(buf + oprd, qop);
     lds_wave_sync();
-    write_shared(0, 0);
+    write_shared(0, 0, jbeg);
     if (jbeg + 3 < jend) load_shared(0, jbeg + 3);
 
-    const uint32_t vl = (uint32_t)p.valid_len;
+    const uint32_t vl = (uint32_t)hop_valid_len(p, b);
     const int nreal = tok0 >= vl ? 0 : (int)min((uint32_t)n, (vl - tok0 + stride - 1) / stride);
     const int qrow = qt * kTile + r32;
     int klo = 0, khi = 0;
@@ -389,7 +407,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
             for (int s2 = 0; s2 < 2; ++s2) ot[t] = mma(vT[t][s2], pop[s2], ot[t]);
         }
         if (j + 1 < jend) {                               // the other slot was last read before this iteration's barrier
-            write_shared(next_set, slot ^ 1);
+            write_shared(next_set, slot ^ 1, j + 1);
             if (j + 4 < jend) load_shared(next_set, j + 4);
         }
     };
@@ -500,12 +518,15 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunke
             if (VS) vp[set][i] = load_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
         }
     };
-    auto write_shared = [&](auto set_tag, int slot) {
+    float rev[4];                                         // rotary encoding: turn rates of this lane's four feature pairs
+    if (p.rope) rope_rates(p, lcol, rev);
+    auto write_shared = [&](auto set_tag, int slot, int j) {   // j: the key tile the registers hold (its rows' positions, for the encoding)
         constexpr int set = decltype(set_tag)::value;
 #pragma unroll
         for (int i = 0; i < kMine; ++i) {
             const uint32_t at = (uint32_t)(slot * kBuf + ((w * kMine + i) * G::kRowsPerPass + lrow) * G::kPitch) + lbyte;
-            *reinterpret_cast<u32x4*>(sK + at) = kp[set][i];
+            const u32x4 kv = p.rope ? rope_chunk(kp[set][i], (float)min(j * kTile + (w * kMine + i) * G::kRowsPerPass + lrow, n - 1), rev) : kp[set][i];
+            *reinterpret_cast<u32x4*>(sK + at) = kv;
             if (VS) *reinterpret_cast<u32x4*>(sV + at) = vp[set][i];
         }
     };
@@ -542,11 +563,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunke
     char* stg = buf + lrow * G::kPitch + lbyte;
     const uint32_t oprd = (uint32_t)(r32 * G::kPitch + hf * 16);
     const uint32_t troff = (uint32_t)((4 * hf + ((lane & 15) >> 2)) * G::kPitch + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2);
-    const uint32_t vl = (uint32_t)p.valid_len;
+    const uint32_t vl = (uint32_t)hop_valid_len(p, b);
     const int nreal = tok0 >= vl ? 0 : (int)min((uint32_t)n, (vl - tok0 + stride - 1) / stride);
     const float sl2 = p.scale * kLog2e;
 
-    write_shared(S0{}, 0);
+    write_shared(S0{}, 0, cur.j);
     if (more_ahead) { load_shared(S0{}, ahead.j); more_ahead = cursor_next(ahead); }
 
     // per query tile
@@ -566,6 +587,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunke
             first_of_tile = false;
             // first step of a query tile: its rows become the B operand, the next query tile's rows are requested
             lds_wave_sync();
+            if (p.rope) {
+#pragma unroll
+                for (int i = 0; i < G::kPasses; ++i) qreg[i] = rope_chunk(qreg[i], (float)min(qt * kTile + i * G::kRowsPerPass + lrow, n - 1), rev);
+            }
             stage_rows<D>(stg, qreg);
             lds_wave_sync();
             read_natural<D>(buf + oprd, qop);
@@ -641,7 +666,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunke
             for (int s2 = 0; s2 < 2; ++s2) ot[tt2] = mma(vT[tt2][s2], pop[s2], ot[tt2]);
         }
         if (has_next) {                                   // the other slot was last read before this step's barrier
-            write_shared(next_set_tag, slot ^ 1);
+            write_shared(next_set_tag, slot ^ 1, nxt.j);
             if (more_ahead) { load_shared(next_set_tag, ahead.j); more_ahead = cursor_next(ahead); }
         }
         if (last_of_tile) {                               // normalise, round, transpose through the own tile, store

@@ -35,6 +35,7 @@ class TaDesc(C.Structure):
         ("q_strides", C.c_int64 * 3), ("kv_strides", C.c_int64 * 3), ("o_strides", C.c_int64 * 3),
         ("window", C.c_int32 * TA_MAX_ORDER), ("valid_len", C.c_int64),
         ("axis_mask", C.c_void_p * TA_MAX_ORDER),
+        ("valid_lens", C.c_void_p), ("rope", C.c_int32), ("rope_base", C.c_float),
     ]
 
 
@@ -142,9 +143,12 @@ def _stream(stream) -> Optional[int]:
 def make_desc(batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dims: Sequence[int], dtype: int,
               causal: bool, scale: float = 0.0, hop_order: Optional[Sequence[int]] = None,
               q_strides=None, kv_strides=None, o_strides=None, window: Optional[Sequence[int]] = None,
-              valid_len: int = 0, axis_masks: Optional[Sequence] = None) -> TaDesc:
+              valid_len: int = 0, axis_masks: Optional[Sequence] = None, valid_lens=None,
+              rope_base: Optional[float] = None) -> TaDesc:
     """`axis_masks`: per axis None or a device tensor of packed bit rows (see pack_axis_mask);
-    the descriptor keeps a reference to each so the memory outlives the plan."""
+    `valid_lens`: None or a device int64 tensor of B lengths; the descriptor keeps a reference to
+    each so the memory outlives the plan.  `rope_base`: None = no encoding inside the hops, else
+    the rotary base (0 = 10000)."""
     d = TaDesc()
     d.batch, d.n_q_heads, d.n_kv_heads, d.head_dim = batch, n_q_heads, n_kv_heads, head_dim
     d.order = len(dims)
@@ -163,6 +167,10 @@ def make_desc(batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dims: 
         t = axis_masks[j] if axis_masks is not None and j < len(axis_masks) else None
         d.axis_mask[j] = _ptr(t) if t is not None else None
         d._mask_refs.append(t)
+    d.valid_lens = _ptr(valid_lens) if valid_lens is not None else None
+    d._mask_refs.append(valid_lens)
+    d.rope = 0 if rope_base is None else 1
+    d.rope_base = 0.0 if rope_base is None else float(rope_base)
     for name, s in (("q_strides", q_strides), ("kv_strides", kv_strides), ("o_strides", o_strides)):
         arr = getattr(d, name)
         for j in range(3):

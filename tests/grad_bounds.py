@@ -57,7 +57,7 @@ HALF_ULP_BF16 = 2.0 ** -8          # largest relative error of one rounding to b
 def backward_reference_and_tolerance(q, k, v, d_o, dims, causal, dtype, launch_heads=8, scale=None, hop_order=None, **mask_kw):
     """The oracle's (dq, dk, dv) and, for each, a per-element tolerance for the HIP path.
 
-    bf16:  tol = 2e-2 + 2^-8 * R, where R sums the absolute values of every quantity that the path
+    bf16:  tol = 2e-2 + 2^-8 * (R + 2 E).  R sums the absolute values of every quantity that the path
     stores in bf16 on the way to that element:
       dq  its running sum after each processed hop (hops are undone last to first; each adds
           its share to the stored dq and rounds), the last of which is the result itself;
@@ -65,8 +65,12 @@ def backward_reference_and_tolerance(q, k, v, d_o, dims, causal, dtype, launch_h
           sums them in fp32, adds the stored dk and rounds;
       dv  the group sum per launch, plus (m - 1) times the magnitude sum of the gradient chain
           (gradient_magnitudes), for the m - 1 inter-hop gradients stored in bf16.
-    The absolute 2e-2 is the forward's bound and covers the roundings of matrix-core operands
-    (attention weights, dS, the saved inter-hop O).
+    E is the root of the sum of squares of the element's individual products dS K scale (dq) or
+    dS Q scale (dk, over the group's heads) over all hops: dS enters the matrix cores rounded to bf16,
+    one independent relative error of at most 2^-9 per product, so the sum of those errors has a
+    standard deviation below 2^-9 E and 2^-7 E is more than four of them.
+    The absolute 2e-2 is the forward's bound and covers what is left (the rounded attention weights
+    in dX, the saved inter-hop O).
     fp32:  tol = 1e-5 + 2^-20 * M with M from gradient_magnitudes (fp32 sums of up to n_i * D terms)."""
     trace = {}
     ref = orc.tensorized_attention_backward(q, k, v, d_o, dims, causal, scale, hop_order, trace=trace, **mask_kw)
@@ -78,6 +82,8 @@ def backward_reference_and_tolerance(q, k, v, d_o, dims, causal, dtype, launch_h
     G = Hq // Hkv
     m = len(dims)
     Rq, Rk, Rv = np.zeros_like(ref[0]), np.zeros_like(ref[1]), (m - 1) * Mv
+    Eq = np.sqrt(trace["dq_sq"])
+    Ek = np.sqrt(trace["dk_sq"].reshape(B, N, Hkv, G, D).sum(3))
     run_q = np.zeros_like(ref[0])
     run_k = np.zeros_like(ref[1])
     for pos in range(m - 1, -1, -1):
@@ -92,7 +98,7 @@ def backward_reference_and_tolerance(q, k, v, d_o, dims, causal, dtype, launch_h
         hs = np.arange(base, min(base + launch_heads, G))
         run_v = run_v + trace["dv_heads"].reshape(B, N, Hkv, G, -1)[:, :, :, hs].sum(3)
         Rv = Rv + np.abs(run_v)
-    return ref, (2e-2 + HALF_ULP_BF16 * Rq, 2e-2 + HALF_ULP_BF16 * Rk, 2e-2 + HALF_ULP_BF16 * Rv)
+    return ref, (2e-2 + HALF_ULP_BF16 * (Rq + 2 * Eq), 2e-2 + HALF_ULP_BF16 * (Rk + 2 * Ek), 2e-2 + HALF_ULP_BF16 * Rv)
 
 
 def check_gradient(got, ref, tol, what, report=None):

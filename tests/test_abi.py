@@ -104,6 +104,9 @@ def test_cost_model_closed_forms():
     (dict(window=(0, -2)), "TA_ERR_INVALID_ARG"),
     (dict(valid_len=-1), "TA_ERR_INVALID_ARG"),
     (dict(valid_len=13), "TA_ERR_SHAPE"),
+    (dict(valid_lens=0x1004), "TA_ERR_INVALID_ARG"),            # not 8-byte aligned
+    (dict(rope_base=-2.0), "TA_ERR_INVALID_ARG"),
+    (dict(rope_base=float("inf")), "TA_ERR_INVALID_ARG"),
 ])
 def test_plan_rejects_bad_descriptors(kw, status):
     args = dict(batch=1, n_q_heads=2, n_kv_heads=2, head_dim=64, dims=(4, 3), dtype=ta.TA_F32, causal=False)
@@ -112,6 +115,19 @@ def test_plan_rejects_bad_descriptors(kw, status):
         ta.ta_plan_create(**args)
     assert ei.value.name == status
     assert ei.value.detail
+
+
+def test_rope_flag_must_be_0_or_1():
+    d = binding.make_desc(1, 2, 2, 64, (4, 3), ta.TA_F32, False)
+    d.rope = 2
+    with pytest.raises(ta.TaError) as e:
+        ta.Plan(d)
+    assert e.value.name == "TA_ERR_INVALID_ARG"
+    # with the encoding on, the fused pair of hops is not offered and the workspace is sized for separate hops
+    p = ta.ta_plan_create(1, 32, 8, 128, (32, 32, 32), ta.TA_BF16, True, rope_base=10000.0)
+    assert p.fused_position() == -1 and p.pair_kernel(1, ta.TA_VIN_O) == "unsupported"
+    assert p.workspace_bytes(False) == 2 * 32768 * 32 * 128 * 2
+    assert p.hop_kernel(1, ta.TA_VIN_O) == "mfma_bf16_n32_shared" and p.hop_backward_kernel(1, ta.TA_VIN_O) == "mfma_bf16_bwd_n32"
 
 
 def test_plan_create_null_pointers():

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import paper_2410_20926_amd as ta
-from gpu_util import TOL, multihop_backward, multihop_forward
+from gpu_util import TOL, multihop_backward, multihop_forward, to_host
 from oracle import tensattn_oracle as orc
 from paper_2410_20926_amd.workloads import make_inputs
 from grad_bounds import check_backward
@@ -146,3 +146,51 @@ def test_table_spelling_causal_is_bit_identical_to_the_causal_flag():
     a, _, _ = multihop_forward(q, k, v, dims, "bf16", True)
     b, _, _ = multihop_forward(q, k, v, dims, "bf16", False, axis_masks=tril)
     assert np.array_equal(a, b)
+
+
+# ---- one padding length per batch element ------------------------------------------------------------------------
+
+LENS_CASES = [
+    # dims, Hq, Hkv, D, causal, dtype, lengths
+    ((5, 7, 3), 4, 2, 64, False, "bf16", [105, 37, 0, 1]),
+    ((2, 32, 32), 8, 2, 128, False, "bf16", [2048, 1500, 1024, 31]),      # fused pair: whole slabs of padding, ragged slabs
+    ((3, 50), 2, 2, 128, True, "bf16", [150, 149, 51]),                   # two key tiles
+    ((130, 3), 4, 1, 128, False, "bf16", [390, 200, 3]),                  # streaming forward, blocked backward
+    ((64, 4), 4, 1, 64, False, "bf16", [256, 100]),
+    ((4, 2, 3), 2, 1, 8, False, "f32", [24, 5, 0]),                       # generic kernels
+    ((5, 37), 4, 1, 40, True, "f32", [185, 90]),
+]
+
+
+@pytest.mark.parametrize("dims,Hq,Hkv,D,causal,dtype,lens", LENS_CASES)
+def test_valid_len_per_batch_element(dims, Hq, Hkv, D, causal, dtype, lens):
+    N, B = int(np.prod(dims)), len(lens)
+    q, k, v, d_o = make_inputs(B, N, Hq, Hkv, D, seed=8800 + N + D, dtype=dtype, with_grad=True)
+    tl = torch.tensor(lens, dtype=torch.int64, device="cuda")
+    for save in (False, True):
+        got, plan, dev = multihop_forward(q, k, v, dims, dtype, causal, save=save, valid_lens=tl)
+        ref = orc.tensorized_attention_forward(q, k, v, dims, causal, valid_len=lens)
+        assert np.isfinite(got).all() and np.abs(got - ref).max() <= TOL[dtype]
+        for b, L in enumerate(lens):
+            assert (got[b, L:] == 0).all()
+    dq, dk, dv = multihop_backward(plan, dev, d_o, dtype)
+    check_backward((dq, dk, dv), q, k, v, d_o, dims, causal, dtype, valid_len=lens)
+    for b, L in enumerate(lens):
+        assert (dq[b, L:] == 0).all() and (dk[b, L:] == 0).all() and (dv[b, L:] == 0).all()
+    # the lengths are read when a kernel runs: the same plan follows a change of the array
+    tl.copy_(torch.tensor(lens[::-1], dtype=torch.int64))
+    o2 = torch.full_like(dev["o"], float("nan"))
+    ta.ta_multihop_forward(plan, dev["q"], dev["k"], dev["v"], o2, dev["ws"], dev["wsb"], True)
+    torch.cuda.synchronize()
+    ref2 = orc.tensorized_attention_forward(q, k, v, dims, causal, valid_len=lens[::-1])
+    assert np.abs(to_host(o2) - ref2).max() <= TOL[dtype]
+
+
+def test_valid_lens_combine_with_valid_len_and_are_clamped():
+    dims, B, Hq, Hkv, D = (6, 16), 3, 2, 1, 64
+    N = 96
+    q, k, v = make_inputs(B, N, Hq, Hkv, D, seed=8900, dtype="bf16")
+    tl = torch.tensor([1000, -5, 50], dtype=torch.int64, device="cuda")         # beyond N, negative, ordinary
+    got, _, _ = multihop_forward(q, k, v, dims, "bf16", False, valid_len=70, valid_lens=tl)
+    ref = orc.tensorized_attention_forward(q, k, v, dims, False, valid_len=[70, 0, 50])
+    assert np.abs(got - ref).max() <= TOL["bf16"]
