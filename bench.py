@@ -9,7 +9,7 @@ already live in HBM.  Prints ONE JSON line:
                       HIP-event timings of every hop launch (algorithmic bytes / time)
   cpu_baseline      : the CPU oracle, as it stands, timed on a bounded sample (whole
                       sequences of a few heads) on the host cores of this machine
-Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c4|c2|c5|c6]
+Usage: python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c4|c2|c5|c6|c3_rope|c4_train]
 """
 from __future__ import annotations
 
@@ -31,18 +31,18 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5", "c6"])
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5", "c6", "c3_rope", "c4_train"])
     ap.add_argument("--rotate", type=int, default=3, help="independent buffer sets cycled through, so that the "
                     "256 MB Infinity Cache cannot serve one step's re-reads from the previous step")
     ap.add_argument("--also", default=None, help="comma-separated further workloads measured in the same run and "
-                    "reported under other_workloads (default: c2,c4,c5,c6 next to c3, none otherwise)")
+                    "reported under other_workloads (default: c2,c4,c5,c6,c3_rope,c4_train next to c3, none otherwise)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true", help="also launch the plain copy kernel on 1 GiB a few "
                     "times, so that a hardware-counter run of this command has a transfer of known size to scale by")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     args = ap.parse_args()
     if args.also is None:
-        args.also = "c2,c4,c5,c6" if args.workload == "c3" else ""
+        args.also = "c2,c4,c5,c6,c3_rope,c4_train" if args.workload == "c3" else ""
     return args
 
 
@@ -50,7 +50,7 @@ def make_sets(torch, w, rotate):
     """`rotate` independent (q, k, v, o, workspace) sets, generated on the device from a seed."""
     import paper_2410_20926_amd as ta
     B, N, Hq, Hkv, D = w.batch, w.seq_len, w.n_q_heads, w.n_kv_heads, w.head_dim
-    plan = ta.ta_plan_create(B, Hq, Hkv, D, w.dims, ta.TA_BF16, w.causal)
+    plan = ta.ta_plan_create(B, Hq, Hkv, D, w.dims, ta.TA_BF16, w.causal, rope_base=w.rope_base)
     gen = torch.Generator(device="cuda")
     gen.manual_seed(w.seed)
     wsb = plan.workspace_bytes(w.backward)
@@ -289,7 +289,7 @@ def measure(torch, ta, w, args, steps, warmup):
 def describe(w):
     return (f"{w.name}: bf16, B={w.batch}, {w.n_q_heads} query / {w.n_kv_heads} kv heads, D={w.head_dim}, "
             f"N={w.seq_len} as {'x'.join(map(str, w.dims))}, {'forward + backward, ' if w.backward else ''}"
-            f"{'causal' if w.causal else 'non-causal'}")
+            f"{'causal' if w.causal else 'non-causal'}{', per-axis rotary encoding inside the hops' if w.rope_base else ''}")
 
 
 def main():

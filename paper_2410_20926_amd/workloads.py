@@ -38,6 +38,7 @@ class Workload:
     causal: bool
     qk_prescale: float          # Q and K are N(0,1) times this
     backward: bool = False
+    rope_base: Optional[float] = None   # the per-axis rotary encoding inside the hops (Sec. 3.2), or None
 
     @property
     def seq_len(self) -> int:
@@ -58,6 +59,10 @@ WORKLOADS = {
     # not one of the five benchmark configurations: the paper's own route to 128k tokens, the
     # first axis of a {32,32,32} model lengthened to 128 (Sec. 4.3)
     "c6": Workload("c6", 6, "bf16", 1, 32, 8, 128, (128, 32, 32), True, 1.0 / math.sqrt(128)),
+    # config 3 with the tensorized positional encoding applied inside every hop (Sec. 3.2)
+    "c3_rope": Workload("c3_rope", 3, "bf16", 1, 32, 8, 128, (32, 32, 32), True, 1.0 / math.sqrt(128), rope_base=10000.0),
+    # config 4's shape as a training step (forward + backward): axes of 64 positions in the backward
+    "c4_train": Workload("c4_train", 4, "bf16", 1, 32, 8, 128, (64, 64, 32), True, 1.0 / math.sqrt(128), backward=True),
 }
 
 
