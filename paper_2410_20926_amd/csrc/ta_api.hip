@@ -57,7 +57,7 @@ ta_status_t static_workspace(void** out) {
     return TA_OK;
 }
 
-enum BwdId : int { BWD_NONE = 0, BWD_MFMA_N32 = 1, BWD_MFMA_BLOCKED = 2, BWD_GENERIC = 3 };
+enum BwdId : int { BWD_NONE = 0, BWD_MFMA_N32 = 1, BWD_MFMA_BLOCKED = 2, BWD_GENERIC = 3, BWD_MFMA_N64 = 4 };
 
 thread_local char g_detail[256] = "";
 
@@ -336,7 +336,8 @@ ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
             pl->kernel_id[i][vin] = kid;
             const ta::BwdParams bp = bwd_params(pl, i, nullptr, nullptr, nullptr, vin, nullptr, nullptr, nullptr, nullptr, 0);
             if (ta::mfma_backward_supports(bp, d->dtype))
-                pl->bwd_id[i][vin] = ta::mfma_backward_is_blocked(bp, d->dtype) ? BWD_MFMA_BLOCKED : BWD_MFMA_N32;
+                pl->bwd_id[i][vin] = ta::mfma_backward_is_blocked(bp, d->dtype) ? BWD_MFMA_BLOCKED
+                                   : ta::mfma_backward_is_two_tile(bp, d->dtype) ? BWD_MFMA_N64 : BWD_MFMA_N32;
             else
                 pl->bwd_id[i][vin] = ta::generic_backward_supports(hp) ? BWD_GENERIC : BWD_NONE;
             pl->pair[i][vin] = false;
@@ -371,6 +372,7 @@ const char* ta_plan_hop_backward_kernel(const ta_plan_t* pl, int axis, int vin) 
     switch (pl->bwd_id[axis][vin]) {
         case BWD_MFMA_N32: return "mfma_bf16_bwd_n32";
         case BWD_MFMA_BLOCKED: return "mfma_bf16_bwd_blocked";
+        case BWD_MFMA_N64: return "mfma_bf16_bwd_n64";
         case BWD_GENERIC: return "generic";
     }
     return "unsupported";

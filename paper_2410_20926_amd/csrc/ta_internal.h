@@ -106,6 +106,7 @@ bool       mfma_forward_feasible(const HopParams& p, int kernel_id);   // layout
 bool       mfma_forward_stream_feasible(const HopParams& p);
 bool       mfma_backward_supports(const BwdParams& bp, int dtype);
 bool       mfma_backward_is_blocked(const BwdParams& bp, int dtype);   // the variant for axes longer than one tile
+bool       mfma_backward_is_two_tile(const BwdParams& bp, int dtype);  // the variant for axes of two tiles
 hipError_t launch_mfma_backward(const BwdParams& bp, hipStream_t s);
 // Fused pair of hops (axes h1 then h2 = the two innermost axes) in one kernel.
 bool       mfma_pair_supports(const HopParams& h1, const HopParams& h2, int dtype);

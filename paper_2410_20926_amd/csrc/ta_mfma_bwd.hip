@@ -835,6 +835,372 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
     }
 }
 
+// LDS of the two-tile kernel: shared K (and X) tiles, two reduction areas, statistics, one transit tile and one row table per wave.
+template <int D>
+constexpr size_t two_tile_lds(int gh, bool vs) {
+    return (size_t)(vs ? 4 : 2) * kTile * Geo<D>::kPitch + (gh > 1 ? 2 * (size_t)BGeo<D>::kRedBytes : 0) + (size_t)gh * 2 * 3 * kTile * 4 +
+           (size_t)2 * gh * BGeo<D>::kBufBytes + (size_t)2 * gh * kTile * 16;
+}
+
+// ---------------------------------------------------------------------------------------
+// Axes of two tiles (32 < n <= 64), groups of 1, 2 or 4 query heads: the same derivative with
+// every tensor tile read from memory ONCE per fibre.  Two waves serve one query head of one
+// fibre: wave (head, t) owns query tile t (the rows of dQ_t) and key tile t (the rows of dK_t
+// and dX_t), and the two exchange their tiles through LDS.  The K tiles (and the X tiles when
+// the value input is per key/value head, VS) are fetched once per workgroup into shared LDS
+// tiles; every wave stages its own Q, X and G tile, one after the other, in its private
+// transit tile, where its partner reads them as MFMA operands:
+//   X staged   hold X_0, X_1 as operands
+//   G staged   dP^T_tc = X_c G_t^T (rows of tile t, every visible key tile c),
+//              dP_at = G_a X_t^T (keys of tile t, every query tile a that sees them)
+//   Q staged   S^T_tc = K_c Q_t^T, S_at = Q_a K_t^T; row statistics of tile t -> LDS; dS^T_tc;
+//              then, with the partner's statistics, P_at and dS_at; dK_t^T = sum_a Q_a^T dS_at
+//   dQ_t^T = sum_c K_c^T dS^T_tc;  G staged again: dX_t^T = sum_a G_a^T P_at
+// dK (and dX under VS) are summed over the heads in a fixed order, as in the one-tile kernel.
+template <int D, int GH, bool VS>
+__global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, StreamBwdParams sp) {
+    using G = BGeo<D>;
+    constexpr int kBuf = kTile * G::kPitch;
+    constexpr int kWavesWg = 2 * GH;
+    constexpr int kShare = 2 * G::kPasses / kWavesWg;     // load passes of the two shared tiles per wave
+    static_assert((2 * G::kPasses) % kWavesWg == 0 && kShare >= 1, "the shared tiles split evenly over the waves");
+    const HopParams& p = bp.hop;
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int hl = w >> 1, t = w & 1;                     // head of the group; tile this wave owns
+    const int g = blockIdx.x;
+    const int h = g * GH + hl;
+    const uint32_t zb = blockIdx.z / sp.fibres_hi;
+    const int64_t f = (int64_t)(blockIdx.z - zb * sp.fibres_hi) * sp.fibres_lo + blockIdx.y;
+    if (f >= p.fibres) return;                            // whole workgroup leaves together
+    const int b = (int)zb;
+    const int hv = VS ? g : h;
+    const int n = p.n;
+    const uint32_t stride = (uint32_t)p.stride;
+    const uint32_t tok0 = (uint32_t)fibre_base_token(f, p.stride, n);
+    const uint32_t vl = (uint32_t)hop_valid_len(p, b);
+    const int nreal = tok0 >= vl ? 0 : (int)min((uint32_t)n, (vl - tok0 + stride - 1) / stride);
+
+    // LDS: shared K tiles | shared X tiles (VS) | two reduction areas | statistics | private tiles | row tables
+    char* sK = smem;
+    char* sX = smem + 2 * kBuf;
+    float* red = reinterpret_cast<float*>(smem + (VS ? 4 : 2) * kBuf) + (GH > 1 ? t * (G::kRedBytes / 4) : 0);
+    float* stats = reinterpret_cast<float*>(smem + (VS ? 4 : 2) * kBuf + (GH > 1 ? 2 * G::kRedBytes : 0)) + hl * (2 * 3 * kTile);
+    char* bufs = smem + (VS ? 4 : 2) * kBuf + (GH > 1 ? 2 * G::kRedBytes : 0) + GH * 2 * 3 * kTile * 4;
+    char* buf = bufs + w * G::kBufBytes;                  // this wave's transit tile
+    const char* pbuf = bufs + (w ^ 1) * G::kBufBytes;     // its partner's
+    u32x4* rowoff = reinterpret_cast<u32x4*>(bufs + kWavesWg * G::kBufBytes) + w * kTile;
+
+    const char* qb = reinterpret_cast<const char*>(p.q.p) + ((int64_t)b * p.q.sb + (int64_t)h * p.q.sh) * 2;
+    const char* kb = reinterpret_cast<const char*>(p.k.p) + ((int64_t)b * p.k.sb + (int64_t)g * p.k.sh) * 2;
+    const char* xb = reinterpret_cast<const char*>(p.vin.p) + ((int64_t)b * p.vin.sb + (int64_t)hv * p.vin.sh) * 2;
+    const char* gb = reinterpret_cast<const char*>(bp.d_o.p) + ((int64_t)b * bp.d_o.sb + (int64_t)h * bp.d_o.sh) * 2;
+    char* dqb = reinterpret_cast<char*>(bp.dq.p) + ((int64_t)b * bp.dq.sb + (int64_t)h * bp.dq.sh) * 2;
+    char* dkb = reinterpret_cast<char*>(bp.dk.p) + ((int64_t)b * bp.dk.sb + (int64_t)g * bp.dk.sh) * 2;
+    char* dxb = reinterpret_cast<char*>(bp.d_vin.p) + ((int64_t)b * bp.d_vin.sb + (int64_t)hv * bp.d_vin.sh) * 2;
+
+    const int lrow = lane / G::kChunks, lcol = lane % G::kChunks;
+    const uint32_t lbyte = lcol * 16;
+    const int r32 = lane & 31, hf = lane >> 5;
+    const float sl2 = p.scale * kLog2e;
+    const int rows_t = min(kTile, n - kTile * t);         // rows of this wave's tile that exist
+
+    // row table of this wave's tile for the epilogue helpers (rows past the fibre alias its last row)
+    if (lane < kTile) {
+        const uint32_t tok = tok0 + (uint32_t)min(kTile * t + lane, n - 1) * stride;
+        rowoff[lane] = u32x4{tok * sp.q_row, tok * sp.k_row, tok * sp.v_row, tok * sp.o_row};
+    }
+
+    // ---- gather: own Q, G (and X) tile, this wave's share of the shared tiles: all requested at once ----
+    u32x4 qraw[G::kPasses], graw[G::kPasses], xraw[VS ? 1 : G::kPasses], ksh[kShare], xsh[VS ? kShare : 1];
+#pragma unroll
+    for (int i = 0; i < G::kPasses; ++i) {
+        const uint32_t tok = tok0 + (uint32_t)min(kTile * t + i * G::kRowsPerPass + lrow, n - 1) * stride;
+        if constexpr (!VS) xraw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xb + (tok * sp.v_row + lbyte)));
+        graw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gb + (tok * sp.o_row + lbyte)));
+        qraw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (tok * sp.q_row + lbyte)));
+    }
+#pragma unroll
+    for (int i = 0; i < kShare; ++i) {
+        const int pidx = w * kShare + i;                  // pass pidx % kPasses of shared tile pidx / kPasses
+        const uint32_t tok = tok0 + (uint32_t)min(kTile * (pidx / G::kPasses) + (pidx % G::kPasses) * G::kRowsPerPass + lrow, n - 1) * stride;
+        ksh[i] = *reinterpret_cast<const u32x4*>(kb + (tok * sp.k_row + lbyte));
+        if constexpr (VS) xsh[i] = *reinterpret_cast<const u32x4*>(xb + (tok * sp.v_row + lbyte));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // rotary encoding: Q and K rows are turned by their position on the axis before they enter LDS
+    float rev[4];
+    if (p.rope) {
+        rope_rates(p, lcol, rev);
+#pragma unroll
+        for (int i = 0; i < G::kPasses; ++i) qraw[i] = rope_chunk(qraw[i], (float)min(kTile * t + i * G::kRowsPerPass + lrow, n - 1), rev);
+#pragma unroll
+        for (int i = 0; i < kShare; ++i) {
+            const int pidx = w * kShare + i;
+            ksh[i] = rope_chunk(ksh[i], (float)min(kTile * (pidx / G::kPasses) + (pidx % G::kPasses) * G::kRowsPerPass + lrow, n - 1), rev);
+        }
+    }
+
+    const uint32_t stg = (uint32_t)(lrow * G::kPitch) + lbyte;                                   // row-major staging offset of this lane's chunk
+    const uint32_t nat = (uint32_t)(r32 * G::kPitch + hf * 16);                                  // natural operand reads
+    const uint32_t trn = (uint32_t)((4 * hf + ((lane & 15) >> 2)) * G::kPitch + (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2);   // transposed operand reads
+
+    // which blocks exist: key tiles some row of query tile t sees, query tiles with a row that sees a key of tile t
+    bool visq[2], visk[2];
+    {
+        int lo, hi, lo2, hi2;
+        visible_range(kTile * t, 0, n, p.causal, p.window, lo, hi);
+        visible_range(min(kTile * t + kTile - 1, n - 1), 0, n, p.causal, p.window, lo2, hi2);
+        visq[0] = lo < kTile && hi2 > 0;
+        visq[1] = hi2 > kTile;
+        seen_range(kTile * t, 0, n, p.causal, p.window, lo, hi);
+        seen_range(min(kTile * t + kTile - 1, n - 1), 0, n, p.causal, p.window, lo2, hi2);
+        visk[0] = lo < kTile && hi2 > 0;
+        visk[1] = hi2 > kTile;
+    }
+
+    // ---- shared tiles into LDS; X staged ------------------------------------------------------------------
+#pragma unroll
+    for (int i = 0; i < kShare; ++i) {
+        const int pidx = w * kShare + i;
+        const uint32_t at = (uint32_t)((pidx / G::kPasses) * kBuf + ((pidx % G::kPasses) * G::kRowsPerPass) * G::kPitch) + stg;
+        *reinterpret_cast<u32x4*>(sK + at) = ksh[i];
+        if constexpr (VS) *reinterpret_cast<u32x4*>(sX + at) = xsh[i];
+    }
+    u32x4 xn[2][G::kKSteps];                              // X_0, X_1 as natural operands
+    if constexpr (!VS) stage_rows<D>(buf + stg, xraw);
+    __syncthreads();                                      // (1) shared tiles and every X tile are in place
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        if (VS) read_natural<D>(sX + c * kBuf + nat, xn[c]);
+        else read_natural<D>((c == t ? buf : pbuf) + nat, xn[c]);
+    }
+    __syncthreads();                                      // (2) the X tiles have been read
+
+    // ---- G staged: dP in both orientations --------------------------------------------------------------
+    stage_rows<D>(buf + stg, graw);
+    __syncthreads();                                      // (3)
+    f32x16 dpT[2], dpN[2];                                // dpT[c]: rows of tile t x keys of tile c;  dpN[a]: keys of tile t x rows of tile a
+    {
+        u32x4 gn[G::kKSteps];
+        read_natural<D>(buf + nat, gn);
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            dpT[c] = f32x16{};
+            if (visq[c]) {
+#pragma unroll
+                for (int s = 0; s < G::kKSteps; ++s) dpT[c] = mma(xn[c][s], gn[s], dpT[c]);
+            }
+        }
+        u32x4 xt[G::kKSteps];                             // X of this wave's own tile (t is the same in every lane)
+#pragma unroll
+        for (int s = 0; s < G::kKSteps; ++s) xt[s] = t ? xn[1][s] : xn[0][s];
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            dpN[a] = f32x16{};
+            if (visk[a]) {
+                read_natural<D>((a == t ? buf : pbuf) + nat, gn);
+#pragma unroll
+                for (int s = 0; s < G::kKSteps; ++s) dpN[a] = mma(gn[s], xt[s], dpN[a]);
+            }
+        }
+    }
+    __syncthreads();                                      // (4) the G tiles have been read
+
+    // ---- Q staged: scores in both orientations, statistics, dS ----------------------------------------
+    stage_rows<D>(buf + stg, qraw);
+    __syncthreads();                                      // (5)
+    f32x16 sT[2], sN[2];
+    {
+        u32x4 qn[G::kKSteps], kn[G::kKSteps];
+        read_natural<D>(buf + nat, qn);
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            sT[c] = f32x16{};
+            if (visq[c]) {
+                read_natural<D>(sK + c * kBuf + nat, kn);
+#pragma unroll
+                for (int s = 0; s < G::kKSteps; ++s) sT[c] = mma(kn[s], qn[s], sT[c]);
+            }
+        }
+    }
+    // rows of tile t: masked softmax over both key tiles, delta, dS^T as B operands
+    u32x4 dsT[2][2];
+    {
+        const int qr = kTile * t + r32;
+        float e[2][16], mx = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const uint32_t vis = visq[c] ? block_vis_keys(p, qr, c, nreal) >> (4 * hf) : 0u;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const bool ok = (vis >> (8 * (r / 4) + (r % 4))) & 1u;
+                e[c][r] = ok ? sT[c][r] * sl2 : -INFINITY;
+                mx = fmaxf(mx, e[c][r]);
+            }
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        if (mx == -INFINITY) mx = 0.f;
+        float sum = 0.f;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { e[c][r] = __builtin_amdgcn_exp2f(e[c][r] - mx); sum += e[c][r]; }
+        sum += __shfl_xor(sum, 32);
+        const float inv = sum > 0.f ? 1.f / sum : 0.f;
+        float delta = 0.f;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) { e[c][r] *= inv; delta += e[c][r] * dpT[c][r]; }
+        delta += __shfl_xor(delta, 32);
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) e[c][r] *= (dpT[c][r] - delta);
+            pack_rows(e[c], dsT[c]);
+        }
+        if (lane < kTile) {
+            float* st = stats + t * (3 * kTile);
+            st[lane] = mx; st[kTile + lane] = inv; st[2 * kTile + lane] = delta;
+        }
+    }
+    {   // the scores with one key per lane, after the row softmax above has released its registers
+        u32x4 qn[G::kKSteps], kn[G::kKSteps];
+        read_natural<D>(sK + t * kBuf + nat, kn);
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            sN[a] = f32x16{};
+            if (visk[a]) {
+                read_natural<D>((a == t ? buf : pbuf) + nat, qn);
+#pragma unroll
+                for (int s = 0; s < G::kKSteps; ++s) sN[a] = mma(qn[s], kn[s], sN[a]);
+            }
+        }
+    }
+    __syncthreads();                                      // (6) both tiles' statistics are visible
+    // keys of tile t: P and dS with one key per lane, as B operands
+    u32x4 pN[2][2], dsN[2][2];
+    {
+        const int kr = kTile * t + r32;
+#pragma unroll
+        for (int a = 0; a < 2; ++a) {
+            float pr[16], ds[16];
+            const uint32_t vis = visk[a] ? block_vis_rows(p, kr, a, nreal) >> (4 * hf) : 0u;
+            const float* st = stats + a * (3 * kTile);
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4 m4 = *reinterpret_cast<const f32x4*>(st + 8 * q4 + 4 * hf);
+                const f32x4 i4 = *reinterpret_cast<const f32x4*>(st + kTile + 8 * q4 + 4 * hf);
+                const f32x4 d4 = *reinterpret_cast<const f32x4*>(st + 2 * kTile + 8 * q4 + 4 * hf);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = 4 * q4 + j;
+                    const bool ok = (vis >> (8 * q4 + j)) & 1u;
+                    const float pv = ok ? __builtin_amdgcn_exp2f(sN[a][r] * sl2 - m4[j]) * i4[j] : 0.f;
+                    pr[r] = pv;
+                    ds[r] = pv * (dpN[a][r] - d4[j]);
+                }
+            }
+            pack_rows(pr, pN[a]);
+            pack_rows(ds, dsN[a]);
+        }
+    }
+    // ---- dK_t^T = sum_a Q_a^T dS_at, while the Q tiles are still staged ----------------------------------
+    f32x16 acc[G::kDTiles];
+#pragma unroll
+    for (int tt = 0; tt < G::kDTiles; ++tt) acc[tt] = f32x16{};
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+        if (visk[a]) {
+            u32x4 qT[G::kDTiles][2];
+            read_transposed<D>((a == t ? buf : pbuf) + trn, qT);
+#pragma unroll
+            for (int tt = 0; tt < G::kDTiles; ++tt)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) acc[tt] = mma(qT[tt][s2], dsN[a][s2], acc[tt]);
+        }
+    }
+    __syncthreads();                                      // (7) the Q tiles have been read: the transit tiles are free
+    const auto enc = unrope(&p, [&](int r) { return (float)(kTile * t + r); });
+    {
+        u32x4 oldk[G::kDTiles * 2] = {};
+        const bool last = hl == GH - 1;                   // the wave that ends up with the group's sum
+        if (bp.accumulate && last) prefetch_tile<D>(oldk, rowoff, 1, dkb, lane);
+        if (GH > 1) chain_sum<D>(acc, red, hl, GH, lane);
+        if (last) store_tile<D, false>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.accumulate != 0, rows_t, lane, 0, enc);
+    }
+    // ---- dQ_t^T = sum_c K_c^T dS^T_tc ------------------------------------------------------------------------
+    {
+        u32x4 oldq[G::kDTiles * 2] = {};
+        if (bp.accumulate) prefetch_tile<D>(oldq, rowoff, 0, dqb, lane);
+#pragma unroll
+        for (int tt = 0; tt < G::kDTiles; ++tt) acc[tt] = f32x16{};
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            if (visq[c]) {
+                u32x4 kT[G::kDTiles][2];
+                read_transposed<D>(sK + c * kBuf + trn, kT);
+#pragma unroll
+                for (int tt = 0; tt < G::kDTiles; ++tt)
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2) acc[tt] = mma(kT[tt][s2], dsT[c][s2], acc[tt]);
+            }
+        }
+        store_tile<D, false>(acc, p.scale, buf, rowoff, 0, dqb, oldq, bp.accumulate != 0, rows_t, lane, 0, enc);
+    }
+    // ---- G staged again: dX_t^T = sum_a G_a^T P_at ---------------------------------------------------------
+    lds_wave_sync();
+    stage_rows<D>(buf + stg, graw);
+    __syncthreads();                                      // (8)
+#pragma unroll
+    for (int tt = 0; tt < G::kDTiles; ++tt) acc[tt] = f32x16{};
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+        if (visk[a]) {
+            u32x4 gT[G::kDTiles][2];
+            read_transposed<D>((a == t ? buf : pbuf) + trn, gT);
+#pragma unroll
+            for (int tt = 0; tt < G::kDTiles; ++tt)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) acc[tt] = mma(gT[tt][s2], pN[a][s2], acc[tt]);
+        }
+    }
+    __syncthreads();                                      // (9) the G tiles have been read
+    if (!VS) {
+        store_tile_plain<D>(acc, 1.f, buf, rowoff, 2, dxb, rows_t, lane);
+    } else {
+        u32x4 none[G::kDTiles * 2] = {};
+        if (GH > 1) chain_sum<D>(acc, red, hl, GH, lane);
+        if (hl == GH - 1) store_tile<D, false>(acc, 1.f, buf, rowoff, 2, dxb, none, false, rows_t, lane);
+    }
+}
+
+template <int D, int GH>
+hipError_t launch_two_tile(const BwdParams& bp, hipStream_t s) {
+    const HopParams& p = bp.hop;
+    StreamBwdParams sp;
+    sp.q_row = (uint32_t)(p.q.st * 2); sp.k_row = (uint32_t)(p.k.st * 2);
+    sp.v_row = (uint32_t)(p.vin.st * 2); sp.o_row = (uint32_t)(bp.d_o.st * 2);
+    sp.tiles = 2;
+    sp.fibres_lo = (uint32_t)(p.fibres < 32768 ? p.fibres : 32768);
+    sp.fibres_hi = (uint32_t)((p.fibres + sp.fibres_lo - 1) / sp.fibres_lo);
+    if ((int64_t)p.B * sp.fibres_hi > 65535) return hipErrorInvalidValue;
+    const bool vs = p.vin_heads != p.Hq;
+    const size_t smem = two_tile_lds<D>(GH, vs);
+    const void* kf = vs ? reinterpret_cast<const void*>(mfma_bwd2_kernel<D, GH, true>) : reinterpret_cast<const void*>(mfma_bwd2_kernel<D, GH, false>);
+    if (smem > 64 * 1024) {
+        const hipError_t e = allow_dynamic_lds(kf, (int)smem);
+        if (e != hipSuccess) return e;
+    }
+    const dim3 grid((unsigned)p.Hkv, sp.fibres_lo, (unsigned)p.B * sp.fibres_hi);
+    if (vs) hipLaunchKernelGGL((mfma_bwd2_kernel<D, GH, true>), grid, dim3(128 * GH), smem, s, bp, sp);
+    else    hipLaunchKernelGGL((mfma_bwd2_kernel<D, GH, false>), grid, dim3(128 * GH), smem, s, bp, sp);
+    return hipGetLastError();
+}
+
 template <int D, bool NARROW>
 hipError_t launch_stream(const BwdParams& bp, hipStream_t s) {
     const HopParams& p = bp.hop;
@@ -875,7 +1241,7 @@ hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
 
 }  // namespace
 
-// 1: the one-tile kernel (n <= 32); 2: the blocked kernel (32 < n <= kStreamMaxN); 0: neither.
+// 1: the one-tile kernel (n <= 32); 3: the two-tile kernel (32 < n <= 64, see there); 2: the blocked kernel (other axes up to kStreamMaxN); 0: none.
 static int backward_variant(const BwdParams& bp, int dtype) {
     const HopParams& p = bp.hop;
     const bool full = p.D == 64 || p.D == 128;
@@ -892,10 +1258,12 @@ static int backward_variant(const BwdParams& bp, int dtype) {
         hp.o = bp.d_o;
         return make_tile_params(hp, 1, &tp) ? 1 : 0;
     }
-    {   // the blocked kernel's grid: (Hkv, fibres_lo, B * fibres_hi)
+    {   // the grid of the kernels below: (Hkv, fibres_lo, B * fibres_hi)
         const int64_t lo = p.fibres < 32768 ? p.fibres : 32768;
         if (p.fibres <= 0 || (int64_t)p.B * ((p.fibres + lo - 1) / lo) > 65535) return 0;
     }
+    // two tiles, full-width heads, groups of 1, 2 or 4 heads: every tile is read once per fibre
+    if (p.n <= 2 * kTile && full && (p.G == 1 || p.G == 2 || p.G == 4)) return 3;
     // the blocked kernel keeps three floats per row and head in LDS
     const size_t tiles = (size_t)(p.n + kTile - 1) / kTile;
     const size_t kbuf = p.D > 64 ? BGeo<128>::kBufBytes : BGeo<64>::kBufBytes;
@@ -906,6 +1274,7 @@ static int backward_variant(const BwdParams& bp, int dtype) {
 
 bool mfma_backward_supports(const BwdParams& bp, int dtype) { return backward_variant(bp, dtype) != 0; }
 bool mfma_backward_is_blocked(const BwdParams& bp, int dtype) { return backward_variant(bp, dtype) == 2; }
+bool mfma_backward_is_two_tile(const BwdParams& bp, int dtype) { return backward_variant(bp, dtype) == 3; }
 
 hipError_t launch_mfma_backward(const BwdParams& user, hipStream_t s) {
     const int variant = backward_variant(user, TA_BF16);
@@ -919,6 +1288,11 @@ hipError_t launch_mfma_backward(const BwdParams& user, hipStream_t s) {
     // dV), in a fixed order, so the result stays deterministic.
     BwdParams bp = user;
     const int G = user.hop.G;
+    if (variant == 3) {
+        bp.wg_heads = G; bp.head_base = 0; bp.acc_k = user.accumulate; bp.acc_x = 0;
+        if (bp.hop.D == 128) return G == 4 ? launch_two_tile<128, 4>(bp, s) : G == 2 ? launch_two_tile<128, 2>(bp, s) : launch_two_tile<128, 1>(bp, s);
+        return G == 4 ? launch_two_tile<64, 4>(bp, s) : G == 2 ? launch_two_tile<64, 2>(bp, s) : launch_two_tile<64, 1>(bp, s);
+    }
     for (int base = 0; base < G; base += 8) {
         bp.wg_heads = G - base > 8 ? 8 : G - base;
         bp.head_base = base;

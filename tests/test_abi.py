@@ -286,7 +286,8 @@ def test_kernels_for_other_head_widths():
     assert p.hop_backward_kernel(1, ta.TA_VIN_O) == "mfma_bf16_bwd_n32"
     two_tiles = ta.ta_plan_create(1, 32, 32, 100, (64, 16), ta.TA_BF16, True)
     assert two_tiles.hop_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_n64"
-    assert two_tiles.hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_blocked"
+    assert two_tiles.hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_blocked"      # narrow heads stay on the blocked kernel
+    assert ta.ta_plan_create(1, 32, 8, 128, (64, 16), ta.TA_BF16, True).hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_n64"
     long_axis = ta.ta_plan_create(1, 8, 2, 96, (128, 4), ta.TA_BF16, True)
     assert long_axis.hop_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_stream_shared_kv"
     odd = ta.ta_plan_create(1, 4, 4, 90, (16, 16), ta.TA_BF16, True)       # even, not a multiple of 4

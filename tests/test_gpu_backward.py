@@ -32,9 +32,13 @@ CASES = [
     ((3, 20), 1, 2, 1, 256, True, "f32"),
     ((32, 16), 1, 4, 1, 128, True, "bf16"),
     ((16, 32, 4), 2, 4, 2, 128, True, "bf16"),
-    ((64, 8), 1, 2, 2, 64, False, "bf16"),           # n = 64: the blocked kernel, two tiles
+    ((64, 8), 1, 2, 2, 64, False, "bf16"),           # n = 64: the two-tile kernel, one head per group
     ((64, 4), 1, 4, 1, 128, True, "bf16"),           # the same, causal, a group of 4 heads (dK, dV summed over it)
-    ((3, 50), 2, 2, 1, 128, True, "bf16"),           # ragged second tile
+    ((3, 50), 2, 2, 1, 128, True, "bf16"),           # ragged second tile, 2 heads per group
+    ((64, 64, 2), 1, 8, 2, 128, True, "bf16"),       # two hops on 64-long axes: as the value-input hop and as a later hop, dQ / dK accumulate
+    ((33, 3), 2, 4, 1, 64, False, "bf16"),           # one row in the second tile
+    ((2, 64), 1, 4, 4, 128, False, "bf16"),          # full second tile, non-causal: all four blocks
+    ((48, 2), 1, 16, 2, 128, True, "bf16"),          # 8 heads per group on a two-tile axis: the blocked kernel
     ((100, 2), 1, 8, 1, 128, False, "bf16"),         # four tiles, 8 heads per group
     ((2, 200), 1, 4, 2, 64, True, "bf16"),           # seven tiles
     ((333,), 1, 2, 2, 128, True, "bf16"),            # one long axis: plain causal attention, 11 tiles
@@ -169,11 +173,13 @@ def test_backward_strided_head_major_layout(dtype):
         check_gradient(to_host(got).transpose(0, 2, 1, 3), ref, tol, name)
 
 
-def test_blocked_backward_is_chosen_for_long_bf16_axes():
+def test_backward_kernel_choice_for_axes_longer_than_one_tile():
     plan = ta.ta_plan_create(1, 32, 8, 128, (64, 64, 32), ta.TA_BF16, True)
-    assert plan.hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_blocked"
-    assert plan.hop_backward_kernel(1, ta.TA_VIN_O) == "mfma_bf16_bwd_blocked"
+    assert plan.hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_n64"
+    assert plan.hop_backward_kernel(1, ta.TA_VIN_O) == "mfma_bf16_bwd_n64"
     assert plan.hop_backward_kernel(2, ta.TA_VIN_O) == "mfma_bf16_bwd_n32"
+    assert ta.ta_plan_create(1, 32, 4, 128, (64, 4), ta.TA_BF16, True).hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_blocked"   # 8 heads per group
+    assert ta.ta_plan_create(1, 8, 2, 128, (65, 4), ta.TA_BF16, True).hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_blocked"    # three tiles
     long_axis = ta.ta_plan_create(1, 8, 2, 128, (1024, 4), ta.TA_BF16, True)
     assert long_axis.hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_blocked"
     too_long = ta.ta_plan_create(1, 8, 2, 128, (2048, 2), ta.TA_BF16, True)
