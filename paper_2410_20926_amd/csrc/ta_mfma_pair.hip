@@ -55,6 +55,7 @@ struct PairParams {
     int64_t valid_len;                       // tokens at or past it (per batch element) are padding; N when there is none
     const int64_t* valid_lens;               // device: one such length per batch element (combined with valid_len), or nullptr
     uint32_t dbytes;                         // bytes of a row (2 * head width)
+    float rope_c0, rope_c1;                  // rotary encoding inside the hops: pair p of a row at position a turns by a * exp2(rope_c0 * p + rope_c1) revolutions
 };
 
 // Phase-A LDS layout.  Token (i, j)'s 64-byte chunk row of Q sits at i * kABlock + j * 64, that
@@ -153,7 +154,13 @@ __device__ inline void update_fibre(char* lds, uint32_t fb, uint32_t rs, const u
 // kD: tile width, 128 (two 128-byte lines per row, four score chunks, two value chunks) or 64.
 // NARROW: the head is narrower than the tile (p.dbytes bytes per row, a multiple of 8); the tile's
 // extra features are zero.
-template <int kD, bool MID, bool NARROW>
+// ROPE: both hops score with Q and K rotated by the position on their own axis (Sec. 3.2).  A token's rows
+// are needed in two versions then, turned by i for the first hop and by j for the second, so the turn is
+// applied to the MFMA operands after they have been read from LDS, where a lane holds four feature pairs of
+// the fibre row r32, whose position is r32 in either kind of fibre.  The sine and cosine of the lane's
+// angles are rounded to bf16 and the turn is two bf16 dot products per pair (v_dot2_f32_bf16: exact
+// products, fp32 sums), so a turned pair is exact up to 2^-9 of its size before its own rounding to bf16.
+template <int kD, bool MID, bool NARROW, bool ROPE>
 __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int lane = threadIdx.x & 63;
@@ -258,17 +265,64 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
             *reinterpret_cast<u32x4*>(dst + kAK) = kreg[pp];
         }
     };
-    auto scores = [&]() {
+    auto scores = [&](int c) {                            // c: the 32-feature chunk in LDS
+        if constexpr (!ROPE) {
 #pragma unroll
-        for (int f = 0; f < kOwn; ++f)
+            for (int f = 0; f < kOwn; ++f)
+#pragma unroll
+                for (int s = 0; s < kCA / 16; ++s) {
+                    const char* ac = lds + col_a[((f >> 1) + 2 * s) & 3] + f * kARow;
+                    const char* ar = lds + row_a[s] + f * kABlock;
+                    sc[f] = mma(*reinterpret_cast<const u32x4*>(ac + kAK), *reinterpret_cast<const u32x4*>(ac), sc[f]);
+                    sr[f] = mma(*reinterpret_cast<const u32x4*>(ar + kAK), *reinterpret_cast<const u32x4*>(ar), sr[f]);
+                    __builtin_amdgcn_sched_barrier(0);    // keeps the operand reads from piling up in registers
+                }
+        } else {
 #pragma unroll
             for (int s = 0; s < kCA / 16; ++s) {
-                const char* ac = lds + col_a[((f >> 1) + 2 * s) & 3] + f * kARow;
-                const char* ar = lds + row_a[s] + f * kABlock;
-                sc[f] = mma(*reinterpret_cast<const u32x4*>(ac + kAK), *reinterpret_cast<const u32x4*>(ac), sc[f]);
-                sr[f] = mma(*reinterpret_cast<const u32x4*>(ar + kAK), *reinterpret_cast<const u32x4*>(ar), sr[f]);
-                __builtin_amdgcn_sched_barrier(0);        // keeps the operand reads from piling up in registers
+                // this lane's operand words of step s are the feature pairs 16 c + 8 s + 4 hf + e of row r32
+                bf16x2 ce[4], co[4];                      // (cos, -sin) and (sin, cos) of each pair's angle
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float rate = __builtin_amdgcn_exp2f(p.rope_c0 * (float)(16 * c + 8 * s + 4 * hf + e) + p.rope_c1);
+                    const float tt = __builtin_amdgcn_fractf((float)r32 * rate);
+                    const float sn = __builtin_amdgcn_sinf(tt), cs = __builtin_amdgcn_cosf(tt);
+                    ce[e] = __builtin_bit_cast(bf16x2, pack_bf16x2(cs, -sn));
+                    co[e] = __builtin_bit_cast(bf16x2, pack_bf16x2(sn, cs));
+                }
+                // The three-operand form of the bf16 dot product with a literal zero to add to (the compiler's own
+                // choice, the two-operand accumulating form, needs a register cleared first for every product).
+                // A dot product's result may be read by a vector instruction only three wait states later: the
+                // eight products of an operand are issued back to back and one s_nop follows the last.
+                auto turn = [&](const u32x4 x) {
+                    float e0, o0, e1, o1, e2, o2, e3, o3;
+                    asm("v_dot2_f32_bf16 %0, %8, %12, 0\n\t"
+                        "v_dot2_f32_bf16 %1, %8, %13, 0\n\t"
+                        "v_dot2_f32_bf16 %2, %9, %14, 0\n\t"
+                        "v_dot2_f32_bf16 %3, %9, %15, 0\n\t"
+                        "v_dot2_f32_bf16 %4, %10, %16, 0\n\t"
+                        "v_dot2_f32_bf16 %5, %10, %17, 0\n\t"
+                        "v_dot2_f32_bf16 %6, %11, %18, 0\n\t"
+                        "v_dot2_f32_bf16 %7, %11, %19, 0\n\t"
+                        "s_nop 2"
+                        : "=&v"(e0), "=&v"(o0), "=&v"(e1), "=&v"(o1), "=&v"(e2), "=&v"(o2), "=&v"(e3), "=&v"(o3)
+                        : "v"(x.x), "v"(x.y), "v"(x.z), "v"(x.w),
+                          "v"(__builtin_bit_cast(uint32_t, ce[0])), "v"(__builtin_bit_cast(uint32_t, co[0])),
+                          "v"(__builtin_bit_cast(uint32_t, ce[1])), "v"(__builtin_bit_cast(uint32_t, co[1])),
+                          "v"(__builtin_bit_cast(uint32_t, ce[2])), "v"(__builtin_bit_cast(uint32_t, co[2])),
+                          "v"(__builtin_bit_cast(uint32_t, ce[3])), "v"(__builtin_bit_cast(uint32_t, co[3])));
+                    return u32x4{pack_bf16x2(e0, o0), pack_bf16x2(e1, o1), pack_bf16x2(e2, o2), pack_bf16x2(e3, o3)};
+                };
+#pragma unroll
+                for (int f = 0; f < kOwn; ++f) {
+                    const char* ac = lds + col_a[((f >> 1) + 2 * s) & 3] + f * kARow;
+                    const char* ar = lds + row_a[s] + f * kABlock;
+                    sc[f] = mma(turn(*reinterpret_cast<const u32x4*>(ac + kAK)), turn(*reinterpret_cast<const u32x4*>(ac)), sc[f]);
+                    sr[f] = mma(turn(*reinterpret_cast<const u32x4*>(ar + kAK)), turn(*reinterpret_cast<const u32x4*>(ar)), sr[f]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
+        }
     };
     static_assert(kD == 4 * kCA || kD == 2 * kCA, "one or two 128-byte lines per row");
     write_chunk(q0);                                      // chunk 0
@@ -276,7 +330,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
     if (kD == 4 * kCA) load_q(r0, r1, 1, 0, 4);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
-    scores();
+    scores(0);
     __syncthreads();
     write_chunk(q1);                                      // chunk 1
     if (kD == 4 * kCA) {
@@ -284,13 +338,13 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
         load_q(r0, r1, 1, 4, 8);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        scores();
+        scores(1);
         __syncthreads();
         write_chunk(r0);                                  // chunk 2
         load_k(3);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        scores();
+        scores(2);
         __syncthreads();
         write_chunk(r1);                                  // chunk 3
     }
@@ -316,7 +370,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
     load_x(0, 0, 8);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
-    scores();
+    scores(kD / kCA - 1);
 
     // softmax of the 8 tiles; `left` = real (unpadded) tokens from the slab's first token on
     const float sl2 = p.scale * kLog2e;
@@ -380,8 +434,19 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
     }
 }
 
+// The instantiation for a tile width (128 or 64), with or without the intermediate output, narrow rows, the encoding.
+template <int kD>
+const void* pair_kernel_of_width(bool mid, bool narrow, bool rope) {
+    if (rope) return narrow ? (mid ? (const void*)mfma_fwd_pair_kernel<kD, true, true, true> : (const void*)mfma_fwd_pair_kernel<kD, false, true, true>)
+                            : (mid ? (const void*)mfma_fwd_pair_kernel<kD, true, false, true> : (const void*)mfma_fwd_pair_kernel<kD, false, false, true>);
+    return narrow ? (mid ? (const void*)mfma_fwd_pair_kernel<kD, true, true, false> : (const void*)mfma_fwd_pair_kernel<kD, false, true, false>)
+                  : (mid ? (const void*)mfma_fwd_pair_kernel<kD, true, false, false> : (const void*)mfma_fwd_pair_kernel<kD, false, false, false>);
+}
+const void* pair_kernel_of(bool wide, bool mid, bool narrow, bool rope) {
+    return wide ? pair_kernel_of_width<128>(mid, narrow, rope) : pair_kernel_of_width<64>(mid, narrow, rope);
+}
+
 bool pair_params(const HopParams& h1, const HopParams& h2, PairParams* pp) {
-    if (h1.rope) return false;                            // the fused kernel scores with Q and K as given
     if (h1.n != kN || h2.n != kN || h1.D < 8 || h1.D > 128 || h1.D % 4 != 0 || h2.stride != 1 || h1.stride != kN) return false;
     const int64_t N = h1.fibres * h1.n;
     if (!fits_u32(h1.q, kSlab) || !fits_u32(h1.k, kSlab) || !fits_u32(h1.vin, kSlab) || !fits_u32(h1.o, kSlab)) return false;
@@ -397,6 +462,7 @@ bool pair_params(const HopParams& h1, const HopParams& h2, PairParams* pp) {
     pp->valid_len = h1.valid_len;
     pp->valid_lens = h1.valid_lens;
     pp->dbytes = (uint32_t)h1.D * 2;
+    pp->rope_c0 = h1.rope_c0; pp->rope_c1 = h1.rope_c1;
     pp->slabs = (uint32_t)slabs;
     pp->groups = (uint32_t)groups;
     pp->q_row = (uint32_t)(h1.q.st * 2); pp->k_row = (uint32_t)(h1.k.st * 2);
@@ -415,12 +481,8 @@ hipError_t launch_mfma_forward_pair(const HopParams& h1, const HopParams& h2, vo
     PairParams pp;
     if (!pair_params(h1, h2, &pp)) return hipErrorInvalidValue;
     pp.mid = o_mid;
-    const bool wide = h1.D > 64, narrow = h1.D != 64 && h1.D != 128, mid = o_mid != nullptr;
-    const void* kf;
-    if (wide) kf = narrow ? (mid ? (const void*)mfma_fwd_pair_kernel<128, true, true> : (const void*)mfma_fwd_pair_kernel<128, false, true>)
-                          : (mid ? (const void*)mfma_fwd_pair_kernel<128, true, false> : (const void*)mfma_fwd_pair_kernel<128, false, false>);
-    else      kf = narrow ? (mid ? (const void*)mfma_fwd_pair_kernel<64, true, true> : (const void*)mfma_fwd_pair_kernel<64, false, true>)
-                          : (mid ? (const void*)mfma_fwd_pair_kernel<64, true, false> : (const void*)mfma_fwd_pair_kernel<64, false, false>);
+    const bool wide = h1.D > 64, narrow = h1.D != 64 && h1.D != 128, mid = o_mid != nullptr, rope = h1.rope != 0;
+    const void* kf = pair_kernel_of(wide, mid, narrow, rope);
     const hipError_t e = allow_dynamic_lds(kf, kLdsBytes);
     if (e != hipSuccess) return e;
     const uint32_t span = 8u * (uint32_t)pp.G;

@@ -123,10 +123,10 @@ def test_rope_flag_must_be_0_or_1():
     with pytest.raises(ta.TaError) as e:
         ta.Plan(d)
     assert e.value.name == "TA_ERR_INVALID_ARG"
-    # with the encoding on, the fused pair of hops is not offered and the workspace is sized for separate hops
+    # the encoding rides on the same kernels, the fused pair of hops included
     p = ta.ta_plan_create(1, 32, 8, 128, (32, 32, 32), ta.TA_BF16, True, rope_base=10000.0)
-    assert p.fused_position() == -1 and p.pair_kernel(1, ta.TA_VIN_O) == "unsupported"
-    assert p.workspace_bytes(False) == 2 * 32768 * 32 * 128 * 2
+    assert p.fused_position() == 1 and p.pair_kernel(1, ta.TA_VIN_O) == "mfma_bf16_pair_n32"
+    assert p.workspace_bytes(False) == 32768 * 32 * 128 * 2
     assert p.hop_kernel(1, ta.TA_VIN_O) == "mfma_bf16_n32_shared" and p.hop_backward_kernel(1, ta.TA_VIN_O) == "mfma_bf16_bwd_n32"
 
 

@@ -72,7 +72,11 @@ from grad_bounds import check_backward
 
 ROPE_CASES = [
     # dims, B, Hq, Hkv, D, causal, dtype
-    ((32, 32), 1, 8, 2, 128, True, "bf16"),          # one tile per fibre, group-shared kernel (K and V shared)
+    ((32, 32), 1, 8, 2, 128, True, "bf16"),          # the two hops fused in one launch (value input V)
+    ((3, 32, 32), 2, 4, 1, 128, False, "bf16"),      # a single hop, then the fused pair (value input a previous O)
+    ((32, 32), 1, 2, 2, 64, True, "bf16"),           # fused pair at head width 64
+    ((2, 32, 32), 1, 4, 4, 100, True, "bf16"),       # fused pair with narrow rows
+    ((32, 16), 1, 8, 2, 128, True, "bf16"),          # one tile per fibre, group-shared kernel (K and V shared)
     ((4, 32, 8), 2, 4, 4, 128, True, "bf16"),        # one head per group: the plain one-tile kernel; packed fibres on the last axis
     ((16, 8), 1, 4, 1, 64, False, "bf16"),           # several fibres per tile: positions restart inside a tile
     ((5, 7, 3), 2, 4, 2, 64, True, "bf16"),          # ragged tiles
@@ -95,7 +99,6 @@ def test_encoded_multihop_forward_and_backward_match_oracle(dims, B, Hq, Hkv, D,
     base = 10000.0 if D >= 64 else 200.0
     q, k, v, d_o = make_inputs(B, N, Hq, Hkv, D, seed=7300 + N + D, dtype=dtype, with_grad=True)
     got, plan, dev = multihop_forward(q, k, v, dims, dtype, causal, save=True, rope_base=base)
-    assert plan.fused_position() == -1                   # the fused pair scores with Q and K as given
     ref = orc.tensorized_attention_forward(q, k, v, dims, causal, rope_base=base)
     plain = orc.tensorized_attention_forward(q, k, v, dims, causal)
     err = np.abs(got - ref).max()
@@ -104,6 +107,9 @@ def test_encoded_multihop_forward_and_backward_match_oracle(dims, B, Hq, Hkv, D,
     assert np.abs(ref - plain).max() > 10 * TOL[dtype]   # the case would notice a missing rotation
     grads = multihop_backward(plan, dev, d_o, dtype)
     check_backward(grads, q, k, v, d_o, dims, causal, dtype, rope_base=base)
+    if plan.fused_position() >= 0:                       # the inference forward of the same plan does not write the tensor between the fused hops
+        inf, _, _ = multihop_forward(q, k, v, dims, dtype, causal, save=False, rope_base=base)
+        assert np.array_equal(inf, got)
 
 
 def test_encoded_hop_equals_standalone_encoding_then_hop():
@@ -127,13 +133,13 @@ def test_encoded_hop_equals_standalone_encoding_then_hop():
 
 
 def test_config3_shape_encoded_full_size_sampled_heads():
-    """32 x 32 x 32, 32 / 8 heads, D = 128, causal, with the encoding on: three single hops."""
+    """32 x 32 x 32, 32 / 8 heads, D = 128, causal, with the encoding on: one hop, then the fused pair."""
     from paper_2410_20926_amd.workloads import WORKLOADS, make_workload_inputs
     w = WORKLOADS["c3"]
     q, k, v = make_workload_inputs(w, with_grad=False)
     q, k = q * np.float32(4.0), k * np.float32(4.0)          # exact in bf16; gives the softmax something to do
     got, plan, _ = multihop_forward(q, k, v, w.dims, "bf16", True, rope_base=10000.0)
-    assert [plan.hop_kernel(a, 0 if a == 0 else 1) for a in range(3)] == ["mfma_bf16_n32_shared_kv", "mfma_bf16_n32_shared", "mfma_bf16_n32_shared"]
+    assert plan.hop_kernel(0, 0) == "mfma_bf16_n32_shared_kv" and plan.fused_position() == 1
     G = w.n_q_heads // w.n_kv_heads
     for h in (0, 7, 13, 22, 31):
         g = h // G
