@@ -200,7 +200,8 @@ __device__ inline void chain_sum(f32x16 (&acc)[Geo<D>::kDTiles], float* red, int
 // blockDim.x = 64 * G (G = query heads per key/value head: 1, 2, 4 or 8); grid = (Hkv, tiles_lo, B * tiles_hi).
 // TABLE: the axis has a caller's bit table; MULTI: the group has more than 8 heads and this launch
 // covers 8 of them (separate instantiations keep the common case free of both).
-template <int D, bool TABLE, bool MULTI, bool NARROW>
+// ROPE: the hop scores with rotary-encoded Q and K (separate instantiations, so that the plain kernel carries none of it).
+template <int D, bool TABLE, bool MULTI, bool NARROW, bool ROPE>
 __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TileParams tp) {
     using G = BGeo<D>;
     const HopParams& p = bp.hop;
@@ -276,7 +277,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
         const int rc = min(row, rows_valid - 1);
         return (float)(rc - (int)((rc + 0.5f) * tp.inv_n) * n);
     };
-    if (p.rope) {
+    if constexpr (ROPE) {
         float rev[4];
         rope_rates(p, lcol, rev);
 #pragma unroll
@@ -287,7 +288,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
             kraw[i] = rope_apply(kraw[i], c, sn);
         }
     }
-    const auto enc = unrope(&p, row_pos);
+    const auto enc = [&]() { if constexpr (ROPE) return unrope(&p, row_pos); else return NoRope{}; }();
 
     char* stg = buf + lrow * G::kPitch + lbyte;                              // row-major staging (this lane's chunk)
     const char* oprd = buf + r32 * G::kPitch + hf * 16;                      // natural operand reads
@@ -485,7 +486,8 @@ __device__ inline uint32_t block_vis_rows(const HopParams& p, int kr, int a, int
     uint32_t v = range_mask(min(max(lo - kTile * a, 0), kTile), min(max(hi - kTile * a, 0), kTile));
     if (p.mask) {
         uint32_t col = 0;
-        for (int q = 0; q < kTile; ++q) {
+#pragma unroll 1
+        for (int q = 0; q < kTile; ++q) {                 // rare path: kept rolled, its 32 loads would otherwise claim registers in every kernel
             const int qr = kTile * a + q;
             if (qr < p.n) col |= ((p.mask[qr * p.mask_words + (kr >> 5)] >> (kr & 31)) & 1u) << q;
         }
@@ -969,13 +971,14 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
         *reinterpret_cast<u32x4*>(sK + at) = ksh[i];
         if constexpr (VS) *reinterpret_cast<u32x4*>(sX + at) = xsh[i];
     }
-    u32x4 xn[2][G::kKSteps];                              // X_0, X_1 as natural operands
+    // X_0, X_1 as natural operands: held in registers when they pass through the transit tiles, read from the
+    // shared tiles where needed otherwise
+    u32x4 xn[VS ? 1 : 2][G::kKSteps];
     if constexpr (!VS) stage_rows<D>(buf + stg, xraw);
     __syncthreads();                                      // (1) shared tiles and every X tile are in place
+    if constexpr (!VS) {
 #pragma unroll
-    for (int c = 0; c < 2; ++c) {
-        if (VS) read_natural<D>(sX + c * kBuf + nat, xn[c]);
-        else read_natural<D>((c == t ? buf : pbuf) + nat, xn[c]);
+        for (int c = 0; c < 2; ++c) read_natural<D>((c == t ? buf : pbuf) + nat, xn[c]);
     }
     __syncthreads();                                      // (2) the X tiles have been read
 
@@ -990,20 +993,24 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
         for (int c = 0; c < 2; ++c) {
             dpT[c] = f32x16{};
             if (visq[c]) {
+                if constexpr (VS) read_natural<D>(sX + c * kBuf + nat, xn[0]);
 #pragma unroll
-                for (int s = 0; s < G::kKSteps; ++s) dpT[c] = mma(xn[c][s], gn[s], dpT[c]);
+                for (int s = 0; s < G::kKSteps; ++s) dpT[c] = mma(xn[VS ? 0 : c][s], gn[s], dpT[c]);
             }
         }
-        u32x4 xt[G::kKSteps];                             // X of this wave's own tile (t is the same in every lane)
-#pragma unroll
-        for (int s = 0; s < G::kKSteps; ++s) xt[s] = t ? xn[1][s] : xn[0][s];
+        if constexpr (VS) read_natural<D>(sX + t * kBuf + nat, xn[0]);        // X of this wave's own tile
 #pragma unroll
         for (int a = 0; a < 2; ++a) {
             dpN[a] = f32x16{};
             if (visk[a]) {
                 read_natural<D>((a == t ? buf : pbuf) + nat, gn);
 #pragma unroll
-                for (int s = 0; s < G::kKSteps; ++s) dpN[a] = mma(gn[s], xt[s], dpN[a]);
+                for (int s = 0; s < G::kKSteps; ++s) {
+                    u32x4 xt;                             // t is the same in every lane: a select, not an indexed register
+                    if constexpr (VS) xt = xn[0][s];
+                    else xt = t ? xn[1][s] : xn[0][s];
+                    dpN[a] = mma(gn[s], xt, dpN[a]);
+                }
             }
         }
     }
@@ -1229,14 +1236,16 @@ hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
     const size_t smem = (size_t)(bp.wg_heads > 1 ? BGeo<D>::kRedBytes : 0) + (size_t)bp.wg_heads * BGeo<D>::kWaveBytes;
     const dim3 grid((unsigned)p.Hkv, tp.tiles_lo, (unsigned)p.B * tp.tiles_hi);
     const dim3 block(64 * bp.wg_heads);
-    if (p.G > bp.wg_heads) {
-        if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true, true, NARROW>), grid, block, smem, s, bp, tp);
-        else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false, true, NARROW>), grid, block, smem, s, bp, tp);
-    } else {
-        if (p.mask) hipLaunchKernelGGL((mfma_bwd_kernel<D, true, false, NARROW>), grid, block, smem, s, bp, tp);
-        else        hipLaunchKernelGGL((mfma_bwd_kernel<D, false, false, NARROW>), grid, block, smem, s, bp, tp);
-    }
-    return hipGetLastError();
+    const bool multi = p.G > bp.wg_heads, table = p.mask != nullptr;
+    const void* kf;
+    if (p.rope) kf = multi ? (table ? (const void*)mfma_bwd_kernel<D, true, true, NARROW, true> : (const void*)mfma_bwd_kernel<D, false, true, NARROW, true>)
+                           : (table ? (const void*)mfma_bwd_kernel<D, true, false, NARROW, true> : (const void*)mfma_bwd_kernel<D, false, false, NARROW, true>);
+    else        kf = multi ? (table ? (const void*)mfma_bwd_kernel<D, true, true, NARROW, false> : (const void*)mfma_bwd_kernel<D, false, true, NARROW, false>)
+                           : (table ? (const void*)mfma_bwd_kernel<D, true, false, NARROW, false> : (const void*)mfma_bwd_kernel<D, false, false, NARROW, false>);
+    BwdParams bpc = bp;
+    TileParams tpc = tp;
+    void* args[2] = {&bpc, &tpc};
+    return hipLaunchKernel(kf, grid, block, args, smem, s);
 }
 
 }  // namespace

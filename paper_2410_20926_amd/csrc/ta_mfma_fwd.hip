@@ -33,7 +33,8 @@ constexpr int kWavesPerBlock = 4;
 
 // KT = number of 32-key tiles a unit may walk (1: n <= 32, 2: n <= 64).
 // NARROW: the head is narrower than the D-wide tile (p.D features of 2 bytes per row); see load_chunk.
-template <int D, int KT, bool NARROW>
+// ROPE: the hop scores with rotary-encoded Q and K (instantiated separately: the plain kernels carry none of it).
+template <int D, int KT, bool NARROW, bool ROPE>
 __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopParams p, TileParams tp) {
     using G = Geo<D>;
     constexpr int kRows = kTile * KT;                     // rows of the unit's fibre set that have a table entry
@@ -152,7 +153,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
         if (KT == 1) { const int rc = min(row, rows_valid - 1); return (float)(rc - (int)((rc + 0.5f) * tp.inv_n) * n); }
         return (float)min(row, n - 1);
     };
-    if (p.rope) {
+    if constexpr (ROPE) {
         rope_rates(p, lcol, rev);
 #pragma unroll
         for (int i = 0; i < G::kPasses; ++i) {
@@ -186,7 +187,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
         st[j] = f32x16{};
         if (j < kt_end) {
             u32x4 kop[G::kKSteps];
-            if (KT > 1 && p.rope) {
+            if constexpr (KT > 1 && ROPE) {
 #pragma unroll
                 for (int i = 0; i < G::kPasses; ++i) kreg[j][i] = rope_chunk(kreg[j][i], row_pos(j * kTile + i * G::kRowsPerPass + lrow), rev);
             }
@@ -333,7 +334,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
 // (a previous O) still goes through the wave's private transit tile.
 // VS: the value input is shared too (first hop).  Then the private tile only carries Q in and O
 // out, one lane per row, and is used in two halves of 16 rows to halve its LDS footprint.
-template <int D, int KT, bool VS, bool NARROW>
+template <int D, int KT, bool VS, bool NARROW, bool ROPE>
 __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel(HopParams p, TileParams tp) {
     using G = Geo<D>;
     constexpr int kRows = kTile * KT;
@@ -446,7 +447,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
 
     // ---- rotary encoding of the gathered rows, by their position on the axis: Q (private) and this
     //      wave's quarter of every K tile, before they enter LDS ---------------------------------
-    if (p.rope) {
+    if constexpr (ROPE) {
         float rev[4];
         rope_rates(p, lcol, rev);
         auto row_pos = [&](int row) -> float {
@@ -608,17 +609,23 @@ hipError_t launch_shared(const HopParams& p, const TileParams& tp, hipStream_t s
     const bool vs = p.vin_heads != p.Hq;
     const size_t smem = (vs ? 2 : 1) * KT * tile + (size_t)kTile * KT * 16 + kWavesPerBlock * (vs ? tile / 2 : tile);
     const dim3 grid((unsigned)(p.Hq / kWavesPerBlock), tp.tiles_lo, (unsigned)p.B * tp.tiles_hi);
-    if (vs) hipLaunchKernelGGL((mfma_fwd_shared_kernel<D, KT, true, NARROW>), grid, dim3(kWavesPerBlock * 64), smem, s, p, tp);
-    else hipLaunchKernelGGL((mfma_fwd_shared_kernel<D, KT, false, NARROW>), grid, dim3(kWavesPerBlock * 64), smem, s, p, tp);
-    return hipGetLastError();
+    const void* kf = p.rope ? (vs ? (const void*)mfma_fwd_shared_kernel<D, KT, true, NARROW, true> : (const void*)mfma_fwd_shared_kernel<D, KT, false, NARROW, true>)
+                            : (vs ? (const void*)mfma_fwd_shared_kernel<D, KT, true, NARROW, false> : (const void*)mfma_fwd_shared_kernel<D, KT, false, NARROW, false>);
+    HopParams pc = p;
+    TileParams tc = tp;
+    void* args[2] = {&pc, &tc};
+    return hipLaunchKernel(kf, grid, dim3(kWavesPerBlock * 64), args, smem, s);
 }
 
 template <int D, int KT, bool NARROW>
 hipError_t launch(const HopParams& p, const TileParams& tp, hipStream_t s) {
     const size_t smem = (size_t)kWavesPerBlock * (Geo<D>::kBufBytes + kTile * KT * 16);
     const dim3 grid((unsigned)((p.Hq + kWavesPerBlock - 1) / kWavesPerBlock), tp.tiles_lo, (unsigned)p.B * tp.tiles_hi);
-    hipLaunchKernelGGL((mfma_fwd_kernel<D, KT, NARROW>), grid, dim3(kWavesPerBlock * 64), smem, s, p, tp);
-    return hipGetLastError();
+    const void* kf = p.rope ? (const void*)mfma_fwd_kernel<D, KT, NARROW, true> : (const void*)mfma_fwd_kernel<D, KT, NARROW, false>;
+    HopParams pc = p;
+    TileParams tc = tp;
+    void* args[2] = {&pc, &tc};
+    return hipLaunchKernel(kf, grid, dim3(kWavesPerBlock * 64), args, smem, s);
 }
 
 }  // namespace
