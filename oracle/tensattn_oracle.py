@@ -57,6 +57,7 @@ __all__ = [
     "band_mask",
     "attention",
     "axis_attention",
+    "axis_attention_by_fibres",
     "tensorized_attention_forward",
     "tensorized_attention_backward",
     "tensorized_rope",
@@ -153,6 +154,40 @@ def axis_attention(q: np.ndarray, k: np.ndarray, o_prev: np.ndarray,
     o_new = np.moveaxis(Onew, -2, axis).reshape(N, o_prev.shape[1])
     if return_probs:
         return o_new, A
+    return o_new
+
+
+def axis_attention_by_fibres(q: np.ndarray, k: np.ndarray, o_prev: np.ndarray, dims: Sequence[int], axis: int,
+                             scale: float, causal: bool, window: int = 0, valid_len: Optional[int] = None,
+                             mask: Optional[np.ndarray] = None) -> np.ndarray:
+    """The same hop as `axis_attention`, written fibre by fibre (Eq. 4 read literally: fix every
+    coordinate but the one on `axis`, take the n rows of that fibre, attend, put the rows back).
+    Slow; the tests hold the batched form above to it."""
+    dims = [int(n) for n in dims]
+    N = int(np.prod(dims)) if dims else 1
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    o_prev = np.asarray(o_prev, dtype=np.float64)
+    n = dims[axis]
+    stride = axis_strides(dims)[axis]
+    allowed = band_mask(n, causal, window)
+    if mask is not None:
+        allowed = np.asarray(mask, dtype=bool) if allowed is None else (allowed & np.asarray(mask, dtype=bool))
+    o_new = np.empty_like(o_prev)
+    seen = np.zeros(N, dtype=bool)
+    for t0 in range(N):
+        if (t0 // stride) % n != 0:            # not the first token of its fibre
+            continue
+        rows = t0 + stride * np.arange(n)      # the fibre through t0: same coordinates on every other axis
+        ok = allowed
+        if valid_len is not None and valid_len < N:
+            real = rows < valid_len
+            pad = real[:, None] & real[None, :]
+            ok = pad if ok is None else (ok & pad)
+        A = _softmax_rows((q[rows] @ k[rows].T) * scale, ok)
+        o_new[rows] = A @ o_prev[rows]
+        seen[rows] = True
+    assert seen.all()
     return o_new
 
 

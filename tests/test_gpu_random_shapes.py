@@ -57,3 +57,32 @@ def test_random_configuration(seed):
     dq, dk, dv = multihop_backward(plan, dev, d_o, c["dtype"])
     check_backward((dq, dk, dv), q, k, v, d_o, c["dims"], c["causal"], c["dtype"], what=str(c), window=c["window"],
                    valid_len=c["valid_len"])
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configuration_with_encoding_and_per_element_lengths(seed):
+    """The same draw with the rotary encoding inside the hops, one padding length per batch element
+    (both at random) and a random hop order: the features added on top of the masks, in combination."""
+    import torch
+    c = draw_case(9500 + seed)
+    rng = np.random.default_rng(700 + seed)
+    N, B, m = int(np.prod(c["dims"])), c["B"], len(c["dims"])
+    rope = float(rng.choice([100.0, 10000.0])) if rng.random() < 0.7 else None
+    lens = [int(rng.integers(0, N + 1)) for _ in range(B)] if rng.random() < 0.6 else None
+    order = tuple(int(a) for a in rng.permutation(m)) if rng.random() < 0.4 else None
+    q, k, v, d_o = make_inputs(B, N, c["Hq"], c["Hkv"], c["D"], seed=100 + seed, dtype=c["dtype"], with_grad=True)
+    plan_kw = dict(window=c["window"], rope_base=rope, hop_order=order)
+    if lens is not None:
+        plan_kw["valid_lens"] = torch.tensor(lens, dtype=torch.int64, device="cuda")
+    got, plan, dev = multihop_forward(q, k, v, c["dims"], c["dtype"], c["causal"], save=True, **plan_kw)
+    okw = dict(window=c["window"], valid_len=lens, rope_base=rope, hop_order=order)
+    ref = orc.tensorized_attention_forward(q, k, v, c["dims"], c["causal"], **okw)
+    what = f"{c} rope={rope} lens={lens} order={order}"
+    assert np.isfinite(got).all(), what
+    err = np.abs(got - ref).max()
+    assert err <= TOL[c["dtype"]], f"{what}: forward max-abs error {err:.3e}"
+    kernels = [plan.hop_backward_kernel(plan.hop_axis(p), 0 if p == 0 else 1) for p in range(m)]
+    if "unsupported" in kernels:
+        return
+    grads = multihop_backward(plan, dev, d_o, c["dtype"])
+    check_backward(grads, q, k, v, d_o, c["dims"], c["causal"], c["dtype"], what=what, **okw)

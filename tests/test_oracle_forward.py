@@ -330,3 +330,20 @@ def test_flop_count_of_an_instrumented_hop_matches_the_cost_models():
     assert total == 4 * N * D * sum(dims)
     fact = json.load(open(GOLDEN))["tensor3_parameter_count"]
     assert fact["rank"] * sum(n * n for n in fact["dims"]) == fact["parameters"]
+
+
+# --- the batched hop against the hop written fibre by fibre -------------------------------------
+
+@pytest.mark.parametrize("dims", [(4, 3, 5), (2, 7), (6,), (3, 1, 4)])
+@pytest.mark.parametrize("causal", [False, True])
+def test_batched_hop_equals_hop_fibre_by_fibre(dims, causal):
+    rng = np.random.default_rng(17)
+    N, D = int(np.prod(dims)), 6
+    q, k, x = rng.standard_normal((N, D)), rng.standard_normal((N, D)), rng.standard_normal((N, 4))
+    table = rng.random((max(dims), max(dims))) < 0.7
+    np.fill_diagonal(table, True)
+    for axis, n in enumerate(dims):
+        for kw in (dict(), dict(window=2), dict(valid_len=N - 3), dict(mask=table[:n, :n])):
+            a = orc.axis_attention(q, k, x, dims, axis, 0.4, causal, **kw)
+            b = orc.axis_attention_by_fibres(q, k, x, dims, axis, 0.4, causal, **kw)
+            np.testing.assert_allclose(a, b, rtol=0, atol=1e-14)

@@ -57,3 +57,37 @@ def test_static_workspace_forward_refuses_what_does_not_fit():
     ta.ta_multihop_forward_static(fits, t, kv, kv, o)
     torch.cuda.synchronize()
     assert torch.count_nonzero(o).item() == 0          # V = 0 gives O = 0, and no NaN is left
+
+
+def test_static_workspace_forward_under_graph_capture():
+    """What the entry point is for: the call allocates nothing and takes no workspace, so it can be
+    captured into a HIP graph as it stands; every replay, with eager work and synchronisations in
+    between, reproduces the eager result.  (The first call on the device, above or here, happens
+    outside the capture: it looks up the address of the library's workspace.)"""
+    dims, B, Hq, Hkv, D = (4, 32, 32), 1, 8, 2, 128
+    N = int(np.prod(dims))
+    plan = ta.ta_plan_create(B, Hq, Hkv, D, dims, ta.TA_BF16, True)
+    gen = torch.Generator(device="cuda"); gen.manual_seed(21)
+    q = torch.randn(B, N, Hq, D, device="cuda", generator=gen).bfloat16()
+    k = torch.randn(B, N, Hkv, D, device="cuda", generator=gen).bfloat16()
+    v = torch.randn(B, N, Hkv, D, device="cuda", generator=gen).bfloat16()
+    o = torch.zeros(B, N, Hq, D, device="cuda", dtype=torch.bfloat16)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        ta.ta_multihop_forward_static(plan, q, k, v, o)               # warm-up on the capture stream
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        ta.ta_multihop_forward_static(plan, q, k, v, o)
+    wsb = plan.workspace_bytes(False)
+    for it in range(3):
+        q.copy_(torch.randn(B, N, Hq, D, device="cuda", generator=gen).bfloat16())
+        v.copy_(torch.randn(B, N, Hkv, D, device="cuda", generator=gen).bfloat16())
+        eager = torch.empty_like(o)
+        ta.ta_multihop_forward(plan, q, k, v, eager, alloc_bytes(wsb), wsb, False)
+        torch.cuda.synchronize()
+        o.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(o, eager), f"replay {it} differs from the eager result"
