@@ -105,8 +105,9 @@ typedef struct ta_desc_t {
      * columns of its query and key projections once (scores are invariant under a common feature
      * permutation).  Which features take which axis is not in the paper: this per-hop form is a reading.
      * The matrix-core kernels take it for axes of up to 4,096 positions (fp32 angles); longer axes, and
-     * fp32 tensors, run on the generic kernels (double-precision angles).  The fused pair of hops is not
-     * used with it. */
+     * fp32 tensors, run on the generic kernels (double-precision angles).  The fused pair of hops takes it
+     * too: there a token's rows are turned by one axis position for the first hop and by the other for
+     * the second, with the rotation's cosines and sines rounded to bf16. */
     int32_t rope;                     /* 0 or 1 */
     float   rope_base;                /* the base; 0 means 10000 */
 } ta_desc_t;

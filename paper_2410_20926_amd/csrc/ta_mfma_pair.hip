@@ -292,8 +292,9 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
                 }
                 // The three-operand form of the bf16 dot product with a literal zero to add to (the compiler's own
                 // choice, the two-operand accumulating form, needs a register cleared first for every product).
-                // A dot product's result may be read by a vector instruction only three wait states later: the
-                // eight products of an operand are issued back to back and one s_nop follows the last.
+                // A dot product's result may be read by another vector instruction only three wait states later,
+                // and its register be overwritten by one only four later: the eight products of an operand are
+                // issued back to back and one s_nop of four wait states follows the last.
                 auto turn = [&](const u32x4 x) {
                     float e0, o0, e1, o1, e2, o2, e3, o3;
                     asm("v_dot2_f32_bf16 %0, %8, %12, 0\n\t"
@@ -304,7 +305,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
                         "v_dot2_f32_bf16 %5, %10, %17, 0\n\t"
                         "v_dot2_f32_bf16 %6, %11, %18, 0\n\t"
                         "v_dot2_f32_bf16 %7, %11, %19, 0\n\t"
-                        "s_nop 2"
+                        "s_nop 3"
                         : "=&v"(e0), "=&v"(o0), "=&v"(e1), "=&v"(o1), "=&v"(e2), "=&v"(o2), "=&v"(e3), "=&v"(o3)
                         : "v"(x.x), "v"(x.y), "v"(x.z), "v"(x.w),
                           "v"(__builtin_bit_cast(uint32_t, ce[0])), "v"(__builtin_bit_cast(uint32_t, co[0])),
