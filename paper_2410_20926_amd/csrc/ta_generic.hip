@@ -469,11 +469,15 @@ hipError_t launch_generic_backward(const BwdParams& bp, int dtype, hipStream_t s
 }
 
 // ------------------------------------------------------------------------------------
-// Plain copy: 16 bytes per lane, grid-stride, used to measure the HBM ceiling.
+// Plain copy: 16 bytes per lane, streaming (non-temporal) loads and stores, four workgroups per
+// compute unit walking the buffer 4 KB at a time.  It measures the copy rate the memory reaches
+// and calibrates the traffic counters (it moves a known number of bytes).
 namespace {
-__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+__global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n16) {
     const size_t step = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += step) dst[i] = src[i];
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += step)
+        __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 }  // namespace
 
@@ -481,9 +485,9 @@ hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s) 
     const size_t n16 = bytes / 16;
     if (n16 == 0) return hipSuccess;
     size_t blocks = (n16 + 255) / 256;
-    if (blocks > 256 * 32) blocks = 256 * 32;
+    if (blocks > 256 * 4) blocks = 256 * 4;
     hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
-                       reinterpret_cast<const uint4*>(src), reinterpret_cast<uint4*>(dst), n16);
+                       reinterpret_cast<const u32x4*>(src), reinterpret_cast<u32x4*>(dst), n16);
     return hipGetLastError();
 }
 
