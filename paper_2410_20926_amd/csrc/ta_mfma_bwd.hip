@@ -1019,7 +1019,7 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
     // ---- Q staged: scores in both orientations, statistics, dS ----------------------------------------
     stage_rows<D>(buf + stg, qraw);
     __syncthreads();                                      // (5)
-    f32x16 sT[2], sN[2];
+    f32x16 sT[2];
     {
         u32x4 qn[G::kKSteps], kn[G::kKSteps];
         read_natural<D>(buf + nat, qn);
@@ -1069,22 +1069,9 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
             for (int r = 0; r < 16; ++r) e[c][r] *= (dpT[c][r] - delta);
             pack_rows(e[c], dsT[c]);
         }
-        if (lane < kTile) {
+        if (lane < kTile) {                               // P = exp2(s - ref) with ref = max + log2(sum): one number instead of two
             float* st = stats + t * (3 * kTile);
-            st[lane] = mx; st[kTile + lane] = inv; st[2 * kTile + lane] = delta;
-        }
-    }
-    {   // the scores with one key per lane, after the row softmax above has released its registers
-        u32x4 qn[G::kKSteps], kn[G::kKSteps];
-        read_natural<D>(sK + t * kBuf + nat, kn);
-#pragma unroll
-        for (int a = 0; a < 2; ++a) {
-            sN[a] = f32x16{};
-            if (visk[a]) {
-                read_natural<D>((a == t ? buf : pbuf) + nat, qn);
-#pragma unroll
-                for (int s = 0; s < G::kKSteps; ++s) sN[a] = mma(qn[s], kn[s], sN[a]);
-            }
+            st[lane] = sum > 0.f ? mx + __builtin_amdgcn_logf(sum) : INFINITY; st[kTile + lane] = delta;
         }
     }
     __syncthreads();                                      // (6) both tiles' statistics are visible
@@ -1094,25 +1081,38 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
         const int kr = kTile * t + r32;
 #pragma unroll
         for (int a = 0; a < 2; ++a) {
-            float pr[16], ds[16];
+            // the scores with one key per lane: S_at = Q_a K_t^T, one query tile at a time (both at once would not fit)
+            f32x16 sN = f32x16{};
+            if (visk[a]) {
+                u32x4 qn[G::kKSteps], kn[G::kKSteps];
+                read_natural<D>(sK + t * kBuf + nat, kn);
+                read_natural<D>((a == t ? buf : pbuf) + nat, qn);
+#pragma unroll
+                for (int s = 0; s < G::kKSteps; ++s) sN = mma(qn[s], kn[s], sN);
+            }
             const uint32_t vis = visk[a] ? block_vis_rows(p, kr, a, nreal) >> (4 * hf) : 0u;
             const float* st = stats + a * (3 * kTile);
+            uint32_t pw[8], dw[8];                        // rounded in pairs as they are formed: sixteen of each in fp32 do not fit
+            float slv = sl2;
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
                 const f32x4 m4 = *reinterpret_cast<const f32x4*>(st + 8 * q4 + 4 * hf);
-                const f32x4 i4 = *reinterpret_cast<const f32x4*>(st + kTile + 8 * q4 + 4 * hf);
-                const f32x4 d4 = *reinterpret_cast<const f32x4*>(st + 2 * kTile + 8 * q4 + 4 * hf);
+                const f32x4 d4 = *reinterpret_cast<const f32x4*>(st + kTile + 8 * q4 + 4 * hf);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
+                for (int j = 0; j < 4; j += 2) {
                     const int r = 4 * q4 + j;
-                    const bool ok = (vis >> (8 * q4 + j)) & 1u;
-                    const float pv = ok ? __builtin_amdgcn_exp2f(sN[a][r] * sl2 - m4[j]) * i4[j] : 0.f;
-                    pr[r] = pv;
-                    ds[r] = pv * (dpN[a][r] - d4[j]);
+                    const bool ok0 = (vis >> (8 * q4 + j)) & 1u, ok1 = (vis >> (8 * q4 + j + 1)) & 1u;
+                    const float pv0 = ok0 ? __builtin_amdgcn_exp2f(sN[r] * slv - m4[j]) : 0.f;
+                    const float pv1 = ok1 ? __builtin_amdgcn_exp2f(sN[r + 1] * slv - m4[j + 1]) : 0.f;
+                    pw[r / 2] = pack_bf16x2(pv0, pv1);
+                    dw[r / 2] = pack_bf16x2(pv0 * (dpN[a][r] - d4[j]), pv1 * (dpN[a][r + 1] - d4[j + 1]));
                 }
+                // The next four rows start from a value that passes through this statement together with the four words
+                // just formed: the compiler cannot form all sixteen weights first (it did, and spilled them).
+                asm volatile("" : "+v"(pw[2 * q4]), "+v"(pw[2 * q4 + 1]), "+v"(dw[2 * q4]), "+v"(dw[2 * q4 + 1]), "+v"(slv));
             }
-            pack_rows(pr, pN[a]);
-            pack_rows(ds, dsN[a]);
+            pN[a][0] = u32x4{pw[0], pw[1], pw[2], pw[3]};  pN[a][1] = u32x4{pw[4], pw[5], pw[6], pw[7]};
+            dsN[a][0] = u32x4{dw[0], dw[1], dw[2], dw[3]}; dsN[a][1] = u32x4{dw[4], dw[5], dw[6], dw[7]};
         }
     }
     // ---- dK_t^T = sum_a Q_a^T dS_at, while the Q tiles are still staged ----------------------------------
