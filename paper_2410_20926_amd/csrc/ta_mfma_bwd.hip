@@ -915,14 +915,8 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
     }
 
     // ---- gather: own Q, G (and X) tile, this wave's share of the shared tiles: all requested at once ----
+    // In the order of their first use (loads complete in order): the shared tiles and X, then G, then Q.
     u32x4 qraw[G::kPasses], graw[G::kPasses], xraw[VS ? 1 : G::kPasses], ksh[kShare], xsh[VS ? kShare : 1];
-#pragma unroll
-    for (int i = 0; i < G::kPasses; ++i) {
-        const uint32_t tok = tok0 + (uint32_t)min(kTile * t + i * G::kRowsPerPass + lrow, n - 1) * stride;
-        if constexpr (!VS) xraw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xb + (tok * sp.v_row + lbyte)));
-        graw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gb + (tok * sp.o_row + lbyte)));
-        qraw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (tok * sp.q_row + lbyte)));
-    }
 #pragma unroll
     for (int i = 0; i < kShare; ++i) {
         const int pidx = w * kShare + i;                  // pass pidx % kPasses of shared tile pidx / kPasses
@@ -930,14 +924,24 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
         ksh[i] = *reinterpret_cast<const u32x4*>(kb + (tok * sp.k_row + lbyte));
         if constexpr (VS) xsh[i] = *reinterpret_cast<const u32x4*>(xb + (tok * sp.v_row + lbyte));
     }
+    uint32_t tokrow[G::kPasses];
+#pragma unroll
+    for (int i = 0; i < G::kPasses; ++i) tokrow[i] = tok0 + (uint32_t)min(kTile * t + i * G::kRowsPerPass + lrow, n - 1) * stride;
+    if constexpr (!VS) {
+#pragma unroll
+        for (int i = 0; i < G::kPasses; ++i) xraw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xb + (tokrow[i] * sp.v_row + lbyte)));
+    }
+#pragma unroll
+    for (int i = 0; i < G::kPasses; ++i) graw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gb + (tokrow[i] * sp.o_row + lbyte)));
+#pragma unroll
+    for (int i = 0; i < G::kPasses; ++i) qraw[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (tokrow[i] * sp.q_row + lbyte)));
     __builtin_amdgcn_sched_barrier(0);
 
-    // rotary encoding: Q and K rows are turned by their position on the axis before they enter LDS
+    // rotary encoding: Q and K rows are turned by their position on the axis before they enter LDS (K here, Q
+    // where it is staged: its rows arrive last)
     float rev[4];
     if (p.rope) {
         rope_rates(p, lcol, rev);
-#pragma unroll
-        for (int i = 0; i < G::kPasses; ++i) qraw[i] = rope_chunk(qraw[i], (float)min(kTile * t + i * G::kRowsPerPass + lrow, n - 1), rev);
 #pragma unroll
         for (int i = 0; i < kShare; ++i) {
             const int pidx = w * kShare + i;
@@ -1017,6 +1021,10 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
     __syncthreads();                                      // (4) the G tiles have been read
 
     // ---- Q staged: scores in both orientations, statistics, dS ----------------------------------------
+    if (p.rope) {
+#pragma unroll
+        for (int i = 0; i < G::kPasses; ++i) qraw[i] = rope_chunk(qraw[i], (float)min(kTile * t + i * G::kRowsPerPass + lrow, n - 1), rev);
+    }
     stage_rows<D>(buf + stg, qraw);
     __syncthreads();                                      // (5)
     f32x16 sT[2];
@@ -1115,6 +1123,9 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
             dsN[a][0] = u32x4{dw[0], dw[1], dw[2], dw[3]}; dsN[a][1] = u32x4{dw[4], dw[5], dw[6], dw[7]};
         }
     }
+    // the previous dQ rows are requested here: the product and the sum below give them time to arrive
+    u32x4 oldq[G::kDTiles * 2] = {};
+    if (bp.accumulate) prefetch_tile<D>(oldq, rowoff, 0, dqb, lane);
     // ---- dK_t^T = sum_a Q_a^T dS_at, while the Q tiles are still staged ----------------------------------
     f32x16 acc[G::kDTiles];
 #pragma unroll
@@ -1141,8 +1152,6 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
     }
     // ---- dQ_t^T = sum_c K_c^T dS^T_tc ------------------------------------------------------------------------
     {
-        u32x4 oldq[G::kDTiles * 2] = {};
-        if (bp.accumulate) prefetch_tile<D>(oldq, rowoff, 0, dqb, lane);
 #pragma unroll
         for (int tt = 0; tt < G::kDTiles; ++tt) acc[tt] = f32x16{};
 #pragma unroll
