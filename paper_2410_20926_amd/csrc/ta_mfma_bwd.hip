@@ -1242,10 +1242,10 @@ hipError_t launch_stream(const BwdParams& bp, hipStream_t s) {
 template <int D, bool NARROW>
 hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
     const HopParams& p = bp.hop;
+    const bool multi = p.G > bp.wg_heads, table = p.mask != nullptr;
     const size_t smem = (size_t)(bp.wg_heads > 1 ? BGeo<D>::kRedBytes : 0) + (size_t)bp.wg_heads * BGeo<D>::kWaveBytes;
     const dim3 grid((unsigned)p.Hkv, tp.tiles_lo, (unsigned)p.B * tp.tiles_hi);
     const dim3 block(64 * bp.wg_heads);
-    const bool multi = p.G > bp.wg_heads, table = p.mask != nullptr;
     const void* kf;
     if (p.rope) kf = multi ? (table ? (const void*)mfma_bwd_kernel<D, true, true, NARROW, true> : (const void*)mfma_bwd_kernel<D, false, true, NARROW, true>)
                            : (table ? (const void*)mfma_bwd_kernel<D, true, false, NARROW, true> : (const void*)mfma_bwd_kernel<D, false, false, NARROW, true>);
@@ -1254,6 +1254,10 @@ hipError_t launch(const BwdParams& bp, const TileParams& tp, hipStream_t s) {
     BwdParams bpc = bp;
     TileParams tpc = tp;
     void* args[2] = {&bpc, &tpc};
+    if (smem > 64 * 1024) {
+        const hipError_t e = allow_dynamic_lds(kf, (int)smem);
+        if (e != hipSuccess) return e;
+    }
     return hipLaunchKernel(kf, grid, block, args, smem, s);
 }
 
