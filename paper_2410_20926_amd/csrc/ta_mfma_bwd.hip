@@ -837,7 +837,8 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
     }
 }
 
-// LDS of the two-tile kernel: shared K (and X) tiles, two reduction areas, statistics, one transit tile and one row table per wave.
+// LDS of the two-tile kernel: shared K (and X) tiles, two reduction areas, statistics (room for three floats per row and
+// tile; two are used: the softmax reference value and delta), one transit tile and one row table per wave.
 template <int D>
 constexpr size_t two_tile_lds(int gh, bool vs) {
     return (size_t)(vs ? 4 : 2) * kTile * Geo<D>::kPitch + (gh > 1 ? 2 * (size_t)BGeo<D>::kRedBytes : 0) + (size_t)gh * 2 * 3 * kTile * 4 +
