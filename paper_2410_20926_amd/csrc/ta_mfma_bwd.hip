@@ -370,7 +370,8 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
 #pragma unroll
         for (int r = 0; r < 16; ++r) e[r] *= (dpT[r] - delta);
         pack_rows(e, dsTop);
-        if (lane < kTile) { stats[lane] = mx; stats[kTile + lane] = inv; stats[2 * kTile + lane] = delta; }
+        // P = exp2(s - ref) with ref = max + log2(sum): one number per row instead of two
+        if (lane < kTile) { stats[lane] = sum > 0.f ? mx + __builtin_amdgcn_logf(sum) : INFINITY; stats[kTile + lane] = delta; }
     }
     lds_wave_sync();
 
@@ -382,23 +383,29 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
         uint32_t tw = 0xffffffffu;
         if (row_real) { seen_range(r32, flo, fhi, p.causal, p.window, lo, hi); if (TABLE) tw = table_column(p, r32 - flo) << flo; }
         const uint32_t vis = (range_mask(lo, hi) & tw & real_rows) >> (4 * hf);
-        float pr[16], ds[16];
+        uint32_t pw[8], dw[8];                            // rounded in pairs as they are formed
+        float slv = sl2;
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             const f32x4 m4 = *reinterpret_cast<const f32x4*>(stats + 8 * q4 + 4 * hf);
-            const f32x4 i4 = *reinterpret_cast<const f32x4*>(stats + kTile + 8 * q4 + 4 * hf);
-            const f32x4 d4 = *reinterpret_cast<const f32x4*>(stats + 2 * kTile + 8 * q4 + 4 * hf);
+            const f32x4 d4 = *reinterpret_cast<const f32x4*>(stats + kTile + 8 * q4 + 4 * hf);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < 4; j += 2) {
                 const int r = 4 * q4 + j;
-                const bool ok = (vis >> (8 * q4 + j)) & 1u;
-                const float pv = ok ? __builtin_amdgcn_exp2f(sN[r] * sl2 - m4[j]) * i4[j] : 0.f;
-                pr[r] = pv;
-                ds[r] = pv * (dpN[r] - d4[j]);
+                const bool ok0 = (vis >> (8 * q4 + j)) & 1u, ok1 = (vis >> (8 * q4 + j + 1)) & 1u;
+                const float pv0 = ok0 ? __builtin_amdgcn_exp2f(sN[r] * slv - m4[j]) : 0.f;
+                const float pv1 = ok1 ? __builtin_amdgcn_exp2f(sN[r + 1] * slv - m4[j + 1]) : 0.f;
+                pw[r / 2] = pack_bf16x2(pv0, pv1);
+                dw[r / 2] = pack_bf16x2(pv0 * (dpN[r] - d4[j]), pv1 * (dpN[r + 1] - d4[j + 1]));
             }
+            // In the instantiations that are short of registers the next four rows start from a value that passes
+            // through this statement together with the words just formed, so that the compiler cannot form all
+            // sixteen weights first and hold them (it then spills); the plain kernel has room and is faster left alone.
+            if constexpr (TABLE || MULTI || NARROW || ROPE)
+                asm volatile("" : "+v"(pw[2 * q4]), "+v"(pw[2 * q4 + 1]), "+v"(dw[2 * q4]), "+v"(dw[2 * q4 + 1]), "+v"(slv));
         }
-        pack_rows(pr, pNop);
-        pack_rows(ds, dsNop);
+        pNop[0] = u32x4{pw[0], pw[1], pw[2], pw[3]};  pNop[1] = u32x4{pw[4], pw[5], pw[6], pw[7]};
+        dsNop[0] = u32x4{dw[0], dw[1], dw[2], dw[3]}; dsNop[1] = u32x4{dw[4], dw[5], dw[6], dw[7]};
     }
 
     // ---- dQ^T = K^T dS^T : per head, stored at once -----------------------------------------
