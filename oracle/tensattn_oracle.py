@@ -29,8 +29,8 @@ Readings taken where the paper is silent:
     band of width w_i along axis i (key c visible from row a iff |a - c| < w_i, and
     c <= a when causal) and padding (tokens at or past `valid_len` are never attended
     to; their own rows see nothing and come out as zero), and an explicit n_i x n_i
-    boolean table per axis (`axis_masks`), all of them intersected; a row left with no
-    visible key comes out as zero.  `valid_len` may also be one length per batch element
+    boolean table per axis (`axis_masks`), shared by the axis's fibres or one per fibre as in
+    Eq. 3, all of them intersected; a row left with no visible key comes out as zero.  `valid_len` may also be one length per batch element
     (Eq. 3's M_i is one table per fibre: sequences of different lengths in one batch);
   - tensorized positional encoding inside the hops (Sec. 3.2), `rope_base`: the hop along
     axis i scores with Q and K rotated by their coordinate on that axis (`tensorized_rope`
@@ -125,7 +125,9 @@ def axis_attention(q: np.ndarray, k: np.ndarray, o_prev: np.ndarray,
     and, on request, A_axis with shape dims[:axis] + dims[axis+1:] + (n, n)
     (batch axes in tensor order, then query index, then key index).
     `window` and `valid_len` add the band and padding masks described above; `mask`
-    is an explicit M_i, boolean [n, n], True where query row a may attend key c."""
+    is an explicit M_i (Eq. 3), True where query row a may attend key c: boolean [n, n], the
+    same table for every fibre, or [F, n, n] with F = N / n, one table per fibre, the fibres
+    numbered in row-major order of their coordinates on the other axes."""
     dims = [int(n) for n in dims]
     N = int(np.prod(dims)) if dims else 1
     q = np.asarray(q, dtype=np.float64)
@@ -146,7 +148,11 @@ def axis_attention(q: np.ndarray, k: np.ndarray, o_prev: np.ndarray,
         allowed = pad if allowed is None else (allowed & pad)
     if mask is not None:
         mask = np.asarray(mask, dtype=bool)
-        assert mask.shape == (n, n)
+        if mask.ndim == 3:                                            # one table per fibre: S's leading axes are the fibres in that order
+            assert mask.shape == (N // n, n, n)
+            mask = mask.reshape(S.shape)
+        else:
+            assert mask.shape == (n, n)
         allowed = mask if allowed is None else (allowed & mask)
     A = _softmax_rows(S, allowed)
     Onew = np.matmul(A, Oi)                                           # [..., n, Dv]
@@ -170,16 +176,19 @@ def axis_attention_by_fibres(q: np.ndarray, k: np.ndarray, o_prev: np.ndarray, d
     o_prev = np.asarray(o_prev, dtype=np.float64)
     n = dims[axis]
     stride = axis_strides(dims)[axis]
-    allowed = band_mask(n, causal, window)
-    if mask is not None:
-        allowed = np.asarray(mask, dtype=bool) if allowed is None else (allowed & np.asarray(mask, dtype=bool))
+    band = band_mask(n, causal, window)
+    mask = None if mask is None else np.asarray(mask, dtype=bool)
     o_new = np.empty_like(o_prev)
     seen = np.zeros(N, dtype=bool)
     for t0 in range(N):
         if (t0 // stride) % n != 0:            # not the first token of its fibre
             continue
         rows = t0 + stride * np.arange(n)      # the fibre through t0: same coordinates on every other axis
-        ok = allowed
+        ok = band
+        if mask is not None:
+            # the fibre's number: its coordinates on the other axes read as one row-major index
+            table = mask[(t0 // (stride * n)) * stride + t0 % stride] if mask.ndim == 3 else mask
+            ok = table if ok is None else (ok & table)
         if valid_len is not None and valid_len < N:
             real = rows < valid_len
             pad = real[:, None] & real[None, :]

@@ -64,15 +64,22 @@ def fibre_probs(q, k, dims, axis, fixed, scale, causal, window=0, valid_len=None
     return A
 
 
-def hop_matrix(q, k, dims, axis, scale, causal, window=0, valid_len=None, mask=None):
+def hop_matrix(q, k, dims, axis, scale, causal, window=0, valid_len=None, mask=None, masks_by_fibre=None):
     """P_axis [N][N]: P[t][u] = A^{(fibre)}[j_axis][k_axis] when tokens t = (j)
-    and u = (k) agree on every other axis, else 0."""
+    and u = (k) agree on every other axis, else 0.  `masks_by_fibre`: one [n][n] table per
+    fibre (Eq. 3), indexed by the fibre's coordinates on the other axes read as a row-major number."""
     N = 1
     for n in dims:
         N *= n
     P = [[0.0] * N for _ in range(N)]
     other = [range(n) if i != axis else range(1) for i, n in enumerate(dims)]
     for fixed in itertools.product(*other):
+        if masks_by_fibre is not None:
+            number = 0
+            for i, n in enumerate(dims):
+                if i != axis:
+                    number = number * n + fixed[i]
+            mask = masks_by_fibre[number]
         A = fibre_probs(q, k, dims, axis, fixed, scale, causal, window, valid_len, mask)
         for a in range(dims[axis]):
             ca = list(fixed)

@@ -234,3 +234,99 @@ def test_valid_len_per_batch_element():
             assert (got[b, L:] == 0).all() and (dq[b, L:] == 0).all() and (dk[b, L:] == 0).all() and (dv[b, L:] == 0).all()
             alone = orc.tensorized_attention_forward(q[b:b + 1], k[b:b + 1], v[b:b + 1], dims, causal, scale=0.7, valid_len=L)
             np.testing.assert_array_equal(alone[0], got[b])
+
+
+# ---- one table per fibre (Eq. 3: M_i has a separate n_i x n_i table for every fibre) -----------------------------
+
+def _random_fibre_masks(rng, F, n, keep_diagonal=True):
+    m = rng.random((F, n, n)) < 0.6
+    if keep_diagonal:
+        m |= np.eye(n, dtype=bool)[None]
+    return m
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_per_fibre_tables_equal_the_scalar_loop_operator(causal):
+    """Every hop takes its own table per fibre; the N x N operator is the product of the per-hop matrices built
+    with scalar loops, each fibre looked up by its coordinates on the other axes."""
+    import bruteforce as bf
+    dims, D = (2, 3, 2), 4
+    N = 12
+    rng = np.random.default_rng(81)
+    q, k, v = rng.standard_normal((N, D)), rng.standard_normal((N, D)), rng.standard_normal((N, 3))
+    masks = [_random_fibre_masks(rng, N // n, n, keep_diagonal=(ax != 1)) for ax, n in enumerate(dims)]   # axis 1 may leave rows empty
+    W = None
+    for axis in range(3):
+        P = bf.hop_matrix(q.tolist(), k.tolist(), dims, axis, 0.5, causal, masks_by_fibre=masks[axis].tolist())
+        W = P if W is None else bf.matmul(P, W)
+    got = orc.tensorized_attention_forward(q[None, :, None], k[None, :, None], v[None, :, None], dims, causal, scale=0.5,
+                                           axis_masks=masks)
+    np.testing.assert_allclose(got[0, :, 0], np.array(W) @ v, rtol=0, atol=1e-12)
+    shared = orc.tensorized_attention_forward(q[None, :, None], k[None, :, None], v[None, :, None], dims, causal, scale=0.5,
+                                              axis_masks=[m[0] for m in masks])
+    assert np.abs(shared - got).max() > 1e-3                    # the tables do differ between fibres
+
+
+def test_equal_tables_in_every_fibre_are_the_shared_table():
+    rng = np.random.default_rng(82)
+    dims, D = (3, 4, 2), 5
+    N = 24
+    q, k, v = (rng.standard_normal((1, N, 2, D)) for _ in range(3))
+    tables = [rng.random((n, n)) < 0.7 for n in dims]
+    a = orc.tensorized_attention_forward(q, k, v, dims, True, axis_masks=tables)
+    b = orc.tensorized_attention_forward(q, k, v, dims, True, axis_masks=[np.broadcast_to(t, (N // t.shape[0],) + t.shape) for t in tables])
+    np.testing.assert_array_equal(a, b)
+
+
+def test_per_fibre_tables_from_segment_ids_are_attention_within_segments():
+    """Documents packed along the innermost axis: the table of a fibre lets a row see the keys of its own segment.
+    Every segment of every fibre then is a plain attention problem of its own (library routine)."""
+    import torch
+    rng = np.random.default_rng(83)
+    dims, D = (3, 8), 6
+    N = 24
+    q, k, v = rng.standard_normal((N, D)), rng.standard_normal((N, D)), rng.standard_normal((N, D))
+    seg = np.sort(rng.integers(0, 3, size=(3, 8)), axis=1)      # segment id of every position of every innermost fibre
+    masks = seg[:, :, None] == seg[:, None, :]                  # [3 fibres, 8, 8]
+    got = orc.axis_attention(q, k, v, dims, 1, D ** -0.5, True, mask=masks)
+    for f in range(3):
+        for s_id in np.unique(seg[f]):
+            rows = f * 8 + np.nonzero(seg[f] == s_id)[0]
+            t = lambda a: torch.from_numpy(a[rows])[None]
+            ref = torch.nn.functional.scaled_dot_product_attention(t(q), t(k), t(v), is_causal=True)[0].numpy()
+            np.testing.assert_allclose(got[rows], ref, rtol=0, atol=1e-12)
+
+
+def test_per_fibre_tables_fibre_by_fibre_and_batched_forms_agree():
+    rng = np.random.default_rng(84)
+    dims, D = (3, 4, 5), 4
+    N = 60
+    q, k, v = rng.standard_normal((N, D)), rng.standard_normal((N, D)), rng.standard_normal((N, 3))
+    for axis, n in enumerate(dims):
+        m = _random_fibre_masks(rng, N // n, n)
+        a = orc.axis_attention(q, k, v, dims, axis, 0.4, True, window=3, valid_len=50, mask=m)
+        b = orc.axis_attention_by_fibres(q, k, v, dims, axis, 0.4, True, window=3, valid_len=50, mask=m)
+        np.testing.assert_allclose(a, b, rtol=0, atol=1e-13)
+
+
+def test_per_fibre_tables_backward_matches_finite_differences():
+    rng = np.random.default_rng(85)
+    dims, D = (3, 2, 4), 4
+    N = 24
+    q, k, v, d_o = (rng.standard_normal((1, N, 2, D)), rng.standard_normal((1, N, 1, D)),
+                    rng.standard_normal((1, N, 1, D)), rng.standard_normal((1, N, 2, D)))
+    masks = [_random_fibre_masks(rng, N // n, n) for n in dims]
+    dq, dk, dv = orc.tensorized_attention_backward(q, k, v, d_o, dims, True, axis_masks=masks)
+
+    def loss():
+        return float(np.sum(orc.tensorized_attention_forward(q, k, v, dims, True, axis_masks=masks) * d_o))
+
+    for x, g in ((q, dq), (k, dk), (v, dv)):
+        flat = x.reshape(-1)
+        for i in rng.choice(x.size, size=8, replace=False):
+            old = flat[i]
+            flat[i] = old + 1e-5; fp = loss()
+            flat[i] = old - 1e-5; fm = loss()
+            flat[i] = old
+            fd = (fp - fm) / 2e-5
+            assert abs(fd - g.reshape(-1)[i]) <= 1e-6 * max(abs(fd), 1e-3), (fd, g.reshape(-1)[i])
