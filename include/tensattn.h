@@ -85,7 +85,7 @@ typedef struct ta_desc_t {
     const void* axis_mask[TA_MAX_ORDER]; /* DEVICE pointers, or NULL for no table on that axis.  Table of axis i:
                                          n_i rows of ceil(n_i / 32) uint32 words, row-major; bit (c % 32) of
                                          word c / 32 of row a is 1 iff query position a may attend key
-                                         position c on that axis (the same table for every fibre, head and
+                                         position c on that axis (the same table for every head and
                                          batch element).  4-byte aligned, caller-owned, read-only, and must
                                          stay valid and unchanged while the plan is in use; entries at or
                                          beyond `order` are ignored. */
@@ -110,6 +110,12 @@ typedef struct ta_desc_t {
      * the second, with the rotation's cosines and sines rounded to bf16. */
     int32_t rope;                     /* 0 or 1 */
     float   rope_base;                /* the base; 0 means 10000 */
+    int32_t axis_mask_per_fibre[TA_MAX_ORDER]; /* 0: axis_mask[i] is one table for every fibre of axis i (above);
+                                         1: it holds one such table per fibre (Eq. 3: M_i has an n_i x n_i table for every
+                                         choice of the other coordinates), N / n_i tables one after the other, the fibres
+                                         numbered by their coordinates on the other axes read as one row-major number
+                                         (the first token of fibre f is (f / stride_i) * stride_i * n_i + f % stride_i).
+                                         The tables are shared by heads and batch elements. */
 } ta_desc_t;
 
 typedef struct ta_plan ta_plan_t;     /* opaque, immutable, host-only, shareable between threads */

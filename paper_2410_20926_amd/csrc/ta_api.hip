@@ -131,6 +131,7 @@ ta::HopParams hop_params(const ta_plan* pl, int axis, const void* q, const void*
     hp.valid_len = pl->desc.valid_len > 0 ? pl->desc.valid_len : pl->N;
     hp.mask = static_cast<const uint32_t*>(pl->desc.axis_mask[axis]);
     hp.mask_words = (pl->dims[axis] + 31) / 32;
+    hp.mask_fibre_words = (hp.mask && pl->desc.axis_mask_per_fibre[axis]) ? (int64_t)pl->dims[axis] * hp.mask_words : 0;
     hp.valid_lens = pl->desc.valid_lens;
     hp.N = pl->N;
     hp.rope = pl->desc.rope;
@@ -249,7 +250,7 @@ const char* ta_last_error_detail(void) { return g_detail; }
 
 void ta_version(int* major, int* minor) {
     if (major) *major = 0;
-    if (minor) *minor = 5;
+    if (minor) *minor = 6;
 }
 
 ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
@@ -276,6 +277,9 @@ ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
         if (reinterpret_cast<uintptr_t>(d->axis_mask[i]) % 4 != 0) return fail(TA_ERR_INVALID_ARG, "axis_mask[%d] is not 4-byte aligned", i);
     if (reinterpret_cast<uintptr_t>(d->valid_lens) % 8 != 0) return fail(TA_ERR_INVALID_ARG, "valid_lens is not 8-byte aligned");
     if (d->rope != 0 && d->rope != 1) return fail(TA_ERR_INVALID_ARG, "rope must be 0 or 1");
+    for (int i = 0; i < d->order && i < TA_MAX_ORDER; ++i)
+        if (d->axis_mask_per_fibre[i] != 0 && d->axis_mask_per_fibre[i] != 1)
+            return fail(TA_ERR_INVALID_ARG, "axis_mask_per_fibre entries must be 0 or 1");
     if (!(d->rope_base >= 0.f) || isinf(d->rope_base)) return fail(TA_ERR_INVALID_ARG, "rope_base must be finite and >= 0");
     if (d->valid_len < 0) return fail(TA_ERR_INVALID_ARG, "valid_len is negative");
     if (d->valid_len > N) return fail(TA_ERR_SHAPE, "valid_len %lld exceeds the sequence length %lld", (long long)d->valid_len, (long long)N);

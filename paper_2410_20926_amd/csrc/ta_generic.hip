@@ -129,6 +129,7 @@ __global__ __launch_bounds__(kThreads) void generic_forward_kernel(HopParams p, 
     const int g = h / p.G;
     const int hv = (p.vin_heads == p.Hq) ? h : g;
     const int64_t tok0 = fibre_base_token(f, p.stride, n);
+    if (p.mask) p.mask += f * p.mask_fibre_words;          // this fibre's table (the same one when the axis has a single table)
     p.valid_len = hop_valid_len(p, b);                  // this batch element's padding length
     const HopParams* enc = p.rope ? &p : nullptr;       // the hop turns Q and K rows by their position
 
@@ -226,6 +227,7 @@ __global__ __launch_bounds__(kThreads) void generic_backward_kernel(BwdParams bp
     const int g = (int)(bid % p.Hkv);
     const int b = (int)(bid / p.Hkv);
     const int64_t tok0 = fibre_base_token(f, p.stride, n);
+    if (p.mask) p.mask += f * p.mask_fibre_words;          // this fibre's table (the same one when the axis has a single table)
     const bool vin_is_o = (p.vin_heads == p.Hq);
     p.valid_len = hop_valid_len(p, b);                  // this batch element's padding length
     const HopParams* enc = p.rope ? &p : nullptr;       // the hop turns Q and K rows by their position

@@ -30,6 +30,7 @@ struct HopParams {
     int64_t valid_len;       // tokens at or past it are padding; equals N when there is none
     const uint32_t* mask;    // device table of this axis (n rows of mask_words words, bit c of row a = visible) or nullptr
     int32_t mask_words;      // ceil(n / 32)
+    int64_t mask_fibre_words;   // words from one fibre's table to the next one's (n * mask_words), or 0: one table for every fibre
     const int64_t* valid_lens;   // device, one padding length per batch element (clamped to [0, N], combined with valid_len), or nullptr
     int64_t N;               // tokens per batch element
     // Rotary encoding inside the hop: Q and K rows are turned by their position a on this axis before

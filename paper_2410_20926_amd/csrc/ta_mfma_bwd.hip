@@ -347,7 +347,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
     {
         int lo = 0, hi = 0;
         uint32_t tw = 0xffffffffu;
-        if (row_real) { visible_range(r32, flo, fhi, p.causal, p.window, lo, hi); if (TABLE) tw = table_word(p, r32 - flo, 0) << flo; }
+        if (row_real) { visible_range(r32, flo, fhi, p.causal, p.window, lo, hi); if (TABLE) tw = table_word(p, f0 + (uint32_t)(flo / n), r32 - flo, 0) << flo; }
         const uint32_t vis = (range_mask(lo, hi) & tw & real_rows) >> (4 * hf);
         float e[16], mx = -INFINITY;
 #pragma unroll
@@ -381,7 +381,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
         // query rows that see this lane's key: its own fibre's rows, from itself on when causal
         int lo = 0, hi = 0;
         uint32_t tw = 0xffffffffu;
-        if (row_real) { seen_range(r32, flo, fhi, p.causal, p.window, lo, hi); if (TABLE) tw = table_column(p, r32 - flo) << flo; }
+        if (row_real) { seen_range(r32, flo, fhi, p.causal, p.window, lo, hi); if (TABLE) tw = table_column(p, f0 + (uint32_t)(flo / n), r32 - flo) << flo; }
         const uint32_t vis = (range_mask(lo, hi) & tw & real_rows) >> (4 * hf);
         uint32_t pw[8], dw[8];                            // rounded in pairs as they are formed
         float slv = sl2;
@@ -476,27 +476,28 @@ struct StreamBwdParams {
 
 // Keys 32 c .. 32 c + 31 that query row qr of the fibre may attend (bit = key), and query
 // rows 32 a .. 32 a + 31 that may attend key kr (bit = query row).
-__device__ inline uint32_t block_vis_keys(const HopParams& p, int qr, int c, int nreal) {
+__device__ inline uint32_t block_vis_keys(const HopParams& p, int64_t fibre, int qr, int c, int nreal) {
     if (qr >= nreal) return 0u;
     int lo, hi;
     visible_range(qr, 0, p.n, p.causal, p.window, lo, hi);
     hi = min(hi, nreal);
     uint32_t v = range_mask(min(max(lo - kTile * c, 0), kTile), min(max(hi - kTile * c, 0), kTile));
-    if (p.mask) v &= p.mask[qr * p.mask_words + c];
+    if (p.mask) v &= p.mask[fibre * p.mask_fibre_words + qr * p.mask_words + c];
     return v;
 }
-__device__ inline uint32_t block_vis_rows(const HopParams& p, int kr, int a, int nreal) {
+__device__ inline uint32_t block_vis_rows(const HopParams& p, int64_t fibre, int kr, int a, int nreal) {
     if (kr >= nreal) return 0u;
     int lo, hi;
     seen_range(kr, 0, p.n, p.causal, p.window, lo, hi);
     hi = min(hi, nreal);
     uint32_t v = range_mask(min(max(lo - kTile * a, 0), kTile), min(max(hi - kTile * a, 0), kTile));
     if (p.mask) {
+        const uint32_t* table = p.mask + fibre * p.mask_fibre_words;
         uint32_t col = 0;
 #pragma unroll 1
         for (int q = 0; q < kTile; ++q) {                 // rare path: kept rolled, its 32 loads would otherwise claim registers in every kernel
             const int qr = kTile * a + q;
-            if (qr < p.n) col |= ((p.mask[qr * p.mask_words + (kr >> 5)] >> (kr & 31)) & 1u) << q;
+            if (qr < p.n) col |= ((table[qr * p.mask_words + (kr >> 5)] >> (kr & 31)) & 1u) << q;
         }
         v &= col;
     }
@@ -633,7 +634,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
             lds_wave_sync();
 #pragma unroll
             for (int s = 0; s < G::kKSteps; ++s) dpT = mma(op[s], gop[s], dpT);
-            const uint32_t vis = block_vis_keys(p, qr, c, nreal) >> (4 * hf);
+            const uint32_t vis = block_vis_keys(p, f, qr, c, nreal) >> (4 * hf);
             float e[16], tmax = -INFINITY;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -689,7 +690,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
             for (int s = 0; s < G::kKSteps; ++s) sT = mma(op[s], qop[s], sT);
             read_transposed<D>(trbase, kT);                // K^T last: it lives only until the products below
             lds_wave_sync();
-            const uint32_t vis = block_vis_keys(p, qr, c, nreal) >> (4 * hf);
+            const uint32_t vis = block_vis_keys(p, f, qr, c, nreal) >> (4 * hf);
             float e[16];
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -749,7 +750,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
             lds_wave_sync();
             read_transposed<D>(trbase, gT);
             lds_wave_sync();
-            const uint32_t vis = block_vis_rows(p, kr, a, nreal) >> (4 * hf);
+            const uint32_t vis = block_vis_rows(p, f, kr, a, nreal) >> (4 * hf);
             float pr[16];
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
@@ -812,7 +813,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
             for (int s = 0; s < G::kKSteps; ++s) sN = mma(op[s], kop[s], sN);
             read_transposed<D>(trbase, qT);
             lds_wave_sync();
-            const uint32_t vis = block_vis_rows(p, kr, a, nreal) >> (4 * hf);
+            const uint32_t vis = block_vis_rows(p, f, kr, a, nreal) >> (4 * hf);
             float ds[16];
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
@@ -1056,7 +1057,7 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
         float e[2][16], mx = -INFINITY;
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-            const uint32_t vis = visq[c] ? block_vis_keys(p, qr, c, nreal) >> (4 * hf) : 0u;
+            const uint32_t vis = visq[c] ? block_vis_keys(p, f, qr, c, nreal) >> (4 * hf) : 0u;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const bool ok = (vis >> (8 * (r / 4) + (r % 4))) & 1u;
@@ -1106,7 +1107,7 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
 #pragma unroll
                 for (int s = 0; s < G::kKSteps; ++s) sN = mma(qn[s], kn[s], sN);
             }
-            const uint32_t vis = visk[a] ? block_vis_rows(p, kr, a, nreal) >> (4 * hf) : 0u;
+            const uint32_t vis = visk[a] ? block_vis_rows(p, f, kr, a, nreal) >> (4 * hf) : 0u;
             const float* st = stats + a * (3 * kTile);
             uint32_t pw[8], dw[8];                        // rounded in pairs as they are formed: sixteen of each in fp32 do not fit
             float slv = sl2;

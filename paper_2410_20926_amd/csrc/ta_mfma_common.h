@@ -189,15 +189,17 @@ __device__ inline void seen_range(int row, int flo, int fhi, int causal, int win
 
 // The caller's bit table of the axis (row a, word j: keys 32 j .. 32 j + 31 visible from query
 // position a), all ones when there is none.
-__device__ inline uint32_t table_word(const HopParams& p, int a, int j) {
-    return p.mask ? p.mask[a * p.mask_words + j] : 0xffffffffu;
+// `fibre`: the fibre's number on this axis (used when every fibre has a table of its own).
+__device__ inline uint32_t table_word(const HopParams& p, uint32_t fibre, int a, int j) {
+    return p.mask ? p.mask[(int64_t)fibre * p.mask_fibre_words + a * p.mask_words + j] : 0xffffffffu;
 }
 // Its transpose for key position c of an axis of at most 32 positions: bit a = query
 // position a sees key c.
-__device__ inline uint32_t table_column(const HopParams& p, int c) {
+__device__ inline uint32_t table_column(const HopParams& p, uint32_t fibre, int c) {
     if (!p.mask) return 0xffffffffu;
+    const uint32_t* t = p.mask + (int64_t)fibre * p.mask_fibre_words;
     uint32_t col = 0;
-    for (int a = 0; a < p.n; ++a) col |= ((p.mask[a] >> c) & 1u) << a;
+    for (int a = 0; a < p.n; ++a) col |= ((t[a] >> c) & 1u) << a;
     return col;
 }
 

@@ -220,10 +220,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
 #pragma unroll
         for (int j = 0; j < KT; ++j) tw[j] = 0xffffffffu;
         if ((real_rows >> qrow) & 1) {
-            const int flo = (KT == 1) ? (int)((qrow + 0.5f) * tp.inv_n) * n : 0;
+            const int fi = (KT == 1) ? (int)((qrow + 0.5f) * tp.inv_n) : 0;      // the row's fibre within the unit
+            const int flo = fi * n;
             visible_range(qrow, flo, flo + n, p.causal, p.window, lo, hi);
 #pragma unroll
-            for (int j = 0; j < KT; ++j) tw[j] = (KT == 1) ? table_word(p, qrow - flo, 0) << flo : table_word(p, qrow, j);
+            for (int j = 0; j < KT; ++j) tw[j] = (KT == 1) ? table_word(p, f0 + fi, qrow - flo, 0) << flo : table_word(p, f0, qrow, j);
         }
 #pragma unroll
         for (int j = 0; j < KT; ++j)
@@ -514,10 +515,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
 #pragma unroll
     for (int j = 0; j < KT; ++j) tw[j] = 0xffffffffu;
     if ((real_rows >> qrow) & 1) {
-        const int flo = (KT == 1) ? (int)((qrow + 0.5f) * tp.inv_n) * n : 0;
+        const int fi = (KT == 1) ? (int)((qrow + 0.5f) * tp.inv_n) : 0;          // the row's fibre within the unit
+        const int flo = fi * n;
         visible_range(qrow, flo, flo + n, p.causal, p.window, lo, hi);
 #pragma unroll
-        for (int j = 0; j < KT; ++j) tw[j] = (KT == 1) ? table_word(p, qrow - flo, 0) << flo : table_word(p, qrow, j);
+        for (int j = 0; j < KT; ++j) tw[j] = (KT == 1) ? table_word(p, f0 + fi, qrow - flo, 0) << flo : table_word(p, f0, qrow, j);
     }
     const float sl2 = p.scale * kLog2e;
     float mx = -INFINITY;

@@ -49,6 +49,7 @@ struct PairParams {
     int32_t window1, window2;                // band widths on the outer / inner axis, 0 = none
     const uint32_t* mask1;                   // bit tables of the outer / inner axis (32 words) or nullptr
     const uint32_t* mask2;
+    uint32_t mask1_fibre, mask2_fibre;       // words from one fibre's table to the next (32), or 0: one table for the axis
     uint32_t slabs;                          // slabs per batch element
     uint32_t groups;                         // B * slabs * Hkv
     uint32_t q_row, k_row, v_row, o_row;     // token pitch of each tensor in bytes
@@ -381,14 +382,17 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
 #pragma unroll
     for (int f = 0; f < kOwn; ++f) {                      // column fibre j = 4 w + f: slab rows i with token 32 i + j < left
         const int64_t room = left - (w * kOwn + f);
-        softmax_tile(sc[f], r32, hf, p.causal, p.window1, p.mask1, room <= 0 ? 0 : (int)min((int64_t)kN, (room + kN - 1) / kN), sl2, p1[f], inv1[f]);
+        // (the column fibre's number on the outer axis: slab, then column)
+        const uint32_t* table = p.mask1 ? p.mask1 + (size_t)(sl * kN + w * kOwn + f) * p.mask1_fibre : nullptr;
+        softmax_tile(sc[f], r32, hf, p.causal, p.window1, table, room <= 0 ? 0 : (int)min((int64_t)kN, (room + kN - 1) / kN), sl2, p1[f], inv1[f]);
     }
     load_x(0, 8, 16);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int f = 0; f < kOwn; ++f) {                      // row fibre i = 4 w + f: columns j with token 32 i + j < left
         const int64_t room = left - (int64_t)(w * kOwn + f) * kN;
-        softmax_tile(sr[f], r32, hf, p.causal, p.window2, p.mask2, room <= 0 ? 0 : (int)min((int64_t)kN, room), sl2, p2[f], inv2[f]);
+        const uint32_t* table = p.mask2 ? p.mask2 + (size_t)(sl * kN + w * kOwn + f) * p.mask2_fibre : nullptr;   // (slab, then row)
+        softmax_tile(sr[f], r32, hf, p.causal, p.window2, table, room <= 0 ? 0 : (int)min((int64_t)kN, room), sl2, p2[f], inv2[f]);
     }
 
     // ===== phase B ==================================================================================
@@ -460,6 +464,7 @@ bool pair_params(const HopParams& h1, const HopParams& h2, PairParams* pp) {
     pp->scale = h1.scale;
     pp->window1 = h1.window; pp->window2 = h2.window;
     pp->mask1 = h1.mask; pp->mask2 = h2.mask;
+    pp->mask1_fibre = (uint32_t)h1.mask_fibre_words; pp->mask2_fibre = (uint32_t)h2.mask_fibre_words;
     pp->valid_len = h1.valid_len;
     pp->valid_lens = h1.valid_lens;
     pp->dbytes = (uint32_t)h1.D * 2;

@@ -139,7 +139,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
         for (int s = 0; s < G::kKSteps; ++s) st = mma(kop[s], qop[s], st);
 
         // ---- mask, running max and sum ------------------------------------------------------
-        const uint32_t tw = qrow < nreal ? table_word(p, qrow, j) : 0u;
+        const uint32_t tw = qrow < nreal ? table_word(p, f, qrow, j) : 0u;
         const uint32_t vis = (range_mask(min(max(klo - kTile * j, 0), kTile), min(max(khi - kTile * j, 0), kTile)) & tw) >> (4 * hf);
         float e[16], tmax = -INFINITY;
 #pragma unroll
@@ -358,7 +358,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
 #pragma unroll
         for (int s = 0; s < G::kKSteps; ++s) st = mma(kop[s], qop[s], st);
 
-        const uint32_t tw = qrow < nreal ? table_word(p, qrow, j) : 0u;
+        const uint32_t tw = qrow < nreal ? table_word(p, f, qrow, j) : 0u;
         const uint32_t vis = (range_mask(min(max(klo - kTile * j, 0), kTile), min(max(khi - kTile * j, 0), kTile)) & tw) >> (4 * hf);
         float e[16], tmax = -INFINITY;
 #pragma unroll
@@ -612,7 +612,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunke
 #pragma unroll
         for (int s = 0; s < G::kKSteps; ++s) st = mma(kop[s], qop[s], st);
 
-        const uint32_t tw = qrow < nreal ? table_word(p, qrow, j) : 0u;
+        const uint32_t tw = qrow < nreal ? table_word(p, f, qrow, j) : 0u;
         const uint32_t vis = (range_mask(min(max(klo - kTile * j, 0), kTile), min(max(khi - kTile * j, 0), kTile)) & tw) >> (4 * hf);
         float e[16], tmax = -INFINITY;
 #pragma unroll

@@ -36,6 +36,7 @@ class TaDesc(C.Structure):
         ("window", C.c_int32 * TA_MAX_ORDER), ("valid_len", C.c_int64),
         ("axis_mask", C.c_void_p * TA_MAX_ORDER),
         ("valid_lens", C.c_void_p), ("rope", C.c_int32), ("rope_base", C.c_float),
+        ("axis_mask_per_fibre", C.c_int32 * TA_MAX_ORDER),
     ]
 
 
@@ -145,7 +146,8 @@ def make_desc(batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dims: 
               q_strides=None, kv_strides=None, o_strides=None, window: Optional[Sequence[int]] = None,
               valid_len: int = 0, axis_masks: Optional[Sequence] = None, valid_lens=None,
               rope_base: Optional[float] = None) -> TaDesc:
-    """`axis_masks`: per axis None or a device tensor of packed bit rows (see pack_axis_mask);
+    """`axis_masks`: per axis None or a device tensor of packed bit rows (see pack_axis_mask), [n, words] for one
+    table shared by the axis's fibres or [fibres, n, words] for one table per fibre;
     `valid_lens`: None or a device int64 tensor of B lengths; the descriptor keeps a reference to
     each so the memory outlives the plan.  `rope_base`: None = no encoding inside the hops, else
     the rotary base (0 = 10000)."""
@@ -166,6 +168,7 @@ def make_desc(batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dims: 
     for j in range(TA_MAX_ORDER):
         t = axis_masks[j] if axis_masks is not None and j < len(axis_masks) else None
         d.axis_mask[j] = _ptr(t) if t is not None else None
+        d.axis_mask_per_fibre[j] = 1 if (t is not None and getattr(t, "ndim", 2) == 3) else 0   # [fibres, n, words]
         d._mask_refs.append(t)
     d.valid_lens = _ptr(valid_lens) if valid_lens is not None else None
     d._mask_refs.append(valid_lens)
@@ -180,17 +183,18 @@ def make_desc(batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, dims: 
 
 def pack_axis_mask(mask):
     """Packs a boolean [n, n] table (row a, column c true = query position a may attend key
-    position c) into the library's layout: uint32 [n, ceil(n / 32)], bit c % 32 of word c / 32.
-    Returns a host array (viewed as int32, which torch can hold); move it to the device and
-    pass it in `axis_masks`."""
+    position c), or [fibres, n, n] with one table per fibre, into the library's layout: uint32
+    [..., n, ceil(n / 32)], bit c % 32 of word c / 32.  Returns a host array (viewed as int32, which
+    torch can hold); move it to the device and pass it in `axis_masks`."""
     import numpy as np
     m = np.asarray(mask, dtype=bool)
-    n = m.shape[0]
-    assert m.shape == (n, n)
+    n = m.shape[-1]
+    assert m.shape[-2:] == (n, n) and m.ndim in (2, 3)
     words = (n + 31) // 32
-    padded = np.zeros((n, words * 32), dtype=bool)
-    padded[:, :n] = m
-    return np.packbits(padded.reshape(n, words, 32), axis=-1, bitorder="little").view(np.uint32).reshape(n, words).view(np.int32)
+    padded = np.zeros(m.shape[:-1] + (words * 32,), dtype=bool)
+    padded[..., :n] = m
+    packed = np.packbits(padded.reshape(m.shape[:-1] + (words, 32)), axis=-1, bitorder="little")
+    return np.ascontiguousarray(packed).view(np.uint32).reshape(m.shape[:-1] + (words,)).view(np.int32)
 
 
 class Plan:

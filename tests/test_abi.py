@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_status_strings():
-    assert ta.ta_version() == (0, 5)
+    assert ta.ta_version() == (0, 6)
     lib = ta.load_library()
     assert lib.ta_status_string(0) == b"TA_OK"
     assert lib.ta_status_string(5) == b"TA_ERR_ALIAS"
@@ -115,6 +115,24 @@ def test_plan_rejects_bad_descriptors(kw, status):
         ta.ta_plan_create(**args)
     assert ei.value.name == status
     assert ei.value.detail
+
+
+def test_per_fibre_mask_flag_must_be_0_or_1_and_packing_keeps_the_fibre_axis():
+    import numpy as np
+    d = binding.make_desc(1, 2, 2, 64, (4, 3), ta.TA_F32, False)
+    d.axis_mask_per_fibre[1] = 3
+    with pytest.raises(ta.TaError) as e:
+        ta.Plan(d)
+    assert e.value.name == "TA_ERR_INVALID_ARG"
+    d.axis_mask_per_fibre[1] = 1
+    d.axis_mask_per_fibre[5] = 9                       # entries at or beyond `order` are ignored
+    ta.Plan(d)
+    m = np.random.default_rng(3).random((7, 40, 40)) < 0.5
+    packed = ta.pack_axis_mask(m).view(np.uint32)
+    assert packed.shape == (7, 40, 2)
+    for f, a, c in ((0, 0, 0), (6, 39, 39), (3, 17, 32), (2, 5, 31)):
+        assert bool((packed[f, a, c // 32] >> (c % 32)) & 1) == bool(m[f, a, c])
+    assert np.array_equal(ta.pack_axis_mask(m[4]), ta.pack_axis_mask(m)[4])
 
 
 def test_rope_flag_must_be_0_or_1():

@@ -194,3 +194,72 @@ def test_valid_lens_combine_with_valid_len_and_are_clamped():
     got, _, _ = multihop_forward(q, k, v, dims, "bf16", False, valid_len=70, valid_lens=tl)
     ref = orc.tensorized_attention_forward(q, k, v, dims, False, valid_len=[70, 0, 50])
     assert np.abs(got - ref).max() <= TOL["bf16"]
+
+
+# ---- one table per fibre (Eq. 3) ------------------------------------------------------------------
+
+def make_fibre_tables(dims, axes, seed):
+    """A random table for every fibre of the masked axes (60 % density, diagonal kept), one row of one
+    fibre fully hidden on the first masked axis."""
+    rng = np.random.default_rng(seed)
+    N = int(np.prod(dims))
+    host, dev = [], []
+    for i, n in enumerate(dims):
+        if i not in axes:
+            host.append(None); dev.append(None)
+            continue
+        m = (rng.random((N // n, n, n)) < 0.6) | np.eye(n, dtype=bool)[None]
+        if i == axes[0] and n > 2:
+            m[(N // n) // 2, n // 2, :] = False
+        host.append(m)
+        dev.append(torch.from_numpy(ta.pack_axis_mask(m)).cuda())
+    return host, dev
+
+
+@pytest.mark.parametrize("dims,B,Hq,Hkv,D,causal,dtype,axes,window,valid_len", TABLE_CASES)
+def test_fibre_table_forward_matches_oracle(dims, B, Hq, Hkv, D, causal, dtype, axes, window, valid_len):
+    N = int(np.prod(dims))
+    q, k, v = make_inputs(B, N, Hq, Hkv, D, seed=5500 + N + D, dtype=dtype)
+    host, dev = make_fibre_tables(dims, axes, 5600 + N)
+    kw = dict(axis_masks=dev)
+    if window is not None:
+        kw["window"] = window
+    if valid_len is not None:
+        kw["valid_len"] = valid_len
+    got, plan, _ = multihop_forward(q, k, v, dims, dtype, causal, **kw)
+    ref = orc.tensorized_attention_forward(q, k, v, dims, causal, window=window, valid_len=valid_len, axis_masks=host)
+    assert np.isfinite(got).all()
+    err = np.abs(got - ref).max()
+    assert err <= TOL[dtype], f"max-abs error {err:.3e}"
+    # the tables do differ between fibres: the first fibre's table for all of them gives another result
+    shared = orc.tensorized_attention_forward(q, k, v, dims, causal, window=window, valid_len=valid_len,
+                                              axis_masks=[None if m is None else m[0] for m in host])
+    assert np.abs(shared - ref).max() > 10 * TOL[dtype]
+
+
+@pytest.mark.parametrize("dims,B,Hq,Hkv,D,causal,dtype,axes,window,valid_len", TABLE_BWD_CASES)
+def test_fibre_table_backward_matches_oracle(dims, B, Hq, Hkv, D, causal, dtype, axes, window, valid_len):
+    N = int(np.prod(dims))
+    q, k, v, d_o = make_inputs(B, N, Hq, Hkv, D, seed=6500 + N + D, dtype=dtype, with_grad=True)
+    host, dev = make_fibre_tables(dims, axes, 6600 + N)
+    kw = dict(axis_masks=dev)
+    if window is not None:
+        kw["window"] = window
+    if valid_len is not None:
+        kw["valid_len"] = valid_len
+    _, plan, devt = multihop_forward(q, k, v, dims, dtype, causal, save=True, **kw)
+    dq, dk, dv = multihop_backward(plan, devt, d_o, dtype)
+    check_backward((dq, dk, dv), q, k, v, d_o, dims, causal, dtype, window=window, valid_len=valid_len, axis_masks=host)
+
+
+def test_equal_fibre_tables_are_bit_identical_to_the_shared_table():
+    dims, B, Hq, Hkv, D = (64, 32, 32), 1, 8, 2, 128          # two-tile first hop, then the fused pair
+    N = int(np.prod(dims))
+    q, k, v = make_inputs(B, N, Hq, Hkv, D, seed=7100, dtype="bf16")
+    rng = np.random.default_rng(7101)
+    tables = [(rng.random((n, n)) < 0.7) | np.eye(n, dtype=bool) for n in dims]
+    shared = [torch.from_numpy(ta.pack_axis_mask(t)).cuda() for t in tables]
+    each = [torch.from_numpy(ta.pack_axis_mask(np.broadcast_to(t, (N // t.shape[0],) + t.shape))).cuda() for t in tables]
+    a, _, _ = multihop_forward(q, k, v, dims, "bf16", True, axis_masks=shared)
+    b, _, _ = multihop_forward(q, k, v, dims, "bf16", True, axis_masks=each)
+    assert np.array_equal(a, b)
