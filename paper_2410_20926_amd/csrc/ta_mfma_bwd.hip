@@ -854,7 +854,8 @@ constexpr size_t two_tile_lds(int gh, bool vs) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Axes of two tiles (32 < n <= 64), groups of 1, 2 or 4 query heads: the same derivative with
+// Axes of two tiles (32 < n <= 64), groups of 1, 2 or 4 query heads (a larger group that is a multiple of 4 goes 4
+// heads per launch, the later launches adding to dK and to the group's dV): the same derivative with
 // every tensor tile read from memory ONCE per fibre.  Two waves serve one query head of one
 // fibre: wave (head, t) owns query tile t (the rows of dQ_t) and key tile t (the rows of dK_t
 // and dX_t), and the two exchange their tiles through LDS.  The K tiles (and the X tiles when
@@ -881,7 +882,7 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int hl = w >> 1, t = w & 1;                     // head of the group; tile this wave owns
     const int g = blockIdx.x;
-    const int h = g * GH + hl;
+    const int h = g * p.G + bp.head_base + hl;            // a group of more than GH heads goes GH heads per launch
     const uint32_t zb = blockIdx.z / sp.fibres_hi;
     const int64_t f = (int64_t)(blockIdx.z - zb * sp.fibres_hi) * sp.fibres_lo + blockIdx.y;
     if (f >= p.fibres) return;                            // whole workgroup leaves together
@@ -1155,9 +1156,9 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
     {
         u32x4 oldk[G::kDTiles * 2] = {};
         const bool last = hl == GH - 1;                   // the wave that ends up with the group's sum
-        if (bp.accumulate && last) prefetch_tile<D>(oldk, rowoff, 1, dkb, lane);
+        if (bp.acc_k && last) prefetch_tile<D>(oldk, rowoff, 1, dkb, lane);
         if (GH > 1) chain_sum<D>(acc, red, hl, GH, lane);
-        if (last) store_tile<D, false>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.accumulate != 0, rows_t, lane, 0, enc);
+        if (last) store_tile<D, false>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.acc_k != 0, rows_t, lane, 0, enc);
     }
     // ---- dQ_t^T = sum_c K_c^T dS^T_tc ------------------------------------------------------------------------
     {
@@ -1197,9 +1198,10 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
     if (!VS) {
         store_tile_plain<D>(acc, 1.f, buf, rowoff, 2, dxb, rows_t, lane);
     } else {
-        u32x4 none[G::kDTiles * 2] = {};
+        u32x4 oldx[G::kDTiles * 2] = {};                  // the sum of the group's earlier launches
+        if (bp.acc_x && hl == GH - 1) prefetch_tile<D>(oldx, rowoff, 2, dxb, lane);
         if (GH > 1) chain_sum<D>(acc, red, hl, GH, lane);
-        if (hl == GH - 1) store_tile<D, false>(acc, 1.f, buf, rowoff, 2, dxb, none, false, rows_t, lane);
+        if (hl == GH - 1) store_tile<D, false>(acc, 1.f, buf, rowoff, 2, dxb, oldx, bp.acc_x != 0, rows_t, lane);
     }
 }
 
@@ -1293,8 +1295,8 @@ static int backward_variant(const BwdParams& bp, int dtype) {
         const int64_t lo = p.fibres < 32768 ? p.fibres : 32768;
         if (p.fibres <= 0 || (int64_t)p.B * ((p.fibres + lo - 1) / lo) > 65535) return 0;
     }
-    // two tiles, full-width heads, groups of 1, 2 or 4 heads: every tile is read once per fibre
-    if (p.n <= 2 * kTile && full && (p.G == 1 || p.G == 2 || p.G == 4)) return 3;
+    // two tiles, full-width heads, groups of 1, 2 or a multiple of 4 heads: every tile is read once per fibre and launch
+    if (p.n <= 2 * kTile && full && (p.G == 1 || p.G == 2 || p.G % 4 == 0)) return 3;
     // the blocked kernel keeps three floats per row and head in LDS
     const size_t tiles = (size_t)(p.n + kTile - 1) / kTile;
     const size_t kbuf = p.D > 64 ? BGeo<128>::kBufBytes : BGeo<64>::kBufBytes;
@@ -1319,10 +1321,18 @@ hipError_t launch_mfma_backward(const BwdParams& user, hipStream_t s) {
     // dV), in a fixed order, so the result stays deterministic.
     BwdParams bp = user;
     const int G = user.hop.G;
-    if (variant == 3) {
-        bp.wg_heads = G; bp.head_base = 0; bp.acc_k = user.accumulate; bp.acc_x = 0;
-        if (bp.hop.D == 128) return G == 4 ? launch_two_tile<128, 4>(bp, s) : G == 2 ? launch_two_tile<128, 2>(bp, s) : launch_two_tile<128, 1>(bp, s);
-        return G == 4 ? launch_two_tile<64, 4>(bp, s) : G == 2 ? launch_two_tile<64, 2>(bp, s) : launch_two_tile<64, 1>(bp, s);
+    if (variant == 3) {                                   // groups of 1, 2 or 4 heads in one launch, larger ones 4 heads per launch
+        const int gh = G >= 4 ? 4 : G;
+        for (int base = 0; base < G; base += gh) {
+            bp.wg_heads = gh; bp.head_base = base;
+            bp.acc_k = base == 0 ? user.accumulate : 1;
+            bp.acc_x = base == 0 ? 0 : 1;
+            hipError_t e;
+            if (bp.hop.D == 128) e = gh == 4 ? launch_two_tile<128, 4>(bp, s) : gh == 2 ? launch_two_tile<128, 2>(bp, s) : launch_two_tile<128, 1>(bp, s);
+            else                 e = gh == 4 ? launch_two_tile<64, 4>(bp, s) : gh == 2 ? launch_two_tile<64, 2>(bp, s) : launch_two_tile<64, 1>(bp, s);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
     }
     for (int base = 0; base < G; base += 8) {
         bp.wg_heads = G - base > 8 ? 8 : G - base;

@@ -54,7 +54,7 @@ def gradient_magnitudes(q, k, v, d_o, dims, causal, scale=None, hop_order=None, 
 HALF_ULP_BF16 = 2.0 ** -8          # largest relative error of one rounding to bfloat16 (8 significant bits)
 
 
-def backward_reference_and_tolerance(q, k, v, d_o, dims, causal, dtype, launch_heads=8, scale=None, hop_order=None, **mask_kw):
+def backward_reference_and_tolerance(q, k, v, d_o, dims, causal, dtype, launch_heads=None, scale=None, hop_order=None, **mask_kw):
     """The oracle's (dq, dk, dv) and, for each, a per-element tolerance for the HIP path.
 
     bf16:  tol = 2e-2 + 2^-8 * (R + 2 E).  R sums the absolute values of every quantity that the path
@@ -62,7 +62,9 @@ def backward_reference_and_tolerance(q, k, v, d_o, dims, causal, dtype, launch_h
       dq  its running sum after each processed hop (hops are undone last to first; each adds
           its share to the stored dq and rounds), the last of which is the result itself;
       dk  the same, per launch: a launch covers up to `launch_heads` query heads of a group,
-          sums them in fp32, adds the stored dk and rounds;
+          sums them in fp32, adds the stored dk and rounds (None: what the library does, 8 heads per
+          launch, 4 on an axis of 33 to 64 positions when the group is a multiple of 4 above 4 and the
+          head width is 64 or 128);
       dv  the group sum per launch, plus (m - 1) times the magnitude sum of the gradient chain
           (gradient_magnitudes), for the m - 1 inter-hop gradients stored in bf16.
     E is the root of the sum of squares of the element's individual products dS K scale (dq) or
@@ -86,16 +88,24 @@ def backward_reference_and_tolerance(q, k, v, d_o, dims, causal, dtype, launch_h
     Ek = np.sqrt(trace["dk_sq"].reshape(B, N, Hkv, G, D).sum(3))
     run_q = np.zeros_like(ref[0])
     run_k = np.zeros_like(ref[1])
+    order = list(range(m)) if hop_order is None else [int(a) for a in hop_order]
+
+    def heads_per_launch(pos):
+        if launch_heads is not None:
+            return launch_heads
+        n = int(dims[order[pos]])
+        return 4 if (32 < n <= 64 and G > 4 and G % 4 == 0 and D in (64, 128)) else 8
+
     for pos in range(m - 1, -1, -1):
         run_q = run_q + trace["dq_hops"][pos]
         Rq += np.abs(run_q)
-        for base in range(0, G, launch_heads):
-            hs = np.arange(base, min(base + launch_heads, G))
+        for base in range(0, G, heads_per_launch(pos)):
+            hs = np.arange(base, min(base + heads_per_launch(pos), G))
             run_k = run_k + trace["dk_hops"][pos].reshape(B, N, Hkv, G, D)[:, :, :, hs].sum(3)
             Rk += np.abs(run_k)
     run_v = np.zeros_like(ref[2])
-    for base in range(0, G, launch_heads):
-        hs = np.arange(base, min(base + launch_heads, G))
+    for base in range(0, G, heads_per_launch(0)):
+        hs = np.arange(base, min(base + heads_per_launch(0), G))
         run_v = run_v + trace["dv_heads"].reshape(B, N, Hkv, G, -1)[:, :, :, hs].sum(3)
         Rv = Rv + np.abs(run_v)
     return ref, (2e-2 + HALF_ULP_BF16 * (Rq + 2 * Eq), 2e-2 + HALF_ULP_BF16 * (Rk + 2 * Ek), 2e-2 + HALF_ULP_BF16 * Rv)

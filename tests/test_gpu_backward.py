@@ -38,7 +38,8 @@ CASES = [
     ((64, 64, 2), 1, 8, 2, 128, True, "bf16"),       # two hops on 64-long axes: as the value-input hop and as a later hop, dQ / dK accumulate
     ((33, 3), 2, 4, 1, 64, False, "bf16"),           # one row in the second tile
     ((2, 64), 1, 4, 4, 128, False, "bf16"),          # full second tile, non-causal: all four blocks
-    ((48, 2), 1, 16, 2, 128, True, "bf16"),          # 8 heads per group on a two-tile axis: the blocked kernel
+    ((48, 2), 1, 16, 2, 128, True, "bf16"),          # 8 heads per group on a two-tile axis: the two-tile kernel, two launches of 4 heads
+    ((40, 3), 1, 12, 1, 64, True, "bf16"),           # 12 heads per group, width 64: three launches, the later ones add to dK and dV
     ((100, 2), 1, 8, 1, 128, False, "bf16"),         # four tiles, 8 heads per group
     ((2, 200), 1, 4, 2, 64, True, "bf16"),           # seven tiles
     ((333,), 1, 2, 2, 128, True, "bf16"),            # one long axis: plain causal attention, 11 tiles
@@ -49,7 +50,8 @@ CASES = [
     ((6, 32), 1, 8, 1, 64, True, "bf16"),            # 8 heads per group: workgroups of 8 waves
     ((4, 16), 1, 16, 1, 128, True, "bf16"),          # 16 heads per group: two launches of 8 heads, the second adds to dK, dV
     ((8, 32), 2, 32, 1, 64, True, "bf16"),           # multi-query: 32 heads on one key/value head, four launches
-    ((64, 4), 1, 16, 1, 128, False, "bf16"),         # the blocked kernel with 16 heads per group
+    ((64, 4), 1, 16, 1, 128, False, "bf16"),         # 16 heads per group on a two-tile axis: four launches of 4 heads
+    ((66, 2), 1, 16, 1, 128, False, "bf16"),         # the blocked kernel with 16 heads per group
     ((6, 5), 1, 12, 1, 64, True, "bf16"),            # 12 heads per group: a launch of 8 and one of 4
     ((8, 16), 1, 7, 1, 128, True, "bf16"),           # 7 heads per group (28 query / 4 key-value heads is a real geometry)
     ((5, 40), 2, 6, 2, 128, False, "bf16"),          # 3 heads per group, blocked kernel on the second axis
@@ -178,7 +180,8 @@ def test_backward_kernel_choice_for_axes_longer_than_one_tile():
     assert plan.hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_n64"
     assert plan.hop_backward_kernel(1, ta.TA_VIN_O) == "mfma_bf16_bwd_n64"
     assert plan.hop_backward_kernel(2, ta.TA_VIN_O) == "mfma_bf16_bwd_n32"
-    assert ta.ta_plan_create(1, 32, 4, 128, (64, 4), ta.TA_BF16, True).hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_blocked"   # 8 heads per group
+    assert ta.ta_plan_create(1, 32, 4, 128, (64, 4), ta.TA_BF16, True).hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_n64"       # 8 heads per group: 4 per launch
+    assert ta.ta_plan_create(1, 24, 4, 128, (64, 4), ta.TA_BF16, True).hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_blocked"   # 6 heads per group
     assert ta.ta_plan_create(1, 8, 2, 128, (65, 4), ta.TA_BF16, True).hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_blocked"    # three tiles
     long_axis = ta.ta_plan_create(1, 8, 2, 128, (1024, 4), ta.TA_BF16, True)
     assert long_axis.hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_blocked"
