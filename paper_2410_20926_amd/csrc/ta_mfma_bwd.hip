@@ -258,17 +258,21 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
     const uint32_t dbytes = (uint32_t)p.D * 2;            // bytes of a row (less than the tile's when NARROW)
     const int r32 = lane & 31, hf = lane >> 5;
 
-    // ---- gather Q, K, X, G rows: every load is issued before the first wait ------------
+    // ---- gather Q, K, X, G rows: every load is issued before the first wait, in the order of first use
+    //      (loads complete in order: Q and K can be staged while X and G are still on their way) ------------
     u32x4 qraw[G::kPasses], kraw[G::kPasses], xraw[G::kPasses], graw[G::kPasses];
+    // Rows read by this wave alone are streamed; rows every wave of the group reads stay cached.
+#pragma unroll
+    for (int i = 0; i < G::kPasses; ++i) qraw[i] = load_chunk<NARROW, true>(qb, rowoff[i * G::kRowsPerPass + lrow].x, lbyte, dbytes);
+#pragma unroll
+    for (int i = 0; i < G::kPasses; ++i) kraw[i] = load_chunk<NARROW, false>(kb, rowoff[i * G::kRowsPerPass + lrow].y, lbyte, dbytes);
 #pragma unroll
     for (int i = 0; i < G::kPasses; ++i) {
-        const u32x4 off = rowoff[i * G::kRowsPerPass + lrow];
-        // Rows read by this wave alone are streamed; rows every wave of the group reads stay cached.
-        qraw[i] = load_chunk<NARROW, true>(qb, off.x, lbyte, dbytes);
-        kraw[i] = load_chunk<NARROW, false>(kb, off.y, lbyte, dbytes);
-        xraw[i] = vin_is_o ? load_chunk<NARROW, true>(xb, off.z, lbyte, dbytes) : load_chunk<NARROW, false>(xb, off.z, lbyte, dbytes);
-        graw[i] = load_chunk<NARROW, true>(gb, off.w, lbyte, dbytes);
+        const uint32_t off = rowoff[i * G::kRowsPerPass + lrow].z;
+        xraw[i] = vin_is_o ? load_chunk<NARROW, true>(xb, off, lbyte, dbytes) : load_chunk<NARROW, false>(xb, off, lbyte, dbytes);
     }
+#pragma unroll
+    for (int i = 0; i < G::kPasses; ++i) graw[i] = load_chunk<NARROW, true>(gb, rowoff[i * G::kRowsPerPass + lrow].w, lbyte, dbytes);
     __builtin_amdgcn_sched_barrier(0);
 
     // rotary encoding: Q and K rows are turned by their position on the axis before anything uses them;
