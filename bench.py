@@ -339,6 +339,32 @@ def main():
     roofline["copy_GBps"] = round(copy_gbs, 1)
     roofline["frac_of_copy"] = round(roofline["achieved"] / copy_gbs, 4)
 
+    # what the memory gives a kernel that only moves the roofline kernel's mix of reads and writes (a forward hop
+    # reads Q, K and its value input and writes O): the library's streaming kernel with the nearest mix it has,
+    # on about as many bytes as one launch of that kernel
+    dom = [h_ for h_ in roofline["per_hop"] if h_["kernel"] == roofline["kernel"]][0]
+    if dom["pass"] in ("fwd", "fwd2"):
+        hv = w.n_kv_heads if dom["hop"] == 0 else w.n_q_heads     # heads of the value input: V for the first hop, an O after it
+        reads, writes = w.n_q_heads + w.n_kv_heads + hv, w.n_q_heads
+        mixes = ((1, 1), (4, 3), (3, 2), (2, 1), (9, 4), (3, 1))
+        r_, w_ = min(mixes, key=lambda m: abs(m[0] / m[1] - reads / writes))
+        units = max(1, int(dom["algorithmic_bytes"] // ((r_ + w_) * 4096)))
+        src = torch.zeros(units * r_ * 4096, dtype=torch.uint8, device="cuda")
+        dst = torch.empty(units * w_ * 4096, dtype=torch.uint8, device="cuda")
+        mix_ms = []
+        for i in range(7):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            ta.ta_stream_mix(src, dst, units, r_, w_)
+            e1.record()
+            torch.cuda.synchronize()
+            if i >= 2:
+                mix_ms.append(e0.elapsed_time(e1))
+        del src, dst
+        mix_gbs = units * (r_ + w_) * 4096 / (sorted(mix_ms)[len(mix_ms) // 2] * 1e-3) / 1e9
+        roofline["stream_same_mix"] = {"reads_to_writes": f"{r_}:{w_}", "GBps": round(mix_gbs, 1),
+                                       "achieved_over_stream": round(roofline["achieved"] / mix_gbs, 4)}
+
     out = {
         "metric": "tensorized-attn tokens/s + per-hop HBM GB/s (% peak) at N=32k, 128k",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

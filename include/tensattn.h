@@ -271,6 +271,12 @@ ta_status_t ta_rope_apply(const ta_plan_t* plan, int which, int axis, float base
  *      from src to dst on `stream`, used to measure the achievable HBM ceiling and to
  *      calibrate hardware counters against a transfer of known size. ------------------- */
 ta_status_t ta_copy_bytes(const void* src, void* dst, size_t bytes, void* stream);
+/* The same with a mix of reads and writes: per unit of 4,096 bytes the kernel reads `reads` consecutive units
+ * of src and writes `writes` consecutive units of dst (src holds units * reads * 4096 bytes, dst units * writes
+ * * 4096), i.e. what the memory gives a kernel that only moves that mix of bytes - the attainable rate that a
+ * hop with the same read : write ratio is measured against.  Mixes 1:1, 3:2, 2:1, 9:4, 3:1, 4:3; any other
+ * -> TA_ERR_UNSUPPORTED. */
+ta_status_t ta_stream_mix(const void* src, void* dst, size_t units, int reads, int writes, void* stream);
 
 /* ---- errors and version ------------------------------------------------------------- */
 const char* ta_status_string(ta_status_t status);

@@ -654,6 +654,17 @@ ta_status_t ta_rope_apply(const ta_plan_t* pl, int which, int axis, float base, 
     return TA_OK;
 }
 
+ta_status_t ta_stream_mix(const void* src, void* dst, size_t units, int reads, int writes, void* stream) {
+    g_detail[0] = 0;
+    if (!src || !dst) return fail(TA_ERR_NULL, "src or dst is NULL");
+    if (!aligned16(src) || !aligned16(dst)) return fail(TA_ERR_INVALID_ARG, "stream mix needs 16-byte alignment");
+    if (units > ((size_t)1 << 40) / 4096 / 16) return fail(TA_ERR_INVALID_ARG, "too many units");
+    hipError_t e = ta::launch_stream_mix(src, dst, units, reads, writes, (hipStream_t)stream);
+    if (e == hipErrorInvalidValue) return fail(TA_ERR_UNSUPPORTED, "no streaming kernel for %d reads : %d writes (1:1, 3:2, 2:1, 9:4, 3:1, 4:3)", reads, writes);
+    if (e != hipSuccess) return fail(TA_ERR_DEVICE, "stream mix launch failed: %s", hipGetErrorString(e));
+    return TA_OK;
+}
+
 ta_status_t ta_copy_bytes(const void* src, void* dst, size_t bytes, void* stream) {
     g_detail[0] = 0;
     if (!src || !dst) return fail(TA_ERR_NULL, "src or dst is NULL");

@@ -483,6 +483,42 @@ __global__ __launch_bounds__(256) void copy_kernel(const u32x4* __restrict__ src
 }
 }  // namespace
 
+// A streaming kernel with a given mix of reads and writes: per unit of 4 KB (256 lanes of 16 bytes) it reads R
+// blocks and writes W blocks, all loads of a unit in flight together.  It shows what the memory gives a kernel that
+// does nothing but move that mix of bytes.
+namespace {
+template <int R, int W>
+__global__ __launch_bounds__(256) void stream_mix_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t units) {
+    for (size_t u = blockIdx.x; u < units; u += gridDim.x) {
+        u32x4 v[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) v[r] = __builtin_nontemporal_load(src + (u * R + r) * 256 + threadIdx.x);
+        u32x4 x = v[0];
+#pragma unroll
+        for (int r = 1; r < R; ++r) x ^= v[r];
+#pragma unroll
+        for (int w = 0; w < W; ++w) __builtin_nontemporal_store(x + (uint32_t)w, dst + (u * W + w) * 256 + threadIdx.x);
+    }
+}
+template <int R, int W>
+hipError_t launch_mix(const void* src, void* dst, size_t units, hipStream_t s) {
+    const unsigned blocks = (unsigned)(units < 256 * 16 ? units : 256 * 16);
+    hipLaunchKernelGGL((stream_mix_kernel<R, W>), dim3(blocks), dim3(256), 0, s, reinterpret_cast<const u32x4*>(src), reinterpret_cast<u32x4*>(dst), units);
+    return hipGetLastError();
+}
+}  // namespace
+
+hipError_t launch_stream_mix(const void* src, void* dst, size_t units, int reads, int writes, hipStream_t s) {
+    if (units == 0) return hipSuccess;
+    if (reads == 1 && writes == 1) return launch_mix<1, 1>(src, dst, units, s);
+    if (reads == 3 && writes == 2) return launch_mix<3, 2>(src, dst, units, s);
+    if (reads == 2 && writes == 1) return launch_mix<2, 1>(src, dst, units, s);
+    if (reads == 9 && writes == 4) return launch_mix<9, 4>(src, dst, units, s);
+    if (reads == 3 && writes == 1) return launch_mix<3, 1>(src, dst, units, s);
+    if (reads == 4 && writes == 3) return launch_mix<4, 3>(src, dst, units, s);
+    return hipErrorInvalidValue;
+}
+
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
     const size_t n16 = bytes / 16;
     if (n16 == 0) return hipSuccess;

@@ -117,5 +117,7 @@ hipError_t launch_rope(const RopeParams& rp, int dtype, hipStream_t s);
 // allowed once per device and kernel).  Remembers what it has set; callable from any thread.
 hipError_t allow_dynamic_lds(const void* kernel, int bytes);
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+// Streaming kernel that reads `reads` and writes `writes` blocks of 4 KB per unit; hipErrorInvalidValue for a mix it has no instantiation for.
+hipError_t launch_stream_mix(const void* src, void* dst, size_t units, int reads, int writes, hipStream_t s);
 
 }  // namespace ta

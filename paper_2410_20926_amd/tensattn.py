@@ -19,7 +19,7 @@ EXPORTS = [
     "ta_plan_create", "ta_plan_destroy", "ta_plan_seq_len", "ta_plan_axis_stride", "ta_plan_axis_fibres",
     "ta_plan_hop_axis", "ta_plan_hop_kernel", "ta_plan_hop_backward_kernel", "ta_plan_hop_bytes", "ta_plan_hop_flops",
     "ta_plan_workspace_bytes", "ta_plan_backward_scratch_bytes", "ta_axis_attn_forward",
-    "ta_axis_attn_backward", "ta_multihop_forward", "ta_multihop_backward", "ta_rope_apply", "ta_copy_bytes",
+    "ta_axis_attn_backward", "ta_multihop_forward", "ta_multihop_backward", "ta_rope_apply", "ta_copy_bytes", "ta_stream_mix",
     "ta_status_string", "ta_last_error_detail", "ta_version",
     "ta_axis_pair_attn_forward", "ta_plan_pair_kernel", "ta_plan_pair_bytes", "ta_plan_fused_position",
     "ta_multihop_forward_static",
@@ -107,6 +107,8 @@ def load_library():
     lib.ta_rope_apply.restype = i
     lib.ta_copy_bytes.argtypes = [vp, vp, sz, vp]
     lib.ta_copy_bytes.restype = i
+    lib.ta_stream_mix.argtypes = [vp, vp, sz, i, i, vp]
+    lib.ta_stream_mix.restype = i
     lib.ta_status_string.argtypes = [i]
     lib.ta_status_string.restype = C.c_char_p
     lib.ta_last_error_detail.argtypes = []
@@ -306,6 +308,10 @@ def ta_rope_apply(plan: Plan, which: int, axis: int, x, y, base: float = 0.0, in
 
 def ta_copy_bytes(src, dst, nbytes: int, stream=None) -> None:
     _check(load_library().ta_copy_bytes(_ptr(src), _ptr(dst), nbytes, _stream(stream)))
+
+
+def ta_stream_mix(src, dst, units: int, reads: int, writes: int, stream=None) -> None:
+    _check(load_library().ta_stream_mix(_ptr(src), _ptr(dst), units, reads, writes, _stream(stream)))
 
 
 def ta_version():

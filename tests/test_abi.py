@@ -205,6 +205,9 @@ def test_entry_points_reject_bad_arguments_without_launching():
     assert status(ta.ta_rope_apply, p, 1, 0, Q, O, -3.0, False, S) == "TA_ERR_INVALID_ARG"
     assert status(ta.ta_copy_bytes, Q, K, 24, S) == "TA_ERR_INVALID_ARG"
     assert status(ta.ta_copy_bytes, None, K, 32, S) == "TA_ERR_NULL"
+    assert status(ta.ta_stream_mix, Q, K, 4, 5, 3, S) == "TA_ERR_UNSUPPORTED"      # no kernel for that mix
+    assert status(ta.ta_stream_mix, None, K, 4, 1, 1, S) == "TA_ERR_NULL"
+    assert status(ta.ta_stream_mix, Q + 8, K, 4, 1, 1, S) == "TA_ERR_INVALID_ARG"
 
 
 def test_multihop_calls_validate_every_hop_before_the_first_launch():

@@ -103,3 +103,27 @@ def test_no_write_outside_outputs_workspace_and_scratch(dims, B, Hq, Hkv, D, dty
     for t_, name in ((g_dq.tensor(shp_q, tdt), "dq"), (g_dk.tensor(shp_kv, tdt), "dk"), (g_dv.tensor(shp_kv, tdt), "dv"),
                      (g_out.tensor(shp_q, tdt), "o")):
         assert bool(torch.isfinite(t_.float()).all()), f"{name} holds values the call did not write"
+
+
+@pytest.mark.parametrize("reads,writes", [(1, 1), (3, 2), (9, 4), (4, 3)])
+def test_measurement_kernels_move_what_they_say(reads, writes):
+    """The copy and the streaming kernel of the measurement aids: every byte they are meant to write is written
+    with the expected value, and nothing outside (they calibrate the traffic counters and give the attainable rate)."""
+    units = 37
+    g = torch.Generator(device="cuda").manual_seed(5)
+    src = torch.randint(0, 2 ** 31 - 1, (units * reads * 1024 + 8,), dtype=torch.int32, device="cuda", generator=g)
+    dst = torch.full((units * writes * 1024 + 8,), -7, dtype=torch.int32, device="cuda")
+    ta.ta_stream_mix(src[4:], dst[4:], units, reads, writes)
+    torch.cuda.synchronize()
+    x = src[4:4 + units * reads * 1024].view(units, reads, 1024)
+    acc = x[:, 0]
+    for r in range(1, reads):
+        acc = acc ^ x[:, r]
+    want = torch.stack([acc + w for w in range(writes)], dim=1).reshape(-1)
+    assert torch.equal(dst[4:4 + units * writes * 1024], want)
+    assert (dst[:4] == -7).all() and (dst[-4:] == -7).all()
+    if reads == 1 and writes == 1:
+        out = torch.full_like(src, -7)
+        ta.ta_copy_bytes(src[4:-4], out[4:-4], (src.numel() - 8) * 4)
+        torch.cuda.synchronize()
+        assert torch.equal(out[4:-4], src[4:-4]) and (out[:4] == -7).all() and (out[-4:] == -7).all()
