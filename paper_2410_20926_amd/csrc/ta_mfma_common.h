@@ -203,6 +203,51 @@ __device__ inline uint32_t table_column(const HopParams& p, uint32_t fibre, int 
     return col;
 }
 
+// One key tile of an online softmax.  st: the scores S^T of the tile (lane = query row, 16 of its keys, the other 16
+// in lane ^ 32); vis32: the keys of the tile this lane's row may attend (bit = key); sl2 = scale * log2(e) > 0.  Updates
+// the running maximum m (log2 domain) and sum l, returns the un-normalised weights, rounded to bf16, as B operands, and
+// the factor `corr` by which everything accumulated before this tile has to be multiplied.
+// The maximum is taken over the raw scores and scaled once, and the scale goes into the exponent's multiply-add; a tile
+// that every row of the wave sees completely (inside the causal triangle, no band, table or padding) skips the masking:
+// the kernels that walk many tiles spend a good part of their time in this vector arithmetic.
+__device__ inline void online_softmax_tile(const f32x16& st, uint32_t vis32, int hf, float sl2, float& m, float& l,
+                                           u32x4 (&pop)[2], float& corr) {
+    float e[16], tmax = -INFINITY;
+    if (__all(vis32 == 0xffffffffu)) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { e[r] = st[r]; tmax = fmaxf(tmax, e[r]); }
+    } else {
+        const uint32_t vis = vis32 >> (4 * hf);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const bool ok = (vis >> (8 * (r / 4) + (r % 4))) & 1u;
+            e[r] = ok ? st[r] : -INFINITY;
+            tmax = fmaxf(tmax, e[r]);
+        }
+    }
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    if (tmax != -INFINITY) tmax *= sl2;
+    const float mnew = fmaxf(m, tmax);
+    const float msafe = mnew == -INFINITY ? 0.f : mnew;
+    corr = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - msafe);
+    m = mnew;
+    float psum = 0.f;
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+        uint32_t wds[4];
+#pragma unroll
+        for (int jp = 0; jp < 4; ++jp) {
+            const int r = 8 * s2 + 2 * jp;
+            const uint32_t pk = pack_bf16x2(__builtin_amdgcn_exp2f(fmaf(e[r], sl2, -msafe)), __builtin_amdgcn_exp2f(fmaf(e[r + 1], sl2, -msafe)));
+            psum += bf16_lo(pk) + bf16_hi(pk);            // sum of the ROUNDED weights
+            wds[jp] = pk;
+        }
+        pop[s2] = u32x4{wds[0], wds[1], wds[2], wds[3]};
+    }
+    psum += __shfl_xor(psum, 32);
+    l = l * corr + psum;
+}
+
 // Launch geometry computed on the host.
 struct TileParams {
     int32_t fpt;          // fibres per 32-row tile (n <= 32), else 1

@@ -140,35 +140,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
 
         // ---- mask, running max and sum ------------------------------------------------------
         const uint32_t tw = qrow < nreal ? table_word(p, f, qrow, j) : 0u;
-        const uint32_t vis = (range_mask(min(max(klo - kTile * j, 0), kTile), min(max(khi - kTile * j, 0), kTile)) & tw) >> (4 * hf);
-        float e[16], tmax = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const bool ok = (vis >> (8 * (r / 4) + (r % 4))) & 1u;
-            e[r] = ok ? st[r] * sl2 : -INFINITY;
-            tmax = fmaxf(tmax, e[r]);
-        }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float mnew = fmaxf(m, tmax);
-        const float msafe = mnew == -INFINITY ? 0.f : mnew;
-        const float corr = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - msafe);
-        m = mnew;
+        const uint32_t vis32 = range_mask(min(max(klo - kTile * j, 0), kTile), min(max(khi - kTile * j, 0), kTile)) & tw;
         u32x4 pop[2];
-        float psum = 0.f;
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-            uint32_t wds[4];
-#pragma unroll
-            for (int jp = 0; jp < 4; ++jp) {
-                const int r = 8 * s2 + 2 * jp;
-                const uint32_t pk = pack_bf16x2(__builtin_amdgcn_exp2f(e[r] - msafe), __builtin_amdgcn_exp2f(e[r + 1] - msafe));
-                psum += bf16_lo(pk) + bf16_hi(pk);        // sum of the ROUNDED weights
-                wds[jp] = pk;
-            }
-            pop[s2] = u32x4{wds[0], wds[1], wds[2], wds[3]};
-        }
-        psum += __shfl_xor(psum, 32);
-        l = l * corr + psum;
+        float corr;
+        online_softmax_tile(st, vis32, hf, sl2, m, l, pop, corr);
 
         // ---- V tile j: LDS transit, transposed operands, then request tile j + 1 ------------
         u32x4 vT[G::kDTiles][2];
@@ -359,35 +334,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
         for (int s = 0; s < G::kKSteps; ++s) st = mma(kop[s], qop[s], st);
 
         const uint32_t tw = qrow < nreal ? table_word(p, f, qrow, j) : 0u;
-        const uint32_t vis = (range_mask(min(max(klo - kTile * j, 0), kTile), min(max(khi - kTile * j, 0), kTile)) & tw) >> (4 * hf);
-        float e[16], tmax = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const bool ok = (vis >> (8 * (r / 4) + (r % 4))) & 1u;
-            e[r] = ok ? st[r] * sl2 : -INFINITY;
-            tmax = fmaxf(tmax, e[r]);
-        }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float mnew = fmaxf(m, tmax);
-        const float msafe = mnew == -INFINITY ? 0.f : mnew;
-        const float corr = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - msafe);
-        m = mnew;
+        const uint32_t vis32 = range_mask(min(max(klo - kTile * j, 0), kTile), min(max(khi - kTile * j, 0), kTile)) & tw;
         u32x4 pop[2];
-        float psum = 0.f;
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-            uint32_t wds[4];
-#pragma unroll
-            for (int jp = 0; jp < 4; ++jp) {
-                const int r = 8 * s2 + 2 * jp;
-                const uint32_t pk = pack_bf16x2(__builtin_amdgcn_exp2f(e[r] - msafe), __builtin_amdgcn_exp2f(e[r + 1] - msafe));
-                psum += bf16_lo(pk) + bf16_hi(pk);        // sum of the ROUNDED weights
-                wds[jp] = pk;
-            }
-            pop[s2] = u32x4{wds[0], wds[1], wds[2], wds[3]};
-        }
-        psum += __shfl_xor(psum, 32);
-        l = l * corr + psum;
+        float corr;
+        online_softmax_tile(st, vis32, hf, sl2, m, l, pop, corr);
 
         u32x4 vT[G::kDTiles][2];
         if constexpr (VS) {
@@ -613,35 +563,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunke
         for (int s = 0; s < G::kKSteps; ++s) st = mma(kop[s], qop[s], st);
 
         const uint32_t tw = qrow < nreal ? table_word(p, f, qrow, j) : 0u;
-        const uint32_t vis = (range_mask(min(max(klo - kTile * j, 0), kTile), min(max(khi - kTile * j, 0), kTile)) & tw) >> (4 * hf);
-        float e[16], tmax = -INFINITY;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const bool ok = (vis >> (8 * (r / 4) + (r % 4))) & 1u;
-            e[r] = ok ? st[r] * sl2 : -INFINITY;
-            tmax = fmaxf(tmax, e[r]);
-        }
-        tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-        const float mnew = fmaxf(m, tmax);
-        const float msafe = mnew == -INFINITY ? 0.f : mnew;
-        const float corr = m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - msafe);
-        m = mnew;
+        const uint32_t vis32 = range_mask(min(max(klo - kTile * j, 0), kTile), min(max(khi - kTile * j, 0), kTile)) & tw;
         u32x4 pop[2];
-        float psum = 0.f;
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-            uint32_t wds[4];
-#pragma unroll
-            for (int jp = 0; jp < 4; ++jp) {
-                const int r = 8 * s2 + 2 * jp;
-                const uint32_t pk = pack_bf16x2(__builtin_amdgcn_exp2f(e[r] - msafe), __builtin_amdgcn_exp2f(e[r + 1] - msafe));
-                psum += bf16_lo(pk) + bf16_hi(pk);        // sum of the ROUNDED weights
-                wds[jp] = pk;
-            }
-            pop[s2] = u32x4{wds[0], wds[1], wds[2], wds[3]};
-        }
-        psum += __shfl_xor(psum, 32);
-        l = l * corr + psum;
+        float corr;
+        online_softmax_tile(st, vis32, hf, sl2, m, l, pop, corr);
 
         // the next step (if any): needed below for the per-head value tile and for the end of this query tile
         Cursor nxt = cur;
