@@ -1159,9 +1159,12 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
     const auto enc = unrope(&p, [&](int r) { return (float)(kTile * t + r); });
     {
         u32x4 oldk[G::kDTiles * 2] = {};
-        const bool last = hl == GH - 1;                   // the wave that ends up with the group's sum
+        // the sum runs up the heads for tile 0 and down for tile 1, so that the two waves that end up with a
+        // sum, and store it, are not the two waves of one head
+        const int hc = t ? GH - 1 - hl : hl;
+        const bool last = hc == GH - 1;                   // the wave that ends up with the group's sum
         if (bp.acc_k && last) prefetch_tile<D>(oldk, rowoff, 1, dkb, lane);
-        if (GH > 1) chain_sum<D>(acc, red, hl, GH, lane);
+        if (GH > 1) chain_sum<D>(acc, red, hc, GH, lane);
         if (last) store_tile<D, false>(acc, p.scale, buf, rowoff, 1, dkb, oldk, bp.acc_k != 0, rows_t, lane, 0, enc);
     }
     // ---- dQ_t^T = sum_c K_c^T dS^T_tc ------------------------------------------------------------------------
@@ -1203,9 +1206,10 @@ __global__ __launch_bounds__(128 * GH, 2) void mfma_bwd2_kernel(BwdParams bp, St
         store_tile_plain<D>(acc, 1.f, buf, rowoff, 2, dxb, rows_t, lane);
     } else {
         u32x4 oldx[G::kDTiles * 2] = {};                  // the sum of the group's earlier launches
-        if (bp.acc_x && hl == GH - 1) prefetch_tile<D>(oldx, rowoff, 2, dxb, lane);
-        if (GH > 1) chain_sum<D>(acc, red, hl, GH, lane);
-        if (hl == GH - 1) store_tile<D, false>(acc, 1.f, buf, rowoff, 2, dxb, oldx, bp.acc_x != 0, rows_t, lane);
+        const int hc = t ? GH - 1 - hl : hl;
+        if (bp.acc_x && hc == GH - 1) prefetch_tile<D>(oldx, rowoff, 2, dxb, lane);
+        if (GH > 1) chain_sum<D>(acc, red, hc, GH, lane);
+        if (hc == GH - 1) store_tile<D, false>(acc, 1.f, buf, rowoff, 2, dxb, oldx, bp.acc_x != 0, rows_t, lane);
     }
 }
 
