@@ -136,6 +136,29 @@ def test_config5_shape_all_groups():
     print(f"config 5: largest error / tolerance over all groups {worst:.3f}")
 
 
+def test_training_step_at_131072_tokens_three_groups():
+    """32/8 heads, D=128, 64x64x32 causal, forward + backward at full size: the two-tile backward on both 64-long
+    axes (once as the hop that emits dV), the one-tile backward on the innermost one; key/value groups 0, 3 and 7,
+    every element."""
+    w = WORKLOADS["c4_train"]
+    q, k, v, d_o = make_workload_inputs(w)
+    _, plan, dev = multihop_forward(q, k, v, w.dims, w.dtype, w.causal, save=True)
+    assert plan.hop_backward_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_bwd_n64"
+    assert plan.hop_backward_kernel(1, ta.TA_VIN_O) == "mfma_bf16_bwd_n64"
+    assert plan.hop_backward_kernel(2, ta.TA_VIN_O) == "mfma_bf16_bwd_n32"
+    dq, dk, dv = multihop_backward(plan, dev, d_o, w.dtype)
+    assert np.isfinite(dq).all() and np.isfinite(dk).all() and np.isfinite(dv).all()
+    G = w.n_q_heads // w.n_kv_heads
+    worst = 0.0
+    for g in (0, 3, 7):
+        hs = slice(g * G, (g + 1) * G)
+        ref, tol = backward_reference_and_tolerance(q[:, :, hs], k[:, :, g:g + 1], v[:, :, g:g + 1], d_o[:, :, hs],
+                                                    w.dims, w.causal, w.dtype)
+        for got, r_, t_, name in zip((dq[:, :, hs], dk[:, :, g:g + 1], dv[:, :, g:g + 1]), ref, tol, ("dq", "dk", "dv")):
+            worst = max(worst, check_gradient(got, r_, t_, f"{name} group {g}"))
+    print(f"64x64x32 training step: largest error / tolerance over three groups {worst:.3f}")
+
+
 def test_backward_is_deterministic_and_leaves_inputs_alone():
     """No atomics anywhere: two runs give bit-identical gradients; q, k, v, dO are untouched."""
     dims, B, Hq, Hkv, D = (8, 32, 16), 1, 8, 2, 128
