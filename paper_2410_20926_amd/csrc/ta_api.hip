@@ -89,6 +89,8 @@ bool strides_ok(const int64_t s[3], int64_t B, int64_t N, int64_t H, int64_t D) 
     int64_t ex[3] = {B, N, H};
     for (int i = 0; i < 3; ++i)
         if (st[i] <= 0 || (st[i] % (D % 8 == 0 ? 8 : D % 4 == 0 ? 4 : 2)) != 0) return false;
+    for (int i = 0; i < 3; ++i)                           // the tensor's span in elements stays far below 2^63
+        if (st[i] > ((int64_t)1 << 56) / ex[i]) return false;
     for (int i = 0; i < 3; ++i)
         for (int j = i + 1; j < 3; ++j)
             if (st[j] < st[i]) { int64_t t = st[i]; st[i] = st[j]; st[j] = t; t = ex[i]; ex[i] = ex[j]; ex[j] = t; }

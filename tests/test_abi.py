@@ -167,6 +167,17 @@ def test_strided_layouts_accepted():
     assert p.seq_len() == 12
 
 
+def test_strides_whose_span_would_overflow_are_refused():
+    """A stride so large that (extent - 1) * stride leaves the 64-bit range is a shape error, not an
+    address wrap in the alias checks."""
+    huge = (1 << 60, 64, 8 * 64)
+    with pytest.raises(ta.TaError) as ei:
+        ta.ta_plan_create(16, 8, 8, 64, (4, 4), ta.TA_BF16, True, q_strides=huge)
+    assert ei.value.name == "TA_ERR_SHAPE"
+    ok = (1 << 40, 8 * 64, 64)
+    assert ta.ta_plan_create(16, 8, 8, 64, (4, 4), ta.TA_BF16, True, q_strides=ok).seq_len() == 16
+
+
 def test_entry_points_reject_bad_arguments_without_launching():
     """All of these return before any HIP call, so they run without a GPU.  The
     addresses are fabricated and never dereferenced."""
