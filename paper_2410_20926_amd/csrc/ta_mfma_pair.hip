@@ -102,20 +102,23 @@ __device__ inline void softmax_tile(const f32x16& st, int r32, int hf, int causa
     }
     mx = fmaxf(mx, __shfl_xor(mx, 32));
     if (mx == -INFINITY) mx = 0.f;
-    float sum = 0.f;
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2) {
         uint32_t wds[4];
 #pragma unroll
         for (int jp = 0; jp < 4; ++jp) {
             const int r = 8 * s2 + 2 * jp;
-            const uint32_t pk = pack_bf16x2(__builtin_amdgcn_exp2f(e[r] - mx), __builtin_amdgcn_exp2f(e[r + 1] - mx));
-            sum += bf16_lo(pk) + bf16_hi(pk);             // sum of the ROUNDED weights
-            wds[jp] = pk;
+            wds[jp] = pack_bf16x2(__builtin_amdgcn_exp2f(e[r] - mx), __builtin_amdgcn_exp2f(e[r + 1] - mx));
         }
         pop[s2] = u32x4{wds[0], wds[1], wds[2], wds[3]};
     }
-    sum += __shfl_xor(sum, 32);
+    // The sum of the ROUNDED weights of a row comes from the matrix unit, which is idle here: a tile of ones times the
+    // weights puts the sum over all 32 keys of query row r32 into every accumulator of the lane.
+    const uint32_t ones = 0x3f803f80u;
+    f32x16 rs = {};
+    rs = mma(u32x4{ones, ones, ones, ones}, pop[0], rs);
+    rs = mma(u32x4{ones, ones, ones, ones}, pop[1], rs);
+    const float sum = rs[0];
     inv = sum > 0.f ? 1.f / sum : 0.f;
 }
 
