@@ -331,6 +331,41 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
     };
     static_assert(kD == 4 * kCA || kD == 2 * kCA, "one or two 128-byte lines per row");
     write_chunk(q0);                                      // chunk 0
+    if constexpr (ROPE && kD == 4 * kCA && !NARROW) {
+        // With the encoding the score steps need a dozen registers more, and the requests below, as many as the plain kernel
+        // keeps in flight, no longer fit: the compiler spilled three of them as they were issued and waited for every load
+        // in flight to do so, three times per slab.  Here the halves of Q's second line are requested separately, 16 to 32
+        // registers at a time; the second halves find their lines in L2 (the first are not marked as last use).
+        auto load_half = [&](u32x4 (&dst)[8], int half, int pp_begin, int pp_end) {
+#pragma unroll
+            for (int pp = pp_begin; pp < pp_end; ++pp) {
+                const u32x4* src = reinterpret_cast<const u32x4*>(qb + (size_t)(16u * pp) * p.q_row + 128 + 64 * half + qoff);
+                dst[pp] = half ? __builtin_nontemporal_load(src) : *src;
+            }
+        };
+        __builtin_amdgcn_sched_barrier(0);
+        load_k(1);
+        load_half(r0, 0, 0, 4);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        scores(0);
+        __syncthreads();
+        write_chunk(q1);                                  // chunk 1
+        load_k(2);
+        load_half(r0, 0, 4, 8);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        scores(1);
+        __syncthreads();
+        write_chunk(r0);                                  // chunk 2
+        load_k(3);
+        load_half(r1, 1, 0, 8);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        scores(2);
+        __syncthreads();
+        write_chunk(r1);                                  // chunk 3
+    } else {
     load_k(1);
     if (kD == 4 * kCA) load_q(r0, r1, 1, 0, 4);
     __builtin_amdgcn_sched_barrier(0);
@@ -352,6 +387,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
         scores(2);
         __syncthreads();
         write_chunk(r1);                                  // chunk 3
+    }
     }
 
     // value rows of the first phase-B chunk (8 lanes per row (unit ub), 8 rows per pass, 16 passes):
