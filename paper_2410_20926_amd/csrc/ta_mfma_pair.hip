@@ -334,32 +334,27 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
     if constexpr (ROPE && kD == 4 * kCA && !NARROW) {
         // With the encoding the score steps need a dozen registers more, and the requests below, as many as the plain kernel
         // keeps in flight, no longer fit: the compiler spilled three of them as they were issued and waited for every load
-        // in flight to do so, three times per slab.  Here the halves of Q's second line are requested separately, 16 to 32
-        // registers at a time; the second halves find their lines in L2 (the first are not marked as last use).
-        auto load_half = [&](u32x4 (&dst)[8], int half, int pp_begin, int pp_end) {
-#pragma unroll
-            for (int pp = pp_begin; pp < pp_end; ++pp) {
-                const u32x4* src = reinterpret_cast<const u32x4*>(qb + (size_t)(16u * pp) * p.q_row + 128 + 64 * half + qoff);
-                dst[pp] = half ? __builtin_nontemporal_load(src) : *src;
-            }
-        };
+        // in flight to do so, three times per slab.  Here at most 80 registers of requests are in flight during a score
+        // step: Q's second line comes two passes early and six late (both halves of a line still together: requested
+        // apart, the second half found its line gone from L2 and fetched it again), and the third K chunk, an L2 hit, is
+        // requested only after the second score step.
         __builtin_amdgcn_sched_barrier(0);
         load_k(1);
-        load_half(r0, 0, 0, 4);
+        load_q(r0, r1, 1, 0, 2);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         scores(0);
         __syncthreads();
         write_chunk(q1);                                  // chunk 1
-        load_k(2);
-        load_half(r0, 0, 4, 8);
+        load_q(r0, r1, 1, 2, 8);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         scores(1);
+        load_k(2);
+        __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         write_chunk(r0);                                  // chunk 2
         load_k(3);
-        load_half(r1, 1, 0, 8);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         scores(2);
