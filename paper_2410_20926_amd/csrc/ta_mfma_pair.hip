@@ -331,8 +331,8 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
     };
     static_assert(kD == 4 * kCA || kD == 2 * kCA, "one or two 128-byte lines per row");
     write_chunk(q0);                                      // chunk 0
-    if constexpr (ROPE && kD == 4 * kCA && !NARROW) {
-        // With the encoding the score steps need a dozen registers more, and the requests below, as many as the plain kernel
+    if constexpr ((ROPE || NARROW) && kD == 4 * kCA) {
+        // With the encoding (or narrow rows, read in 8-byte pieces) the score steps need a dozen registers more, and the requests below, as many as the plain kernel
         // keeps in flight, no longer fit: the compiler spilled three of them as they were issued and waited for every load
         // in flight to do so, three times per slab.  Here at most 80 registers of requests are in flight during a score
         // step: Q's second line comes two passes early and six late (both halves of a line still together: requested
