@@ -364,6 +364,31 @@ def main():
         mix_gbs = units * (r_ + w_) * 4096 / (sorted(mix_ms)[len(mix_ms) // 2] * 1e-3) / 1e9
         roofline["stream_same_mix"] = {"reads_to_writes": f"{r_}:{w_}", "GBps": round(mix_gbs, 1),
                                        "achieved_over_stream": round(roofline["achieved"] / mix_gbs, 4)}
+    # The fused pair moves its bytes in a pattern that LDS capacity dictates (128-byte lines of one head's rows at the
+    # token pitch, the four heads of a group on four workgroups): the same traffic without the arithmetic, and for
+    # comparison with 1 KB of a token's head group at a time (the pattern of the single-hop kernels).
+    if roofline["kernel"] == "mfma_bf16_pair_n32" and w.head_dim == 128 and w.seq_len % 1024 == 0:
+        T = w.batch * w.seq_len
+        bufs = [(torch.zeros(T * w.n_q_heads * 128, dtype=torch.int16, device="cuda"), torch.zeros(T * w.n_kv_heads * 128, dtype=torch.int16, device="cuda"),
+                 torch.zeros(T * w.n_q_heads * 128, dtype=torch.int16, device="cuda"), torch.empty(T * w.n_q_heads * 128, dtype=torch.int16, device="cuda"))
+                for _ in range(2)]
+        rates = {}
+        for granule in (1, 3):
+            ms = []
+            for i in range(8):
+                q_, k_, x_, o_ = bufs[i % 2]
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                ta.ta_stream_slabs(q_, k_, x_, o_, T, w.n_q_heads, w.n_kv_heads, granule)
+                e1.record()
+                torch.cuda.synchronize()
+                if i >= 2:
+                    ms.append(e0.elapsed_time(e1))
+            rates[granule] = dom["algorithmic_bytes"] / (sorted(ms)[len(ms) // 2] * 1e-3) / 1e9
+        del bufs
+        roofline["stream_same_pattern"] = {"GBps": round(rates[1], 1), "achieved_over_stream": round(roofline["achieved"] / rates[1], 4),
+                                           "pattern": "128-byte lines of one head's rows, one workgroup per (1,024-token slab, head)",
+                                           "GBps_with_1KB_head_groups": round(rates[3], 1)}
 
     out = {
         "metric": "tensorized-attn tokens/s + per-hop HBM GB/s (% peak) at N=32k, 128k",

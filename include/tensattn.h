@@ -277,6 +277,19 @@ ta_status_t ta_copy_bytes(const void* src, void* dst, size_t bytes, void* stream
  * hop with the same read : write ratio is measured against.  Mixes 1:1, 3:2, 2:1, 9:4, 3:1, 4:3; any other
  * -> TA_ERR_UNSUPPORTED. */
 ta_status_t ta_stream_mix(const void* src, void* dst, size_t units, int reads, int writes, void* stream);
+/* The bytes of one pass of the fused pair (ta_axis_pair_attn_forward) in the pair's own access pattern and
+ * nothing else: dense token-major tensors q, x, o [tokens, n_q_heads, 128] and k [tokens, n_kv_heads, 128] of
+ * 2-byte elements (256-byte rows), tokens a multiple of 1,024.  One workgroup per (slab of 1,024 consecutive
+ * tokens, query head), the heads of a key/value head on workgroups that run side by side, reads the slab's Q,
+ * K (of its key/value head) and X rows and writes its O rows (o = x when q and k hold zeros), in pieces of
+ *   granule = 1: one 128-byte line of a row at a time, every row of the slab, then the other line (what the
+ *                pair does: its chunks of LDS hold half a row of every token);
+ *   granule = 2: whole 256-byte rows;
+ *   granule = 3: one workgroup per (slab, key/value head) moves the 1 KB of a token's whole head group at once.
+ * It shows what the memory gives for that pattern: the rate the pair is measured against.  Other values of
+ * granule, tokens not a multiple of 1,024, n_q_heads not a multiple of n_kv_heads -> TA_ERR_INVALID_ARG. */
+ta_status_t ta_stream_slabs(const void* q, const void* k, const void* x, void* o, int64_t tokens, int n_q_heads,
+                            int n_kv_heads, int granule, void* stream);
 
 /* ---- errors and version ------------------------------------------------------------- */
 const char* ta_status_string(ta_status_t status);

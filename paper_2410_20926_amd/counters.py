@@ -101,7 +101,7 @@ def summarise(wl: str, raw: str, out_dir: str) -> str:
         scale = (1 << 30) / (sum(copy) / len(copy))
         out.append(f"  copy_kernel on 1 GiB: {sum(copy) / len(copy) / 1e6:.1f} MB on this counter -> scale {scale:.3f}")
         for k, d in per.items():
-            if k == "copy_kernel" or k.startswith("stream_mix_kernel"):      # the measurement aids
+            if k == "copy_kernel" or k.startswith("stream_mix_kernel") or k.startswith("stream_slab"):      # the measurement aids
                 continue
             v = [x * 1024 * scale for x in d[c]]
             uniq = []
@@ -117,7 +117,7 @@ def summarise(wl: str, raw: str, out_dir: str) -> str:
         for i in (1, 2):
             out.append("command: " + cmds[2 + i])
             for k, d in counter_rows(f"{raw}/sq_{wl}_{i}/{wl}_counter_collection.csv").items():
-                if k != "copy_kernel" and not k.startswith("stream_mix_kernel"):
+                if k != "copy_kernel" and not k.startswith("stream_mix_kernel") and not k.startswith("stream_slab"):
                     for c, v in d.items():
                         vals[k][c] = sum(v) / len(v)
         for k, v in vals.items():

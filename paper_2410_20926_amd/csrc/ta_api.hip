@@ -252,7 +252,7 @@ const char* ta_last_error_detail(void) { return g_detail; }
 
 void ta_version(int* major, int* minor) {
     if (major) *major = 0;
-    if (minor) *minor = 6;
+    if (minor) *minor = 7;
 }
 
 ta_status_t ta_plan_create(const ta_desc_t* d, ta_plan_t** out) {
@@ -664,6 +664,21 @@ ta_status_t ta_stream_mix(const void* src, void* dst, size_t units, int reads, i
     hipError_t e = ta::launch_stream_mix(src, dst, units, reads, writes, (hipStream_t)stream);
     if (e == hipErrorInvalidValue) return fail(TA_ERR_UNSUPPORTED, "no streaming kernel for %d reads : %d writes (1:1, 3:2, 2:1, 9:4, 3:1, 4:3)", reads, writes);
     if (e != hipSuccess) return fail(TA_ERR_DEVICE, "stream mix launch failed: %s", hipGetErrorString(e));
+    return TA_OK;
+}
+
+ta_status_t ta_stream_slabs(const void* q, const void* k, const void* x, void* o, int64_t tokens, int n_q_heads,
+                            int n_kv_heads, int granule, void* stream) {
+    g_detail[0] = 0;
+    if (!q || !k || !x || !o) return fail(TA_ERR_NULL, "q, k, x or o is NULL");
+    if (!aligned16(q) || !aligned16(k) || !aligned16(x) || !aligned16(o)) return fail(TA_ERR_INVALID_ARG, "slab streaming needs 16-byte alignment");
+    if (tokens < 0 || tokens % 1024 != 0 || tokens > ((int64_t)1 << 32)) return fail(TA_ERR_INVALID_ARG, "tokens must be a multiple of 1024, at most 2^32");
+    if (n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads != 0 || n_q_heads > 1024)
+        return fail(TA_ERR_INVALID_ARG, "head counts: 1 <= n_kv_heads, n_q_heads a multiple of it, at most 1024");
+    if (granule < 1 || granule > 3) return fail(TA_ERR_INVALID_ARG, "granule must be 1, 2 or 3");
+    hipError_t e = ta::launch_stream_slabs(q, k, x, o, tokens, n_q_heads, n_kv_heads, granule, (hipStream_t)stream);
+    if (e == hipErrorInvalidValue) return fail(TA_ERR_INVALID_ARG, "too many slabs for one launch");
+    if (e != hipSuccess) return fail(TA_ERR_DEVICE, "slab streaming launch failed: %s", hipGetErrorString(e));
     return TA_OK;
 }
 

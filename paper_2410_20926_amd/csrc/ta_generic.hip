@@ -519,6 +519,134 @@ hipError_t launch_stream_mix(const void* src, void* dst, size_t units, int reads
     return hipErrorInvalidValue;
 }
 
+// The fused pair's traffic in the pair's access pattern, without its arithmetic (see ta_stream_slabs in the header).
+namespace {
+constexpr int kSlabTokens = 1024;
+constexpr int kRowBytes = 256;
+
+// One workgroup of 256 lanes per (slab, query head); workgroup ids as in the pair kernel: the heads of a key/value
+// head are 8 ids apart.  PIECE = 128: 8 lanes per row, a line of every row, then the other line; 256: 16 lanes per row.
+template <int PIECE>
+__global__ __launch_bounds__(256) void stream_slab_kernel(const char* __restrict__ q, const char* __restrict__ k, const char* __restrict__ x,
+                                                          char* __restrict__ o, uint32_t groups, int Hq, int Hkv) {
+    const int G = Hq / Hkv;
+    const uint32_t span = 8u * (uint32_t)G;
+    const uint32_t blk = blockIdx.x / span, rem = blockIdx.x - blk * span;
+    const uint32_t hg = rem >> 3, gi = blk * 8u + (rem & 7u);
+    if (gi >= groups) return;
+    const uint32_t g = gi % (uint32_t)Hkv, sl = gi / (uint32_t)Hkv, h = g * (uint32_t)G + hg;
+    const size_t qp = (size_t)Hq * kRowBytes, kp = (size_t)Hkv * kRowBytes;
+    const char* qb = q + (size_t)sl * kSlabTokens * qp + (size_t)h * kRowBytes;
+    const char* kb = k + (size_t)sl * kSlabTokens * kp + (size_t)g * kRowBytes;
+    const char* xb = x + (size_t)sl * kSlabTokens * qp + (size_t)h * kRowBytes;
+    char* ob = o + (size_t)sl * kSlabTokens * qp + (size_t)h * kRowBytes;
+    constexpr int kLanes = PIECE / 16, kRows = 256 / kLanes, kPieces = kRowBytes / PIECE;
+    const int lane = (int)threadIdx.x % kLanes, row0 = (int)threadIdx.x / kLanes;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (int piece = 0; piece < kPieces; ++piece)
+        for (int r = row0; r < kSlabTokens; r += 4 * kRows) {
+            u32x4 v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (size_t)(r + kRows * j) * qp + piece * PIECE + lane * 16));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc ^= v[j];
+        }
+    for (int piece = 0; piece < kPieces; ++piece)
+        for (int r = row0; r < kSlabTokens; r += 4 * kRows) {
+            u32x4 v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = *reinterpret_cast<const u32x4*>(kb + (size_t)(r + kRows * j) * kp + piece * PIECE + lane * 16);   // shared with the group's other heads through L2
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc ^= v[j];
+        }
+    // a value that is zero whenever q and k are: the loads above cannot be dropped, and o = x then
+    const uint32_t fold = acc.x | acc.y | acc.z | acc.w;
+    for (int piece = 0; piece < kPieces; ++piece)
+        for (int r = row0; r < kSlabTokens; r += 4 * kRows) {
+            u32x4 v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xb + (size_t)(r + kRows * j) * qp + piece * PIECE + lane * 16));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) __builtin_nontemporal_store(v[j] ^ fold, reinterpret_cast<u32x4*>(ob + (size_t)(r + kRows * j) * qp + piece * PIECE + lane * 16));
+        }
+}
+
+// One workgroup per (slab, key/value head): the whole head group of a token, G * 256 bytes, at once; K once.
+__global__ __launch_bounds__(256) void stream_slab_group_kernel(const char* __restrict__ q, const char* __restrict__ k, const char* __restrict__ x,
+                                                                char* __restrict__ o, uint32_t groups, int Hq, int Hkv) {
+    const uint32_t gi = blockIdx.x;
+    if (gi >= groups) return;
+    const int G = Hq / Hkv;
+    const uint32_t g = gi % (uint32_t)Hkv, sl = gi / (uint32_t)Hkv;
+    const size_t qp = (size_t)Hq * kRowBytes, kp = (size_t)Hkv * kRowBytes;
+    const size_t gbytes = (size_t)G * kRowBytes;          // bytes of a token's head group
+    const char* qb = q + (size_t)sl * kSlabTokens * qp + g * gbytes;
+    const char* kb = k + (size_t)sl * kSlabTokens * kp + (size_t)g * kRowBytes;
+    const char* xb = x + (size_t)sl * kSlabTokens * qp + g * gbytes;
+    char* ob = o + (size_t)sl * kSlabTokens * qp + g * gbytes;
+    const uint32_t per_tok = (uint32_t)(gbytes / 16);       // 16-byte units of a token's head group
+    const uint32_t units = (uint32_t)kSlabTokens * per_tok;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    if (256u % per_tok == 0u) {
+        // the usual group sizes (1, 2, 4, 8, 16 heads): a pass of the 256 lanes covers 256 / per_tok whole tokens, eight
+        // passes are in flight per lane
+        const uint32_t step = 256u / per_tok;
+        const uint32_t tok0 = threadIdx.x / per_tok, off = (threadIdx.x % per_tok) * 16u;
+        for (uint32_t r = tok0; r < (uint32_t)kSlabTokens; r += 8 * step) {
+            u32x4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (size_t)(r + j * step) * qp + off));
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc ^= v[j];
+        }
+        for (int r = (int)threadIdx.x / 16; r < kSlabTokens; r += 4 * 16) {
+            u32x4 v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + (size_t)(r + 16 * j) * kp + ((int)threadIdx.x % 16) * 16));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc ^= v[j];
+        }
+        const uint32_t fold = acc.x | acc.y | acc.z | acc.w;
+        for (uint32_t r = tok0; r < (uint32_t)kSlabTokens; r += 8 * step) {
+            u32x4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xb + (size_t)(r + j * step) * qp + off));
+#pragma unroll
+            for (int j = 0; j < 8; ++j) __builtin_nontemporal_store(v[j] ^ fold, reinterpret_cast<u32x4*>(ob + (size_t)(r + j * step) * qp + off));
+        }
+        return;
+    }
+    // any other group size: unit u = (token, unit within the group), one unit per lane and trip
+    for (uint32_t u = threadIdx.x; u < units; u += 256)
+        acc ^= __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(qb + (size_t)(u / per_tok) * qp + (u % per_tok) * 16));
+    for (int r = (int)threadIdx.x / 16; r < kSlabTokens; r += 16)
+        acc ^= __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb + (size_t)r * kp + ((int)threadIdx.x % 16) * 16));
+    const uint32_t fold = acc.x | acc.y | acc.z | acc.w;
+    for (uint32_t u = threadIdx.x; u < units; u += 256) {
+        const size_t at = (size_t)(u / per_tok) * qp + (u % per_tok) * 16;
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xb + at));
+        __builtin_nontemporal_store(v ^ fold, reinterpret_cast<u32x4*>(ob + at));
+    }
+}
+}  // namespace
+
+hipError_t launch_stream_slabs(const void* q, const void* k, const void* x, void* o, int64_t tokens, int Hq, int Hkv, int granule, hipStream_t s) {
+    if (tokens == 0) return hipSuccess;
+    const int64_t groups = tokens / kSlabTokens * Hkv;
+    const int G = Hq / Hkv;
+    if (groups > (int64_t)1 << 24 || (granule != 3 && ((groups + 7) / 8) * 8 * G > 0x7fffffffLL)) return hipErrorInvalidValue;
+    const char* qc = static_cast<const char*>(q);
+    const char* kc = static_cast<const char*>(k);
+    const char* xc = static_cast<const char*>(x);
+    char* oc = static_cast<char*>(o);
+    const unsigned grid = (unsigned)(((groups + 7) / 8) * 8 * G);
+    if (granule == 1) hipLaunchKernelGGL((stream_slab_kernel<128>), dim3(grid), dim3(256), 0, s, qc, kc, xc, oc, (uint32_t)groups, Hq, Hkv);
+    else if (granule == 2) hipLaunchKernelGGL((stream_slab_kernel<256>), dim3(grid), dim3(256), 0, s, qc, kc, xc, oc, (uint32_t)groups, Hq, Hkv);
+    else if (granule == 3) hipLaunchKernelGGL(stream_slab_group_kernel, dim3((unsigned)groups), dim3(256), 0, s, qc, kc, xc, oc, (uint32_t)groups, Hq, Hkv);
+    else return hipErrorInvalidValue;
+    return hipGetLastError();
+}
+
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
     const size_t n16 = bytes / 16;
     if (n16 == 0) return hipSuccess;

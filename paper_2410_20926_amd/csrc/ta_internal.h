@@ -119,5 +119,6 @@ hipError_t allow_dynamic_lds(const void* kernel, int bytes);
 hipError_t launch_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 // Streaming kernel that reads `reads` and writes `writes` blocks of 4 KB per unit; hipErrorInvalidValue for a mix it has no instantiation for.
 hipError_t launch_stream_mix(const void* src, void* dst, size_t units, int reads, int writes, hipStream_t s);
+hipError_t launch_stream_slabs(const void* q, const void* k, const void* x, void* o, int64_t tokens, int Hq, int Hkv, int granule, hipStream_t s);
 
 }  // namespace ta

@@ -19,7 +19,7 @@ EXPORTS = [
     "ta_plan_create", "ta_plan_destroy", "ta_plan_seq_len", "ta_plan_axis_stride", "ta_plan_axis_fibres",
     "ta_plan_hop_axis", "ta_plan_hop_kernel", "ta_plan_hop_backward_kernel", "ta_plan_hop_bytes", "ta_plan_hop_flops",
     "ta_plan_workspace_bytes", "ta_plan_backward_scratch_bytes", "ta_axis_attn_forward",
-    "ta_axis_attn_backward", "ta_multihop_forward", "ta_multihop_backward", "ta_rope_apply", "ta_copy_bytes", "ta_stream_mix",
+    "ta_axis_attn_backward", "ta_multihop_forward", "ta_multihop_backward", "ta_rope_apply", "ta_copy_bytes", "ta_stream_mix", "ta_stream_slabs",
     "ta_status_string", "ta_last_error_detail", "ta_version",
     "ta_axis_pair_attn_forward", "ta_plan_pair_kernel", "ta_plan_pair_bytes", "ta_plan_fused_position",
     "ta_multihop_forward_static",
@@ -109,6 +109,8 @@ def load_library():
     lib.ta_copy_bytes.restype = i
     lib.ta_stream_mix.argtypes = [vp, vp, sz, i, i, vp]
     lib.ta_stream_mix.restype = i
+    lib.ta_stream_slabs.argtypes = [vp, vp, vp, vp, C.c_int64, i, i, i, vp]
+    lib.ta_stream_slabs.restype = i
     lib.ta_status_string.argtypes = [i]
     lib.ta_status_string.restype = C.c_char_p
     lib.ta_last_error_detail.argtypes = []
@@ -312,6 +314,11 @@ def ta_copy_bytes(src, dst, nbytes: int, stream=None) -> None:
 
 def ta_stream_mix(src, dst, units: int, reads: int, writes: int, stream=None) -> None:
     _check(load_library().ta_stream_mix(_ptr(src), _ptr(dst), units, reads, writes, _stream(stream)))
+
+
+def ta_stream_slabs(q, k, x, o, tokens: int, n_q_heads: int, n_kv_heads: int, granule: int, stream=None) -> None:
+    _check(load_library().ta_stream_slabs(_ptr(q), _ptr(k), _ptr(x), _ptr(o), tokens, n_q_heads, n_kv_heads, granule,
+                                          _stream(stream)))
 
 
 def ta_version():

@@ -33,7 +33,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_version_and_status_strings():
-    assert ta.ta_version() == (0, 6)
+    assert ta.ta_version() == (0, 7)
     lib = ta.load_library()
     assert lib.ta_status_string(0) == b"TA_OK"
     assert lib.ta_status_string(5) == b"TA_ERR_ALIAS"
@@ -219,6 +219,11 @@ def test_entry_points_reject_bad_arguments_without_launching():
     assert status(ta.ta_stream_mix, Q, K, 4, 5, 3, S) == "TA_ERR_UNSUPPORTED"      # no kernel for that mix
     assert status(ta.ta_stream_mix, None, K, 4, 1, 1, S) == "TA_ERR_NULL"
     assert status(ta.ta_stream_mix, Q + 8, K, 4, 1, 1, S) == "TA_ERR_INVALID_ARG"
+    assert status(ta.ta_stream_slabs, Q, K, V, None, 1024, 4, 2, 1, S) == "TA_ERR_NULL"
+    assert status(ta.ta_stream_slabs, Q, K, V, O, 1000, 4, 2, 1, S) == "TA_ERR_INVALID_ARG"   # not a multiple of 1024
+    assert status(ta.ta_stream_slabs, Q, K, V, O, 1024, 4, 3, 1, S) == "TA_ERR_INVALID_ARG"   # heads do not divide
+    assert status(ta.ta_stream_slabs, Q, K, V, O, 1024, 4, 2, 4, S) == "TA_ERR_INVALID_ARG"   # no such granule
+    assert status(ta.ta_stream_slabs, Q, K, V, O + 8, 1024, 4, 2, 1, S) == "TA_ERR_INVALID_ARG"
 
 
 def test_multihop_calls_validate_every_hop_before_the_first_launch():

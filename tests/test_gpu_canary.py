@@ -127,3 +127,28 @@ def test_measurement_kernels_move_what_they_say(reads, writes):
         ta.ta_copy_bytes(src[4:-4], out[4:-4], (src.numel() - 8) * 4)
         torch.cuda.synchronize()
         assert torch.equal(out[4:-4], src[4:-4]) and (out[:4] == -7).all() and (out[-4:] == -7).all()
+
+
+@pytest.mark.parametrize("granule", [1, 2, 3])
+@pytest.mark.parametrize("heads", [(8, 2), (4, 4), (3, 1)])
+def test_slab_streaming_kernel_moves_what_it_says(granule, heads):
+    """The kernel that repeats the fused pair's traffic without its arithmetic: with zeros for Q and K the output
+    is the value input, with anything else every output row is still written, and nothing outside the tensors is."""
+    Hq, Hkv = heads
+    tokens = 2048
+    g = torch.Generator(device="cuda").manual_seed(9)
+    nq, nk = tokens * Hq * 128, tokens * Hkv * 128
+    x = torch.randint(-2 ** 15, 2 ** 15 - 1, (nq,), dtype=torch.int16, device="cuda", generator=g)
+    for zeros in (True, False):
+        q = torch.zeros(nq, dtype=torch.int16, device="cuda") if zeros else torch.randint(1, 2 ** 15 - 1, (nq,), dtype=torch.int16, device="cuda", generator=g)
+        k = torch.zeros(nk, dtype=torch.int16, device="cuda") if zeros else torch.randint(1, 2 ** 15 - 1, (nk,), dtype=torch.int16, device="cuda", generator=g)
+        o = torch.full((nq + 16,), -7, dtype=torch.int16, device="cuda")
+        ta.ta_stream_slabs(q, k, x, o[8:], tokens, Hq, Hkv, granule)
+        torch.cuda.synchronize()
+        assert (o[:8] == -7).all() and (o[-8:] == -7).all()
+        if zeros:
+            assert torch.equal(o[8:-8], x)
+        else:
+            # every 16-byte unit is the input's unit xor one 32-bit word repeated four times
+            d = (o[8:-8] ^ x).view(torch.int32).view(-1, 4)
+            assert bool((d == d[:, :1]).all())
