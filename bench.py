@@ -29,8 +29,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5", "c6", "c3_rope", "c4_train"])
     ap.add_argument("--rotate", type=int, default=3, help="independent buffer sets cycled through, so that the "
                     "256 MB Infinity Cache cannot serve one step's re-reads from the previous step")
