@@ -193,7 +193,8 @@ const char* ta_plan_pair_kernel(const ta_plan_t* plan, int axis, int vin);
 /* Algorithmic HBM bytes of the fused pair: Q, K, value input read once, O written once. */
 double      ta_plan_pair_bytes(const ta_plan_t* plan, int axis, int vin);
 /* Hop position at which ta_multihop_forward switches to the fused pair for the last two
- * hops, or -1 when it runs every hop on its own. */
+ * hops, or -1 when it runs every hop on its own (no fused kernel for the plan, a hop order other than the
+ * default, or a head width that is not a multiple of 32, for which the pair is slower than the two hops). */
 int         ta_plan_fused_position(const ta_plan_t* plan);
 
 /* ---- per-axis attention, backward (the paper gives none: Sec. 3.2 only states that a

@@ -263,16 +263,18 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
     u32x4 qraw[G::kPasses], kraw[G::kPasses], xraw[G::kPasses], graw[G::kPasses];
     // Rows read by this wave alone are streamed; rows every wave of the group reads stay cached.
 #pragma unroll
-    for (int i = 0; i < G::kPasses; ++i) qraw[i] = load_chunk<NARROW, true>(qb, rowoff[i * G::kRowsPerPass + lrow].x, lbyte, dbytes);
+    for (int i = 0; i < G::kPasses; ++i) qraw[i] = gather_chunk<NARROW, true>(qb, rowoff[i * G::kRowsPerPass + lrow].x, lbyte, dbytes);
 #pragma unroll
-    for (int i = 0; i < G::kPasses; ++i) kraw[i] = load_chunk<NARROW, false>(kb, rowoff[i * G::kRowsPerPass + lrow].y, lbyte, dbytes);
+    for (int i = 0; i < G::kPasses; ++i) kraw[i] = gather_chunk<NARROW, false>(kb, rowoff[i * G::kRowsPerPass + lrow].y, lbyte, dbytes);
+    if (vin_is_o) {                                        // one choice for all eight requests, not one per request
 #pragma unroll
-    for (int i = 0; i < G::kPasses; ++i) {
-        const uint32_t off = rowoff[i * G::kRowsPerPass + lrow].z;
-        xraw[i] = vin_is_o ? load_chunk<NARROW, true>(xb, off, lbyte, dbytes) : load_chunk<NARROW, false>(xb, off, lbyte, dbytes);
+        for (int i = 0; i < G::kPasses; ++i) xraw[i] = gather_chunk<NARROW, true>(xb, rowoff[i * G::kRowsPerPass + lrow].z, lbyte, dbytes);
+    } else {
+#pragma unroll
+        for (int i = 0; i < G::kPasses; ++i) xraw[i] = gather_chunk<NARROW, false>(xb, rowoff[i * G::kRowsPerPass + lrow].z, lbyte, dbytes);
     }
 #pragma unroll
-    for (int i = 0; i < G::kPasses; ++i) graw[i] = load_chunk<NARROW, true>(gb, rowoff[i * G::kRowsPerPass + lrow].w, lbyte, dbytes);
+    for (int i = 0; i < G::kPasses; ++i) graw[i] = gather_chunk<NARROW, true>(gb, rowoff[i * G::kRowsPerPass + lrow].w, lbyte, dbytes);
     __builtin_amdgcn_sched_barrier(0);
 
     // rotary encoding: Q and K rows are turned by their position on the axis before anything uses them;
@@ -561,7 +563,7 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
 #pragma unroll
         for (int i = 0; i < G::kPasses; ++i) {
             const uint32_t rr = (uint32_t)min(kTile * t + i * G::kRowsPerPass + lrow, n - 1);
-            raw[i] = load_chunk<NARROW, false>(base, (tok0 + rr * stride) * pitch, lbyte, dbytes);
+            raw[i] = gather_chunk<NARROW, false>(base, (tok0 + rr * stride) * pitch, lbyte, dbytes);
         }
     };
     // rotary encoding: every gathered Q or K tile is turned, row by row, by its position on the axis

@@ -56,6 +56,53 @@ __device__ inline u32x4 load_chunk(const char* base, uint32_t rowoff, uint32_t l
         return u32x4{lo.x, lo.y, hi.x, hi.y};
     }
 }
+// The same chunk for the row gathers, where the lanes of a row are consecutive lanes that hold consecutive chunks of
+// the whole tile row (chunk = lane % 8 or lane % 16) and every lane of the wave takes part.  NARROW rows start on a
+// multiple of 8 bytes; strided 8-byte halves (load_chunk) ask for every cache line twice and reach 3.5 TB/s in a plain
+// streaming kernel on 200-byte rows, 16-byte requests on 16-byte boundaries 4.65 TB/s.  So a lane asks for the aligned
+// 16 bytes that start at or 8 bytes before its chunk (those 8 bytes lie inside the tensor's span: the tensor itself
+// starts on a 16-byte boundary), never for bytes past the end of the row, and a row that starts 8 bytes into an
+// aligned unit takes the second half of each chunk from the next lane.  Rows are at least 16 bytes long.
+template <bool NARROW, bool NT>
+__device__ inline u32x4 gather_chunk(const char* base, uint32_t rowoff, uint32_t lbyte, uint32_t dbytes) {
+    if constexpr (!NARROW) {
+        return load_chunk<false, NT>(base, rowoff, lbyte, dbytes);
+    } else {
+        const char* row = base + rowoff;
+        const uint32_t mis = (uint32_t)(reinterpret_cast<uintptr_t>(row) & 8u);
+        const int32_t s = (int32_t)lbyte - (int32_t)mis;           // where this lane's aligned unit starts, relative to the row
+        // One 16-byte request per lane and no branch (a branch per chunk would make every request wait for the one
+        // before): a unit that would pass the end of the row is replaced by the row's last 16 bytes, whose second
+        // half is the unit's first (the row's length is a multiple of 8, so exactly 8 bytes of the unit are inside).
+        const bool full = s + 16 <= (int32_t)dbytes, tail = !full && s + 8 <= (int32_t)dbytes;
+        const u32x4* src = reinterpret_cast<const u32x4*>(row + (full ? s : (int32_t)dbytes - 16));
+        u32x4 a = NT ? __builtin_nontemporal_load(src) : *src;
+        if (tail) a = u32x4{a.z, a.w, 0u, 0u};
+        if (!full && !tail) a = u32x4{0u, 0u, 0u, 0u};
+        // lane i takes the first half of lane i + 1's unit (row_shl:1 within 16 lanes; nothing comes in at the end)
+        const uint32_t nx = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a.x, 0x101, 0xf, 0xf, true);
+        const uint32_t ny = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)a.y, 0x101, 0xf, 0xf, true);
+        u32x4 out = mis ? u32x4{a.z, a.w, nx, ny} : a;
+        if (lbyte + 8 > dbytes) { out.x = 0u; out.y = 0u; }
+        if (lbyte + 16 > dbytes) { out.z = 0u; out.w = 0u; }
+        return out;
+    }
+}
+// A finished output row leaves its row-major LDS tile (`lds_chunk` = this lane's 16-byte chunk of it, `lbyte` bytes into
+// the row).  NARROW: as 8-byte pieces that are contiguous within each store instruction (the lane that holds chunk c
+// writes piece c of the row, then piece chunks + c), read from LDS in that order: the two halves of a chunk, 16 bytes
+// apart from the next lane's, would leave every cache line half written by either instruction.
+template <bool NARROW, int CHUNKS>
+__device__ inline void store_row_chunk(char* base, uint32_t rowoff, const char* lds_chunk, uint32_t lbyte, uint32_t dbytes) {
+    if constexpr (!NARROW) {
+        __builtin_nontemporal_store(*reinterpret_cast<const u32x4*>(lds_chunk), reinterpret_cast<u32x4*>(base + (rowoff + lbyte)));
+    } else {
+        const uint32_t p0 = lbyte / 2, p1 = 8u * CHUNKS + lbyte / 2;   // byte offsets of the two pieces within the row
+        const char* lds_row = lds_chunk - lbyte;
+        if (p0 + 8 <= dbytes) __builtin_nontemporal_store(*reinterpret_cast<const u32x2*>(lds_row + p0), reinterpret_cast<u32x2*>(base + (rowoff + p0)));
+        if (p1 + 8 <= dbytes) __builtin_nontemporal_store(*reinterpret_cast<const u32x2*>(lds_row + p1), reinterpret_cast<u32x2*>(base + (rowoff + p1)));
+    }
+}
 template <bool NARROW>
 __device__ inline void store_chunk(char* base, uint32_t rowoff, uint32_t lbyte, uint32_t dbytes, const u32x4 v) {
     if constexpr (!NARROW) {

@@ -22,6 +22,8 @@
 //      yields the two keys of one feature column, which is the A-operand layout of V^T;
 //   5. O^T is scaled by 1/rowsum in fp32, rounded to bf16, transposed through LDS and
 //      stored with 16-byte coalesced stores (fold).
+#include <type_traits>
+
 #include "ta_mfma_common.h"
 
 namespace ta {
@@ -121,27 +123,34 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
     const bool v_once = (KT == 1) && (p.G == 1 || p.vin_heads == p.Hq);
     u32x4 qreg[G::kPasses], kreg[KT][G::kPasses], vreg[KT][G::kPasses];
     uint32_t ooff[G::kPasses], voff[KT][G::kPasses];
+    // (the choice between last-use and cached requests is made once, outside the loops: a choice per request is a branch
+    // per request, and with narrow rows, whose chunks are put together from two lanes, every request then waits for the one before)
+    auto gather_kv = [&](auto k_nt, auto v_nt) {
 #pragma unroll
-    for (int j = 0; j < KT; ++j) {
-        if (j < kt_end) {
+        for (int j = 0; j < KT; ++j) {
+            if (j < kt_end) {
 #pragma unroll
-            for (int i = 0; i < G::kPasses; ++i) {
-                const u32x4 off = rowoff[j * kTile + i * G::kRowsPerPass + lrow];
-                kreg[j][i] = k_once ? load_chunk<NARROW, true>(kb, off.y, lbyte, dbytes) : load_chunk<NARROW, false>(kb, off.y, lbyte, dbytes);
-                voff[j][i] = off.z;
-                if (j == 0) vreg[j][i] = v_once ? load_chunk<NARROW, true>(vb, voff[j][i], lbyte, dbytes) : load_chunk<NARROW, false>(vb, voff[j][i], lbyte, dbytes);
-                if (KT == 1) {
-                    qreg[i] = load_chunk<NARROW, true>(qb, off.x, lbyte, dbytes);
-                    ooff[i] = off.w;
+                for (int i = 0; i < G::kPasses; ++i) {
+                    const u32x4 off = rowoff[j * kTile + i * G::kRowsPerPass + lrow];
+                    kreg[j][i] = gather_chunk<NARROW, decltype(k_nt)::value>(kb, off.y, lbyte, dbytes);
+                    voff[j][i] = off.z;
+                    if (j == 0) vreg[j][i] = gather_chunk<NARROW, decltype(v_nt)::value>(vb, voff[j][i], lbyte, dbytes);
+                    if (KT == 1) {
+                        qreg[i] = gather_chunk<NARROW, true>(qb, off.x, lbyte, dbytes);
+                        ooff[i] = off.w;
+                    }
                 }
             }
         }
-    }
+    };
+    if (k_once && v_once) gather_kv(std::true_type{}, std::true_type{});
+    else if (v_once) gather_kv(std::false_type{}, std::true_type{});
+    else gather_kv(std::false_type{}, std::false_type{});      // (k_once implies v_once)
     if (KT > 1) {
 #pragma unroll
         for (int i = 0; i < G::kPasses; ++i) {
             const u32x4 off = rowoff[qt * kTile + i * G::kRowsPerPass + lrow];
-            qreg[i] = load_chunk<NARROW, true>(qb, off.x, lbyte, dbytes);
+            qreg[i] = gather_chunk<NARROW, true>(qb, off.x, lbyte, dbytes);
             ooff[i] = off.w;
         }
     }
@@ -200,7 +209,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
             lds_wave_sync();
             if (KT > 1 && j == 0 && kt_end > 1) {         // K tile 0 is out of its registers: request V tile 1
 #pragma unroll
-                for (int i = 0; i < G::kPasses; ++i) vreg[1][i] = load_chunk<NARROW, false>(vb, voff[1][i], lbyte, dbytes);
+                for (int i = 0; i < G::kPasses; ++i) vreg[1][i] = gather_chunk<NARROW, false>(vb, voff[1][i], lbyte, dbytes);
                 __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
@@ -319,8 +328,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
     for (int i = 0; i < G::kPasses; ++i) {
         const int row = qt * kTile + i * G::kRowsPerPass + lrow;
         if (row < rows_valid) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
-            store_chunk<NARROW>(ob, ooff[i], lbyte, dbytes, v);
+            store_row_chunk<NARROW, G::kChunks>(ob, ooff[i], stg + i * G::kRowsPerPass * G::kPitch, lbyte, dbytes);
         }
     }
 }
@@ -422,7 +430,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
 #pragma unroll
     for (int i = 0; i < G::kPasses; ++i) {
         const u32x4 off = rowoff[qt * kTile + i * G::kRowsPerPass + lrow];
-        qreg[i] = load_chunk<NARROW, true>(qb, off.x, lbyte, dbytes);
+        qreg[i] = gather_chunk<NARROW, true>(qb, off.x, lbyte, dbytes);
         ooff[i] = off.w;
     }
 #pragma unroll
@@ -431,15 +439,15 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
 #pragma unroll
             for (int i = 0; i < kShare; ++i) {
                 const u32x4 off = rowoff[j * kTile + (w * kShare + i) * G::kRowsPerPass + lrow];
-                ksh[j][i] = load_chunk<NARROW, false>(kb, off.y, lbyte, dbytes);
-                if (v_shared) vsh[j][i] = load_chunk<NARROW, false>(vb, off.z, lbyte, dbytes);
+                ksh[j][i] = gather_chunk<NARROW, false>(kb, off.y, lbyte, dbytes);
+                if (v_shared) vsh[j][i] = gather_chunk<NARROW, false>(vb, off.z, lbyte, dbytes);
             }
             if (!v_shared) {
 #pragma unroll
                 for (int i = 0; i < G::kPasses; ++i) {
                     const u32x4 off = rowoff[j * kTile + i * G::kRowsPerPass + lrow];
-                    vreg[j][i] = (KT == 1) ? load_chunk<NARROW, true>(vb, off.z, lbyte, dbytes)
-                                           : load_chunk<NARROW, false>(vb, off.z, lbyte, dbytes);   // with two query tiles a value tile is read twice: keep it cached
+                    vreg[j][i] = (KT == 1) ? gather_chunk<NARROW, true>(vb, off.z, lbyte, dbytes)
+                                           : gather_chunk<NARROW, false>(vb, off.z, lbyte, dbytes);   // with two query tiles a value tile is read twice: keep it cached
                 }
             }
         }
@@ -597,8 +605,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
         for (int i = 0; i < kHalfPasses; ++i) {
             const int row = qt * kTile + (hs * kHalfPasses + i) * G::kRowsPerPass + lrow;
             if (row < rows_valid) {
-                const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
-                store_chunk<NARROW>(ob, ooff[hs * kHalfPasses + i], lbyte, dbytes, v);
+                store_row_chunk<NARROW, G::kChunks>(ob, ooff[hs * kHalfPasses + i], stg + i * G::kRowsPerPass * G::kPitch, lbyte, dbytes);
             }
         }
         lds_wave_sync();

@@ -65,16 +65,18 @@ struct PairParams {
 // the halves of a 128-byte line and walk through the units; consecutive i (a column fibre) are
 // an odd number of units apart: both access patterns cover all banks.
 
-// Narrow heads (rows of `dbytes` < 2 kD bytes, 8-byte aligned): the 16-byte chunk at `addr`, which
-// starts `at` bytes into its row, as two 8-byte pieces, each only if it lies inside the row; what
-// lies outside reads as zero and is not written.
+// Narrow heads (rows of `dbytes` < 2 kD bytes, 8-byte aligned, at least 16 bytes): the 16-byte chunk at `addr`, which
+// starts `at` bytes into its row; what lies outside the row reads as zero and is not written.  One 16-byte request
+// per lane and no branch (with a branch per request every request waits for the one before): a chunk that would pass
+// the end of the row is replaced by the row's last 16 bytes, whose second half is the chunk's first.
 template <bool NT>
 __device__ inline u32x4 narrow_load(const char* addr, uint32_t at, uint32_t dbytes) {
-    u32x2 lo = {0u, 0u}, hi = {0u, 0u};
-    const u32x2* a = reinterpret_cast<const u32x2*>(addr);
-    if (at + 8 <= dbytes) lo = NT ? __builtin_nontemporal_load(a) : *a;
-    if (at + 16 <= dbytes) hi = NT ? __builtin_nontemporal_load(a + 1) : a[1];
-    return u32x4{lo.x, lo.y, hi.x, hi.y};
+    const bool full = at + 16 <= dbytes, tail = !full && at + 8 <= dbytes;
+    const u32x4* a = reinterpret_cast<const u32x4*>(full ? addr : addr + ((int32_t)dbytes - 16 - (int32_t)at));
+    u32x4 v = NT ? __builtin_nontemporal_load(a) : *a;
+    if (tail) v = u32x4{v.z, v.w, 0u, 0u};
+    if (!full && !tail) v = u32x4{0u, 0u, 0u, 0u};
+    return v;
 }
 __device__ inline void narrow_store(char* addr, uint32_t at, uint32_t dbytes, const u32x4 v) {
     u32x2* a = reinterpret_cast<u32x2*>(addr);
@@ -397,7 +399,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
             const u32x4* src = reinterpret_cast<const u32x4*>(xb + (t * p.v_row + (uint32_t)(c * (kCB * 2) + ub * 16)));
             if constexpr (NARROW) {
                 const uint32_t at = (uint32_t)(c * (kCB * 2) + ub * 16);
-                xreg[pp] = vin_is_o ? narrow_load<true>(reinterpret_cast<const char*>(src), at, p.dbytes) : narrow_load<false>(reinterpret_cast<const char*>(src), at, p.dbytes);
+                xreg[pp] = narrow_load<true>(reinterpret_cast<const char*>(src), at, p.dbytes);   // (a per-group V too: one choice per request would be a branch per request)
             } else {
                 xreg[pp] = vin_is_o ? __builtin_nontemporal_load(src) : *src;   // a per-group V is read by every head of the group
             }

@@ -77,9 +77,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
     for (int i = 0; i < G::kPasses; ++i) {
         const uint32_t rq = (uint32_t)min(qt * kTile + i * G::kRowsPerPass + lrow, n - 1);
         const uint32_t rk = (uint32_t)min(jbeg * kTile + i * G::kRowsPerPass + lrow, n - 1);
-        qreg[i] = load_chunk<NARROW, true>(qb, rq * sp.q_step, lbyte, dbytes);   // read by this wave alone
-        kreg[i] = load_chunk<NARROW, false>(kb, rk * sp.k_step, lbyte, dbytes);
-        vreg[i] = load_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
+        qreg[i] = gather_chunk<NARROW, true>(qb, rq * sp.q_step, lbyte, dbytes);   // read by this wave alone
+        kreg[i] = gather_chunk<NARROW, false>(kb, rk * sp.k_step, lbyte, dbytes);
+        vreg[i] = gather_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
         ooff[i] = rq * sp.o_step + lbyte;
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -131,7 +131,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
 #pragma unroll
             for (int i = 0; i < G::kPasses; ++i) {
                 const uint32_t rk = (uint32_t)min((j + 1) * kTile + i * G::kRowsPerPass + lrow, n - 1);
-                kreg[i] = load_chunk<NARROW, false>(kb, rk * sp.k_step, lbyte, dbytes);
+                kreg[i] = gather_chunk<NARROW, false>(kb, rk * sp.k_step, lbyte, dbytes);
             }
         }
         f32x16 st = {};
@@ -155,7 +155,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
 #pragma unroll
             for (int i = 0; i < G::kPasses; ++i) {
                 const uint32_t rk = (uint32_t)min((j + 1) * kTile + i * G::kRowsPerPass + lrow, n - 1);
-                vreg[i] = load_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
+                vreg[i] = gather_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
             }
         }
 #pragma unroll
@@ -183,8 +183,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
     for (int i = 0; i < G::kPasses; ++i) {
         const int row = qt * kTile + i * G::kRowsPerPass + lrow;
         if (row < n) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
-            store_chunk<NARROW>(ob, ooff[i] - lbyte, lbyte, dbytes, v);
+            store_row_chunk<NARROW, G::kChunks>(ob, ooff[i] - lbyte, stg + i * G::kRowsPerPass * G::kPitch, lbyte, dbytes);
         }
     }
 }
@@ -253,8 +252,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
 #pragma unroll
                 for (int i = 0; i < kMine; ++i) {
                     const uint32_t rk = (uint32_t)min(j * kTile + (w * kMine + i) * G::kRowsPerPass + lrow, n - 1);
-                    kp[sidx][i] = load_chunk<NARROW, false>(kb, rk * sp.k_step, lbyte, dbytes);
-                    if (VS) vp[sidx][i] = load_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
+                    kp[sidx][i] = gather_chunk<NARROW, false>(kb, rk * sp.k_step, lbyte, dbytes);
+                    if (VS) vp[sidx][i] = gather_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
                 }
             }
     };
@@ -277,13 +276,13 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
 #pragma unroll
         for (int i = 0; i < (VS ? 0 : G::kPasses); ++i) {
             const uint32_t rk = (uint32_t)min(j * kTile + i * G::kRowsPerPass + lrow, n - 1);
-            vreg[i] = load_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
+            vreg[i] = gather_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
         }
     };
 #pragma unroll
     for (int i = 0; i < G::kPasses; ++i) {
         const uint32_t rq = (uint32_t)min(qt * kTile + i * G::kRowsPerPass + lrow, n - 1);
-        qreg[i] = load_chunk<NARROW, true>(qb, rq * sp.q_step, lbyte, dbytes);
+        qreg[i] = gather_chunk<NARROW, true>(qb, rq * sp.q_step, lbyte, dbytes);
         ooff[i] = rq * sp.o_step + lbyte;
     }
     load_shared(0, jbeg);
@@ -383,8 +382,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
     for (int i = 0; i < G::kPasses; ++i) {
         const int row = qt * kTile + i * G::kRowsPerPass + lrow;
         if (row < n) {
-            const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
-            store_chunk<NARROW>(ob, ooff[i] - lbyte, lbyte, dbytes, v);
+            store_row_chunk<NARROW, G::kChunks>(ob, ooff[i] - lbyte, stg + i * G::kRowsPerPass * G::kPitch, lbyte, dbytes);
         }
     }
 }
@@ -464,8 +462,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunke
 #pragma unroll
         for (int i = 0; i < kMine; ++i) {
             const uint32_t rk = (uint32_t)min(j * kTile + (w * kMine + i) * G::kRowsPerPass + lrow, n - 1);
-            kp[set][i] = load_chunk<NARROW, false>(kb, rk * sp.k_step, lbyte, dbytes);
-            if (VS) vp[set][i] = load_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
+            kp[set][i] = gather_chunk<NARROW, false>(kb, rk * sp.k_step, lbyte, dbytes);
+            if (VS) vp[set][i] = gather_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
         }
     };
     float rev[4];                                         // rotary encoding: turn rates of this lane's four feature pairs
@@ -484,14 +482,14 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunke
 #pragma unroll
         for (int i = 0; i < (VS ? 0 : G::kPasses); ++i) {
             const uint32_t rk = (uint32_t)min(j * kTile + i * G::kRowsPerPass + lrow, n - 1);
-            vreg[i] = load_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
+            vreg[i] = gather_chunk<NARROW, false>(vb, rk * sp.v_step, lbyte, dbytes);
         }
     };
     auto load_q = [&](int qt) {
 #pragma unroll
         for (int i = 0; i < G::kPasses; ++i) {
             const uint32_t rq = (uint32_t)min(qt * kTile + i * G::kRowsPerPass + lrow, n - 1);
-            qreg[i] = load_chunk<NARROW, true>(qb, rq * sp.q_step, lbyte, dbytes);
+            qreg[i] = gather_chunk<NARROW, true>(qb, rq * sp.q_step, lbyte, dbytes);
         }
     };
     using S0 = std::integral_constant<int, 0>;
@@ -611,8 +609,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunke
             for (int i = 0; i < G::kPasses; ++i) {
                 const int row = qt * kTile + i * G::kRowsPerPass + lrow;
                 if (row < n) {
-                    const u32x4 v = *reinterpret_cast<const u32x4*>(stg + i * G::kRowsPerPass * G::kPitch);
-                    store_chunk<NARROW>(ob, (uint32_t)row * sp.o_step, lbyte, dbytes, v);
+                    store_row_chunk<NARROW, G::kChunks>(ob, (uint32_t)row * sp.o_step, stg + i * G::kRowsPerPass * G::kPitch, lbyte, dbytes);
                 }
             }
         }

@@ -174,11 +174,20 @@ def test_pair_at_other_head_widths(causal, valid_len, Hq, Hkv, D):
     q, k, v, d_o = make_inputs(B, N, Hq, Hkv, D, seed=8700, dtype="bf16", qk_scale=0.125, with_grad=True)
     kw = {} if valid_len is None else dict(valid_len=valid_len)
     got, plan, _ = multihop_forward(q, k, v, dims, "bf16", causal, **kw)
-    assert plan.fused_position() == 1 and plan.pair_kernel(1, ta.TA_VIN_O) == "mfma_bf16_pair_n32"
+    # the multi-hop call fuses only where the pair is the faster choice (rows that are whole 64-byte pieces)
+    assert plan.fused_position() == (1 if D % 32 == 0 else -1) and plan.pair_kernel(1, ta.TA_VIN_O) == "mfma_bf16_pair_n32"
     ref = orc.tensorized_attention_forward(q, k, v, dims, causal, valid_len=valid_len)
     assert np.isfinite(got).all() and np.abs(got - ref).max() <= TOL["bf16"]
     saved, plan_s, dev = multihop_forward(q, k, v, dims, "bf16", causal, save=True, **kw)
     assert np.array_equal(saved, got)
+    # the pair kernel itself at this width, called directly after a first hop of its own
+    dq_, dk_, dv_ = to_dev(q, "bf16"), to_dev(k, "bf16"), to_dev(v, "bf16")
+    first = torch.empty_like(dq_)
+    direct = torch.full_like(dq_, float("nan"))
+    ta.ta_axis_attn_forward(plan, 0, dq_, dk_, dv_, ta.TA_VIN_KV, first)
+    ta.ta_axis_pair_attn_forward(plan, 1, dq_, dk_, first, ta.TA_VIN_O, direct)
+    torch.cuda.synchronize()
+    assert np.abs(to_host(direct) - ref).max() <= TOL["bf16"]
     dq, dk, dv = multihop_backward(plan_s, dev, d_o, "bf16")
     check_backward((dq, dk, dv), q, k, v, d_o, dims, causal, "bf16", valid_len=valid_len)
 
