@@ -210,10 +210,12 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_kernel(BwdParams bp, TilePara
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nw = MULTI ? bp.wg_heads : p.G;
 
-    const int g = blockIdx.x;
+    uint32_t bx, ty;
+    workgroup_xy<NARROW>(bx, ty);
+    const int g = (int)bx;
     const int h = g * p.G + (MULTI ? bp.head_base : 0) + w;
     const uint32_t zb = blockIdx.z / tp.tiles_hi;
-    const uint32_t tt = (blockIdx.z - zb * tp.tiles_hi) * tp.tiles_lo + blockIdx.y;
+    const uint32_t tt = (blockIdx.z - zb * tp.tiles_hi) * tp.tiles_lo + ty;
     if (tt >= tp.tiles) return;                           // whole workgroup leaves together
     const int b = (int)zb;
     const bool vin_is_o = (p.vin_heads == p.Hq);
@@ -519,10 +521,12 @@ __global__ __launch_bounds__(512, 2) void mfma_bwd_stream_kernel(BwdParams bp, S
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nw = bp.wg_heads;
-    const int g = blockIdx.x;
+    uint32_t bx, by;
+    workgroup_xy<NARROW>(bx, by);
+    const int g = (int)bx;
     const int h = g * p.G + bp.head_base + w;
     const uint32_t zb = blockIdx.z / sp.fibres_hi;
-    const int64_t f = (int64_t)(blockIdx.z - zb * sp.fibres_hi) * sp.fibres_lo + blockIdx.y;
+    const int64_t f = (int64_t)(blockIdx.z - zb * sp.fibres_hi) * sp.fibres_lo + by;
     if (f >= p.fibres) return;                            // whole workgroup leaves together
     const int b = (int)zb;
     const bool vin_is_o = (p.vin_heads == p.Hq);

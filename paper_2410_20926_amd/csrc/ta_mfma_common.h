@@ -39,21 +39,24 @@ __device__ inline f32x16 mma(const u32x4 a, const u32x4 b, const f32x16 c) {   /
 }
 
 // One lane's 16-byte chunk (8 features starting at byte `lbyte` of the row at `base + rowoff`).  NARROW:
-// the row holds only `dbytes` bytes (a head width that is a multiple of 4 but not of 8 features,
-// or simply narrower than the tile): the chunk is read as two 8-byte halves, each only if it
-// lies inside the row, and what lies outside is zero, so that the tile's extra features are
-// zero in every operand.  Rows are then only 8-byte aligned, which the 8-byte accesses respect.
+// the row holds only `dbytes` bytes (at least 16; a head width that is a multiple of 4 but not of 8 features,
+// or simply narrower than the tile) and starts on a multiple of 8 bytes: what lies outside the row reads as
+// zero, so that the tile's extra features are zero in every operand.  One 16-byte request per lane (on an
+// 8-byte boundary where the row starts on one) and no branch: a branch per request makes every request wait
+// for the one before.  A chunk that would pass the end of the row is replaced by the row's last 16 bytes,
+// whose second half is the chunk's first (the row's length is a multiple of 8).
 template <bool NARROW, bool NT>
 __device__ inline u32x4 load_chunk(const char* base, uint32_t rowoff, uint32_t lbyte, uint32_t dbytes) {
     if constexpr (!NARROW) {
         const u32x4* a = reinterpret_cast<const u32x4*>(base + (rowoff + lbyte));
         return NT ? __builtin_nontemporal_load(a) : *a;
     } else {
-        u32x2 lo = {0u, 0u}, hi = {0u, 0u};
-        const u32x2* a = reinterpret_cast<const u32x2*>(base + (rowoff + lbyte));
-        if (lbyte + 8 <= dbytes) lo = NT ? __builtin_nontemporal_load(a) : *a;
-        if (lbyte + 16 <= dbytes) hi = NT ? __builtin_nontemporal_load(a + 1) : a[1];
-        return u32x4{lo.x, lo.y, hi.x, hi.y};
+        const bool full = lbyte + 16 <= dbytes, tail = !full && lbyte + 8 <= dbytes;
+        const u32x4* a = reinterpret_cast<const u32x4*>(base + (rowoff + (full ? lbyte : dbytes - 16)));
+        u32x4 v = NT ? __builtin_nontemporal_load(a) : *a;
+        if (tail) v = u32x4{v.z, v.w, 0u, 0u};
+        if (!full && !tail) v = u32x4{0u, 0u, 0u, 0u};
+        return v;
     }
 }
 // The same chunk for the row gathers, where the lanes of a row are consecutive lanes that hold consecutive chunks of
@@ -99,8 +102,9 @@ __device__ inline void store_row_chunk(char* base, uint32_t rowoff, const char* 
     } else {
         const uint32_t p0 = lbyte / 2, p1 = 8u * CHUNKS + lbyte / 2;   // byte offsets of the two pieces within the row
         const char* lds_row = lds_chunk - lbyte;
-        if (p0 + 8 <= dbytes) __builtin_nontemporal_store(*reinterpret_cast<const u32x2*>(lds_row + p0), reinterpret_cast<u32x2*>(base + (rowoff + p0)));
-        if (p1 + 8 <= dbytes) __builtin_nontemporal_store(*reinterpret_cast<const u32x2*>(lds_row + p1), reinterpret_cast<u32x2*>(base + (rowoff + p1)));
+        // (through the cache, so that L2 can join a row's first and last line with the neighbouring heads' parts)
+        if (p0 + 8 <= dbytes) *reinterpret_cast<u32x2*>(base + (rowoff + p0)) = *reinterpret_cast<const u32x2*>(lds_row + p0);
+        if (p1 + 8 <= dbytes) *reinterpret_cast<u32x2*>(base + (rowoff + p1)) = *reinterpret_cast<const u32x2*>(lds_row + p1);
     }
 }
 template <bool NARROW>
@@ -108,9 +112,12 @@ __device__ inline void store_chunk(char* base, uint32_t rowoff, uint32_t lbyte, 
     if constexpr (!NARROW) {
         __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(base + (rowoff + lbyte)));
     } else {
-        u32x2* a = reinterpret_cast<u32x2*>(base + (rowoff + lbyte));
-        if (lbyte + 8 <= dbytes) __builtin_nontemporal_store(u32x2{v.x, v.y}, a);
-        if (lbyte + 16 <= dbytes) __builtin_nontemporal_store(u32x2{v.z, v.w}, a + 1);
+        // a whole chunk in one store (on an 8-byte boundary where the row starts on one), the row's last 8 bytes on their own
+        // (through the cache: a row's first and last cache line may be shared with the neighbouring heads' rows, and
+        // L2 can put the parts together before the line goes to memory)
+        char* a = base + (rowoff + lbyte);
+        if (lbyte + 16 <= dbytes) *reinterpret_cast<u32x4*>(a) = v;
+        else if (lbyte + 8 <= dbytes) *reinterpret_cast<u32x2*>(a) = u32x2{v.x, v.y};
     }
 }
 
@@ -293,6 +300,27 @@ __device__ inline void online_softmax_tile(const f32x16& st, uint32_t vis32, int
     }
     psum += __shfl_xor(psum, 32);
     l = l * corr + psum;
+}
+
+// Workgroup numbering of the NARROW instantiations.  Rows that are not whole 64-byte pieces share their first and last
+// piece with the neighbouring heads' rows.  Workgroup ids go round the 8 XCDs, so with the plain numbering (head block
+// = blockIdx.x, fastest) neighbouring heads are written from different L2s and every shared piece reaches memory as two
+// partial writes.  Here each XCD takes a contiguous run of the (blockIdx.y, blockIdx.x) sequence instead: neighbouring
+// head blocks follow each other on one XCD, and their rows, stored through the cache, leave its L2 as whole lines
+// (head width 100, 32 heads, 32k tokens: a backward hop 620 -> 400 us).  bx, by: the pair to use in place of
+// blockIdx.x and blockIdx.y.
+template <bool NARROW>
+__device__ inline void workgroup_xy(uint32_t& bx, uint32_t& by) {
+    bx = blockIdx.x; by = blockIdx.y;
+    if constexpr (NARROW) {
+        const uint32_t gx = gridDim.x, total = gx * gridDim.y;
+        if (total % 8u == 0u) {
+            const uint32_t lin = blockIdx.x + gx * blockIdx.y;
+            const uint32_t seq = (lin & 7u) * (total / 8u) + (lin >> 3);
+            bx = seq % gx;
+            by = seq / gx;
+        }
+    }
 }
 
 // Launch geometry computed on the host.

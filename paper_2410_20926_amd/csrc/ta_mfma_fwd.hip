@@ -47,9 +47,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_kernel(HopPar
 
     // block -> (head block, tile, batch); heads fastest so that co-resident waves read
     // the same tokens (whole DRAM rows) and the four waves of a block share K
-    const int h = blockIdx.x * kWavesPerBlock + w;
+    uint32_t bx, by;
+    workgroup_xy<NARROW>(bx, by);
+    const int h = (int)bx * kWavesPerBlock + w;
     const uint32_t zb = blockIdx.z / tp.tiles_hi;
-    const uint32_t tt = (blockIdx.z - zb * tp.tiles_hi) * tp.tiles_lo + blockIdx.y;
+    const uint32_t tt = (blockIdx.z - zb * tp.tiles_hi) * tp.tiles_lo + by;
     if (h >= p.Hq || tt >= tp.tiles) return;              // no workgroup barrier below
     const int b = (int)zb;
     const int g = h / p.G;
@@ -354,9 +356,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_shared_kernel
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 
-    const int h = blockIdx.x * kWavesPerBlock + w;                          // host guarantees Hq % 4 == 0 and G % 4 == 0
+    uint32_t bx, by;
+    workgroup_xy<NARROW>(bx, by);
+    const int h = (int)bx * kWavesPerBlock + w;                             // host guarantees Hq % 4 == 0 and G % 4 == 0
     const uint32_t zb = blockIdx.z / tp.tiles_hi;
-    const uint32_t tt = (blockIdx.z - zb * tp.tiles_hi) * tp.tiles_lo + blockIdx.y;
+    const uint32_t tt = (blockIdx.z - zb * tp.tiles_hi) * tp.tiles_lo + by;
     if (tt >= tp.tiles) return;                                             // the whole workgroup leaves together
     const int b = (int)zb;
     const int g = h / p.G;

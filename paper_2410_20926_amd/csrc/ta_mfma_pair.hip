@@ -79,9 +79,9 @@ __device__ inline u32x4 narrow_load(const char* addr, uint32_t at, uint32_t dbyt
     return v;
 }
 __device__ inline void narrow_store(char* addr, uint32_t at, uint32_t dbytes, const u32x4 v) {
-    u32x2* a = reinterpret_cast<u32x2*>(addr);
-    if (at + 8 <= dbytes) __builtin_nontemporal_store(u32x2{v.x, v.y}, a);
-    if (at + 16 <= dbytes) __builtin_nontemporal_store(u32x2{v.z, v.w}, a + 1);
+    // a whole chunk in one store, the row's last 8 bytes on their own; through the cache (see the kernel's numbering)
+    if (at + 16 <= dbytes) *reinterpret_cast<u32x4*>(addr) = v;
+    else if (at + 8 <= dbytes) *reinterpret_cast<u32x2*>(addr) = u32x2{v.x, v.y};
 }
 
 // Masked row softmax of one 32 x 32 score tile held as S^T (lane = query row, 16 keys per
@@ -179,8 +179,16 @@ __global__ __launch_bounds__(64 * kWaves, 2) void mfma_fwd_pair_kernel(PairParam
     // through that XCD's L2.
     const bool vin_is_o = (p.vin_heads == p.Hq);
     const uint32_t span = 8u * (uint32_t)p.G;
-    const uint32_t blk = blockIdx.x / span, rem = blockIdx.x - blk * span;
-    const uint32_t hg = rem >> 3, gi = blk * 8u + (rem & 7u);
+    uint32_t blk = blockIdx.x / span, rem = blockIdx.x - blk * span;
+    uint32_t hg = rem >> 3, gi = blk * 8u + (rem & 7u);
+    if constexpr (NARROW) {
+        // Narrow rows share their first and last cache line with the neighbouring heads' rows: every XCD takes a
+        // contiguous run of the (slab, head) sequence, so that neighbouring heads are written, through the cache, from
+        // one L2 and reach memory as whole lines (see workgroup_xy).  The grid is a multiple of 8 workgroups.
+        const uint32_t seq = (blockIdx.x & 7u) * (gridDim.x / 8u) + (blockIdx.x >> 3);
+        gi = seq / (uint32_t)p.G;
+        hg = seq - gi * (uint32_t)p.G;
+    }
     if (gi >= p.groups) return;                           // whole workgroup leaves together
     const uint32_t g = gi % (uint32_t)p.Hkv;
     const uint32_t sl = (gi / (uint32_t)p.Hkv) % p.slabs;

@@ -36,9 +36,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_kernel
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int h = blockIdx.x * kWavesPerBlock + w;
+    uint32_t bx, by;
+    workgroup_xy<NARROW>(bx, by);
+    const int h = (int)bx * kWavesPerBlock + w;
     const uint32_t zb = blockIdx.z / sp.tiles_hi;
-    const uint32_t tt = (blockIdx.z - zb * sp.tiles_hi) * sp.tiles_lo + blockIdx.y;
+    const uint32_t tt = (blockIdx.z - zb * sp.tiles_hi) * sp.tiles_lo + by;
     if (h >= p.Hq || tt >= sp.tiles) return;              // no workgroup barrier below
     const int b = (int)zb;
     const int g = h / p.G;
@@ -203,9 +205,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_shared
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int h = blockIdx.x * kWavesPerBlock + w;
+    uint32_t bx, by;
+    workgroup_xy<NARROW>(bx, by);
+    const int h = (int)bx * kWavesPerBlock + w;
     const uint32_t zb = blockIdx.z / sp.tiles_hi;
-    const uint32_t tt = (blockIdx.z - zb * sp.tiles_hi) * sp.tiles_lo + blockIdx.y;
+    const uint32_t tt = (blockIdx.z - zb * sp.tiles_hi) * sp.tiles_lo + by;
     if (tt >= sp.tiles) return;                           // whole workgroup leaves together (every head exists: 4 divides G)
     const int b = (int)zb;
     const int g = h / p.G;
@@ -404,9 +408,11 @@ __global__ __launch_bounds__(kWavesPerBlock * 64, 2) void mfma_fwd_stream_chunke
     extern __shared__ __attribute__((aligned(16))) char smem[];
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int h = blockIdx.x * kWavesPerBlock + w;
+    uint32_t bx, by;
+    workgroup_xy<NARROW>(bx, by);
+    const int h = (int)bx * kWavesPerBlock + w;
     const uint32_t zb = blockIdx.z / sp.tiles_hi;
-    const uint32_t tt = (blockIdx.z - zb * sp.tiles_hi) * sp.tiles_lo + blockIdx.y;
+    const uint32_t tt = (blockIdx.z - zb * sp.tiles_hi) * sp.tiles_lo + by;
     if (tt >= sp.tiles) return;                           // whole workgroup leaves together (every head exists: 4 divides G)
     const int b = (int)zb;
     const int g = h / p.G;
