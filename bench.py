@@ -31,7 +31,7 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5", "c6", "c3_rope", "c4_train"])
+    ap.add_argument("--workload", default="c3", choices=["c2", "c3", "c4", "c5", "c6", "c3_rope", "c4_train", "c3_w100_train"])
     ap.add_argument("--rotate", type=int, default=3, help="independent buffer sets cycled through, so that the "
                     "256 MB Infinity Cache cannot serve one step's re-reads from the previous step")
     ap.add_argument("--also", default=None, help="comma-separated further workloads measured in the same run and "
@@ -42,7 +42,7 @@ def parse_args():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     args = ap.parse_args()
     if args.also is None:
-        args.also = "c2,c4,c5,c6,c3_rope,c4_train" if args.workload == "c3" else ""
+        args.also = "c2,c4,c5,c6,c3_rope,c4_train,c3_w100_train" if args.workload == "c3" else ""
     return args
 
 

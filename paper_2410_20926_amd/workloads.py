@@ -63,6 +63,9 @@ WORKLOADS = {
     "c3_rope": Workload("c3_rope", 3, "bf16", 1, 32, 8, 128, (32, 32, 32), True, 1.0 / math.sqrt(128), rope_base=10000.0),
     # config 4's shape as a training step (forward + backward): axes of 64 positions in the backward
     "c4_train": Workload("c4_train", 4, "bf16", 1, 32, 8, 128, (64, 64, 32), True, 1.0 / math.sqrt(128), backward=True),
+    # the attention geometry of the smallest of the paper's three backbones (Sec. 4.1): 32 heads of width 100, no grouping,
+    # as a training step on config 3's shape; rows of 200 bytes, neither 16-byte aligned nor whole cache lines
+    "c3_w100_train": Workload("c3_w100_train", 3, "bf16", 1, 32, 32, 100, (32, 32, 32), True, 0.1, backward=True),
 }
 
 
