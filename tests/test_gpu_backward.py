@@ -136,6 +136,30 @@ def test_config5_shape_all_groups():
     print(f"config 5: largest error / tolerance over all groups {worst:.3f}")
 
 
+def test_width_100_training_step_full_size():
+    """32 ungrouped heads of width 100 (rows of 200 bytes: neither 16-byte aligned nor whole cache lines), 32x32x32 causal,
+    forward + backward at full size, in the launch configuration the bench times (workgroups renumbered per XCD, the hops
+    on their own): the forward on every head, the gradients on heads 0 and 1 (an aligned and a misaligned row start),
+    17 and 31, every element."""
+    w = WORKLOADS["c3_w100_train"]
+    q, k, v, d_o = make_workload_inputs(w)
+    o, plan, dev = multihop_forward(q, k, v, w.dims, w.dtype, w.causal, save=True)
+    assert plan.fused_position() == -1 and plan.hop_kernel(0, ta.TA_VIN_KV) == "mfma_bf16_n32"
+    assert plan.hop_backward_kernel(1, ta.TA_VIN_O) == "mfma_bf16_bwd_n32"
+    ref_o = orc.tensorized_attention_forward(q, k, v, w.dims, w.causal)
+    err = float(np.abs(o - ref_o).max())
+    assert np.isfinite(o).all() and err <= 2e-2, f"forward: max-abs error {err:.3e}"
+    dq, dk, dv = multihop_backward(plan, dev, d_o, w.dtype)
+    assert np.isfinite(dq).all() and np.isfinite(dk).all() and np.isfinite(dv).all()
+    worst = 0.0
+    for h in (0, 1, 17, 31):
+        hs = slice(h, h + 1)
+        ref, tol = backward_reference_and_tolerance(q[:, :, hs], k[:, :, hs], v[:, :, hs], d_o[:, :, hs], w.dims, w.causal, w.dtype)
+        for got, r_, t_, name in zip((dq[:, :, hs], dk[:, :, hs], dv[:, :, hs]), ref, tol, ("dq", "dk", "dv")):
+            worst = max(worst, check_gradient(got, r_, t_, f"{name} head {h}"))
+    print(f"width 100: forward max-abs error {err:.3e}; largest gradient error / tolerance {worst:.3f}")
+
+
 def test_training_step_at_131072_tokens_three_groups():
     """32/8 heads, D=128, 64x64x32 causal, forward + backward at full size: the two-tile backward on both 64-long
     axes (once as the hop that emits dV), the one-tile backward on the innermost one; key/value groups 0, 3 and 7,
