@@ -35,7 +35,7 @@ def parse_args():
     ap.add_argument("--rotate", type=int, default=3, help="independent buffer sets cycled through, so that the "
                     "256 MB Infinity Cache cannot serve one step's re-reads from the previous step")
     ap.add_argument("--also", default=None, help="comma-separated further workloads measured in the same run and "
-                    "reported under other_workloads (default: c2,c4,c5,c6,c3_rope,c4_train next to c3, none otherwise)")
+                    "reported under other_workloads (default: c2,c4,c5,c6,c3_rope,c4_train,c3_w100_train next to c3, none otherwise)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true", help="also launch the plain copy kernel on 1 GiB a few "
                     "times, so that a hardware-counter run of this command has a transfer of known size to scale by")
